@@ -1,0 +1,396 @@
+"""Pins for the CPU oracle: each check is something other than the oracle itself.
+
+The paper prints no worked numeric example of gating, dispatch or the expert
+FFN (it names the layer and cites GShard / Switch, Section 5.2 and Section
+3.3.2), so the pins are: brute force in plain Python loops on tiny inputs,
+invariants, closed forms, and special cases that collapse to torch library
+routines (softmax, gelu, silu, linear, topk) evaluated in float64.
+"""
+import itertools
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import moe_oracle as O
+from workloads import WORKLOADS, make_layer, zipf_masses, bf16_round
+
+pytestmark = pytest.mark.filterwarnings("ignore")
+
+
+def tiny(T=24, d=16, f=32, E=4, k=2, act="gelu", dtype="f32", seed=7, **kw):
+    wl = WORKLOADS["tiny"].scaled(T=T, d_model=d, d_ff=f, E=E, k=k, act=act, dtype=dtype, seed=seed, **kw)
+    return wl, make_layer(wl, with_bias=True)
+
+
+# ------------------------------------------------------------------ gate: brute force
+def brute_topk(zrow, k):
+    return sorted(range(len(zrow)), key=lambda e: (-zrow[e], e))[:k]
+
+
+@pytest.mark.parametrize("E,k", [(4, 1), (4, 2), (5, 3), (8, 8), (3, 1)])
+def test_topk_matches_bruteforce_random(E, k):
+    rng = np.random.default_rng(E * 10 + k)
+    z = rng.standard_normal((32, E))
+    got = O.topk_by_logit(z, k)
+    for t in range(z.shape[0]):
+        assert list(got[t]) == brute_topk(list(z[t]), k)
+
+
+def test_topk_ties_lower_index_first():
+    # every row is a multiset with repeated values: all orderings of a small alphabet
+    rows = [list(p) for p in itertools.product([0.0, 1.0, -2.0], repeat=4)]
+    z = np.array(rows)
+    for k in (1, 2, 3, 4):
+        got = O.topk_by_logit(z, k)
+        for t, row in enumerate(rows):
+            assert list(got[t]) == brute_topk(row, k), (row, k)
+
+
+def test_gate_logits_exact_small_integers():
+    # integer-valued inputs: every partial sum is exact, so the value is fixed regardless of order
+    rng = np.random.default_rng(3)
+    x = rng.integers(-4, 5, size=(6, 5)).astype(np.float64)
+    w = rng.integers(-3, 4, size=(5, 3)).astype(np.float64)
+    b = np.array([1.0, -2.0, 0.0])
+    z = O.gate_logits(x, w, b)
+    for t in range(6):
+        for e in range(3):
+            assert z[t, e] == sum(x[t, i] * w[i, e] for i in range(5)) + b[e]
+
+
+def test_gate_transposed_operand_would_fail():
+    # asymmetric hand-made case: z = x W, not x W^T
+    x = np.array([[1.0, 2.0]])
+    w = np.array([[1.0, 10.0], [100.0, 1000.0]])
+    z = O.gate_logits(x, w, None)
+    assert z.tolist() == [[201.0, 2010.0]]
+    p, idx, wgt = O.gate(x, w, None, 1, False)
+    assert idx.tolist() == [[1]]
+
+
+def test_softmax_against_torch_and_sums_to_one():
+    rng = np.random.default_rng(0)
+    z = rng.standard_normal((50, 16)) * 5
+    p = O.softmax_rows(z)
+    ref = torch.softmax(torch.from_numpy(z), dim=1).numpy()
+    assert np.allclose(p, ref, rtol=1e-13, atol=0)
+    assert np.abs(p.sum(1) - 1).max() < 1e-12
+    # shift invariance and a closed form
+    assert np.allclose(O.softmax_rows(z + 1000.0), p, rtol=1e-12)
+    two = O.softmax_rows(np.array([[0.0, math.log(3.0)]]))
+    assert np.allclose(two, [[0.25, 0.75]], rtol=1e-14)
+
+
+@pytest.mark.parametrize("k,renorm", [(1, False), (2, True), (2, False), (4, True)])
+def test_gate_weights(k, renorm):
+    wl, L = tiny(E=4, k=k)
+    p, idx, w = O.gate(L["x"], L["w_router"], L["b_router"], k, renorm)
+    z = torch.from_numpy(L["x"]).double() @ torch.from_numpy(L["w_router"]).double()
+    tv, ti = torch.topk(z, k, dim=1)           # no ties in random data
+    assert np.array_equal(idx, ti.numpy().astype(np.int32))
+    pt = torch.softmax(z, dim=1)
+    sel = torch.gather(pt, 1, ti)
+    if renorm:
+        sel = sel / sel.sum(1, keepdim=True)
+        assert np.abs(w.sum(1) - 1).max() < 1e-12
+    assert np.allclose(w, sel.numpy(), rtol=1e-12)
+    if k == 4 and renorm:
+        # k == E: weights are the whole softmax, reordered
+        assert np.allclose(np.sort(w, 1), np.sort(p, 1), rtol=1e-12)
+
+
+def test_gate_bias_shifts_routing():
+    wl, L = tiny(E=4, k=1)
+    b = np.array([0.0, 0.0, 50.0, 0.0], dtype=np.float32)
+    _, idx, w = O.gate(L["x"], L["w_router"], b, 1, False)
+    assert (idx == 2).all() and (w > 0.999).all()
+
+
+# ------------------------------------------------------------------ capacity
+def test_capacity_closed_forms():
+    assert O.capacity(256, 4, 1, 1.25) == 80
+    assert O.capacity(8192, 16, 2, 1.25) == 1280
+    assert O.capacity(32768, 8, 2, 1.0) == 8192
+    assert O.capacity(16384, 8, 1, 0.0) == O.DROPLESS
+    assert O.capacity(16384, 8, 1, -1.0) == O.DROPLESS
+    assert O.capacity(10, 3, 1, 1.0) == 4          # ceil(10/3)
+    assert O.capacity(9, 3, 1, 1.0) == 3
+    assert O.capacity(1, 64, 1, 0.01) == 1         # never below one slot
+    # float32 value of 1.1 is slightly above 11/10: 10*1.1f/1 rounds up to 12, not 11
+    assert float(np.float32(1.1)) > 1.1
+    assert O.capacity(10, 1, 1, 1.1) == 12
+    for T, E, k, cf in [(7, 3, 2, 1.5), (100, 7, 2, 0.3), (33, 5, 1, 2.0)]:
+        exact = Fraction(k * T) * Fraction(float(np.float32(cf))) / E
+        assert O.capacity(T, E, k, cf) == max(1, math.ceil(exact))
+
+
+# ------------------------------------------------------------------ dispatch: brute force
+def brute_slotting(idx, E, C):
+    T, k = idx.shape
+    counts = [0] * E
+    kept = [0] * E
+    slot = {}
+    for a in range(k * T):
+        j, t = divmod(a, T)
+        e = int(idx[t, j])
+        if kept[e] < C:
+            slot[a] = (e, kept[e])
+            kept[e] += 1
+        counts[e] += 1
+    offsets = [0]
+    for e in range(E):
+        offsets.append(offsets[-1] + kept[e])
+    a2r = [-1] * (k * T)
+    for a, (e, s) in slot.items():
+        a2r[a] = offsets[e] + s
+    r2a = [None] * offsets[-1]
+    for a, r in enumerate(a2r):
+        if r >= 0:
+            r2a[r] = a
+    return counts, offsets, a2r, r2a
+
+
+@pytest.mark.parametrize("T,E,k,C", [(16, 4, 1, 3), (16, 4, 2, 5), (31, 3, 2, 100), (8, 2, 2, 1),
+                                     (20, 5, 3, 4), (5, 4, 1, O.DROPLESS)])
+def test_dispatch_plan_matches_bruteforce(T, E, k, C):
+    rng = np.random.default_rng(T + E + k)
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    counts, offsets, a2r, r2a = O.dispatch_plan(idx, E, C)
+    bc, bo, ba, br = brute_slotting(idx, E, C)
+    assert counts.tolist() == bc and offsets.tolist() == bo
+    assert a2r.tolist() == ba and r2a.tolist() == br
+
+
+def test_dispatch_invariants_overflow():
+    rng = np.random.default_rng(5)
+    T, E, k, C = 200, 4, 2, 60
+    z = rng.standard_normal((T, E)) + np.array([2.0, 0, 0, -1.0])     # skew so that expert 0 overflows
+    idx = O.topk_by_logit(z, k)
+    x = rng.standard_normal((T, 8))
+    counts, offsets, a2r, r2a, xd = O.dispatch(x, idx, E, C)
+    assert counts.sum() == k * T and counts[0] > C
+    kept = np.minimum(counts, C)
+    assert np.array_equal(np.diff(offsets), kept) and offsets[0] == 0
+    R = offsets[-1]
+    assert (a2r >= 0).sum() == R and len(r2a) == R
+    assert np.array_equal(a2r[r2a], np.arange(R))            # inverse on kept rows
+    experts_of_a = idx.T.reshape(-1)
+    for e in range(E):
+        rows = np.arange(offsets[e], offsets[e + 1])
+        a_rows = r2a[rows]
+        assert (experts_of_a[a_rows] == e).all()
+        assert (np.diff(a_rows) > 0).all()                   # rows of an expert sorted by assignment id
+        dropped = np.nonzero((experts_of_a == e) & (a2r < 0))[0]
+        if dropped.size:
+            assert dropped.min() > a_rows.max()              # drops follow token order
+    assert np.array_equal(xd, x[r2a % T])                    # rows are pure copies
+    # all first choices outrank all second choices
+    first_dropped = (a2r[:T] < 0) & (experts_of_a[:T] == 0)
+    second_kept = (a2r[T:] >= 0) & (experts_of_a[T:] == 0)
+    assert not (first_dropped.any() and second_kept.any())
+
+
+def test_infinite_capacity_equals_dropless_and_empty_expert():
+    idx = np.array([[0], [0], [2], [0]], dtype=np.int32)      # expert 1 and 3 receive nothing
+    a = O.dispatch_plan(idx, 4, O.DROPLESS)
+    b = O.dispatch_plan(idx, 4, 10 ** 6)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+    assert a[0].tolist() == [3, 0, 1, 0] and a[1].tolist() == [0, 3, 3, 4, 4]
+    assert a[2].tolist() == [0, 1, 3, 2]
+
+
+# ------------------------------------------------------------------ expert FFN vs torch library
+def torch_dense_ffn(x, L, e, act):
+    xt = torch.from_numpy(np.asarray(x)).double()
+    if act == "gelu":
+        h = F.gelu(F.linear(xt, torch.from_numpy(L["w1"][e]).double().T, torch.from_numpy(L["b1"][e]).double()))
+        return F.linear(h, torch.from_numpy(L["w2"][e]).double().T, torch.from_numpy(L["b2"][e]).double())
+    g = F.linear(xt, torch.from_numpy(L["w_gate_proj"][e]).double().T)
+    u = F.linear(xt, torch.from_numpy(L["w_up"][e]).double().T)
+    return F.linear(F.silu(g) * u, torch.from_numpy(L["w_down"][e]).double().T)
+
+
+def test_activations_against_library_and_closed_forms():
+    u = np.linspace(-6, 6, 241)
+    assert np.allclose(O.gelu(u), F.gelu(torch.from_numpy(u)).numpy(), rtol=1e-13, atol=1e-15)
+    assert np.allclose(O.silu(u), F.silu(torch.from_numpy(u)).numpy(), rtol=1e-13, atol=1e-15)
+    assert O.gelu(np.array([0.0]))[0] == 0.0 and O.silu(np.array([0.0]))[0] == 0.0
+    # gelu(u) - gelu(-u) = u and silu(u) - silu(-u) = u
+    assert np.allclose(O.gelu(u) - O.gelu(-u), u, atol=1e-14)
+    assert np.allclose(O.silu(u) - O.silu(-u), u, atol=1e-14)
+    # Phi(1) = 0.8413447460685429...
+    assert abs(O.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_single_expert_is_dense_ffn(act):
+    wl, L = tiny(T=20, d=16, f=24, E=1, k=1, act=act)
+    r = O.layer_forward(L["x"], L, E=1, k=1, capacity_factor=0.0, renormalize=False, act=act)
+    assert (r["topk_idx"] == 0).all() and np.allclose(r["topk_w"], 1.0)
+    ref = torch_dense_ffn(L["x"], L, 0, act).numpy()
+    assert np.allclose(r["out"], ref, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(r["xd"], L["x"])
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_k_equals_E_is_full_softmax_mixture(act):
+    wl, L = tiny(T=12, d=8, f=20, E=3, k=3, act=act, seed=11)
+    r = O.layer_forward(L["x"], L, E=3, k=3, capacity_factor=0.0, renormalize=True, act=act)
+    z = torch.from_numpy(L["x"]).double() @ torch.from_numpy(L["w_router"]).double() \
+        + torch.from_numpy(L["b_router"]).double()
+    p = torch.softmax(z, dim=1)
+    ref = sum(p[:, e:e + 1] * torch_dense_ffn(L["x"], L, e, act) for e in range(3)).numpy()
+    assert np.allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_identity_experts_top1_returns_gate_weighted_input(act):
+    T, d, E = 30, 6, 4
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((T, d))
+    eye = np.eye(d)
+    L = {"w_router": rng.standard_normal((d, E)), "b_router": None}
+    if act == "gelu":
+        # gelu(u) - gelu(-u) = u  ->  W1 = [I, -I], W2 = [I; -I] is the identity map
+        L["w1"] = np.tile(np.concatenate([eye, -eye], 1)[None], (E, 1, 1))
+        L["w2"] = np.tile(np.concatenate([eye, -eye], 0)[None], (E, 1, 1))
+        L["b1"] = None
+        L["b2"] = None
+    else:
+        # last feature is the constant 1 so that the "up" projection can be 1 everywhere
+        x[:, -1] = 1.0
+        up = np.zeros((d, 2 * d))
+        up[-1, :] = 1.0
+        L["w_gate_proj"] = np.tile(np.concatenate([eye, -eye], 1)[None], (E, 1, 1))
+        L["w_up"] = np.tile(up[None], (E, 1, 1))
+        L["w_down"] = np.tile(np.concatenate([eye, -eye], 0)[None], (E, 1, 1))
+    r = O.layer_forward(x, L, E=E, k=1, capacity_factor=0.0, renormalize=False, act=act)
+    p1 = r["probs"].max(1)
+    assert np.allclose(r["yd"], r["xd"], atol=1e-13)
+    assert np.allclose(r["out"], p1[:, None] * x, atol=1e-13)
+
+
+def test_expert_rows_use_their_own_expert():
+    # expert e multiplies by (e+1): catches an off-by-one in the offsets or expert index
+    T, d, E = 16, 4, 4
+    rng = np.random.default_rng(9)
+    x = np.abs(rng.standard_normal((T, d))) + 30.0           # gelu(u) == u to 1e-16 relative for u > 30
+    eye = np.eye(d)
+    L = {"w1": np.stack([eye] * E), "w2": np.stack([(e + 1) * eye for e in range(E)]), "b1": None, "b2": None}
+    offsets = np.array([0, 3, 3, 10, 16], dtype=np.int32)
+    yd = O.expert_ffn(x, offsets, L, "gelu")
+    scale = np.repeat(np.arange(1, E + 1), np.diff(offsets))
+    assert np.allclose(yd, scale[:, None] * x, rtol=1e-14)
+
+
+# ------------------------------------------------------------------ combine + whole layer
+def test_combine_bruteforce_with_drops_and_residual():
+    rng = np.random.default_rng(4)
+    T, k, d, R = 9, 2, 3, 11
+    a2r = np.full(k * T, -1, dtype=np.int32)
+    a2r[rng.permutation(k * T)[:R]] = rng.permutation(R)
+    a2r[0] = -1
+    a2r[T] = -1                                               # token 0 loses both choices
+    yd = rng.standard_normal((R, d))
+    w = rng.random((T, k))
+    res = rng.standard_normal((T, d))
+    out = O.combine(yd, a2r, w, res)
+    for t in range(T):
+        acc = [res[t, c] for c in range(d)]
+        for j in range(k):
+            r = a2r[j * T + t]
+            if r >= 0:
+                for c in range(d):
+                    acc[c] += w[t, j] * yd[r, c]
+        assert np.allclose(out[t], acc, rtol=1e-14)
+    assert np.array_equal(out[0], res[0])
+    assert np.array_equal(O.combine(yd, a2r, w, None)[0], np.zeros(d))
+
+
+def test_layer_bruteforce_token_by_token():
+    wl, L = tiny(T=40, d=8, f=12, E=4, k=2, seed=21)
+    kw = dict(E=4, k=2, capacity_factor=0.5, renormalize=True, act="gelu")
+    r = O.layer_forward(L["x"], L, **kw)
+    assert r["capacity"] == 10 and (r["assign_to_row"] < 0).any()     # some drops
+    z = L["x"].astype(np.float64) @ L["w_router"].astype(np.float64) + L["b_router"]
+    used = [0] * 4
+    keep = {}
+    for a in range(2 * 40):
+        j, t = divmod(a, 40)
+        e = brute_topk(list(z[t]), 2)[j]
+        if used[e] < 10:
+            used[e] += 1
+            keep[(t, j)] = e
+    for t in range(40):
+        p = torch.softmax(torch.from_numpy(z[t]), 0).numpy()
+        top = brute_topk(list(z[t]), 2)
+        s = p[top[0]] + p[top[1]]
+        ref = np.zeros(8)
+        for j in range(2):
+            if (t, j) in keep:
+                ref += p[top[j]] / s * torch_dense_ffn(L["x"][t:t + 1], L, top[j], "gelu").numpy()[0]
+        assert np.allclose(r["out"][t], ref, rtol=1e-11, atol=1e-13)
+    samp = O.sampled_tokens_forward(L["x"], L, r, np.array([0, 5, 39]), act="gelu")
+    assert np.allclose(samp, r["out"][[0, 5, 39]], rtol=1e-12, atol=1e-13)
+
+
+def test_token_permutation_equivariance_when_dropless():
+    wl, L = tiny(T=32, d=8, f=16, E=4, k=2, seed=5)
+    kw = dict(E=4, k=2, capacity_factor=0.0, renormalize=True, act="gelu")
+    a = O.layer_forward(L["x"], L, **kw)["out"]
+    perm = np.random.default_rng(0).permutation(32)
+    b = O.layer_forward(L["x"][perm], L, **kw)["out"]
+    assert np.allclose(b, a[perm], rtol=1e-12, atol=1e-13)
+
+
+def test_workload_statistics():
+    m = zipf_masses(8, 1.2)
+    assert np.allclose(m, [0.4286, 0.1866, 0.1147, 0.0812, 0.0621, 0.0499, 0.0415, 0.0353], atol=6e-5)
+    a = np.array([1.0, 1.00390625, 1.005859375, 3.1415926, -2.7], dtype=np.float32)
+    assert np.array_equal(bf16_round(a), torch.from_numpy(a).to(torch.bfloat16).float().numpy())
+    wl = WORKLOADS["skew"].scaled(T=4096)
+    L = make_layer(wl)
+    r = O.gate(L["x"], L["w_router"], L["b_router"], 1, False)
+    share = np.bincount(r[1][:, 0], minlength=8) / 4096
+    assert share[0] > 0.45 and share.argmax() == 0            # literal Zipf log-prior: heavier than 40 %
+    L40 = make_layer(WORKLOADS["skew40"].scaled(T=4096))
+    r40 = O.gate(L40["x"], L40["w_router"], L40["b_router"], 1, False)
+    assert 0.33 < (r40[1][:, 0] == 0).mean() < 0.48
+
+
+# ------------------------------------------------------------------ ring schedule (Section 3.3.2)
+@pytest.mark.parametrize("N,K,steps", [(6, 2, 2), (5, 2, 3), (24, 4, 1), (3, 3, 2), (2, 4, 2), (7, 3, 2)])
+def test_ring_schedule_invariants(N, K, steps):
+    ev = O.ring_schedule(N, K, steps)
+    Ke = min(K, N)
+    resident = {}                       # slot -> layer
+    computes = []
+    for i, (kind, layer, slot) in enumerate(ev):
+        assert 0 <= slot < Ke and 0 <= layer < N
+        if kind == "load":
+            resident[slot] = layer
+        else:
+            assert resident.get(slot) == layer      # a layer computes only from a slot holding it
+            computes.append(layer)
+            if Ke < N:
+                # release-then-load: the very next event refills this slot with the layer K ahead
+                assert ev[i + 1] == ("load", (len(computes) - 1 + Ke) % N, slot)
+        assert len(resident) <= Ke                  # never more than K sections resident
+    assert computes == [g % N for g in range(steps * N)]
+    assert ev[:Ke] == [("load", l, l) for l in range(Ke)]          # step 2 of the timeline: preload K
+    loads = sum(1 for e in ev if e[0] == "load")
+    assert loads == (Ke + steps * N if Ke < N else Ke)
+
+
+def test_stack_forward_is_residual_chain():
+    wl, L0 = tiny(T=10, d=8, f=12, E=2, k=1, seed=1)
+    _, L1 = tiny(T=10, d=8, f=12, E=2, k=1, seed=2)
+    kw = dict(E=2, k=1, capacity_factor=0.0, renormalize=False, act="gelu")
+    h1 = L0["x"] + O.layer_forward(L0["x"], L0, **kw)["out"]
+    h2 = h1 + O.layer_forward(h1, L1, **kw)["out"]
+    assert np.allclose(O.stack_forward(L0["x"], [L0, L1], **kw), h2, rtol=1e-13)
