@@ -1,0 +1,270 @@
+/*
+ * moesys.h - C ABI of the MI355X (gfx950) MoE-layer forward library.
+ *
+ * The library implements the data-parallel hot path that the MoESys paper's
+ * training and inference system exists to keep fed: the forward pass of a
+ * sparsely-gated Mixture-of-Experts layer on one GPU (top-k softmax gate,
+ * capacity-bounded dispatch, per-expert FFN, gate-weighted combine), and the
+ * paper's ring memory offloading of expert parameters (Section 3.3.2).
+ *
+ * General rules of the boundary
+ *  - Every pointer marked "device" is caller-owned HBM; "host" is caller-owned
+ *    host memory ("pinned host" must come from hipHostMalloc / a pinned torch
+ *    tensor).  The library allocates no device memory and keeps no reference
+ *    to caller buffers after a call returns, except moe_ring (stated there).
+ *  - Every compute call only enqueues work on the given HIP stream
+ *    (hipStream_t passed as void*; NULL = the default stream) and never
+ *    synchronises the device; per-expert row counts stay in HBM and are read
+ *    by the kernels, never by the host (the paper's motivation for avoiding
+ *    host<->device round trips in routing, Section 1 and Section 3.3.1).
+ *  - Arguments are validated before any launch; errors are return codes, and
+ *    moe_last_error() gives a thread-local explanation.  A call that returns
+ *    an error has launched nothing.
+ *  - All matrices are dense row-major.  Token activations x[T,d_model];
+ *    router weight w_router[d_model,E] (input-major) in float32.
+ *  - dtype = MOE_F32: x, expert weights, xd, h, yd, out are float32.
+ *    dtype = MOE_BF16: they are bfloat16 (raw 16-bit), accumulated in float32
+ *    on the MFMA units; h, yd and out are rounded to bfloat16 once each.
+ *    The gate always produces float32 weights (softmax in fp32, Section 5.2).
+ */
+#ifndef MOESYS_H
+#define MOESYS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = 1, /* null pointer, bad size, k > E, misaligned d ...   */
+  MOE_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for         */
+  MOE_ERR_WORKSPACE = 3,   /* workspace pointer null/misaligned or too small     */
+  MOE_ERR_HIP = 4,         /* a HIP runtime call failed (see moe_last_error)     */
+  MOE_ERR_STATE = 5        /* ring used out of order                             */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+typedef enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 } moe_act;
+
+/* Expert weight layout.  OUTPUT_MAJOR ([E,out,in], the contraction index
+ * contiguous) is the layout the bf16 MFMA kernels read; INPUT_MAJOR
+ * ([E,in,out]) is accepted by the float32 kernels and converted once, outside
+ * the hot path, with moe_transpose_expert_weights. */
+typedef enum { MOE_LAYOUT_INPUT_MAJOR = 0, MOE_LAYOUT_OUTPUT_MAJOR = 1 } moe_layout;
+
+#define MOE_MAX_EXPERTS 256
+#define MOE_MAX_TOPK 8
+#define MOE_DROPLESS INT32_MAX
+
+typedef struct {
+  int32_t T;        /* tokens in this call                        (>= 0)            */
+  int32_t d_model;  /* multiple of 64                                               */
+  int32_t d_ff;     /* multiple of 64                                               */
+  int32_t E;        /* experts, 1..MOE_MAX_EXPERTS                                  */
+  int32_t k;        /* experts per token, 1..min(E, MOE_MAX_TOPK)                   */
+  float capacity_factor; /* <= 0: dropless; else C = ceil(k*T*CF/E), at least 1     */
+  int32_t renormalize;   /* 1: top-k weights divided by their sum (GShard top-2);
+                            0: weights are the softmax probabilities (Switch top-1) */
+  int32_t act;      /* moe_act                                                      */
+  int32_t dtype;    /* moe_dtype                                                    */
+} moe_config;
+
+/* Expert parameters, all device pointers.  GELU experts use w1,b1,w2,b2;
+ * SwiGLU experts use w_gate_proj,w_up,w_down.  Biases may be NULL (= zero).
+ *   INPUT_MAJOR : w1,w_gate_proj,w_up [E,d_model,d_ff];  w2,w_down [E,d_ff,d_model]
+ *   OUTPUT_MAJOR: w1,w_gate_proj,w_up [E,d_ff,d_model];  w2,w_down [E,d_model,d_ff]
+ * b1 [E,d_ff], b2 [E,d_model] in the activation dtype.
+ * w_router [d_model,E] and b_router [E] (nullable) are float32. */
+typedef struct {
+  const void* w1;
+  const void* b1;
+  const void* w2;
+  const void* b2;
+  const void* w_gate_proj;
+  const void* w_up;
+  const void* w_down;
+  const float* w_router;
+  const float* b_router;
+  int32_t layout; /* moe_layout of the expert matrices */
+} moe_weights;
+
+/* Byte offsets of every intermediate inside the workspace of moe_layer_forward
+ * (so that a caller, e.g. a parity test, can read them back). */
+typedef struct {
+  size_t topk_idx;       /* int32 [T,k]                                   */
+  size_t topk_w;         /* float [T,k]                                   */
+  size_t expert_counts;  /* int32 [E]    assignments per expert before capacity */
+  size_t expert_offsets; /* int32 [E+1]  first dispatched row of each expert    */
+  size_t assign_to_row;  /* int32 [k*T]  row of assignment a=j*T+t, -1 dropped  */
+  size_t row_to_assign;  /* int32 [k*T]  first R entries valid                  */
+  size_t xd;             /* dtype [R_max,d_model] dispatched rows               */
+  size_t h;              /* dtype [R_max,d_ff]    hidden activations            */
+  size_t yd;             /* dtype [R_max,d_model] expert outputs                */
+  size_t scratch;        /* dispatch bookkeeping scratch                        */
+  size_t total;          /* == moe_workspace_bytes(cfg, MOE_WS_LAYER)           */
+  int64_t r_max;         /* min(k*T, E*C): upper bound of dispatched rows       */
+} moe_ws_layout;
+
+typedef enum { MOE_WS_LAYER = 0, MOE_WS_DISPATCH = 1, MOE_WS_FFN = 2 } moe_ws_kind;
+
+/* ---- host-only helpers (no GPU needed) ---------------------------------- */
+
+const char* moe_status_string(int32_t status);
+/* Thread-local text describing the last error returned on this thread. */
+const char* moe_last_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t moe_version(void);
+
+/* Validates cfg (same checks every compute call performs). */
+int32_t moe_config_check(const moe_config* cfg);
+
+/* Expert capacity C = ceil(k*T*CF/E) in exact integer arithmetic (CF is the
+ * float32 value given), at least 1; MOE_DROPLESS if capacity_factor <= 0.
+ * The paper leaves capacity unspecified; this is the GShard/Switch form of the
+ * gates it evaluates (Section 5.2).  Returns -1 on an invalid cfg. */
+int32_t moe_capacity(const moe_config* cfg);
+
+/* Bytes of device workspace needed by moe_layer_forward (MOE_WS_LAYER),
+ * moe_dispatch (MOE_WS_DISPATCH) or moe_expert_ffn (MOE_WS_FFN).  Workspaces
+ * must be 256-byte aligned.  Returns 0 on an invalid cfg. */
+size_t moe_workspace_bytes(const moe_config* cfg, int32_t kind);
+int32_t moe_workspace_layout(const moe_config* cfg, moe_ws_layout* out);
+
+/* ---- the hot path -------------------------------------------------------- */
+
+/* Top-k softmax gate (the GShard top-2 / top-1 gates of Section 5.2, softmax
+ * in fp32 as Section 5.2 states).
+ *   z[t,e] = sum_i x[t,i]*w_router[i,e] + b_router[e];  p = softmax_e(z)
+ *   topk_idx[t,0..k) = experts of the k largest z[t,.], descending, equal
+ *                      logits -> lower expert index first
+ *   topk_w[t,j] = p[t,topk_idx[t,j]]  (divided by their sum if renormalize)
+ * Logits that decide the ranking are accumulated so that the selection equals
+ * the one made on exactly computed logits (products of the stored values are
+ * exact in float64; see the kernel for the fast path / exact path split).
+ * x device [T,d_model] (cfg.dtype); w_router device [d_model,E] f32; b_router
+ * device [E] f32 or NULL; topk_idx device int32 [T,k]; topk_w device f32
+ * [T,k]; probs device f32 [T,E] or NULL. */
+int32_t moe_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                 int32_t* topk_idx, float* topk_w, float* probs, void* stream);
+
+/* Capacity-bounded, order-preserving dispatch.  Assignment a = j*T + t
+ * (choice-major: every first choice outranks every second choice; inside a
+ * choice, token order).  Expert e keeps its first min(count_e, C) assignments;
+ * kept rows of expert e are rows [expert_offsets[e], expert_offsets[e+1]) of
+ * xd in increasing a; the rest are dropped (assign_to_row = -1).
+ * expert_counts device int32 [E] (before capacity); expert_offsets device
+ * int32 [E+1]; assign_to_row device int32 [k*T]; row_to_assign device int32
+ * [k*T] (first R valid, rest untouched); xd device [R_max,d_model] (rows >= R
+ * untouched); ws device scratch of moe_workspace_bytes(cfg, MOE_WS_DISPATCH).
+ * xd may be NULL to build the routing tables only. */
+int32_t moe_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                     int32_t* expert_counts, int32_t* expert_offsets, int32_t* assign_to_row,
+                     int32_t* row_to_assign, void* xd, void* ws, size_t ws_bytes, void* stream);
+
+/* Per-expert FFN (the sparsely activated "switching FFN" of Section 3.2) on
+ * the dispatched rows: for r in [expert_offsets[e], expert_offsets[e+1])
+ *   GELU  : yd[r] = gelu(xd[r] W1_e + b1_e) W2_e + b2_e,  gelu(u) = u*Phi(u)
+ *   SwiGLU: yd[r] = (silu(xd[r] Wg_e) * (xd[r] Wu_e)) Wd_e
+ * as two grouped GEMMs with the activation fused into the first one's
+ * epilogue.  expert_offsets is read on the device.  xd device [R_max,d_model];
+ * yd device [R_max,d_model]; ws device scratch (holds h[R_max,d_ff]) of
+ * moe_workspace_bytes(cfg, MOE_WS_FFN).  MOE_BF16 needs MOE_LAYOUT_OUTPUT_MAJOR
+ * weights (MOE_ERR_UNSUPPORTED otherwise). */
+int32_t moe_expert_ffn(const moe_config* cfg, const moe_weights* w, const void* xd,
+                       const int32_t* expert_offsets, void* yd, void* ws, size_t ws_bytes,
+                       void* stream);
+
+/* Gate-weighted combine:
+ *   out[t] = residual[t] + sum_{j<k, assign_to_row[j*T+t] >= 0} topk_w[t,j] * yd[assign_to_row[j*T+t]]
+ * accumulated in fp32, rounded once to cfg.dtype.  Dropped choices add nothing
+ * and surviving weights are not rescaled.  residual device [T,d_model] or
+ * NULL; out device [T,d_model]; out may alias residual. */
+int32_t moe_combine(const moe_config* cfg, const void* yd, const int32_t* assign_to_row,
+                    const float* topk_w, const void* residual, void* out, void* stream);
+
+/* gate -> dispatch -> expert FFN -> combine on one stream with one workspace
+ * (moe_workspace_bytes(cfg, MOE_WS_LAYER); layout from moe_workspace_layout).
+ * x device [T,d_model]; residual device [T,d_model] or NULL; out device
+ * [T,d_model] (may alias residual, must not alias x unless residual == x). */
+int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const void* x,
+                          const void* residual, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Same as moe_layer_forward, additionally recording HIP events on `stream`
+ * around every kernel so that a bench can attribute time per stage.  `timer`
+ * comes from moe_timer_create.  Adds event-record overhead; not the call to
+ * time end to end. */
+typedef struct moe_timer moe_timer;
+enum { MOE_STAGE_GATE = 0, MOE_STAGE_DISPATCH = 1, MOE_STAGE_GEMM1 = 2, MOE_STAGE_GEMM2 = 3,
+       MOE_STAGE_COMBINE = 4, MOE_STAGE_COUNT = 5 };
+int32_t moe_timer_create(moe_timer** out);
+int32_t moe_timer_destroy(moe_timer* t);
+int32_t moe_layer_forward_timed(const moe_config* cfg, const moe_weights* w, const void* x,
+                                const void* residual, void* out, void* ws, size_t ws_bytes,
+                                void* stream, moe_timer* timer);
+/* Waits for the last timed call to finish and writes MOE_STAGE_COUNT stage
+ * durations in milliseconds (host array). */
+int32_t moe_timer_read(moe_timer* t, float* stage_ms);
+
+/* One-time weight preparation, outside the hot path: dst[e,c,r] = src[e,r,c]
+ * for E matrices of rows x cols elements of cfg-style dtype (device, distinct
+ * buffers).  Converts INPUT_MAJOR expert matrices to OUTPUT_MAJOR. */
+int32_t moe_transpose_expert_weights(const void* src, void* dst, int32_t E, int32_t rows,
+                                     int32_t cols, int32_t dtype, void* stream);
+
+/* ---- ring memory offloading (Section 3.3.2) ------------------------------ */
+/*
+ * The N layers' expert parameter blobs live in pinned host memory; K sections
+ * of one caller-provided HBM region hold K of them.  After layer i has been
+ * computed its section is released and refilled asynchronously, on a separate
+ * copy stream, with the blob of the layer K positions ahead, so copies overlap
+ * the following layers' compute ("calculation-released-load").  Layers must be
+ * used in order 0,1,..,N-1,0,1,... (repeated inference steps wrap around); the
+ * g-th use overall occupies section g mod K.
+ *
+ * The ring keeps the pointers it is given (dev_base, host_layers[i]) until
+ * moe_ring_destroy; the caller keeps them alive.  It owns its events and, if
+ * copy_stream is NULL, its own copy stream (default priority).
+ */
+typedef struct moe_ring moe_ring;
+
+/* Backend of the ring: the HIP runtime by default; tests replace it to check
+ * the schedule on a machine without a GPU.  All functions return 0 on success.
+ * Streams and events are opaque handles. */
+typedef struct {
+  void* user;
+  int32_t (*copy_h2d_async)(void* user, void* dst_dev, const void* src_host, size_t bytes, void* stream);
+  int32_t (*event_create)(void* user, void** event);
+  int32_t (*event_destroy)(void* user, void* event);
+  int32_t (*event_record)(void* user, void* event, void* stream);
+  int32_t (*stream_wait_event)(void* user, void* stream, void* event);
+  int32_t (*event_synchronize)(void* user, void* event);
+  int32_t (*event_elapsed_ms)(void* user, void* start, void* stop, float* ms);
+} moe_ring_backend;
+
+/* dev_base: device region of at least n_sections*layer_bytes bytes (256-byte
+ * aligned); host_layers: host array of n_layers pinned-host blob pointers,
+ * each layer_bytes long (the array itself is copied).  n_sections > n_layers
+ * is clamped to n_layers (everything resident, no refills).  Enqueues the
+ * initial load of layers 0..K-1 on the copy stream.  backend NULL = HIP. */
+int32_t moe_ring_create(void* dev_base, size_t budget_bytes, int32_t n_sections,
+                        const void* const* host_layers, int32_t n_layers, size_t layer_bytes,
+                        void* copy_stream, const moe_ring_backend* backend, moe_ring** out);
+/* Makes `compute_stream` wait until `layer`'s blob is in its section and
+ * returns the section's device address in *dev_ptr.  MOE_ERR_STATE if `layer`
+ * is not the next layer in sequence. */
+int32_t moe_ring_acquire(moe_ring* r, int32_t layer, void* compute_stream, const void** dev_ptr);
+/* Declares `layer`'s compute enqueued on compute_stream: the copy stream waits
+ * for it and then refills the section with layer (layer+K) mod N. */
+int32_t moe_ring_release(moe_ring* r, int32_t layer, void* compute_stream);
+/* Waits for all enqueued copies; reports totals since creation.  copy_ms is
+ * the sum of the copies' own durations from events (nullable outputs). */
+int32_t moe_ring_stats(moe_ring* r, uint64_t* bytes_copied, uint64_t* copies, double* copy_ms);
+int32_t moe_ring_destroy(moe_ring* r);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOESYS_H */

@@ -1,0 +1,297 @@
+"""ctypes binding of libmoesys_hip.so: argument marshalling only.
+
+Every function has the name and meaning of its C counterpart in
+``include/moesys.h``.  Tensors are torch CUDA tensors (torch supplies device
+memory and streams, nothing else); bf16 tensors are ``torch.bfloat16``.  If the
+library has not been built the import of :func:`lib` fails loudly - there is no
+CPU or eager fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libmoesys_hip.so")
+_lib = None
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_ACT_GELU, MOE_ACT_SWIGLU = 0, 1
+MOE_LAYOUT_INPUT_MAJOR, MOE_LAYOUT_OUTPUT_MAJOR = 0, 1
+MOE_WS_LAYER, MOE_WS_DISPATCH, MOE_WS_FFN = 0, 1, 2
+MOE_DROPLESS = 2 ** 31 - 1
+STAGE_NAMES = ["gate", "dispatch", "gemm1", "gemm2", "combine"]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str):
+        super().__init__(f"{where}: status {status}: {detail}")
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d_model", C.c_int32), ("d_ff", C.c_int32), ("E", C.c_int32),
+                ("k", C.c_int32), ("capacity_factor", C.c_float), ("renormalize", C.c_int32),
+                ("act", C.c_int32), ("dtype", C.c_int32)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p),
+                ("w_gate_proj", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
+                ("w_router", C.c_void_p), ("b_router", C.c_void_p), ("layout", C.c_int32)]
+
+
+class _WsLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("topk_idx", "topk_w", "expert_counts", "expert_offsets",
+                                          "assign_to_row", "row_to_assign", "xd", "h", "yd", "scratch",
+                                          "total")] + [("r_max", C.c_int64)]
+
+
+RING_COPY_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p)
+RING_EVCREATE_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.POINTER(C.c_void_p))
+RING_EV_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_void_p)
+RING_EV2_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p)
+RING_ELAPSED_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_float))
+
+
+class RingBackend(C.Structure):
+    _fields_ = [("user", C.c_void_p), ("copy_h2d_async", RING_COPY_FN), ("event_create", RING_EVCREATE_FN),
+                ("event_destroy", RING_EV_FN), ("event_record", RING_EV2_FN), ("stream_wait_event", RING_EV2_FN),
+                ("event_synchronize", RING_EV_FN), ("event_elapsed_ms", RING_ELAPSED_FN)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Loads the built library; raises if it is missing (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2205_10034_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        L.moe_status_string.restype = C.c_char_p
+        L.moe_status_string.argtypes = [C.c_int32]
+        L.moe_last_error.restype = C.c_char_p
+        L.moe_version.restype = C.c_int32
+        L.moe_config_check.argtypes = [C.POINTER(_Config)]
+        L.moe_capacity.argtypes = [C.POINTER(_Config)]
+        L.moe_workspace_bytes.restype = C.c_size_t
+        L.moe_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int32]
+        L.moe_workspace_layout.argtypes = [C.POINTER(_Config), C.POINTER(_WsLayout)]
+        vp = C.c_void_p
+        L.moe_gate.argtypes = [C.POINTER(_Config)] + [vp] * 7
+        L.moe_dispatch.argtypes = [C.POINTER(_Config)] + [vp] * 8 + [C.c_size_t, vp]
+        L.moe_expert_ffn.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
+        L.moe_combine.argtypes = [C.POINTER(_Config)] + [vp] * 6
+        L.moe_layer_forward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
+        L.moe_layer_forward_timed.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp, vp]
+        L.moe_timer_create.argtypes = [C.POINTER(vp)]
+        L.moe_timer_destroy.argtypes = [vp]
+        L.moe_timer_read.argtypes = [vp, C.POINTER(C.c_float)]
+        L.moe_transpose_expert_weights.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.moe_ring_create.argtypes = [vp, C.c_size_t, C.c_int32, C.POINTER(vp), C.c_int32, C.c_size_t, vp,
+                                      C.POINTER(RingBackend), C.POINTER(vp)]
+        L.moe_ring_acquire.argtypes = [vp, C.c_int32, vp, C.POINTER(vp)]
+        L.moe_ring_release.argtypes = [vp, C.c_int32, vp]
+        L.moe_ring_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+        L.moe_ring_destroy.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+def _check(st: int, where: str) -> None:
+    if st != 0:
+        raise MoEError(st, where, lib().moe_last_error().decode())
+
+
+@dataclass
+class MoEConfig:
+    T: int
+    d_model: int
+    d_ff: int
+    E: int
+    k: int
+    capacity_factor: float = 0.0
+    renormalize: bool = False
+    act: str = "gelu"
+    dtype: str = "bf16"
+
+    def c(self) -> _Config:
+        return _Config(self.T, self.d_model, self.d_ff, self.E, self.k, float(self.capacity_factor),
+                       int(bool(self.renormalize)), {"gelu": 0, "swiglu": 1}[self.act],
+                       {"f32": 0, "bf16": 1}[self.dtype])
+
+    @staticmethod
+    def from_workload(wl, **kw) -> "MoEConfig":
+        d = dict(T=wl.T, d_model=wl.d_model, d_ff=wl.d_ff, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor,
+                 renormalize=wl.renormalize, act=wl.act, dtype=wl.dtype)
+        d.update(kw)
+        return MoEConfig(**d)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Weights:
+    """Device pointers of one layer's parameters (keeps the tensors alive)."""
+
+    def __init__(self, tensors: Dict[str, "object"], layout: str = "output_major"):
+        self.tensors = dict(tensors)
+        self.layout = layout
+        g = lambda n: _ptr(self.tensors.get(n))
+        self.c = _Weights(g("w1"), g("b1"), g("w2"), g("b2"), g("w_gate_proj"), g("w_up"), g("w_down"),
+                          g("w_router"), g("b_router"),
+                          MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR)
+
+
+def moe_capacity(cfg: MoEConfig) -> int:
+    c = cfg.c()
+    v = lib().moe_capacity(C.byref(c))
+    if v < 0:
+        _check(lib().moe_config_check(C.byref(c)), "moe_capacity")
+    return v
+
+
+def moe_workspace_bytes(cfg: MoEConfig, kind: int = MOE_WS_LAYER) -> int:
+    c = cfg.c()
+    v = lib().moe_workspace_bytes(C.byref(c), kind)
+    if v == 0:
+        _check(lib().moe_config_check(C.byref(c)), "moe_workspace_bytes")
+    return v
+
+
+def moe_workspace_layout(cfg: MoEConfig) -> Dict[str, int]:
+    c, L = cfg.c(), _WsLayout()
+    _check(lib().moe_workspace_layout(C.byref(c), C.byref(L)), "moe_workspace_layout")
+    return {n: getattr(L, n) for n, _ in _WsLayout._fields_}
+
+
+def moe_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs=None, stream=None):
+    c = cfg.c()
+    _check(lib().moe_gate(C.byref(c), _ptr(x), _ptr(w_router), _ptr(b_router), _ptr(topk_idx), _ptr(topk_w),
+                          _ptr(probs), _stream(stream)), "moe_gate")
+
+
+def moe_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
+                 stream=None):
+    c = cfg.c()
+    _check(lib().moe_dispatch(C.byref(c), _ptr(x), _ptr(topk_idx), _ptr(expert_counts), _ptr(expert_offsets),
+                              _ptr(assign_to_row), _ptr(row_to_assign), _ptr(xd), _ptr(ws),
+                              ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "moe_dispatch")
+
+
+def moe_expert_ffn(cfg, weights: Weights, xd, expert_offsets, yd, ws, stream=None):
+    c = cfg.c()
+    _check(lib().moe_expert_ffn(C.byref(c), C.byref(weights.c), _ptr(xd), _ptr(expert_offsets), _ptr(yd), _ptr(ws),
+                                ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "moe_expert_ffn")
+
+
+def moe_combine(cfg, yd, assign_to_row, topk_w, residual, out, stream=None):
+    c = cfg.c()
+    _check(lib().moe_combine(C.byref(c), _ptr(yd), _ptr(assign_to_row), _ptr(topk_w), _ptr(residual), _ptr(out),
+                             _stream(stream)), "moe_combine")
+
+
+def moe_layer_forward(cfg, weights: Weights, x, residual, out, ws, stream=None):
+    c = cfg.c()
+    _check(lib().moe_layer_forward(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
+                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "moe_layer_forward")
+
+
+class StageTimer:
+    def __init__(self):
+        self.h = C.c_void_p()
+        _check(lib().moe_timer_create(C.byref(self.h)), "moe_timer_create")
+
+    def read(self) -> List[float]:
+        arr = (C.c_float * len(STAGE_NAMES))()
+        _check(lib().moe_timer_read(self.h, arr), "moe_timer_read")
+        return list(arr)
+
+    def close(self):
+        if self.h:
+            lib().moe_timer_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_layer_forward_timed(cfg, weights: Weights, x, residual, out, ws, timer: StageTimer, stream=None):
+    c = cfg.c()
+    _check(lib().moe_layer_forward_timed(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out),
+                                         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream), timer.h),
+           "moe_layer_forward_timed")
+
+
+def moe_transpose_expert_weights(src, dst, stream=None):
+    """dst[e,c,r] = src[e,r,c] for a 3-D tensor [E, rows, cols]."""
+    import torch
+    E, rows, cols = src.shape
+    dt = MOE_BF16 if src.dtype == torch.bfloat16 else MOE_F32
+    _check(lib().moe_transpose_expert_weights(_ptr(src), _ptr(dst), E, rows, cols, dt, _stream(stream)),
+           "moe_transpose_expert_weights")
+
+
+class Ring:
+    """moe_ring_* wrapper.  ``host_layers`` are pinned host tensors (or raw addresses with a custom backend)."""
+
+    def __init__(self, dev_base, budget_bytes: int, n_sections: int, host_layers: Sequence, layer_bytes: int,
+                 copy_stream=None, backend: Optional[RingBackend] = None):
+        self._keep = (dev_base, list(host_layers), copy_stream, backend)
+        ptrs = (C.c_void_p * len(host_layers))(*[h if isinstance(h, int) else h.data_ptr() for h in host_layers])
+        self.h = C.c_void_p()
+        cs = None if copy_stream is None else (copy_stream if isinstance(copy_stream, int) else copy_stream.cuda_stream)
+        base = dev_base if isinstance(dev_base, int) else dev_base.data_ptr()
+        _check(lib().moe_ring_create(base, budget_bytes, n_sections, ptrs, len(host_layers), layer_bytes, cs,
+                                     C.byref(backend) if backend is not None else None, C.byref(self.h)),
+               "moe_ring_create")
+
+    def acquire(self, layer: int, compute_stream=None) -> int:
+        p = C.c_void_p()
+        s = compute_stream if isinstance(compute_stream, int) else _stream(compute_stream)
+        _check(lib().moe_ring_acquire(self.h, layer, s, C.byref(p)), "moe_ring_acquire")
+        return p.value
+
+    def release(self, layer: int, compute_stream=None) -> None:
+        s = compute_stream if isinstance(compute_stream, int) else _stream(compute_stream)
+        _check(lib().moe_ring_release(self.h, layer, s), "moe_ring_release")
+
+    def stats(self):
+        b, n, ms = C.c_uint64(), C.c_uint64(), C.c_double()
+        _check(lib().moe_ring_stats(self.h, C.byref(b), C.byref(n), C.byref(ms)), "moe_ring_stats")
+        return {"bytes_copied": b.value, "copies": n.value, "copy_ms": ms.value}
+
+    def close(self):
+        if self.h:
+            lib().moe_ring_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,203 @@
+// Capacity-bounded, order-preserving token-to-expert dispatch.
+//
+// The paper gives no dispatch algorithm (it names routing and its imbalance,
+// Section 1 and Section 4.1); this is the GShard/Switch capacity rule of the
+// gates it evaluates (Section 5.2), kept entirely on the device so that no
+// count ever travels to the host (the H2D/D2H round trips Section 3.3.1 sets
+// out to remove).
+//
+// Assignment a = j*T + t.  Three bookkeeping kernels and one copy kernel:
+//   count : per block of DISPATCH_BLOCK assignments, a per-expert histogram
+//   scan  : per expert, exclusive scan of the block histograms -> block bases,
+//           total counts, kept = min(count, C), expert_offsets
+//   assign: each block ranks its assignments per expert in order (wave ballots
+//           + cross-wave prefix), slot = block base + rank, row = offset + slot
+//           if slot < C else -1
+//   gather: one wavefront per token reads x[t] once and writes its <= k rows.
+// Everything is integer arithmetic or byte copies: results are bit-exact and
+// independent of scheduling (no atomics whose order could matter: the LDS
+// histogram atomics only add).
+#include "moesys_internal.h"
+
+namespace moesys {
+namespace {
+
+constexpr int BT = 256;                       // threads per bookkeeping block
+constexpr int ROUNDS = DISPATCH_BLOCK / BT;   // assignment rounds per block
+
+__device__ __forceinline__ int expert_of(const int32_t* topk_idx, int a, int T, int k) {
+  const int j = a / T, t = a - j * T;
+  return topk_idx[(size_t)t * k + j];
+}
+
+__global__ __launch_bounds__(BT) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx, int T, int k,
+                                                            int E, int32_t* __restrict__ block_hist) {
+  __shared__ int hist[MOE_MAX_EXPERTS];
+  for (int e = threadIdx.x; e < E; e += BT) hist[e] = 0;
+  __syncthreads();
+  const int A = T * k;
+  const int base = blockIdx.x * DISPATCH_BLOCK;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int a = base + r * BT + threadIdx.x;
+    if (a < A) atomicAdd(&hist[expert_of(topk_idx, a, T, k)], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += BT) block_hist[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+// One block; thread e walks expert e's column of block_hist (coalesced across e).
+__global__ __launch_bounds__(MOE_MAX_EXPERTS) void dispatch_scan_kernel(int32_t* __restrict__ block_hist,
+                                                                        int nblocks, int E, int C,
+                                                                        int32_t* __restrict__ counts,
+                                                                        int32_t* __restrict__ offsets) {
+  __shared__ int kept[MOE_MAX_EXPERTS];
+  const int e = threadIdx.x;
+  if (e < E) {
+    int run = 0;
+    for (int b = 0; b < nblocks; ++b) {
+      const int h = block_hist[(size_t)b * E + e];
+      block_hist[(size_t)b * E + e] = run;  // becomes the block's base slot
+      run += h;
+    }
+    counts[e] = run;
+    kept[e] = min(run, C);
+  }
+  __syncthreads();
+  if (e == 0) {
+    int off = 0;
+    for (int i = 0; i < E; ++i) {
+      offsets[i] = off;
+      off += kept[i];
+    }
+    offsets[E] = off;
+  }
+}
+
+__global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __restrict__ topk_idx, int T, int k,
+                                                             int E, int C, const int32_t* __restrict__ block_base,
+                                                             const int32_t* __restrict__ offsets,
+                                                             int32_t* __restrict__ a2r, int32_t* __restrict__ r2a) {
+  constexpr int NW = BT / 64;
+  __shared__ int running[MOE_MAX_EXPERTS];       // slots already handed out in this block, per expert
+  __shared__ int wave_cnt[NW][MOE_MAX_EXPERTS];  // this round's per-wave counts
+  __shared__ int off_s[MOE_MAX_EXPERTS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int e = threadIdx.x; e < E; e += BT) {
+    running[e] = block_base[(size_t)blockIdx.x * E + e];
+    off_s[e] = offsets[e];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) wave_cnt[w][e] = 0;
+  }
+  __syncthreads();
+  const int A = T * k;
+  const int base = blockIdx.x * DISPATCH_BLOCK;
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int a = base + r * BT + threadIdx.x;
+    const bool valid = a < A;
+    const int e = valid ? expert_of(topk_idx, a, T, k) : -1;
+    // rank among the wave's lanes with the same expert, in lane (= assignment) order
+    int rank = 0;
+    unsigned long long todo = __ballot(valid);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int e0 = __shfl(e, leader, 64);
+      const unsigned long long same = __ballot(e == e0);
+      if (e == e0) {
+        rank = __popcll(same & ((1ull << lane) - 1ull));
+        if (lane == leader) wave_cnt[wave][e0] = __popcll(same);
+      }
+      todo &= ~same;
+    }
+    __syncthreads();
+    if (valid) {
+      int slot = running[e] + rank;
+#pragma unroll
+      for (int w = 0; w < NW; ++w)
+        if (w < wave) slot += wave_cnt[w][e];
+      const int row = slot < C ? off_s[e] + slot : -1;
+      a2r[a] = row;
+      if (row >= 0) r2a[row] = a;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < E; i += BT) {
+      int add = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        add += wave_cnt[w][i];
+        wave_cnt[w][i] = 0;
+      }
+      running[i] += add;
+    }
+    __syncthreads();
+  }
+}
+
+// One wavefront per token: read the row once (16 B per lane per step), write it to each kept row.
+__global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __restrict__ x, int T, int k,
+                                                              int row_vec,  // 16-byte vectors per row
+                                                              const int32_t* __restrict__ a2r,
+                                                              uint4* __restrict__ xd) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  int rows[MOE_MAX_TOPK];
+  bool any = false;
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+    rows[j] = j < k ? a2r[(size_t)j * T + t] : -1;
+    any |= rows[j] >= 0;
+  }
+  if (!any) return;
+  const uint4* src = x + (size_t)t * row_vec;
+  for (int v = lane; v < row_vec; v += 64) {
+    const uint4 val = src[v];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_TOPK; ++j)
+      if (rows[j] >= 0) xd[(size_t)rows[j] * row_vec + v] = val;
+  }
+}
+
+}  // namespace
+
+int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx, int32_t* counts,
+                        int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, hipStream_t s) {
+  const int T = cfg->T, k = cfg->k, E = cfg->E;
+  const int C = moe_capacity(cfg);
+  const int nblocks = (int)dispatch_blocks(cfg);
+  int32_t* block_hist = (int32_t*)ws;
+  if (nblocks > 0)
+    hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist);
+  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E, C,
+                     counts, offsets);
+  if (nblocks > 0) {
+    hipLaunchKernelGGL(dispatch_assign_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist,
+                       offsets, a2r, r2a);
+    if (xd) {
+      const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
+      hipLaunchKernelGGL(dispatch_gather_kernel, dim3((T + 3) / 4), dim3(256), 0, s, (const uint4*)x, T, k,
+                         row_vec, a2r, (uint4*)xd);
+    }
+  }
+  return check_hip(hipGetLastError(), "dispatch launch");
+}
+
+}  // namespace moesys
+
+using namespace moesys;
+
+extern "C" int32_t moe_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                                int32_t* expert_counts, int32_t* expert_offsets, int32_t* assign_to_row,
+                                int32_t* row_to_assign, void* xd, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if (!expert_counts || !expert_offsets) return fail(MOE_ERR_INVALID_ARG, "moe_dispatch: expert_counts/expert_offsets are NULL");
+  if (cfg->T > 0 && (!topk_idx || !assign_to_row || !row_to_assign))
+    return fail(MOE_ERR_INVALID_ARG, "moe_dispatch: topk_idx, assign_to_row and row_to_assign must be non-NULL");
+  if (cfg->T > 0 && xd && !x) return fail(MOE_ERR_INVALID_ARG, "moe_dispatch: xd given but x is NULL");
+  const size_t need = moe_workspace_bytes(cfg, MOE_WS_DISPATCH);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
+    return fail(MOE_ERR_WORKSPACE, "moe_dispatch: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
+  return launch_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
+                         (hipStream_t)stream);
+}

@@ -1,0 +1,312 @@
+"""GPU parity: every stage and the whole layer, through the C ABI, against the fp64 oracle.
+
+Bars: routing tables (top-k indices, counts, offsets, permutations) and the dispatched rows are
+bit-exact; fp32 gate weights within 1e-5 relative; bf16 expert outputs / layer outputs within 1e-2
+relative Frobenius error; fp32 outputs within 1e-5 relative Frobenius error.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2205_10034_amd as M
+from oracle import moe_oracle as O
+from workloads import WORKLOADS, make_layer
+
+from gpu_util import alloc_ws, rel_fro, run_layer, tdtype, to_dev, to_np, upload_weights
+
+pytestmark = pytest.mark.gpu
+
+GATE_RTOL = 1e-5
+BF16_TOL = 1e-2
+F32_TOL = 1e-5
+
+
+def small(name, **kw):
+    return WORKLOADS[name].scaled(**kw)
+
+
+# ----------------------------------------------------------------------------- gate
+GATE_CASES = [
+    small("tiny"),
+    small("tiny", T=37, E=5, k=3, renormalize=True),
+    small("gpt", T=1000),
+    small("gpt", T=515, E=64, k=2, d_model=512),
+    small("gpt", T=300, E=100, k=4, d_model=256),
+    small("gpt", T=64, E=256, k=8, d_model=128),
+    small("skew", T=2048),
+    small("gpt", T=3, E=2, k=2, renormalize=False),
+]
+
+
+@pytest.mark.parametrize("wl", GATE_CASES, ids=lambda w: f"{w.name}-T{w.T}-E{w.E}-k{w.k}-{w.dtype}")
+def test_gate(wl):
+    print(f"gate case {wl}", flush=True)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    x = to_dev(L["x"], wl.dtype)
+    wr, br = to_dev(L["w_router"], "f32"), to_dev(L["b_router"], "f32")
+    idx = torch.full((wl.T, wl.k), -7, dtype=torch.int32, device="cuda")
+    w = torch.zeros((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    probs = torch.zeros((wl.T, wl.E), dtype=torch.float32, device="cuda")
+    M.moe_gate(cfg, x, wr, br if wl.router_bias != "none" else None, idx, w, probs)
+    torch.cuda.synchronize()
+    p_ref, idx_ref, w_ref = O.gate(L["x"], L["w_router"], L["b_router"], wl.k, wl.renormalize)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=GATE_RTOL, atol=0)
+    assert np.allclose(probs.cpu().numpy(), p_ref, rtol=GATE_RTOL, atol=1e-30)
+
+
+def test_gate_exact_ties_lower_index_first():
+    # integer-valued x and router: logits are exact on both sides; columns repeat, so ties are real
+    rng = np.random.default_rng(0)
+    T, d, E = 200, 64, 6
+    x = rng.integers(-3, 4, size=(T, d)).astype(np.float32)
+    base = rng.integers(-2, 3, size=(d, 3)).astype(np.float32)
+    wr = np.concatenate([base, base], axis=1)                  # expert e and e+3 always tie
+    cfg = M.MoEConfig(T=T, d_model=d, d_ff=64, E=E, k=4, renormalize=True, dtype="bf16")
+    idx = torch.empty((T, 4), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, 4), dtype=torch.float32, device="cuda")
+    M.moe_gate(cfg, to_dev(x, "bf16"), to_dev(wr, "f32"), None, idx, w, None)
+    torch.cuda.synchronize()
+    _, idx_ref, w_ref = O.gate(x, wr, None, 4, True)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=GATE_RTOL)
+
+
+# ------------------------------------------------------------------------- dispatch
+def run_dispatch(cfg, x_np, idx_np, with_rows=True):
+    x = to_dev(x_np, cfg.dtype)
+    idx = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int32)).cuda()
+    A = cfg.k * cfg.T
+    counts = torch.full((cfg.E,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((cfg.E + 1,), -1, dtype=torch.int32, device="cuda")
+    a2r = torch.full((max(A, 1),), -5, dtype=torch.int32, device="cuda")
+    r2a = torch.full((max(A, 1),), -5, dtype=torch.int32, device="cuda")
+    rmax = M.moe_workspace_layout(cfg)["r_max"]
+    xd = torch.zeros((max(rmax, 1), cfg.d_model), dtype=tdtype(cfg.dtype), device="cuda") if with_rows else None
+    ws = alloc_ws(cfg, 1)
+    M.moe_dispatch(cfg, x, idx, counts, offsets, a2r, r2a, xd, ws)
+    torch.cuda.synchronize()
+    return counts.cpu().numpy(), offsets.cpu().numpy(), a2r.cpu().numpy()[:A], r2a.cpu().numpy(), xd
+
+
+DISPATCH_CASES = [
+    dict(T=256, E=4, k=1, cf=1.25), dict(T=1000, E=16, k=2, cf=1.25), dict(T=5000, E=8, k=1, cf=0.0),
+    dict(T=3000, E=64, k=2, cf=0.0), dict(T=1025, E=3, k=3, cf=0.5), dict(T=700, E=130, k=4, cf=1.0),
+    dict(T=1, E=2, k=2, cf=1.0), dict(T=4097, E=8, k=2, cf=0.05),
+]
+
+
+@pytest.mark.parametrize("c", DISPATCH_CASES, ids=lambda c: "T{T}-E{E}-k{k}-cf{cf}".format(**c))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_dispatch(c, dtype):
+    print(f"dispatch case {c} {dtype}", flush=True)
+    rng = np.random.default_rng(c["T"] + c["E"])
+    T, E, k = c["T"], c["E"], c["k"]
+    z = rng.standard_normal((T, E)) + 1.5 * rng.standard_normal(E)        # uneven loads
+    idx = O.topk_by_logit(z, k)
+    wl = small("gpt", T=T, E=E, k=k, d_model=128, dtype=dtype)
+    x_np = make_layer(wl.scaled(E=1, d_ff=64))["x"]
+    cfg = M.MoEConfig(T=T, d_model=128, d_ff=64, E=E, k=k, capacity_factor=c["cf"], dtype=dtype)
+    C = O.capacity(T, E, k, c["cf"])
+    assert M.moe_capacity(cfg) == C
+    counts, offsets, a2r, r2a, xd = run_dispatch(cfg, x_np, idx)
+    rc, ro, ra, rr, rxd = O.dispatch(x_np, idx, E, C)
+    assert np.array_equal(counts, rc) and np.array_equal(offsets, ro)
+    assert np.array_equal(a2r, ra)
+    R = int(ro[-1])
+    assert np.array_equal(r2a[:R], rr)
+    assert np.array_equal(to_np(xd[:R]), rxd)                                # byte copies
+    if c["cf"] > 0 and c["cf"] < 1:
+        assert (ra < 0).any()
+
+
+def test_dispatch_all_tokens_one_expert_and_empty_experts():
+    T, E, k = 3000, 8, 1
+    idx = np.full((T, 1), 5, dtype=np.int32)
+    x_np = make_layer(small("gpt", T=T, E=1, d_model=64, d_ff=64))["x"]
+    for cf in (0.0, 1.0):
+        cfg = M.MoEConfig(T=T, d_model=64, d_ff=64, E=E, k=k, capacity_factor=cf)
+        C = O.capacity(T, E, k, cf)
+        counts, offsets, a2r, r2a, xd = run_dispatch(cfg, x_np, idx)
+        rc, ro, ra, rr, rxd = O.dispatch(x_np, idx, E, C)
+        assert np.array_equal(counts, rc) and np.array_equal(offsets, ro) and np.array_equal(a2r, ra)
+        R = int(ro[-1])
+        assert R == min(T, C) and np.array_equal(r2a[:R], rr) and np.array_equal(to_np(xd[:R]), rxd)
+
+
+def test_empty_batch():
+    cfg = M.MoEConfig(T=0, d_model=64, d_ff=64, E=4, k=2, capacity_factor=1.0)
+    counts = torch.full((4,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((5,), -1, dtype=torch.int32, device="cuda")
+    ws = alloc_ws(cfg, 1)
+    M.moe_dispatch(cfg, None, None, counts, offsets, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert counts.cpu().tolist() == [0] * 4 and offsets.cpu().tolist() == [0] * 5
+
+
+# ----------------------------------------------------------------- expert FFN + combine
+FFN_CASES = [
+    small("tiny", T=300, E=4, d_model=128, d_ff=256, act="gelu", dtype="f32"),
+    small("tiny", T=300, E=3, d_model=64, d_ff=192, act="swiglu", dtype="f32"),
+    small("gpt", T=1500, E=4, d_model=256, d_ff=512, act="gelu"),          # 256-wide tiles, ragged rows
+    small("gpt", T=900, E=5, d_model=192, d_ff=320, act="gelu"),           # narrow-tile fallback
+    small("gpt", T=1500, E=4, d_model=256, d_ff=384, act="swiglu"),
+    small("gpt", T=700, E=3, d_model=192, d_ff=192, act="swiglu"),
+]
+
+
+@pytest.mark.parametrize("wl", FFN_CASES, ids=lambda w: f"{w.act}-{w.dtype}-T{w.T}-E{w.E}-d{w.d_model}-f{w.d_ff}")
+def test_expert_ffn_and_combine(wl):
+    print(f"ffn case {wl}", flush=True)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    ref = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor,
+                          renormalize=wl.renormalize, act=wl.act)
+    W = upload_weights(L, wl.dtype)
+    R = int(ref["expert_offsets"][-1])
+    xd = to_dev(ref["xd"], wl.dtype)
+    offsets = torch.from_numpy(ref["expert_offsets"]).cuda()
+    yd = torch.zeros((max(R, 1), wl.d_model), dtype=tdtype(wl.dtype), device="cuda")
+    ws = alloc_ws(cfg, 2)
+    M.moe_expert_ffn(cfg, W, xd, offsets, yd, ws)
+    torch.cuda.synchronize()
+    tol = BF16_TOL if wl.dtype == "bf16" else F32_TOL
+    err = rel_fro(to_np(yd[:R]), ref["yd"])
+    print("yd rel fro", err, flush=True)
+    assert err < tol
+    # per-expert check too: a wrong expert index on a small expert must not hide in the norm
+    for e in range(wl.E):
+        lo, hi = ref["expert_offsets"][e], ref["expert_offsets"][e + 1]
+        if hi > lo:
+            assert rel_fro(to_np(yd[lo:hi]), ref["yd"][lo:hi]) < tol
+    # combine on the oracle's routing and the GPU's yd
+    a2r = torch.from_numpy(ref["assign_to_row"]).cuda()
+    tw = torch.from_numpy(ref["topk_w"].astype(np.float32)).cuda()
+    res_np = make_layer(wl.scaled(seed=wl.seed + 99))["x"]
+    res = to_dev(res_np, wl.dtype)
+    out = torch.empty((wl.T, wl.d_model), dtype=tdtype(wl.dtype), device="cuda")
+    M.moe_combine(cfg, yd, a2r, tw, res, out)
+    torch.cuda.synchronize()
+    ref_out = O.combine(to_np(yd[:R]).astype(np.float64), ref["assign_to_row"], tw.cpu().numpy().astype(np.float64), res_np)
+    assert rel_fro(to_np(out), ref_out) < (4e-3 if wl.dtype == "bf16" else 1e-6)   # one rounding of the sum
+    M.moe_combine(cfg, yd, a2r, tw, None, out)
+    torch.cuda.synchronize()
+    ref_out = O.combine(to_np(yd[:R]).astype(np.float64), ref["assign_to_row"], tw.cpu().numpy().astype(np.float64), None)
+    assert rel_fro(to_np(out), ref_out) < (4e-3 if wl.dtype == "bf16" else 1e-6)
+
+
+def test_f32_ffn_input_major_layout():
+    wl = small("tiny", T=200, E=3, d_model=64, d_ff=128)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    ref = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor, renormalize=False, act="gelu")
+    W = upload_weights(L, "f32", layout="input_major")
+    r = run_layer(cfg, W, to_dev(L["x"], "f32"))
+    assert np.array_equal(r["topk_idx"], ref["topk_idx"])
+    assert rel_fro(r["out"], ref["out"]) < F32_TOL
+
+
+# ------------------------------------------------------------------------- whole layer
+def check_layer(wl, L, r, ref, tol):
+    assert np.array_equal(r["topk_idx"], ref["topk_idx"])
+    assert np.allclose(r["topk_w"], ref["topk_w"], rtol=GATE_RTOL, atol=0)
+    assert np.array_equal(r["expert_counts"], ref["expert_counts"])
+    assert np.array_equal(r["expert_offsets"], ref["expert_offsets"])
+    assert np.array_equal(r["assign_to_row"], ref["assign_to_row"])
+    assert np.array_equal(r["row_to_assign"], ref["row_to_assign"])
+    assert np.array_equal(r["xd"], ref["xd"])
+
+
+LAYER_CASES = [
+    ("tiny", {}),
+    ("tiny", dict(T=777, capacity_factor=0.5, k=2, renormalize=True)),
+    ("gpt", dict(T=1300, E=8)),
+    ("gpt", dict(T=2048, E=16, capacity_factor=0.7)),
+    ("skew", dict(T=3001)),
+    ("large", dict(T=1536, d_model=512, d_ff=1024, E=4)),
+    ("ring", dict(T=1024, d_model=256, d_ff=512, E=64)),
+    ("gpt", dict(T=130, E=4, k=4)),
+]
+
+
+@pytest.mark.parametrize("name,kw", LAYER_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_layer_forward_small(name, kw):
+    wl = small(name, **kw)
+    print(f"layer case {wl}", flush=True)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    ref = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor,
+                          renormalize=wl.renormalize, act=wl.act)
+    W = upload_weights(L, wl.dtype)
+    r = run_layer(cfg, W, to_dev(L["x"], wl.dtype))
+    check_layer(wl, L, r, ref, None)
+    tol = BF16_TOL if wl.dtype == "bf16" else F32_TOL
+    e_yd, e_out = rel_fro(r["yd"], ref["yd"]), rel_fro(r["out"], ref["out"])
+    print(f"rel fro yd {e_yd:.3e} out {e_out:.3e}", flush=True)
+    assert e_yd < tol and e_out < tol
+    # with residual, in place on the residual buffer
+    res = to_dev(L["x"], wl.dtype).clone()
+    ws = alloc_ws(cfg)
+    M.moe_layer_forward(cfg, W, res, res, res, ws)
+    torch.cuda.synchronize()
+    ref_res = ref["out"] + L["x"]
+    assert rel_fro(to_np(res), ref_res) < tol
+
+
+@pytest.mark.parametrize("name", ["gpt", "skew", "skew40"])
+def test_layer_forward_full_size(name):
+    """Full configuration in the launch shape the bench times; the oracle runs the whole layer."""
+    wl = WORKLOADS[name]
+    print(f"full-size layer {wl}", flush=True)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    ref = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor,
+                          renormalize=wl.renormalize, act=wl.act)
+    W = upload_weights(L, wl.dtype, nullable_bias=True)
+    r = run_layer(cfg, W, to_dev(L["x"], wl.dtype))
+    check_layer(wl, L, r, ref, None)
+    e_yd, e_out = rel_fro(r["yd"], ref["yd"]), rel_fro(r["out"], ref["out"])
+    print(f"{name}: loads {ref['expert_counts'].tolist()} rel fro yd {e_yd:.3e} out {e_out:.3e}", flush=True)
+    assert e_yd < BF16_TOL and e_out < BF16_TOL
+
+
+def test_layer_forward_large_sampled():
+    """32768 x 4096 x 14336 SwiGLU: routing compared in full, outputs on sampled tokens the oracle
+    computes one by one (the full fp64 FFN is 23 TFLOP)."""
+    wl = WORKLOADS["large"]
+    print(f"full-size layer {wl}", flush=True)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    p, idx, w = O.gate(L["x"], L["w_router"], L["b_router"], wl.k, wl.renormalize)
+    C = O.capacity(wl.T, wl.E, wl.k, wl.capacity_factor)
+    counts, offsets, a2r, r2a = O.dispatch_plan(idx, wl.E, C)
+    W = upload_weights(L, wl.dtype, nullable_bias=True)
+    r = run_layer(cfg, W, to_dev(L["x"], wl.dtype))
+    assert np.array_equal(r["topk_idx"], idx) and np.allclose(r["topk_w"], w, rtol=GATE_RTOL, atol=0)
+    assert np.array_equal(r["expert_counts"], counts) and np.array_equal(r["expert_offsets"], offsets)
+    assert np.array_equal(r["assign_to_row"], a2r) and np.array_equal(r["row_to_assign"], r2a)
+    assert (a2r < 0).any()                                   # capacity factor 1.0 drops some
+    R = int(offsets[-1])
+    assert np.array_equal(r["xd"][::97], L["x"][r2a[::97] % wl.T])
+    rng = np.random.default_rng(0)
+    dropped_tok = np.nonzero((a2r[:wl.T] < 0) | (a2r[wl.T:] < 0))[0][:8]
+    toks = np.unique(np.concatenate([rng.integers(0, wl.T, 40), dropped_tok, [0, wl.T - 1]]))
+    plan = dict(topk_idx=idx, topk_w=w, assign_to_row=a2r)
+    ref = O.sampled_tokens_forward(L["x"], L, plan, toks, act=wl.act)
+    err = rel_fro(r["out"][toks], ref)
+    print(f"large: loads {counts.tolist()} dropped {(a2r < 0).sum()} sampled rel fro {err:.3e}", flush=True)
+    assert err < BF16_TOL
+    for i, t in enumerate(toks):
+        assert rel_fro(r["out"][t], ref[i]) < 3 * BF16_TOL
+
+
+def test_determinism():
+    wl = small("gpt", T=2048, E=8)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    a = run_layer(cfg, W, x)["out_tensor"]
+    b = run_layer(cfg, W, x)["out_tensor"]
+    assert torch.equal(a, b)
