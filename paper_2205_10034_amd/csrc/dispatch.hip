@@ -40,7 +40,10 @@ __global__ __launch_bounds__(BT) void dispatch_count_kernel(const int32_t* __res
 #pragma unroll
   for (int r = 0; r < ROUNDS; ++r) {
     const int a = base + r * BT + threadIdx.x;
-    if (a < A) atomicAdd(&hist[expert_of(topk_idx, a, T, k)], 1);
+    if (a < A) {
+      const int e = expert_of(topk_idx, a, T, k);
+      if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);  // an index outside 0..E-1 is ignored (dropped)
+    }
   }
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += BT) block_hist[(size_t)blockIdx.x * E + e] = hist[e];
@@ -94,8 +97,9 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
   const int base = blockIdx.x * DISPATCH_BLOCK;
   for (int r = 0; r < ROUNDS; ++r) {
     const int a = base + r * BT + threadIdx.x;
-    const bool valid = a < A;
-    const int e = valid ? expert_of(topk_idx, a, T, k) : -1;
+    const int e_in = a < A ? expert_of(topk_idx, a, T, k) : -1;
+    const bool valid = (unsigned)e_in < (unsigned)E;
+    const int e = valid ? e_in : -1;
     // rank among the wave's lanes with the same expert, in lane (= assignment) order
     int rank = 0;
     unsigned long long todo = __ballot(valid);
@@ -118,6 +122,8 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
       const int row = slot < C ? off_s[e] + slot : -1;
       a2r[a] = row;
       if (row >= 0) r2a[row] = a;
+    } else if (a < A) {
+      a2r[a] = -1;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < E; i += BT) {
