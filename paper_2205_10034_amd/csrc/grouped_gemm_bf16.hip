@@ -9,10 +9,12 @@
 // MFMA units, one rounding to bf16 at the end.
 //
 // CDNA4 mapping.  A workgroup owns a TOK x FEAT output tile and walks K in
-// steps of 64.  Operand tiles are staged in LDS as rows of 64 bf16 (128 B)
+// steps of 64.  Operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging) as rows of 64 bf16 (128 B)
 // whose eight 16-byte chunks are XOR-swizzled with the row index, so the
 // per-lane 16-byte fragment reads of v_mfma_f32_32x32x16_bf16 spread over all
-// banks.  The MFMA "A" operand is the weight fragment and the "B" operand the
+// banks; two stages alternate so that the next K-step streams in while the
+// current one is multiplied.  The MFMA "A" operand is the weight fragment and the "B" operand the
 // activation fragment: the accumulator then holds, per lane, one token and
 // runs of four consecutive output features, which store as packed 8-byte
 // pieces.  Tiles are enumerated on the device from expert_offsets (no host
@@ -42,8 +44,9 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as
 __device__ __forceinline__ float gelu_exact(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu(float u) { return u / (1.f + __expf(-u)); }
 
-// Byte offset of 16-byte chunk `c` (0..7) of row `r` inside a swizzled tile.
-__device__ __forceinline__ int lds_off(int r, int c) { return r * ROW_BYTES + ((c ^ (r & 7)) << 4); }
+// LDS tile layout: row r (64 bf16 = 128 B) keeps its logical 16-byte chunk c at physical chunk
+// c ^ ((r >> 1) & 7).  The LDS serves 16 lanes x 16 B per clock over 256 B of banks; with this key any 16
+// consecutive rows read at one logical chunk hit 16 distinct 16-byte bank groups (measured conflict-free).
 
 struct TileInfo {
   int expert, row0, rows;  // first dispatched row and valid rows (<= TOK) of this tile
@@ -78,12 +81,23 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
     const int mid = (lo + hi) >> 1;
     if (s_pref[mid] <= mt) lo = mid; else hi = mid;
   }
+  // every lane computed the same values; say so to the compiler (they feed scalar descriptors)
+  lo = __builtin_amdgcn_readfirstlane(lo);
   ti.expert = lo;
-  const int r0 = offsets[lo] + (mt - s_pref[lo]) * TOK;
+  const int r0 = __builtin_amdgcn_readfirstlane(offsets[lo] + (mt - s_pref[lo]) * TOK);
   ti.row0 = r0;
-  ti.rows = min(TOK, offsets[lo + 1] - r0);
+  ti.rows = __builtin_amdgcn_readfirstlane(min(TOK, offsets[lo + 1] - r0));
+  ti.ntile = __builtin_amdgcn_readfirstlane(ti.ntile);
   return true;
 }
+
+// Raw buffer descriptor over [base, base+bytes): loads past the end return zero without touching memory,
+// which is how rows beyond an expert's last row are masked.
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+#endif
 
 // TOK x FEAT tile, WT x WF wavefronts; each wavefront owns (TOK/WT) tokens x (FEAT/WF) LDS feature rows.
 template <int TOK, int FEAT, int WT, int WF, int EPI>
@@ -95,48 +109,70 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
     const int32_t* __restrict__ offsets,  // [E+1]
     uint16_t* __restrict__ out,           // [R, N]
     int E, int N, int K) {
-  constexpr int NT = WT * WF * 64;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer descriptors are device-only types)
+  constexpr int NW = WT * WF;
   constexpr int WTOK = TOK / WT, WFEAT = FEAT / WF;
   constexpr int TB = WTOK / 32, FB = WFEAT / 32;  // 32x32 MFMA blocks per wavefront
   constexpr int A_BYTES = TOK * ROW_BYTES, B_BYTES = FEAT * ROW_BYTES;
-  constexpr int A_CHUNKS = TOK * 8 / NT, B_CHUNKS = FEAT * 8 / NT;
   // SwiGLU: LDS feature rows [0,FEAT/2) come from Wg, [FEAT/2,FEAT) from Wu, for FEAT/2 output features
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
-  static_assert(TOK * 8 % NT == 0 && FEAT * 8 % NT == 0, "tile/threads mismatch");
+  constexpr int B_ROWS = OUT_FEAT;                                   // rows per weight matrix per tile
+  constexpr int A_LOADS = TOK / 8 / NW, B_LOADS = B_ROWS / 8 / NW;   // wave-instructions per wavefront per stage
+  static_assert(TOK % (8 * NW) == 0 && B_ROWS % (8 * NW) == 0, "tile/wavefront mismatch");
   static_assert(EPI != EPI_SWIGLU || FB == 2, "SwiGLU wave tile is one gate block + one up block");
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // two stages, as separate arrays so that the compiler can tell the stage being filled by LDS DMA from
+  // the stage being read
+  __shared__ __attribute__((aligned(1024))) unsigned char sA0[A_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB0[B_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sA1[A_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB1[B_BYTES];
   __shared__ int s_pref[MOE_MAX_EXPERTS + 1];
 
   TileInfo ti;
   const int n_tiles = N / OUT_FEAT;
   if (!find_tile<TOK>(offsets, E, n_tiles, s_pref, ti)) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave / WF, wf = wave % WF;
   const int feat0 = ti.ntile * OUT_FEAT;
+  const uint32_t row_bytes = (uint32_t)K * 2u;
 
-  // ---- global -> register staging addresses -------------------------------------------------
-  const uint16_t* a_src[A_CHUNKS];
-  int a_dst[A_CHUNKS];
+  // ---- buffer descriptors and per-lane offsets of every direct-to-LDS load ---------------------
+  const uint16_t* a_base_ptr = act + (size_t)ti.row0 * K;
+  const uint16_t* b_base_ptr = wa + ((size_t)ti.expert * N + feat0) * K;
+  const uint16_t* b2_base_ptr = (EPI == EPI_SWIGLU ? wb : wa) + ((size_t)ti.expert * N + feat0) * K;
+  const uint32_t a_bytes = (uint32_t)ti.rows * row_bytes, b_bytes = (uint32_t)B_ROWS * row_bytes;
+  int a_voff[A_LOADS], b_voff[B_LOADS];
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    const int c = tid + i * NT, r = c >> 3, cc = c & 7;
-    const int rr = ti.row0 + min(r, ti.rows - 1);  // rows past the expert's end re-read its last row
-    a_src[i] = act + (size_t)rr * K + cc * 8;
-    a_dst[i] = lds_off(r, cc);
+  for (int i = 0; i < A_LOADS; ++i) {
+    const int r = (i * NW + wave) * 8 + (lane >> 3);
+    a_voff[i] = r * (int)row_bytes + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
   }
-  const uint16_t* b_src[B_CHUNKS];
-  int b_dst[B_CHUNKS];
 #pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) {
-    const int c = tid + i * NT, r = c >> 3, cc = c & 7;
-    const uint16_t* base = wa;
-    int n = feat0 + r;
-    if (EPI == EPI_SWIGLU && r >= FEAT / 2) { base = wb; n = feat0 + r - FEAT / 2; }
-    b_src[i] = base + ((size_t)ti.expert * N + n) * K + cc * 8;
-    b_dst[i] = lds_off(r, cc);
+  for (int i = 0; i < B_LOADS; ++i) {
+    const int r = (i * NW + wave) * 8 + (lane >> 3);
+    b_voff[i] = r * (int)row_bytes + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
   }
+  // One instruction moves 64 lanes x 16 B = eight 128-byte rows of a tile; lane l lands at row (l>>3),
+  // physical chunk (l&7), and voff addresses the logical chunk that the swizzle maps there.  The K-step is
+  // selected by the uniform offset.  `live` = false turns the stage into no-ops (zero-length descriptors).
+#define MOE_TILE_LOADS(rsrc, voff, n_loads, lds_tile)                                                            \
+  _Pragma("unroll") for (int i_ = 0; i_ < (n_loads); ++i_)                                                       \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                  \
+          rsrc, (__attribute__((address_space(3))) void*)((lds_tile) + (i_ * NW + wave) * 1024), 16, voff[i_], koff, 0, 0)
+  auto issue_stage = [&](int kt, bool live, unsigned char* A, unsigned char* B) {
+    const int koff = kt * ROW_BYTES;
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a_base_ptr, live ? a_bytes : 0u);
+    const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(b_base_ptr, live ? b_bytes : 0u);
+    MOE_TILE_LOADS(a_rsrc, a_voff, A_LOADS, A);
+    MOE_TILE_LOADS(b_rsrc, b_voff, B_LOADS, B);
+    if (EPI == EPI_SWIGLU) {
+      const __amdgpu_buffer_rsrc_t b2_rsrc = make_rsrc(b2_base_ptr, live ? b_bytes : 0u);
+      MOE_TILE_LOADS(b2_rsrc, b_voff, B_LOADS, B + B_ROWS * ROW_BYTES);
+    }
+  };
+#undef MOE_TILE_LOADS
 
   f32x16 acc[TB][FB];
 #pragma unroll
@@ -146,61 +182,80 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  u32x4 a_reg[A_CHUNKS], b_reg[B_CHUNKS];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + kt * KSTEP);
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) b_reg[i] = *reinterpret_cast<const u32x4*>(b_src[i] + kt * KSTEP);
-  };
-  auto store_lds = [&](int buf) {
-    unsigned char* A = smem + buf * (A_BYTES + B_BYTES);
-    unsigned char* B = A + A_BYTES;
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(A + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4*>(B + b_dst[i]) = b_reg[i];
-  };
-
-  // fragment rows of this lane
+  // LDS byte address of this lane's fragment row with chunk key folded in: chunk for K sub-step ks is
+  // (2*ks + half) ^ key = ((half ^ key) ^ 2*ks), i.e. base ^ (ks << 5).
   const int frow = lane & 31, fhalf = lane >> 5;
-  auto compute = [&](int buf) {
-    const unsigned char* A = smem + buf * (A_BYTES + B_BYTES);
-    const unsigned char* B = A + A_BYTES;
+  int a_base[TB], w_base[FB];
 #pragma unroll
-    for (int ks = 0; ks < KSTEP / 16; ++ks) {
-      bf16x8 af[TB], wfrag[FB];
+  for (int i = 0; i < TB; ++i) {
+    const int r = wt * WTOK + i * 32 + frow;
+    a_base[i] = r * ROW_BYTES + ((fhalf ^ ((r >> 1) & 7)) << 4);
+  }
 #pragma unroll
-      for (int i = 0; i < TB; ++i) {
-        const int r = wt * WTOK + i * 32 + frow;
-        af[i] = *reinterpret_cast<const bf16x8*>(A + lds_off(r, 2 * ks + fhalf));
-      }
+  for (int j = 0; j < FB; ++j) {
+    int r;
+    if (EPI == EPI_SWIGLU) r = j * (FEAT / 2) + wf * 32 + frow;  // j=0 gate rows, j=1 up rows
+    else r = wf * WFEAT + j * 32 + frow;
+    w_base[j] = r * ROW_BYTES + ((fhalf ^ ((r >> 1) & 7)) << 4);
+  }
+
+  auto read_frags = [&](const unsigned char* A, const unsigned char* B, int ks, bf16x8 (&af)[TB], bf16x8 (&wfr)[FB]) {
 #pragma unroll
-      for (int j = 0; j < FB; ++j) {
-        int r;
-        if (EPI == EPI_SWIGLU) r = j * (FEAT / 2) + wf * 32 + frow;  // j=0 gate rows, j=1 up rows
-        else r = wf * WFEAT + j * 32 + frow;
-        wfrag[j] = *reinterpret_cast<const bf16x8*>(B + lds_off(r, 2 * ks + fhalf));
-      }
+    for (int i = 0; i < TB; ++i) af[i] = *reinterpret_cast<const bf16x8*>(A + (a_base[i] ^ (ks << 5)));
 #pragma unroll
-      for (int i = 0; i < TB; ++i)
+    for (int j = 0; j < FB; ++j) wfr[j] = *reinterpret_cast<const bf16x8*>(B + (w_base[j] ^ (ks << 5)));
+  };
+  auto mfma_all = [&](const bf16x8 (&af)[TB], const bf16x8 (&wfr)[FB]) {
 #pragma unroll
-        for (int j = 0; j < FB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[j], af[i], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < TB; ++i)
+#pragma unroll
+      for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[j], af[i], acc[i][j], 0, 0, 0);
+  };
+  // Asks the scheduler to alternate one MFMA with one LDS read (n pairs), then `tail` MFMAs.
+  auto interleave = [&](int) {
+#pragma unroll
+    for (int q = 0; q < TB + FB; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, TB * FB - (TB + FB), 0);
   };
 
+  // One K-step.  On entry fr[0] holds the fragments of sub-step 0 of the current stage (CA, CB), and the
+  // loads of the next stage (NA, NB) were issued one K-step ago.  Sub-steps 0..2 multiply while the next
+  // sub-step's fragments are read; then one barrier (all reads of the current stage done, next stage
+  // landed); the current stage's buffers are refilled with stage kt+2 and the last sub-step multiplies
+  // while sub-step 0 of the next stage is read.
+  bf16x8 af[2][TB], wfr[2][FB];
   const int KT = K / KSTEP;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt + 1 < KT; ++kt) {
-    load_global(kt + 1);
-    compute(kt & 1);
-    store_lds((kt + 1) & 1);
+  auto step = [&](int kt, unsigned char* CA, unsigned char* CB, unsigned char* NA, unsigned char* NB) {
+    read_frags(CA, CB, 1, af[1], wfr[1]);
+    mfma_all(af[0], wfr[0]);
+    interleave(0);
+    read_frags(CA, CB, 2, af[0], wfr[0]);
+    mfma_all(af[1], wfr[1]);
+    interleave(0);
+    read_frags(CA, CB, 3, af[1], wfr[1]);
+    mfma_all(af[0], wfr[0]);
+    interleave(0);
     __syncthreads();
+    issue_stage(kt + 2, kt + 2 < KT, CA, CB);
+    read_frags(NA, NB, 0, af[0], wfr[0]);
+    mfma_all(af[1], wfr[1]);
+    interleave(0);
+  };
+
+  issue_stage(0, true, sA0, sB0);
+  __syncthreads();
+  issue_stage(1, 1 < KT, sA1, sB1);
+  read_frags(sA0, sB0, 0, af[0], wfr[0]);
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    step(kt, sA0, sB0, sA1, sB1);
+    step(kt + 1, sA1, sB1, sA0, sB0);
   }
-  compute((KT - 1) & 1);
+  if (kt < KT) step(kt, sA0, sB0, sA1, sB1);
+  __syncthreads();  // no LDS DMA may be in flight past this point (the last stages issued were no-ops)
 
   // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
 #pragma unroll
@@ -246,6 +301,7 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
         }
     }
   }
+#endif
 }
 
 template <int TOK, int FEAT, int WT, int WF, int EPI>
@@ -265,15 +321,8 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   int64_t total = mt * (N / OUT_FEAT);
   total = (total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
   if (total > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: too many tiles");
-  constexpr size_t shmem = 2 * (size_t)(TOK + FEAT) * ROW_BYTES;
   auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(max dynamic LDS)");
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WT * WF * 64), shmem, s, act, wa, wb, bias, offsets, out,
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out,
                      cfg->E, N, K);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
