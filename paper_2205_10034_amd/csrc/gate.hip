@@ -1,6 +1,17 @@
 // Top-k softmax gate (GShard top-2 / top-1 gating, Section 5.2; softmax in fp32, Section 5.2).
 //
-// Exact path: one wavefront works on TPW tokens at a time.  Each lane owns a
+// Two kernels.
+//
+// Fast path (bf16 activations, E <= 64), HBM-bound: the logits are a skinny GEMM on the MFMA units.
+// Activations are bfloat16 already; every float32 router weight is split into three bfloat16 pieces
+// (w = hi + mid + lo exactly), so every product is exact in float32 and the only rounding is the
+// accumulation: float32 inside a 64-wide K chunk (24 roundings at most), float64 across chunks and
+// across the four wavefronts that share the K range.  The logits therefore carry an error of about
+// 1e-7.  Ranking needs more: it must equal the ranking of the exactly computed logits.  Any token whose
+// k+1 leading logits have two neighbours closer than GATE_MARGIN is recomputed by the whole workgroup
+// with float64 accumulation of the (exact) products and ranked on those values.
+//
+// Exact path (float32 activations, or E > 64): one wavefront works on TPW tokens at a time.  Each lane owns a
 // strided slice of d_model and accumulates the logits of NE experts in
 // float64 (the product of two float32 / bfloat16 values is exact in float64,
 // so only the summation rounds, at 2^-53 relative).  A reduce-scatter over the
@@ -179,11 +190,292 @@ __global__ __launch_bounds__(WAVES * 64) void gate_exact_kernel(
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Fast path.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int FT_TOK = 32;           // tokens per workgroup (two 16-token MFMA tiles)
+constexpr int FT_KC = 64;            // K chunk: two 16x16x32 MFMA steps
+constexpr int FT_ROW = (FT_KC + 8) * 2;  // LDS row of one expert's chunk, padded to 144 B (conflict-free reads)
+constexpr float GATE_MARGIN = 1e-4f; // neighbours among the k+1 leading logits closer than this -> exact recompute
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
+
+// Keeps the KEEP best (z, e) pairs seen so far, best first; among equal logits the lower expert index
+// ranks first (the comparison must also hold for entries pushed down the list by a newcomer).
+template <int KEEP>
+struct TopList {
+  double z[KEEP];
+  int e[KEEP];
+  float p[KEEP];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) { z[i] = -INFINITY; e[i] = 0x7fffffff; p[i] = 0.f; }
+  }
+  __device__ __forceinline__ void offer(double zn, int en) {
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) {
+      const bool better = zn > z[i] || (zn == z[i] && en < e[i]);
+      const double tz = better ? z[i] : zn;
+      const int te = better ? e[i] : en;
+      z[i] = better ? zn : z[i];
+      e[i] = better ? en : e[i];
+      zn = tz;
+      en = te;
+    }
+  }
+};
+
+// Softmax (fp32) + top-k of one token from its E float64 logits zsrc[e*stride]; one thread.
+// Returns true if two neighbours among the k+1 leading logits are closer than `margin`.
+__device__ __forceinline__ bool finalize_token(const double* zsrc, int stride, int E, int k, int renorm, float margin,
+                                               int32_t* __restrict__ idx_out, float* __restrict__ w_out,
+                                               float* __restrict__ probs_out) {
+  TopList<MOE_MAX_TOPK + 1> top;
+  top.init();
+  float mx = -INFINITY;
+  for (int e = 0; e < E; ++e) {
+    const double z = zsrc[e * stride];
+    top.offer(z, e);
+    mx = fmaxf(mx, (float)z);
+  }
+  float sum = 0.f;
+  for (int e = 0; e < E; ++e) sum += expf((float)zsrc[e * stride] - mx);
+  const float inv = 1.f / sum;
+  if (probs_out)
+    for (int e = 0; e < E; ++e) probs_out[e] = expf((float)zsrc[e * stride] - mx) / sum;
+  float wsum = 0.f;
+  float w[MOE_MAX_TOPK];
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+    w[j] = j < k ? expf((float)top.z[j] - mx) / sum : 0.f;
+    wsum += w[j];
+  }
+  (void)inv;
+  bool close = false;
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+    if (j < k) {
+      idx_out[j] = top.e[j];
+      w_out[j] = renorm ? w[j] / wsum : w[j];
+      if (j + 1 < E) close |= (float)(top.z[j] - top.z[j + 1]) < margin;
+    }
+  }
+  return close;
+}
+
+// EB = number of 16-expert blocks (E <= 16*EB).
+template <int EB>
+__global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
+                                                        const float* __restrict__ br, int T, int d, int E, int k,
+                                                        int renorm, int32_t* __restrict__ topk_idx,
+                                                        float* __restrict__ topk_w, float* __restrict__ probs) {
+  constexpr int EP = EB * 16;
+  constexpr int W_WAVE_BYTES = 3 * EP * FT_ROW;  // one wavefront's hi/mid/lo chunk
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int s_flag[FT_TOK];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned char* wl = smem + wave * W_WAVE_BYTES;
+  const int t0 = blockIdx.x * FT_TOK;
+  const int tl = lane & 15, kq = lane >> 4;  // MFMA operand coordinates of this lane
+
+  // activation rows of this lane's two token tiles (clamped: tail tokens recompute the last row, never stored)
+  const uint16_t* xrow[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) xrow[q] = x + (size_t)min(t0 + q * 16 + tl, T - 1) * d + kq * 16;
+
+  double zacc[2][EB][4];
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int b = 0; b < EB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) zacc[q][b][r] = 0.0;
+
+  // router-weight micro-tiles of this lane: 4 consecutive k x 4 consecutive experts each
+  constexpr int MT_PER_LANE = (FT_KC / 4) * (EP / 4) / 64;  // = EB
+  const int n_chunks = d / FT_KC;
+  const int iters = (n_chunks + 3) / 4;
+
+  u32x4 xa[2][2];  // [tile][half of the lane's 32 bytes]
+  float wv[MT_PER_LANE][4][4];
+  auto load_chunk = [&](int c) {
+    const int k0 = c * FT_KC;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      xa[q][0] = *reinterpret_cast<const u32x4*>(xrow[q] + k0);
+      xa[q][1] = *reinterpret_cast<const u32x4*>(xrow[q] + k0 + 8);
+    }
+#pragma unroll
+    for (int m = 0; m < MT_PER_LANE; ++m) {
+      const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = eg * 4 + j;
+          wv[m][i][j] = e < E ? wr[(size_t)(k0 + kg * 4 + i) * E + e] : 0.f;
+        }
+    }
+  };
+
+  int c = wave;  // chunks wave, wave+4, ...
+  if (c < n_chunks) load_chunk(c);
+  for (int it = 0; it < iters; ++it, c += 4) {
+    const bool live = c < n_chunks;
+    if (live) {
+      // split this chunk's router weights into three bf16 pieces and stage them K-contiguous per expert
+#pragma unroll
+      for (int m = 0; m < MT_PER_LANE; ++m) {
+        const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float w = wv[m][i][j];
+            hi[i] = bf16_bits_rne(w);
+            const float r1 = w - __uint_as_float(hi[i] << 16);
+            mid[i] = bf16_bits_rne(r1);
+            const float r2 = r1 - __uint_as_float(mid[i] << 16);
+            lo[i] = bf16_bits_rne(r2);
+          }
+          unsigned char* row = wl + (eg * 4 + j) * FT_ROW + kg * 8;
+          u32x2 v;
+          v.x = hi[0] | (hi[1] << 16); v.y = hi[2] | (hi[3] << 16);
+          *reinterpret_cast<u32x2*>(row) = v;
+          v.x = mid[0] | (mid[1] << 16); v.y = mid[2] | (mid[3] << 16);
+          *reinterpret_cast<u32x2*>(row + EP * FT_ROW) = v;
+          v.x = lo[0] | (lo[1] << 16); v.y = lo[2] | (lo[3] << 16);
+          *reinterpret_cast<u32x2*>(row + 2 * EP * FT_ROW) = v;
+        }
+      }
+    }
+    bf16x8 xb[2][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      xb[q][0] = __builtin_bit_cast(bf16x8, xa[q][0]);
+      xb[q][1] = __builtin_bit_cast(bf16x8, xa[q][1]);
+    }
+    if (c + 4 < n_chunks) load_chunk(c + 4);  // next chunk streams in while this one is multiplied
+    __syncthreads();                          // this wavefront's LDS writes are visible to its own reads
+    if (live) {
+      f32x4 acc[2][EB];
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int b = 0; b < EB; ++b) acc[q][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+          for (int b = 0; b < EB; ++b) {
+            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * EP + b * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) acc[q][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[q][s2], acc[q][b], 0, 0, 0);
+          }
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int b = 0; b < EB; ++b)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) zacc[q][b][r] += (double)acc[q][b][r];
+    }
+    __syncthreads();  // the chunk in LDS may be overwritten
+  }
+
+  // ---- cross-wavefront sum of the partial logits (float64) and per-token finalisation ------------
+  double* part = reinterpret_cast<double*>(smem);  // [4][EP][FT_TOK]
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int b = 0; b < EB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        part[((size_t)wave * EP + b * 16 + kq * 4 + r) * FT_TOK + q * 16 + tl] = zacc[q][b][r];
+  __syncthreads();
+  double* zfin = part + 4 * EP * FT_TOK;  // [EP][FT_TOK]
+  for (int i = tid; i < EP * FT_TOK; i += 256) {
+    const int e = i / FT_TOK;
+    double z = part[i];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) z += part[(size_t)w * EP * FT_TOK + i];
+    if (e < E && br) z += (double)br[e];
+    zfin[i] = z;
+  }
+  __syncthreads();
+  if (tid < FT_TOK) {
+    const int t = t0 + tid;
+    bool flag = false;
+    if (t < T)
+      flag = finalize_token(zfin + tid, FT_TOK, E, k, renorm, GATE_MARGIN, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
+                            probs ? probs + (size_t)t * E : nullptr);
+    s_flag[tid] = flag ? 1 : 0;
+  }
+  __syncthreads();
+
+  // ---- exact recompute of the rare tokens whose ranking is within the margin -------------------
+  double* zex = part;           // [EP]
+  double* wsum = part + EP;     // [4][NE]
+  for (int tt = 0; tt < FT_TOK; ++tt) {
+    if (!s_flag[tt]) continue;  // uniform
+    const int t = t0 + tt;
+    for (int c0 = 0; c0 < E; c0 += NE) {
+      const int ne = min(NE, E - c0);
+      double acc[NE];
+#pragma unroll
+      for (int e = 0; e < NE; ++e) acc[e] = 0.0;
+      for (int i = tid; i < d; i += 256) {
+        const double xv = (double)bf16_to_f32(x[(size_t)t * d + i]);
+        const float* wrow = wr + (size_t)i * E + c0;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) acc[e] = fma(xv, (double)(e < ne ? wrow[e] : 0.f), acc[e]);
+      }
+      const double zsum = reduce_scatter16(acc, lane);
+      if ((lane & 3) == 0) wsum[wave * NE + ((lane >> 2) & 15)] = zsum;
+      __syncthreads();
+      if (tid < ne) zex[c0 + tid] = wsum[tid] + wsum[NE + tid] + wsum[2 * NE + tid] + wsum[3 * NE + tid] + (br ? (double)br[c0 + tid] : 0.0);
+      __syncthreads();
+    }
+    if (tid == 0)
+      finalize_token(zex, 1, E, k, renorm, 0.f, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
+                     probs ? probs + (size_t)t * E : nullptr);
+    __syncthreads();
+  }
+}
+
+template <int EB>
+int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                    int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
+  constexpr int EP = EB * 16;
+  const size_t w_bytes = (size_t)4 * 3 * EP * FT_ROW;
+  const size_t z_bytes = (size_t)5 * EP * FT_TOK * sizeof(double);
+  const size_t shmem = w_bytes > z_bytes ? w_bytes : z_bytes;
+  auto kern = gate_mfma_kernel<EB>;
+  if (shmem > 65536) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
+  }
+  hipLaunchKernelGGL(kern, dim3((cfg->T + FT_TOK - 1) / FT_TOK), dim3(256), shmem, s, (const uint16_t*)x, w_router,
+                     b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+  return check_hip(hipGetLastError(), "gate launch");
+}
+
 }  // namespace
 
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   if (cfg->T == 0) return MOE_OK;
+  if (cfg->dtype == MOE_BF16 && cfg->E <= 64) {
+    if (cfg->E <= 16) return launch_fast<1>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
+    if (cfg->E <= 32) return launch_fast<2>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
+    return launch_fast<4>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
+  }
   const int per_block = WAVES * TPW;
   dim3 grid((cfg->T + per_block - 1) / per_block), block(WAVES * 64);
   const int Epad = (cfg->E + NE - 1) / NE * NE;
