@@ -9,17 +9,25 @@
 // MFMA units, one rounding to bf16 at the end.
 //
 // CDNA4 mapping.  A workgroup owns a TOK x FEAT output tile and walks K in
-// steps of 64.  Operand tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4, no register staging) as rows of 64 bf16 (128 B)
-// whose eight 16-byte chunks are XOR-swizzled with the row index, so the
-// per-lane 16-byte fragment reads of v_mfma_f32_32x32x16_bf16 spread over all
-// banks; two stages alternate so that the next K-step streams in while the
-// current one is multiplied.  The MFMA "A" operand is the weight fragment and the "B" operand the
-// activation fragment: the accumulator then holds, per lane, one token and
-// runs of four consecutive output features, which store as packed 8-byte
-// pieces.  Tiles are enumerated on the device from expert_offsets (no host
-// round trip), and consecutive tile ids are folded so that the workgroups that
-// land on one XCD share operand tiles in that XCD's L2.
+// steps of KS (32 or 64).  Operand tiles go from global memory straight into
+// LDS (buffer_load ... lds, 16 bytes per lane, no register staging) as rows of
+// KS bf16 whose 16-byte chunks are XOR-swizzled with the row index, so that the
+// per-lane 16-byte fragment reads of v_mfma_f32_32x32x16_bf16 are free of bank
+// conflicts; two LDS stages alternate so that the next K-step streams in while
+// the current one is multiplied, with ONE barrier per K-step placed before the
+// step's last sub-step so that the first fragments of the next step are read
+// under the tail of the current one.  The MFMA "A" operand is the weight
+// fragment and the "B" operand the activation fragment: the accumulator then
+// holds, per lane, one token and runs of four consecutive output features,
+// which store as packed 8-byte pieces.  Rows past an expert's end are masked by
+// the buffer descriptor (loads return zero, stores are skipped), never padded
+// in memory.  Tiles are enumerated on the device from expert_offsets (no host
+// round trip) in an order that makes the workgroups resident on one XCD share
+// operand tiles in that XCD's L2, and the eight XCDs walk the same weight
+// columns at the same time so that HBM serves each weight tile once.  When the
+// last round of 256x256 tiles would occupy a minority of the CUs, those tiles
+// are handed to a second launch that cuts each into four 256x64 tiles.
+#include <cstdlib>
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -30,9 +38,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int KSTEP = 64;          // K elements per LDS stage
-constexpr int ROW_BYTES = KSTEP * 2;
 constexpr int NUM_XCD = 8;
+constexpr int CU_PER_XCD = 32;
+constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
+constexpr int BIG_FEAT = 256;       // feature width of the tile grid that orders the work
+constexpr int SPLIT_MAX_LEFTOVER = 96;  // split the last round's tiles if there are at most this many
+static_assert(SPLIT_MAX_LEFTOVER + 64 <= NUM_CU, "the narrow launch covers NUM_CU slots after the cut");
 
 enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2 };
 
@@ -41,22 +52,52 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-__device__ __forceinline__ float gelu_exact(float u) { return 0.5f * u * (1.f + erff(u * 0.70710678118654752f)); }
-__device__ __forceinline__ float silu(float u) { return u / (1.f + __expf(-u)); }
-
-// LDS tile layout: row r (64 bf16 = 128 B) keeps its logical 16-byte chunk c at physical chunk
-// c ^ ((r >> 1) & 7).  The LDS serves 16 lanes x 16 B per clock over 256 B of banks; with this key any 16
-// consecutive rows read at one logical chunk hit 16 distinct 16-byte bank groups (measured conflict-free).
+// gelu(u) = u*Phi(u) = (u + |u| * erf(|u|/sqrt 2)) / 2 with erf from the five-term rational formula
+// 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7): far below the bf16 rounding of h, at
+// under half the instruction count of the library erff, which matters because this runs on every
+// element of h while the matrix pipes wait.
+__device__ __forceinline__ float gelu_fast(float u) {
+  const float ax = fabsf(u) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
+  const float erf_abs = fmaf(-p, e, 1.0f);
+  return 0.5f * fmaf(fabsf(u), erf_abs, u);
+}
+__device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
 struct TileInfo {
   int expert, row0, rows;  // first dispatched row and valid rows (<= TOK) of this tile
   int ntile;               // feature tile index
 };
 
-// Maps blockIdx.x to a tile.  Returns false if this workgroup has nothing to do.
-template <int TOK>
-__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, int* s_pref,
-                                          TileInfo& ti) {
+// Tile order.  The work is ordered on a grid of TOK x 256 tiles.  Token tiles (of all experts, in row
+// order) are grouped GM at a time and feature tiles GN at a time, GM*GN <= 32 = the workgroups one XCD
+// starts together, so that an XCD's resident workgroups reuse GM activation tiles and GN weight tiles out
+// of its L2.  The hardware hands workgroup i to XCD i mod 8; consecutive blocks b = 8q + xcd are laid out
+// so that the eight XCDs work on eight token groups of the SAME feature group at the same time (one HBM
+// read of those weights serves all of them through the shared cache level).  A trailing partial set of
+// token groups is spread over the XCDs feature group by feature group instead, to keep them equally loaded.
+//
+// Slot i (the dispatch order) -> tile.  `cut` splits the slots between the two launches: if the tiles
+// after the last full round of NUM_CU are few, the main launch stops at the cut and a second launch
+// handles every later tile as SPLIT narrower tiles.  Both launches derive the cut from the same device
+// data, so every tile is computed exactly once.
+__host__ __device__ inline int group_n(int n_tiles) { return n_tiles < 8 ? n_tiles : 8; }
+__host__ __device__ inline bool grid_is_dense(int n_tiles) {
+  const int GN = group_n(n_tiles);
+  return (CU_PER_XCD % GN) == 0 && (n_tiles % GN) == 0;
+}
+
+// SPLIT = 1: the main launch (blockIdx.x is the slot).  SPLIT > 1: the launch for the last round's tiles
+// (blockIdx.x / SPLIT counts slots from the cut; blockIdx.x % SPLIT picks the narrow tile, in *sub).
+template <int TOK, int SPLIT>
+__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, bool allow_split,
+                                          int* s_pref, TileInfo& ti, int* sub) {
   // s_pref[e] = number of token tiles of experts < e ; s_pref[E] = total
   for (int e = threadIdx.x; e < E; e += blockDim.x) s_pref[e + 1] = (offsets[e + 1] - offsets[e] + TOK - 1) / TOK;
   __syncthreads();
@@ -69,13 +110,31 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
     }
   }
   __syncthreads();
-  const int total = s_pref[E] * n_tiles;
-  const int chunk = (total + NUM_XCD - 1) / NUM_XCD;
-  const int xcd = blockIdx.x % NUM_XCD, local = blockIdx.x / NUM_XCD;
-  const int L = xcd * chunk + local;
-  if (local >= chunk || L >= total) return false;
-  const int mt = L / n_tiles;
-  ti.ntile = L - mt * n_tiles;
+  const int MT = s_pref[E];
+  const int total = MT * n_tiles;
+  const int leftover = total % NUM_CU;
+  const bool split_mode = allow_split && leftover > 0 && leftover <= SPLIT_MAX_LEFTOVER;
+  const int cut = total - leftover;
+  int slot;
+  if (SPLIT == 1) {
+    slot = blockIdx.x;
+    if (split_mode && slot >= cut) return false;
+  } else {
+    if (!split_mode) return false;
+    slot = cut + blockIdx.x / SPLIT;
+    *sub = blockIdx.x % SPLIT;
+  }
+  const int GN = group_n(n_tiles), GM = CU_PER_XCD / GN;
+  const int MG = (MT + GM - 1) / GM, NG = (n_tiles + GN - 1) / GN;
+  const int xcd = slot % NUM_XCD, local = slot / NUM_XCD;
+  const int q = local / CU_PER_XCD, t = local % CU_PER_XCD;
+  const int b = q * NUM_XCD + xcd;
+  if (t >= GM * GN || b >= MG * NG) return false;
+  const int msg = b / (NUM_XCD * NG), rem = b - msg * NUM_XCD * NG;
+  const int P = min(NUM_XCD, MG - msg * NUM_XCD);
+  const int ng = rem / P, mg = msg * NUM_XCD + rem % P;
+  const int mt = mg * GM + t / GN, nt = ng * GN + t % GN;
+  if (mt >= MT || nt >= n_tiles) return false;
   int lo = 0, hi = E;  // largest e with s_pref[e] <= mt
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
@@ -87,7 +146,7 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
   const int r0 = __builtin_amdgcn_readfirstlane(offsets[lo] + (mt - s_pref[lo]) * TOK);
   ti.row0 = r0;
   ti.rows = __builtin_amdgcn_readfirstlane(min(TOK, offsets[lo + 1] - r0));
-  ti.ntile = __builtin_amdgcn_readfirstlane(ti.ntile);
+  ti.ntile = __builtin_amdgcn_readfirstlane(nt);
   return true;
 }
 
@@ -99,30 +158,44 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 }
 #endif
 
-// TOK x FEAT tile, WT x WF wavefronts; each wavefront owns (TOK/WT) tokens x (FEAT/WF) LDS feature rows.
-template <int TOK, int FEAT, int WT, int WF, int EPI>
-__global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
+// TOK x FEAT tile, WT x WF wavefronts, K-step KS; each wavefront owns (TOK/WT) tokens x (FEAT/WF) LDS
+// feature rows.  WPE = wavefronts per SIMD the register budget is sized for.  SPLIT = 1 for the main
+// launch; SPLIT > 1 for the launch that cuts the last round's 256-wide tiles into SPLIT narrow ones.
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int SPLIT, int EPI>
+__global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
     const uint16_t* __restrict__ wb,      // [E, N, K]   (Wu, SwiGLU only)
     const uint16_t* __restrict__ bias,    // [E, N] or NULL
     const int32_t* __restrict__ offsets,  // [E+1]
     uint16_t* __restrict__ out,           // [R, N]
-    int E, int N, int K) {
+    int E, int N, int K, int allow_split) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer descriptors are device-only types)
   constexpr int NW = WT * WF;
   constexpr int WTOK = TOK / WT, WFEAT = FEAT / WF;
   constexpr int TB = WTOK / 32, FB = WFEAT / 32;  // 32x32 MFMA blocks per wavefront
+  constexpr int ROW_BYTES = KS * 2;               // one LDS row
+  constexpr int CHUNKS = KS / 8;                  // 16-byte chunks per row
+  constexpr int RPB = 256 / ROW_BYTES;            // rows per 256 bytes (the LDS bank period for 16-byte reads)
+  constexpr int RPI = 1024 / ROW_BYTES;           // rows moved by one wave-wide 16-byte-per-lane load
+  constexpr int NSUB = KS / 16;                   // MFMA sub-steps per K-step
   constexpr int A_BYTES = TOK * ROW_BYTES, B_BYTES = FEAT * ROW_BYTES;
   // SwiGLU: LDS feature rows [0,FEAT/2) come from Wg, [FEAT/2,FEAT) from Wu, for FEAT/2 output features
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
-  constexpr int B_ROWS = OUT_FEAT;                                   // rows per weight matrix per tile
-  constexpr int A_LOADS = TOK / 8 / NW, B_LOADS = B_ROWS / 8 / NW;   // wave-instructions per wavefront per stage
-  static_assert(TOK % (8 * NW) == 0 && B_ROWS % (8 * NW) == 0, "tile/wavefront mismatch");
+  constexpr int B_ROWS = OUT_FEAT;                                    // rows per weight matrix per tile
+  constexpr int A_LOADS = TOK / RPI / NW, B_LOADS = B_ROWS / RPI / NW;  // wave-instructions per wavefront per stage
+  // tiles are ordered on a grid whose feature width is GRID_FEAT; a SPLIT launch cuts each grid tile
+  constexpr int GRID_FEAT = OUT_FEAT * SPLIT;
+  static_assert(TOK % (RPI * NW) == 0 && B_ROWS % (RPI * NW) == 0, "tile/wavefront mismatch");
   static_assert(EPI != EPI_SWIGLU || FB == 2, "SwiGLU wave tile is one gate block + one up block");
+  static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");
 
-  // two stages, as separate arrays so that the compiler can tell the stage being filled by LDS DMA from
-  // the stage being read
+  // LDS tile layout: row r keeps its logical 16-byte chunk c at physical chunk c ^ key(r), key(r) =
+  // (r / RPB) mod CHUNKS.  The LDS serves 16 lanes x 16 B per clock over a 256-byte bank period; with this
+  // key any 16 consecutive rows read at one logical chunk land on 16 distinct 16-byte bank groups
+  // (measured conflict-free on gfx950, where keying on r mod 8 gives 2-way conflicts).
+  // Two stages, as separate arrays so that the compiler can tell the stage being filled by LDS DMA from
+  // the stage being read.
   __shared__ __attribute__((aligned(1024))) unsigned char sA0[A_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sB0[B_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sA1[A_BYTES];
@@ -130,12 +203,12 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
   __shared__ int s_pref[MOE_MAX_EXPERTS + 1];
 
   TileInfo ti;
-  const int n_tiles = N / OUT_FEAT;
-  if (!find_tile<TOK>(offsets, E, n_tiles, s_pref, ti)) return;
+  int sub = 0;
+  if (!find_tile<TOK, SPLIT>(offsets, E, N / GRID_FEAT, allow_split != 0, s_pref, ti, &sub)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave / WF, wf = wave % WF;
-  const int feat0 = ti.ntile * OUT_FEAT;
+  const int feat0 = ti.ntile * GRID_FEAT + __builtin_amdgcn_readfirstlane(sub) * OUT_FEAT;
   const uint32_t row_bytes = (uint32_t)K * 2u;
 
   // ---- buffer descriptors and per-lane offsets of every direct-to-LDS load ---------------------
@@ -146,16 +219,16 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
   int a_voff[A_LOADS], b_voff[B_LOADS];
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i) {
-    const int r = (i * NW + wave) * 8 + (lane >> 3);
-    a_voff[i] = r * (int)row_bytes + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
+    const int r = (i * NW + wave) * RPI + lane / CHUNKS;
+    a_voff[i] = r * (int)row_bytes + (((lane % CHUNKS) ^ ((r / RPB) % CHUNKS)) << 4);
   }
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i) {
-    const int r = (i * NW + wave) * 8 + (lane >> 3);
-    b_voff[i] = r * (int)row_bytes + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
+    const int r = (i * NW + wave) * RPI + lane / CHUNKS;
+    b_voff[i] = r * (int)row_bytes + (((lane % CHUNKS) ^ ((r / RPB) % CHUNKS)) << 4);
   }
-  // One instruction moves 64 lanes x 16 B = eight 128-byte rows of a tile; lane l lands at row (l>>3),
-  // physical chunk (l&7), and voff addresses the logical chunk that the swizzle maps there.  The K-step is
+  // One instruction moves 64 lanes x 16 B = RPI rows of a tile; lane l lands at row l/CHUNKS, physical
+  // chunk l%CHUNKS, and voff addresses the logical chunk that the swizzle maps there.  The K-step is
   // selected by the uniform offset.  `live` = false turns the stage into no-ops (zero-length descriptors).
 #define MOE_TILE_LOADS(rsrc, voff, n_loads, lds_tile)                                                            \
   _Pragma("unroll") for (int i_ = 0; i_ < (n_loads); ++i_)                                                       \
@@ -182,21 +255,21 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // LDS byte address of this lane's fragment row with chunk key folded in: chunk for K sub-step ks is
-  // (2*ks + half) ^ key = ((half ^ key) ^ 2*ks), i.e. base ^ (ks << 5).
+  // LDS byte address of this lane's fragment row with chunk key folded in: the chunk of K sub-step ks is
+  // (2*ks + half) ^ key = (half ^ key) ^ 2*ks, i.e. base ^ (ks << 5).
   const int frow = lane & 31, fhalf = lane >> 5;
   int a_base[TB], w_base[FB];
 #pragma unroll
   for (int i = 0; i < TB; ++i) {
     const int r = wt * WTOK + i * 32 + frow;
-    a_base[i] = r * ROW_BYTES + ((fhalf ^ ((r >> 1) & 7)) << 4);
+    a_base[i] = r * ROW_BYTES + ((fhalf ^ ((r / RPB) % CHUNKS)) << 4);
   }
 #pragma unroll
   for (int j = 0; j < FB; ++j) {
     int r;
     if (EPI == EPI_SWIGLU) r = j * (FEAT / 2) + wf * 32 + frow;  // j=0 gate rows, j=1 up rows
     else r = wf * WFEAT + j * 32 + frow;
-    w_base[j] = r * ROW_BYTES + ((fhalf ^ ((r >> 1) & 7)) << 4);
+    w_base[j] = r * ROW_BYTES + ((fhalf ^ ((r / RPB) % CHUNKS)) << 4);
   }
 
   auto read_frags = [&](const unsigned char* A, const unsigned char* B, int ks, bf16x8 (&af)[TB], bf16x8 (&wfr)[FB]) {
@@ -211,38 +284,36 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
 #pragma unroll
       for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[j], af[i], acc[i][j], 0, 0, 0);
   };
-  // Asks the scheduler to alternate one MFMA with one LDS read (n pairs), then `tail` MFMAs.
-  auto interleave = [&](int) {
+  // Asks the scheduler to alternate one MFMA with one LDS read, then the remaining MFMAs.
+  auto interleave = [&]() {
+    constexpr int PAIRS = TB + FB < TB * FB ? TB + FB : TB * FB;
 #pragma unroll
-    for (int q = 0; q < TB + FB; ++q) {
+    for (int q = 0; q < PAIRS; ++q) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, TB * FB - (TB + FB), 0);
+    if (TB * FB > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, TB * FB - PAIRS, 0);
   };
 
   // One K-step.  On entry fr[0] holds the fragments of sub-step 0 of the current stage (CA, CB), and the
-  // loads of the next stage (NA, NB) were issued one K-step ago.  Sub-steps 0..2 multiply while the next
-  // sub-step's fragments are read; then one barrier (all reads of the current stage done, next stage
-  // landed); the current stage's buffers are refilled with stage kt+2 and the last sub-step multiplies
-  // while sub-step 0 of the next stage is read.
+  // loads of the next stage (NA, NB) were issued one K-step ago.  All sub-steps but the last multiply
+  // while the next sub-step's fragments are read; then one barrier (every read of the current stage is
+  // done, the next stage has landed); the current stage's buffers are refilled with stage kt+2 and the
+  // last sub-step multiplies while sub-step 0 of the next stage is read.
   bf16x8 af[2][TB], wfr[2][FB];
-  const int KT = K / KSTEP;
+  const int KT = K / KS;
   auto step = [&](int kt, unsigned char* CA, unsigned char* CB, unsigned char* NA, unsigned char* NB) {
-    read_frags(CA, CB, 1, af[1], wfr[1]);
-    mfma_all(af[0], wfr[0]);
-    interleave(0);
-    read_frags(CA, CB, 2, af[0], wfr[0]);
-    mfma_all(af[1], wfr[1]);
-    interleave(0);
-    read_frags(CA, CB, 3, af[1], wfr[1]);
-    mfma_all(af[0], wfr[0]);
-    interleave(0);
+#pragma unroll
+    for (int ks = 0; ks + 1 < NSUB; ++ks) {
+      read_frags(CA, CB, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
+      mfma_all(af[ks & 1], wfr[ks & 1]);
+      interleave();
+    }
     __syncthreads();
     issue_stage(kt + 2, kt + 2 < KT, CA, CB);
     read_frags(NA, NB, 0, af[0], wfr[0]);
-    mfma_all(af[1], wfr[1]);
-    interleave(0);
+    mfma_all(af[(NSUB - 1) & 1], wfr[(NSUB - 1) & 1]);
+    interleave();
   };
 
   issue_stage(0, true, sA0, sB0);
@@ -255,7 +326,6 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
     step(kt + 1, sA1, sB1, sA0, sB0);
   }
   if (kt < KT) step(kt, sA0, sB0, sA1, sB1);
-  __syncthreads();  // no LDS DMA may be in flight past this point (the last stages issued were no-ops)
 
   // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
 #pragma unroll
@@ -291,7 +361,7 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             float u = acc[tb][fb][4 * i + r] + bv[r];
-            if (EPI == EPI_GELU) u = gelu_exact(u);
+            if (EPI == EPI_GELU) u = gelu_fast(u);
             p[r] = f32_to_bf16_bits(u);
           }
           u32x2 v;
@@ -304,58 +374,86 @@ __global__ __launch_bounds__(WT * WF * 64) void grouped_gemm_kernel(
 #endif
 }
 
-template <int TOK, int FEAT, int WT, int WF, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int SPLIT, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
-               const uint16_t* bias, const int32_t* offsets, uint16_t* out, int N, int K, hipStream_t s) {
+               const uint16_t* bias, const int32_t* offsets, uint16_t* out, int N, int K, bool allow_split,
+               hipStream_t s) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
-  if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
-  if (K % KSTEP) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KSTEP);
+  constexpr int GRID_FEAT = OUT_FEAT * SPLIT;
+  if (N % GRID_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, GRID_FEAT);
+  if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
+  if ((int64_t)TOK * K * 2 >= ((int64_t)1 << 31)) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d too large", K);
   const int64_t rmax = max_rows(cfg);
   if (rmax == 0) return MOE_OK;
-  int64_t mt = rmax / TOK + cfg->E;  // every expert may end in one partial tile
-  const int64_t C = moe_capacity(cfg);
-  if (C != MOE_DROPLESS) {
-    const int64_t by_cap = (int64_t)cfg->E * ((C + TOK - 1) / TOK);
-    if (by_cap < mt) mt = by_cap;
+  int64_t total;
+  if (SPLIT == 1) {
+    int64_t mt = rmax / TOK + cfg->E;  // every expert may end in one partial tile
+    const int64_t C = moe_capacity(cfg);
+    if (C != MOE_DROPLESS) {
+      const int64_t by_cap = (int64_t)cfg->E * ((C + TOK - 1) / TOK);
+      if (by_cap < mt) mt = by_cap;
+    }
+    const int n_tiles = N / GRID_FEAT;
+    const int GN = group_n(n_tiles), GM = CU_PER_XCD / GN;
+    const int64_t MG = (mt + GM - 1) / GM, NG = (n_tiles + GN - 1) / GN;
+    total = (MG * NG + NUM_XCD - 1) / NUM_XCD * CU_PER_XCD * NUM_XCD;  // whole blocks on every XCD
+  } else {
+    // Slots from the cut to the last tile: the leftover tiles (<= SPLIT_MAX_LEFTOVER) plus the empty slots
+    // of the last, partial token group (< GM * n_tiles <= 64 for the grids splitting is enabled on).
+    total = (int64_t)NUM_CU * SPLIT;
   }
-  int64_t total = mt * (N / OUT_FEAT);
-  total = (total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
   if (total > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: too many tiles");
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, EPI>;
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, SPLIT, EPI>;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out,
-                     cfg->E, N, K);
+                     cfg->E, N, K, allow_split ? 1 : 0);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
+}
+
+// MOESYS_GEMM_SPLIT=0 disables the narrow-tile launch for the last round (tuning aid).
+bool split_enabled() {
+  static const bool v = [] { const char* e = getenv("MOESYS_GEMM_SPLIT"); return !e || atoi(e) != 0; }();
+  return v;
+}
+
+// One grouped GEMM = the 256x256x64 launch (8 wavefronts, one workgroup per CU: the highest arithmetic
+// intensity that fits the 160 KB LDS) plus, when the feature count lets the slot grid be dense, the
+// narrow-tile launch for the last round.  Feature counts that are multiples of 64 but not of 256 use
+// narrow tiles throughout.
+template <int EPI>
+int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
+                 const int32_t* offsets, uint16_t* o, int N, int K, hipStream_t s) {
+  constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
+  if (N % BF == 0) {
+    const bool sp = split_enabled() && grid_is_dense(N / BF) && N / BF <= 16;
+    int32_t st = launch<256, 256, 2, 4, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, sp, s);
+    if (st != MOE_OK || !sp) return st;
+    if constexpr (EPI == EPI_SWIGLU)  // 128 output features -> two tiles of 64 (gate rows + up rows side by side)
+      return launch<256, 128, 4, 2, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
+    else
+      return launch<256, 64, 4, 2, 64, 2, 4, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
+  }
+  if constexpr (EPI == EPI_SWIGLU)
+    return launch<128, 128, 2, 2, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
+  else
+    return launch<128, 64, 4, 1, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
 }
 
 }  // namespace
 
-// Tile choice: 256x256 (8 wavefronts) when the feature count allows, else a 128-token tile with 64
-// output features (4 wavefronts) so that any multiple of 64 is served.
 int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
                           void* h, hipStream_t s) {
-  const uint16_t* a = (const uint16_t*)xd;
-  uint16_t* o = (uint16_t*)h;
-  const int N = cfg->d_ff, K = cfg->d_model;
-  if (cfg->act == MOE_ACT_SWIGLU) {
-    const uint16_t *wg = (const uint16_t*)w->w_gate_proj, *wu = (const uint16_t*)w->w_up;
-    if (N % 128 == 0) return launch<256, 256, 2, 4, EPI_SWIGLU>(cfg, a, wg, wu, nullptr, offsets, o, N, K, s);
-    return launch<128, 128, 2, 2, EPI_SWIGLU>(cfg, a, wg, wu, nullptr, offsets, o, N, K, s);
-  }
-  const uint16_t *w1 = (const uint16_t*)w->w1, *b1 = (const uint16_t*)w->b1;
-  if (N % 256 == 0) return launch<256, 256, 2, 4, EPI_GELU>(cfg, a, w1, nullptr, b1, offsets, o, N, K, s);
-  return launch<128, 64, 4, 1, EPI_GELU>(cfg, a, w1, nullptr, b1, offsets, o, N, K, s);
+  if (cfg->act == MOE_ACT_SWIGLU)
+    return gemm_any<EPI_SWIGLU>(cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up,
+                                nullptr, offsets, (uint16_t*)h, cfg->d_ff, cfg->d_model, s);
+  return gemm_any<EPI_GELU>(cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets,
+                            (uint16_t*)h, cfg->d_ff, cfg->d_model, s);
 }
 
 int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
                           void* yd, hipStream_t s) {
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
-  const uint16_t* a = (const uint16_t*)h;
-  const uint16_t* w2 = (const uint16_t*)(sw ? w->w_down : w->w2);
-  const uint16_t* b2 = (const uint16_t*)(sw ? nullptr : w->b2);
-  uint16_t* o = (uint16_t*)yd;
-  const int N = cfg->d_model, K = cfg->d_ff;
-  if (N % 256 == 0) return launch<256, 256, 2, 4, EPI_BIAS>(cfg, a, w2, nullptr, b2, offsets, o, N, K, s);
-  return launch<128, 64, 4, 1, EPI_BIAS>(cfg, a, w2, nullptr, b2, offsets, o, N, K, s);
+  return gemm_any<EPI_BIAS>(cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
+                            (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, cfg->d_model, cfg->d_ff, s);
 }
 
 }  // namespace moesys
