@@ -161,7 +161,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // TOK x FEAT tile, WT x WF wavefronts, K-step KS; each wavefront owns (TOK/WT) tokens x (FEAT/WF) LDS
 // feature rows.  WPE = wavefronts per SIMD the register budget is sized for.  SPLIT = 1 for the main
 // launch; SPLIT > 1 for the launch that cuts the last round's 256-wide tiles into SPLIT narrow ones.
-template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int SPLIT, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int SPLIT, int EPI>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
@@ -194,12 +194,14 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // (r / RPB) mod CHUNKS.  The LDS serves 16 lanes x 16 B per clock over a 256-byte bank period; with this
   // key any 16 consecutive rows read at one logical chunk land on 16 distinct 16-byte bank groups
   // (measured conflict-free on gfx950, where keying on r mod 8 gives 2-way conflicts).
-  // Two stages, as separate arrays so that the compiler can tell the stage being filled by LDS DMA from
-  // the stage being read.
-  __shared__ __attribute__((aligned(1024))) unsigned char sA0[A_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char sB0[B_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char sA1[A_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char sB1[B_BYTES];
+  // NST stages (2 or 4), each one array holding the token tile then the feature tile: separate arrays so
+  // that the compiler can tell a stage being filled by LDS DMA from the stage being read.
+  constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static_assert(NST == 2 || NST == 4, "two or four LDS stages");
+  __shared__ __attribute__((aligned(1024))) unsigned char s0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char s1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char s2[NST == 4 ? STAGE_BYTES : 16];
+  __shared__ __attribute__((aligned(1024))) unsigned char s3[NST == 4 ? STAGE_BYTES : 16];
   __shared__ int s_pref[MOE_MAX_EXPERTS + 1];
 
   TileInfo ti;
@@ -234,7 +236,9 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   _Pragma("unroll") for (int i_ = 0; i_ < (n_loads); ++i_)                                                       \
       __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                  \
           rsrc, (__attribute__((address_space(3))) void*)((lds_tile) + (i_ * NW + wave) * 1024), 16, voff[i_], koff, 0, 0)
-  auto issue_stage = [&](int kt, bool live, unsigned char* A, unsigned char* B) {
+  auto issue_stage = [&](int kt, bool live, unsigned char* stage) {
+    unsigned char* A = stage;
+    unsigned char* B = stage + A_BYTES;
     const int koff = kt * ROW_BYTES;
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a_base_ptr, live ? a_bytes : 0u);
     const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(b_base_ptr, live ? b_bytes : 0u);
@@ -295,37 +299,68 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     if (TB * FB > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, TB * FB - PAIRS, 0);
   };
 
-  // One K-step.  On entry fr[0] holds the fragments of sub-step 0 of the current stage (CA, CB), and the
-  // loads of the next stage (NA, NB) were issued one K-step ago.  All sub-steps but the last multiply
-  // while the next sub-step's fragments are read; then one barrier (every read of the current stage is
-  // done, the next stage has landed); the current stage's buffers are refilled with stage kt+2 and the
-  // last sub-step multiplies while sub-step 0 of the next stage is read.
+  // One K-step on the stage in `cur`.  On entry fr[0] holds the fragments of sub-step 0 of that stage and
+  // the loads of the following NST-1 stages are in flight.  All sub-steps but the last multiply while the
+  // next sub-step's fragments are read; then every wavefront waits until its own share of the NEXT stage
+  // has landed (the younger NST-2 batches may stay in flight: the counter retires loads in order) and until
+  // its fragment reads are done, and the workgroup meets at one barrier; the current stage's buffer is then
+  // refilled with stage kt+NST, and the last sub-step multiplies while sub-step 0 of the next stage is read.
+  constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS * (EPI == EPI_SWIGLU ? 2 : 1);
+  constexpr int IN_FLIGHT = (NST - 2) * LOADS_PER_STAGE;  // loads allowed to be outstanding at the barrier
+  static_assert(IN_FLIGHT < 64, "vmcnt is a 6-bit counter");
+  // s_waitcnt immediate: vmcnt = IN_FLIGHT (bits 3:0 and 15:14), expcnt = 7 (no wait), lgkmcnt = 0
+  constexpr int WAIT_IMM = (IN_FLIGHT & 15) | ((IN_FLIGHT >> 4) << 14) | (7 << 4);
+  auto stage_barrier = [&]() {
+    asm volatile("s_waitcnt %0\n\ts_barrier" ::"n"(WAIT_IMM) : "memory");
+  };
   bf16x8 af[2][TB], wfr[2][FB];
   const int KT = K / KS;
-  auto step = [&](int kt, unsigned char* CA, unsigned char* CB, unsigned char* NA, unsigned char* NB) {
+  auto step = [&](int kt, unsigned char* cur, unsigned char* nxt) {
 #pragma unroll
     for (int ks = 0; ks + 1 < NSUB; ++ks) {
-      read_frags(CA, CB, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
+      read_frags(cur, cur + A_BYTES, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
       mfma_all(af[ks & 1], wfr[ks & 1]);
       interleave();
     }
-    __syncthreads();
-    issue_stage(kt + 2, kt + 2 < KT, CA, CB);
-    read_frags(NA, NB, 0, af[0], wfr[0]);
+    stage_barrier();
+    issue_stage(kt + NST, kt + NST < KT, cur);
+    read_frags(nxt, nxt + A_BYTES, 0, af[0], wfr[0]);
     mfma_all(af[(NSUB - 1) & 1], wfr[(NSUB - 1) & 1]);
     interleave();
   };
 
-  issue_stage(0, true, sA0, sB0);
-  __syncthreads();
-  issue_stage(1, 1 < KT, sA1, sB1);
-  read_frags(sA0, sB0, 0, af[0], wfr[0]);
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    step(kt, sA0, sB0, sA1, sB1);
-    step(kt + 1, sA1, sB1, sA0, sB0);
+  issue_stage(0, true, s0);
+  issue_stage(1, 1 < KT, s1);
+  if (NST == 4) {
+    issue_stage(2, 2 < KT, s2);
+    issue_stage(3, 3 < KT, s3);
   }
-  if (kt < KT) step(kt, sA0, sB0, sA1, sB1);
+  {  // stage 0 has landed for every wavefront
+    constexpr int PRO = (NST - 1) * LOADS_PER_STAGE;
+    constexpr int PRO_IMM = (PRO & 15) | ((PRO >> 4) << 14) | (7 << 4);
+    static_assert(PRO < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt %0\n\ts_barrier" ::"n"(PRO_IMM) : "memory");
+  }
+  read_frags(s0, s0 + A_BYTES, 0, af[0], wfr[0]);
+  int kt = 0;
+  if (NST == 2) {
+    for (; kt + 1 < KT; kt += 2) {
+      step(kt, s0, s1);
+      step(kt + 1, s1, s0);
+    }
+    if (kt < KT) step(kt, s0, s1);
+  } else {
+    for (; kt + 3 < KT; kt += 4) {
+      step(kt, s0, s1);
+      step(kt + 1, s1, s2);
+      step(kt + 2, s2, s3);
+      step(kt + 3, s3, s0);
+    }
+    if (kt < KT) step(kt, s0, s1);
+    if (kt + 1 < KT) step(kt + 1, s1, s2);
+    if (kt + 2 < KT) step(kt + 2, s2, s3);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only zero-length loads remain; retire them before exit
 
   // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
 #pragma unroll
@@ -374,7 +409,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #endif
 }
 
-template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int SPLIT, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int SPLIT, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, int N, int K, bool allow_split,
                hipStream_t s) {
@@ -403,15 +438,24 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
     total = (int64_t)NUM_CU * SPLIT;
   }
   if (total > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: too many tiles");
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, SPLIT, EPI>;
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, SPLIT, EPI>;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out,
                      cfg->E, N, K, allow_split ? 1 : 0);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
-// MOESYS_GEMM_SPLIT=0 disables the narrow-tile launch for the last round (tuning aid).
+// MOESYS_GEMM_SPLIT=1 enables the narrow-tile launch for the last round.  Off by default: measured on
+// MI355X the K loop of a narrow tile is bound by the same per-step memory latency as the wide tile's, so
+// a quarter-width tile takes almost as long as a full one and the split loses.
 bool split_enabled() {
-  static const bool v = [] { const char* e = getenv("MOESYS_GEMM_SPLIT"); return !e || atoi(e) != 0; }();
+  static const bool v = [] { const char* e = getenv("MOESYS_GEMM_SPLIT"); return e && atoi(e) != 0; }();
+  return v;
+}
+
+// MOESYS_GEMM_DEEP=1 selects four 32-deep LDS stages instead of two 64-deep ones.  Off by default:
+// measured ~7 % slower on MI355X (twice the barriers, no gain from the longer prefetch distance).
+bool deep_pipeline() {
+  static const bool v = [] { const char* e = getenv("MOESYS_GEMM_DEEP"); return e && atoi(e) != 0; }();
   return v;
 }
 
@@ -419,23 +463,48 @@ bool split_enabled() {
 // intensity that fits the 160 KB LDS) plus, when the feature count lets the slot grid be dense, the
 // narrow-tile launch for the last round.  Feature counts that are multiples of 64 but not of 256 use
 // narrow tiles throughout.
-template <int EPI>
+// Token-tile height.  256 rows is the default; 320 rows (10 MFMA row blocks, still within the 160 KB LDS)
+// is chosen when, for the row count an evenly loaded expert would get, it saves enough whole rounds of
+// NUM_CU tiles to pay for the taller tile (e.g. ~1024 rows per expert: 4 tiles of 320 instead of 5 of 256).
+// The estimate only steers the choice; any routing is handled by either height.
+static int pick_tile_rows(const moe_config* cfg, int n_tiles) {
+  static const int forced = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
+  if (forced == 256 || forced == 320) return forced;
+  const int64_t A = (int64_t)cfg->k * cfg->T;
+  int64_t rows = (A + cfg->E - 1) / cfg->E;
+  rows += (rows * 2 + 24) / 25;  // 8 % head-room for uneven routing
+  const int64_t C = moe_capacity(cfg);
+  if (rows > C) rows = C;
+  if (rows < 1) rows = 1;
+  int best = 256;
+  int64_t best_cost = -1;
+  for (int tok : {256, 320}) {
+    const int64_t tiles = (int64_t)cfg->E * ((rows + tok - 1) / tok) * n_tiles;
+    const int64_t cost = (tiles + NUM_CU - 1) / NUM_CU * tok;
+    if (best_cost < 0 || cost < best_cost) { best = tok; best_cost = cost; }
+  }
+  return best;
+}
+
+template <int EPI, int KSB, int NSB>
 int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
                  const int32_t* offsets, uint16_t* o, int N, int K, hipStream_t s) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
     const bool sp = split_enabled() && grid_is_dense(N / BF) && N / BF <= 16;
-    int32_t st = launch<256, 256, 2, 4, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, sp, s);
+    if (!sp && KSB == 64 && pick_tile_rows(cfg, N / BF) == 320)
+      return launch<320, 256, 2, 4, 64, 2, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
+    int32_t st = launch<256, 256, 2, 4, KSB, NSB, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, sp, s);
     if (st != MOE_OK || !sp) return st;
     if constexpr (EPI == EPI_SWIGLU)  // 128 output features -> two tiles of 64 (gate rows + up rows side by side)
-      return launch<256, 128, 4, 2, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
+      return launch<256, 128, 4, 2, 64, 2, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
     else
-      return launch<256, 64, 4, 2, 64, 2, 4, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
+      return launch<256, 64, 4, 2, 64, 2, 2, 4, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, true, s);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
+    return launch<128, 128, 2, 2, 64, 2, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
   else
-    return launch<128, 64, 4, 1, 64, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
+    return launch<128, 64, 4, 1, 64, 2, 2, 1, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, false, s);
 }
 
 }  // namespace
@@ -443,16 +512,16 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
 int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
                           void* h, hipStream_t s) {
   if (cfg->act == MOE_ACT_SWIGLU)
-    return gemm_any<EPI_SWIGLU>(cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up,
+    return (deep_pipeline() ? gemm_any<EPI_SWIGLU, 32, 4> : gemm_any<EPI_SWIGLU, 64, 2>)(cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up,
                                 nullptr, offsets, (uint16_t*)h, cfg->d_ff, cfg->d_model, s);
-  return gemm_any<EPI_GELU>(cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets,
+  return (deep_pipeline() ? gemm_any<EPI_GELU, 32, 4> : gemm_any<EPI_GELU, 64, 2>)(cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets,
                             (uint16_t*)h, cfg->d_ff, cfg->d_model, s);
 }
 
 int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
                           void* yd, hipStream_t s) {
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
-  return gemm_any<EPI_BIAS>(cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
+  return (deep_pipeline() ? gemm_any<EPI_BIAS, 32, 4> : gemm_any<EPI_BIAS, 64, 2>)(cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
                             (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, cfg->d_model, cfg->d_ff, s);
 }
 
