@@ -198,84 +198,89 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int FT_TOK = 32;           // tokens per workgroup (two 16-token MFMA tiles)
+constexpr int FT_TOK = 16;           // tokens per workgroup (one 16-token MFMA tile)
 constexpr int FT_KC = 64;            // K chunk: two 16x16x32 MFMA steps
 constexpr int FT_ROW = (FT_KC + 8) * 2;  // LDS row of one expert's chunk, padded to 144 B (conflict-free reads)
 constexpr float GATE_MARGIN = 1e-4f; // neighbours among the k+1 leading logits closer than this -> exact recompute
 
 __device__ __forceinline__ uint32_t bf16_bits_rne(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
 
-// Keeps the KEEP best (z, e) pairs seen so far, best first; among equal logits the lower expert index
-// ranks first (the comparison must also hold for entries pushed down the list by a newcomer).
-template <int KEEP>
-struct TopList {
-  double z[KEEP];
-  int e[KEEP];
-  float p[KEEP];
-  __device__ __forceinline__ void init() {
-#pragma unroll
-    for (int i = 0; i < KEEP; ++i) { z[i] = -INFINITY; e[i] = 0x7fffffff; p[i] = 0.f; }
-  }
-  __device__ __forceinline__ void offer(double zn, int en) {
-#pragma unroll
-    for (int i = 0; i < KEEP; ++i) {
-      const bool better = zn > z[i] || (zn == z[i] && en < e[i]);
-      const double tz = better ? z[i] : zn;
-      const int te = better ? e[i] : en;
-      z[i] = better ? zn : z[i];
-      e[i] = better ? en : e[i];
-      zn = tz;
-      en = te;
-    }
-  }
-};
-
-// Softmax (fp32) + top-k of one token from its E float64 logits zsrc[e*stride]; one thread.
-// Returns true if two neighbours among the k+1 leading logits are closer than `margin`.
-__device__ __forceinline__ bool finalize_token(const double* zsrc, int stride, int E, int k, int renorm, float margin,
+// Softmax (fp32) + top-k of one token by a group of 8 adjacent lanes.  Lane `sub` of the group holds the
+// float64 logits of experts sub, sub+8, ... (NPL of them, -inf beyond E).  k+1 rounds of group-wide
+// arg-max (ties -> lower expert) pick the experts in rank order; the extra round only measures the gap
+// to the first expert NOT selected.  Returns true (to every lane of the group) if two neighbours among
+// those k+1 logits are closer than `margin`.
+template <int NPL>
+__device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E, int k, int renorm, float margin,
                                                int32_t* __restrict__ idx_out, float* __restrict__ w_out,
                                                float* __restrict__ probs_out) {
-  TopList<MOE_MAX_TOPK + 1> top;
-  top.init();
   float mx = -INFINITY;
-  for (int e = 0; e < E; ++e) {
-    const double z = zsrc[e * stride];
-    top.offer(z, e);
-    mx = fmaxf(mx, (float)z);
-  }
-  float sum = 0.f;
-  for (int e = 0; e < E; ++e) sum += expf((float)zsrc[e * stride] - mx);
-  const float inv = 1.f / sum;
-  if (probs_out)
-    for (int e = 0; e < E; ++e) probs_out[e] = expf((float)zsrc[e * stride] - mx) / sum;
-  float wsum = 0.f;
-  float w[MOE_MAX_TOPK];
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
-    w[j] = j < k ? expf((float)top.z[j] - mx) / sum : 0.f;
-    wsum += w[j];
+  for (int i = 0; i < NPL; ++i) mx = fmaxf(mx, (float)z[i]);
+#pragma unroll
+  for (int m = 1; m <= 4; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  float ex[NPL], sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    ex[i] = (sub + 8 * i) < E ? expf((float)z[i] - mx) : 0.f;
+    sum += ex[i];
   }
-  (void)inv;
+#pragma unroll
+  for (int m = 1; m <= 4; m <<= 1) sum += __shfl_xor(sum, m, 64);
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    ex[i] = ex[i] / sum;
+    if (probs_out && (sub + 8 * i) < E) probs_out[sub + 8 * i] = ex[i];
+  }
+  float my_w = 0.f, wsum = 0.f;
+  int my_idx = 0;
+  double prev = INFINITY;
   bool close = false;
+  for (int r = 0; r <= k; ++r) {
+    double bz = -INFINITY;
+    int be = 0x7fffffff;
+    float bp = 0.f;
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
-    if (j < k) {
-      idx_out[j] = top.e[j];
-      w_out[j] = renorm ? w[j] / wsum : w[j];
-      if (j + 1 < E) close |= (float)(top.z[j] - top.z[j + 1]) < margin;
+    for (int i = 0; i < NPL; ++i) {
+      const int e = sub + 8 * i;
+      if (e < E && (z[i] > bz || (z[i] == bz && e < be))) { bz = z[i]; be = e; bp = ex[i]; }
     }
+#pragma unroll
+    for (int m = 1; m <= 4; m <<= 1) {
+      const double oz = shfl_xor_f64(bz, m);
+      const int oe = __shfl_xor(be, m, 64);
+      const float op = __shfl_xor(bp, m, 64);
+      if (oz > bz || (oz == bz && oe < be)) { bz = oz; be = oe; bp = op; }
+    }
+#pragma unroll
+    for (int i = 0; i < NPL; ++i)
+      if (sub + 8 * i == be) z[i] = -INFINITY;  // retire the winner (every lane of the group agrees on be)
+    if (r < k) {
+      if (sub == r) { my_idx = be; my_w = bp; }
+      wsum += bp;
+    }
+    if (r > 0) close |= (float)(prev - bz) < margin;
+    prev = bz;
+  }
+  if (sub < k) {
+    idx_out[sub] = my_idx;
+    w_out[sub] = renorm ? my_w / wsum : my_w;
   }
   return close;
 }
 
-// EB = number of 16-expert blocks (E <= 16*EB).
-template <int EB>
+// EB = number of 16-expert blocks (E <= 16*EB).  One workgroup = 16 tokens (one MFMA token tile); its four
+// wavefronts split the K range chunk by chunk and meet once, to add their partial logits.  VEC: the router
+// weights can be read four experts at a time (E a multiple of 4, 16-byte aligned base).
+template <int EB, bool VEC>
 __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
                                                         const float* __restrict__ br, int T, int d, int E, int k,
                                                         int renorm, int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_w, float* __restrict__ probs) {
   constexpr int EP = EB * 16;
+  constexpr int NPL = EP / 8;                    // logits per lane in the 8-lane finalisation groups
   constexpr int W_WAVE_BYTES = 3 * EP * FT_ROW;  // one wavefront's hi/mid/lo chunk
+  constexpr int PF = EB == 1 ? 4 : 2;            // chunks in flight per wavefront (register-staged)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_flag[FT_TOK];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -283,139 +288,144 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   const int t0 = blockIdx.x * FT_TOK;
   const int tl = lane & 15, kq = lane >> 4;  // MFMA operand coordinates of this lane
 
-  // activation rows of this lane's two token tiles (clamped: tail tokens recompute the last row, never stored)
-  const uint16_t* xrow[2];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) xrow[q] = x + (size_t)min(t0 + q * 16 + tl, T - 1) * d + kq * 16;
+  // activation row of this lane (clamped: tail tokens recompute the last row, never stored)
+  const uint16_t* xrow = x + (size_t)min(t0 + tl, T - 1) * d + kq * 16;
 
-  double zacc[2][EB][4];
+  double zacc[EB][4];
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int b = 0; b < EB; ++b)
 #pragma unroll
-    for (int b = 0; b < EB; ++b)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) zacc[q][b][r] = 0.0;
+    for (int r = 0; r < 4; ++r) zacc[b][r] = 0.0;
 
   // router-weight micro-tiles of this lane: 4 consecutive k x 4 consecutive experts each
   constexpr int MT_PER_LANE = (FT_KC / 4) * (EP / 4) / 64;  // = EB
   const int n_chunks = d / FT_KC;
-  const int iters = (n_chunks + 3) / 4;
 
-  u32x4 xa[2][2];  // [tile][half of the lane's 32 bytes]
-  float wv[MT_PER_LANE][4][4];
-  auto load_chunk = [&](int c) {
-    const int k0 = c * FT_KC;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      xa[q][0] = *reinterpret_cast<const u32x4*>(xrow[q] + k0);
-      xa[q][1] = *reinterpret_cast<const u32x4*>(xrow[q] + k0 + 8);
-    }
-#pragma unroll
-    for (int m = 0; m < MT_PER_LANE; ++m) {
-      const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = eg * 4 + j;
-          wv[m][i][j] = e < E ? wr[(size_t)(k0 + kg * 4 + i) * E + e] : 0.f;
-        }
-    }
-  };
+  // PF register stages.  Every stage load is unconditional (a chunk index past the end re-reads the last
+  // chunk and is never used), so the number of loads in flight is fixed and the wait before a stage's
+  // first use can leave the younger stages outstanding.
+  u32x4 xa[PF][2];
+  float wv[PF][MT_PER_LANE][4][4];
+#define GATE_LOAD_STAGE(s_, c_)                                                                         \
+  {                                                                                                     \
+    const int k0_ = min((c_), n_chunks - 1) * FT_KC;                                                    \
+    xa[s_][0] = *reinterpret_cast<const u32x4*>(xrow + k0_);                                            \
+    xa[s_][1] = *reinterpret_cast<const u32x4*>(xrow + k0_ + 8);                                        \
+    _Pragma("unroll") for (int m = 0; m < MT_PER_LANE; ++m) {                                           \
+      const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);                             \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
+        const float* wp = wr + (size_t)(k0_ + kg * 4 + i) * E;                                          \
+        if (VEC) {                                                                                      \
+          const f32x4 v = *reinterpret_cast<const f32x4*>(wp + min(eg * 4, E - 4));                     \
+          const bool ok = eg * 4 < E;                                                                   \
+          wv[s_][m][i][0] = ok ? v[0] : 0.f; wv[s_][m][i][1] = ok ? v[1] : 0.f;                         \
+          wv[s_][m][i][2] = ok ? v[2] : 0.f; wv[s_][m][i][3] = ok ? v[3] : 0.f;                         \
+        } else {                                                                                        \
+          _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
+            const int e = eg * 4 + j;                                                                   \
+            const float v = wp[min(e, E - 1)];                                                          \
+            wv[s_][m][i][j] = e < E ? v : 0.f;                                                          \
+          }                                                                                             \
+        }                                                                                               \
+      }                                                                                                 \
+    }                                                                                                   \
+  }
 
-  int c = wave;  // chunks wave, wave+4, ...
-  if (c < n_chunks) load_chunk(c);
-  for (int it = 0; it < iters; ++it, c += 4) {
-    const bool live = c < n_chunks;
-    if (live) {
-      // split this chunk's router weights into three bf16 pieces and stage them K-contiguous per expert
+  // chunks wave, wave+4, ...  The LDS staging area is private to the wavefront and LDS operations of one
+  // wavefront execute in order, so no barrier is needed inside this loop.
 #pragma unroll
-      for (int m = 0; m < MT_PER_LANE; ++m) {
-        const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
+  for (int s = 0; s < PF; ++s) GATE_LOAD_STAGE(s, wave + 4 * s)
+  for (int base = wave; base < n_chunks; base += 4 * PF) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          uint32_t hi[4], mid[4], lo[4];
+    for (int s = 0; s < PF; ++s) {
+      const int c = base + 4 * s;
+      const bool live = c < n_chunks;  // uniform
+      bf16x8 xb[2];
+      if (live) {
+        // split this chunk's router weights into three bf16 pieces and stage them K-contiguous per expert
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float w = wv[m][i][j];
-            hi[i] = bf16_bits_rne(w);
-            const float r1 = w - __uint_as_float(hi[i] << 16);
-            mid[i] = bf16_bits_rne(r1);
-            const float r2 = r1 - __uint_as_float(mid[i] << 16);
-            lo[i] = bf16_bits_rne(r2);
+        for (int m = 0; m < MT_PER_LANE; ++m) {
+          const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float w = wv[s][m][i][j];
+              hi[i] = bf16_bits_rne(w);
+              const float r1 = w - __uint_as_float(hi[i] << 16);
+              mid[i] = bf16_bits_rne(r1);
+              const float r2 = r1 - __uint_as_float(mid[i] << 16);
+              lo[i] = bf16_bits_rne(r2);
+            }
+            unsigned char* row = wl + (eg * 4 + j) * FT_ROW + kg * 8;
+            u32x2 v;
+            v.x = hi[0] | (hi[1] << 16); v.y = hi[2] | (hi[3] << 16);
+            *reinterpret_cast<u32x2*>(row) = v;
+            v.x = mid[0] | (mid[1] << 16); v.y = mid[2] | (mid[3] << 16);
+            *reinterpret_cast<u32x2*>(row + EP * FT_ROW) = v;
+            v.x = lo[0] | (lo[1] << 16); v.y = lo[2] | (lo[3] << 16);
+            *reinterpret_cast<u32x2*>(row + 2 * EP * FT_ROW) = v;
           }
-          unsigned char* row = wl + (eg * 4 + j) * FT_ROW + kg * 8;
-          u32x2 v;
-          v.x = hi[0] | (hi[1] << 16); v.y = hi[2] | (hi[3] << 16);
-          *reinterpret_cast<u32x2*>(row) = v;
-          v.x = mid[0] | (mid[1] << 16); v.y = mid[2] | (mid[3] << 16);
-          *reinterpret_cast<u32x2*>(row + EP * FT_ROW) = v;
-          v.x = lo[0] | (lo[1] << 16); v.y = lo[2] | (lo[3] << 16);
-          *reinterpret_cast<u32x2*>(row + 2 * EP * FT_ROW) = v;
         }
+        xb[0] = __builtin_bit_cast(bf16x8, xa[s][0]);
+        xb[1] = __builtin_bit_cast(bf16x8, xa[s][1]);
       }
-    }
-    bf16x8 xb[2][2];
+      GATE_LOAD_STAGE(s, c + 4 * PF)  // refill this register stage
+      if (live) {
+        asm volatile("" ::: "memory");  // keep the LDS reads below the LDS writes above (same wavefront: in order)
+        f32x4 acc[EB];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      xb[q][0] = __builtin_bit_cast(bf16x8, xa[q][0]);
-      xb[q][1] = __builtin_bit_cast(bf16x8, xa[q][1]);
-    }
-    if (c + 4 < n_chunks) load_chunk(c + 4);  // next chunk streams in while this one is multiplied
-    __syncthreads();                          // this wavefront's LDS writes are visible to its own reads
-    if (live) {
-      f32x4 acc[2][EB];
+        for (int b = 0; b < EB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+        for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-        for (int b = 0; b < EB; ++b) acc[q][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int p = 0; p < 3; ++p)
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int p = 0; p < 3; ++p)
-#pragma unroll
-          for (int b = 0; b < EB; ++b) {
-            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * EP + b * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
-#pragma unroll
-            for (int q = 0; q < 2; ++q) acc[q][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[q][s2], acc[q][b], 0, 0, 0);
-          }
-#pragma unroll
-      for (int q = 0; q < 2; ++q)
+            for (int b = 0; b < EB; ++b) {
+              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * EP + b * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
+              acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[s2], acc[b], 0, 0, 0);
+            }
 #pragma unroll
         for (int b = 0; b < EB; ++b)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) zacc[q][b][r] += (double)acc[q][b][r];
+          for (int r = 0; r < 4; ++r) zacc[b][r] += (double)acc[b][r];
+        asm volatile("" ::: "memory");
+      }
     }
-    __syncthreads();  // the chunk in LDS may be overwritten
   }
+#undef GATE_LOAD_STAGE
+  __syncthreads();  // every wavefront is done with its staging area
 
   // ---- cross-wavefront sum of the partial logits (float64) and per-token finalisation ------------
   double* part = reinterpret_cast<double*>(smem);  // [4][EP][FT_TOK]
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int b = 0; b < EB; ++b)
 #pragma unroll
-    for (int b = 0; b < EB; ++b)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        part[((size_t)wave * EP + b * 16 + kq * 4 + r) * FT_TOK + q * 16 + tl] = zacc[q][b][r];
+    for (int r = 0; r < 4; ++r) part[((size_t)wave * EP + b * 16 + kq * 4 + r) * FT_TOK + tl] = zacc[b][r];
   __syncthreads();
-  double* zfin = part + 4 * EP * FT_TOK;  // [EP][FT_TOK]
-  for (int i = tid; i < EP * FT_TOK; i += 256) {
-    const int e = i / FT_TOK;
-    double z = part[i];
+  if (tid < FT_TOK * 8) {
+    const int tok = tid >> 3, sub = tid & 7;
+    const int t = t0 + tok;
+    double z[NPL];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) z += part[(size_t)w * EP * FT_TOK + i];
-    if (e < E && br) z += (double)br[e];
-    zfin[i] = z;
-  }
-  __syncthreads();
-  if (tid < FT_TOK) {
-    const int t = t0 + tid;
+    for (int i = 0; i < NPL; ++i) {
+      const int e = sub + 8 * i;
+      double v = -INFINITY;
+      if (e < E) {
+        v = part[(size_t)e * FT_TOK + tok];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) v += part[((size_t)w * EP + e) * FT_TOK + tok];
+        if (br) v += (double)br[e];
+      }
+      z[i] = v;
+    }
+    const int tc = min(t, T - 1);  // tail tokens run the same code on the last row, without storing
     bool flag = false;
     if (t < T)
-      flag = finalize_token(zfin + tid, FT_TOK, E, k, renorm, GATE_MARGIN, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
-                            probs ? probs + (size_t)t * E : nullptr);
-    s_flag[tid] = flag ? 1 : 0;
+      flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_MARGIN, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
+                                 probs ? probs + (size_t)tc * E : nullptr);
+    if (sub == 0) s_flag[tok] = flag ? 1 : 0;
   }
   __syncthreads();
 
@@ -442,9 +452,13 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
       if (tid < ne) zex[c0 + tid] = wsum[tid] + wsum[NE + tid] + wsum[2 * NE + tid] + wsum[3 * NE + tid] + (br ? (double)br[c0 + tid] : 0.0);
       __syncthreads();
     }
-    if (tid == 0)
-      finalize_token(zex, 1, E, k, renorm, 0.f, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
-                     probs ? probs + (size_t)t * E : nullptr);
+    if (tid < 8) {
+      double z[NPL];
+#pragma unroll
+      for (int i = 0; i < NPL; ++i) z[i] = (tid + 8 * i) < E ? zex[tid + 8 * i] : -INFINITY;
+      finalize_group<NPL>(z, tid, E, k, renorm, 0.f, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
+                          probs ? probs + (size_t)t * E : nullptr);
+    }
     __syncthreads();
   }
 }
@@ -454,9 +468,10 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   constexpr int EP = EB * 16;
   const size_t w_bytes = (size_t)4 * 3 * EP * FT_ROW;
-  const size_t z_bytes = (size_t)5 * EP * FT_TOK * sizeof(double);
+  const size_t z_bytes = (size_t)4 * EP * FT_TOK * sizeof(double) + 256;
   const size_t shmem = w_bytes > z_bytes ? w_bytes : z_bytes;
-  auto kern = gate_mfma_kernel<EB>;
+  const bool vec = cfg->E % 4 == 0 && ((uintptr_t)w_router & 15) == 0;
+  auto kern = vec ? gate_mfma_kernel<EB, true> : gate_mfma_kernel<EB, false>;
   if (shmem > 65536) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
