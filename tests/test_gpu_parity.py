@@ -227,6 +227,7 @@ LAYER_CASES = [
     ("large", dict(T=1536, d_model=512, d_ff=1024, E=4)),
     ("ring", dict(T=1024, d_model=256, d_ff=512, E=64)),
     ("gpt", dict(T=130, E=4, k=4)),
+    ("ring", dict(d_ff=2048)),                      # 4096 tokens over 64 experts: ~128 rows per expert
 ]
 
 
