@@ -100,7 +100,8 @@ typedef struct {
   size_t expert_offsets; /* int32 [E+1]  first dispatched row of each expert    */
   size_t assign_to_row;  /* int32 [k*T]  row of assignment a=j*T+t, -1 dropped  */
   size_t row_to_assign;  /* int32 [k*T]  first R entries valid                  */
-  size_t xd;             /* dtype [R_max,d_model] dispatched rows               */
+  size_t xd;             /* dtype [R_max,d_model] dispatched rows (MOE_F32 only: the
+                            bf16 FFN gathers its rows from x through row_to_assign) */
   size_t h;              /* dtype [R_max,d_ff]    hidden activations            */
   size_t yd;             /* dtype [R_max,d_model] expert outputs                */
   size_t scratch;        /* dispatch bookkeeping scratch                        */

@@ -81,7 +81,7 @@ static void layout_of(const moe_config* c, moe_ws_layout* L) {
   L->xd = take(R * c->d_model * s);
   L->h = take(R * c->d_ff * s);
   L->yd = take(R * c->d_model * s);
-  L->scratch = take((size_t)dispatch_blocks(c) * c->E * 4 + 256);
+  L->scratch = take(((size_t)dispatch_blocks(c) + 1) * c->E * 4 + 256);
   L->total = off;
   L->r_max = (int64_t)R;
 }
@@ -134,7 +134,7 @@ size_t moe_workspace_bytes(const moe_config* cfg, int32_t kind) {
   layout_of(cfg, &L);
   switch (kind) {
     case MOE_WS_LAYER: return L.total;
-    case MOE_WS_DISPATCH: return align_up((size_t)dispatch_blocks(cfg) * cfg->E * 4 + 256, 256);
+    case MOE_WS_DISPATCH: return align_up(((size_t)dispatch_blocks(cfg) + 1) * cfg->E * 4 + 256, 256);
     case MOE_WS_FFN: return align_up((size_t)L.r_max * cfg->d_ff * elem_size(cfg->dtype), 256) + 256;
     default: fail(MOE_ERR_INVALID_ARG, "workspace kind %d unknown", kind); return 0;
   }

@@ -6,14 +6,18 @@
 // count ever travels to the host (the H2D/D2H round trips Section 3.3.1 sets
 // out to remove).
 //
-// Assignment a = j*T + t.  Three bookkeeping kernels and one copy kernel:
+// Assignment a = j*T + t.  Bookkeeping kernels and one copy kernel:
 //   count : per block of DISPATCH_BLOCK assignments, a per-expert histogram
-//   scan  : per expert, exclusive scan of the block histograms -> block bases,
-//           total counts, kept = min(count, C), expert_offsets
-//   assign: each block ranks its assignments per expert in order (wave ballots
-//           + cross-wave prefix), slot = block base + rank, row = offset + slot
-//           if slot < C else -1
-//   gather: one wavefront per token reads x[t] once and writes its <= k rows.
+//   scan  : per expert, exclusive scan of the block histograms -> block bases
+//           (only for many blocks; with few blocks every assign block sums the
+//           histograms before it by itself, which saves a launch)
+//   assign: totals -> counts, kept = min(count, C), expert_offsets; each block
+//           ranks its assignments per expert in order (wave ballots + cross-wave
+//           prefix), slot = block base + rank, row = offset + slot if slot < C
+//           else -1
+//   gather: one wavefront per token reads x[t] once and writes its <= k rows
+//           (skipped by moe_layer_forward, whose first GEMM gathers the rows
+//           from x by row_to_assign itself).
 // Everything is integer arithmetic or byte copies: results are bit-exact and
 // independent of scheduling (no atomics whose order could matter: the LDS
 // histogram atomics only add).
@@ -22,8 +26,9 @@
 namespace moesys {
 namespace {
 
-constexpr int BT = 256;                       // threads per bookkeeping block
-constexpr int ROUNDS = DISPATCH_BLOCK / BT;   // assignment rounds per block
+constexpr int BT = 256;  // threads per bookkeeping block = assignments per block
+static_assert(BT == DISPATCH_BLOCK, "one assignment per thread");
+constexpr int FUSED_SCAN_MAX_BLOCKS = 256;  // above this the block bases come from the scan kernel
 
 __device__ __forceinline__ int expert_of(const int32_t* topk_idx, int a, int T, int k) {
   const int j = a / T, t = a - j * T;
@@ -35,26 +40,19 @@ __global__ __launch_bounds__(BT) void dispatch_count_kernel(const int32_t* __res
   __shared__ int hist[MOE_MAX_EXPERTS];
   for (int e = threadIdx.x; e < E; e += BT) hist[e] = 0;
   __syncthreads();
-  const int A = T * k;
-  const int base = blockIdx.x * DISPATCH_BLOCK;
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int a = base + r * BT + threadIdx.x;
-    if (a < A) {
-      const int e = expert_of(topk_idx, a, T, k);
-      if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);  // an index outside 0..E-1 is ignored (dropped)
-    }
+  const int a = blockIdx.x * DISPATCH_BLOCK + threadIdx.x;
+  if (a < T * k) {
+    const int e = expert_of(topk_idx, a, T, k);
+    if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);  // an index outside 0..E-1 is ignored (dropped)
   }
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += BT) block_hist[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-// One block; thread e walks expert e's column of block_hist (coalesced across e).
+// One block; thread e walks expert e's column of block_hist (coalesced across e) and turns it into the
+// exclusive prefix; the totals go to the extra row block_hist[nblocks][.].
 __global__ __launch_bounds__(MOE_MAX_EXPERTS) void dispatch_scan_kernel(int32_t* __restrict__ block_hist,
-                                                                        int nblocks, int E, int C,
-                                                                        int32_t* __restrict__ counts,
-                                                                        int32_t* __restrict__ offsets) {
-  __shared__ int kept[MOE_MAX_EXPERTS];
+                                                                        int nblocks, int E) {
   const int e = threadIdx.x;
   if (e < E) {
     int run = 0;
@@ -63,79 +61,92 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void dispatch_scan_kernel(int32_t*
       block_hist[(size_t)b * E + e] = run;  // becomes the block's base slot
       run += h;
     }
-    counts[e] = run;
-    kept[e] = min(run, C);
-  }
-  __syncthreads();
-  if (e == 0) {
-    int off = 0;
-    for (int i = 0; i < E; ++i) {
-      offsets[i] = off;
-      off += kept[i];
-    }
-    offsets[E] = off;
+    block_hist[(size_t)nblocks * E + e] = run;
   }
 }
 
+// prefixed = true: block_hist holds exclusive prefixes and a totals row (scan kernel ran);
+// prefixed = false: block_hist holds raw histograms and every block sums what it needs itself.
 __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __restrict__ topk_idx, int T, int k,
-                                                             int E, int C, const int32_t* __restrict__ block_base,
-                                                             const int32_t* __restrict__ offsets,
+                                                             int E, int C, const int32_t* __restrict__ block_hist,
+                                                             int nblocks, int prefixed,
+                                                             int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
                                                              int32_t* __restrict__ a2r, int32_t* __restrict__ r2a) {
   constexpr int NW = BT / 64;
-  __shared__ int running[MOE_MAX_EXPERTS];       // slots already handed out in this block, per expert
-  __shared__ int wave_cnt[NW][MOE_MAX_EXPERTS];  // this round's per-wave counts
-  __shared__ int off_s[MOE_MAX_EXPERTS];
+  __shared__ int base_s[MOE_MAX_EXPERTS];        // slots of this expert handed out by earlier blocks
+  __shared__ int total_s[MOE_MAX_EXPERTS];       // assignments per expert before capacity
+  __shared__ int wave_cnt[NW][MOE_MAX_EXPERTS];  // per-wave counts of this block
+  __shared__ int off_s[MOE_MAX_EXPERTS + 1];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int e = threadIdx.x; e < E; e += BT) {
-    running[e] = block_base[(size_t)blockIdx.x * E + e];
-    off_s[e] = offsets[e];
+    base_s[e] = prefixed ? block_hist[(size_t)blockIdx.x * E + e] : 0;
+    total_s[e] = prefixed ? block_hist[(size_t)nblocks * E + e] : 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) wave_cnt[w][e] = 0;
   }
   __syncthreads();
-  const int A = T * k;
-  const int base = blockIdx.x * DISPATCH_BLOCK;
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int a = base + r * BT + threadIdx.x;
-    const int e_in = a < A ? expert_of(topk_idx, a, T, k) : -1;
-    const bool valid = (unsigned)e_in < (unsigned)E;
-    const int e = valid ? e_in : -1;
-    // rank among the wave's lanes with the same expert, in lane (= assignment) order
-    int rank = 0;
-    unsigned long long todo = __ballot(valid);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int e0 = __shfl(e, leader, 64);
-      const unsigned long long same = __ballot(e == e0);
-      if (e == e0) {
-        rank = __popcll(same & ((1ull << lane) - 1ull));
-        if (lane == leader) wave_cnt[wave][e0] = __popcll(same);
+  if (!prefixed) {
+    // integer adds: the sums do not depend on the order the LDS atomics land in
+    const int n = nblocks * E;
+    for (int i = threadIdx.x; i < n; i += BT) {
+      const int b = i / E, e = i - b * E;
+      const int h = block_hist[i];
+      if (h) {
+        atomicAdd(&total_s[e], h);
+        if (b < (int)blockIdx.x) atomicAdd(&base_s[e], h);
       }
-      todo &= ~same;
     }
     __syncthreads();
-    if (valid) {
-      int slot = running[e] + rank;
+  }
+  if (threadIdx.x == 0) {
+    int off = 0;
+    for (int e = 0; e < E; ++e) {
+      off_s[e] = off;
+      off += min(total_s[e], C);
+    }
+    off_s[E] = off;
+  }
+  const int a = blockIdx.x * DISPATCH_BLOCK + threadIdx.x;
+  const int e_in = a < T * k ? expert_of(topk_idx, a, T, k) : -1;
+  const bool valid = (unsigned)e_in < (unsigned)E;
+  const int e = valid ? e_in : -1;
+  // rank among the wave's lanes with the same expert, in lane (= assignment) order
+  int rank = 0;
+  unsigned long long todo = __ballot(valid);
+  while (todo) {
+    const int leader = __ffsll((long long)todo) - 1;
+    const int e0 = __shfl(e, leader, 64);
+    const unsigned long long same = __ballot(e == e0);
+    if (e == e0) {
+      rank = __popcll(same & ((1ull << lane) - 1ull));
+      if (lane == leader) wave_cnt[wave][e0] = __popcll(same);
+    }
+    todo &= ~same;
+  }
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i <= E; i += BT) {
+      offsets[i] = off_s[i];
+      if (i < E) counts[i] = total_s[i];
+    }
+  if (valid) {
+    int slot = base_s[e] + rank;
 #pragma unroll
-      for (int w = 0; w < NW; ++w)
-        if (w < wave) slot += wave_cnt[w][e];
-      const int row = slot < C ? off_s[e] + slot : -1;
-      a2r[a] = row;
-      if (row >= 0) r2a[row] = a;
-    } else if (a < A) {
-      a2r[a] = -1;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < E; i += BT) {
-      int add = 0;
-#pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        add += wave_cnt[w][i];
-        wave_cnt[w][i] = 0;
-      }
-      running[i] += add;
-    }
-    __syncthreads();
+    for (int w = 0; w < NW; ++w)
+      if (w < wave) slot += wave_cnt[w][e];
+    const int row = slot < C ? off_s[e] + slot : -1;
+    a2r[a] = row;
+    if (row >= 0) r2a[row] = a;
+  } else if (a < T * k) {
+    a2r[a] = -1;
+  }
+}
+
+// With no assignment at all the tables still have to say so.
+__global__ void dispatch_empty_kernel(int E, int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+  for (int i = threadIdx.x; i <= E; i += blockDim.x) {
+    offsets[i] = 0;
+    if (i < E) counts[i] = 0;
   }
 }
 
@@ -171,19 +182,21 @@ int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* top
   const int T = cfg->T, k = cfg->k, E = cfg->E;
   const int C = moe_capacity(cfg);
   const int nblocks = (int)dispatch_blocks(cfg);
-  int32_t* block_hist = (int32_t*)ws;
-  if (nblocks > 0)
-    hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist);
-  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E, C,
-                     counts, offsets);
-  if (nblocks > 0) {
-    hipLaunchKernelGGL(dispatch_assign_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist,
-                       offsets, a2r, r2a);
-    if (xd) {
-      const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
-      hipLaunchKernelGGL(dispatch_gather_kernel, dim3((T + 3) / 4), dim3(256), 0, s, (const uint4*)x, T, k,
-                         row_vec, a2r, (uint4*)xd);
-    }
+  int32_t* block_hist = (int32_t*)ws;  // [nblocks + 1][E]
+  if (nblocks == 0) {
+    hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, counts, offsets);
+    return check_hip(hipGetLastError(), "dispatch launch");
+  }
+  hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist);
+  const int prefixed = nblocks > FUSED_SCAN_MAX_BLOCKS;
+  if (prefixed)
+    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E);
+  hipLaunchKernelGGL(dispatch_assign_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist, nblocks,
+                     prefixed, counts, offsets, a2r, r2a);
+  if (xd) {
+    const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
+    hipLaunchKernelGGL(dispatch_gather_kernel, dim3((T + 3) / 4), dim3(256), 0, s, (const uint4*)x, T, k, row_vec, a2r,
+                       (uint4*)xd);
   }
   return check_hip(hipGetLastError(), "dispatch launch");
 }

@@ -8,7 +8,7 @@
 
 namespace moesys {
 
-int32_t launch_gemm1_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, hipStream_t);
+int32_t launch_gemm1_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, const int32_t*, hipStream_t);
 int32_t launch_gemm2_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, hipStream_t);
 
 namespace {
@@ -118,8 +118,9 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ sr
 }  // namespace
 
 int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets, void* h,
-                     hipStream_t s) {
-  if (cfg->dtype == MOE_BF16) return launch_gemm1_bf16(cfg, w, xd, offsets, h, s);
+                     const int32_t* row_map, hipStream_t s) {
+  if (cfg->dtype == MOE_BF16) return launch_gemm1_bf16(cfg, w, xd, offsets, h, row_map, s);
+  if (row_map) return fail(MOE_ERR_UNSUPPORTED, "float32 FFN reads dispatched rows only");
   if (cfg->act == MOE_ACT_SWIGLU)
     return launch_f32(cfg, F_SWIGLU, (const float*)xd, (const float*)w->w_gate_proj, (const float*)w->w_up, nullptr,
                       offsets, (float*)h, cfg->d_ff, cfg->d_model, w->layout, s);
@@ -150,7 +151,7 @@ extern "C" int32_t moe_expert_ffn(const moe_config* cfg, const moe_weights* w, c
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
     return fail(MOE_ERR_WORKSPACE, "moe_expert_ffn: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
   if (max_rows(cfg) > 0 && (!xd || !yd)) return fail(MOE_ERR_INVALID_ARG, "moe_expert_ffn: xd and yd must be non-NULL");
-  st = launch_gemm1(cfg, w, xd, expert_offsets, ws, (hipStream_t)stream);
+  st = launch_gemm1(cfg, w, xd, expert_offsets, ws, nullptr, (hipStream_t)stream);
   if (st != MOE_OK) return st;
   return launch_gemm2(cfg, w, ws, expert_offsets, yd, (hipStream_t)stream);
 }

@@ -175,7 +175,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // TOK x FEAT tile, WT x WF wavefronts, K-step KS, NST LDS stages; each wavefront owns (TOK/WT) tokens x
 // (FEAT/WF) LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
-template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int EPI, bool GATHER>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
@@ -183,7 +183,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ bias,    // [E, N] or NULL
     const int32_t* __restrict__ offsets,  // [E+1]
     uint16_t* __restrict__ out,           // [R, N]
-    int E, int N, int K) {
+    const int32_t* __restrict__ row_map,  // GATHER: row_to_assign; act is then x[T,K] and row r reads token row_map[r] mod T
+    int T, int E, int N, int K) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer descriptors are device-only types)
   constexpr int NW = WT * WF;
   constexpr int WTOK = TOK / WT, WFEAT = FEAT / WF;
@@ -227,13 +228,35 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   TileWalker<TOK> walk;
   walk.init(s_pref[E], n_tiles);
 
-  // ---- per-lane constants: offsets of every direct-to-LDS load, LDS fragment addresses ----------
+  // ---- per-lane offsets of every direct-to-LDS load, LDS fragment addresses ----------------------
+  // (with a row map the token-tile offsets are recomputed per tile from the gathered token indices)
   int a_voff[A_LOADS], b_voff[B_LOADS];
+  // byte offset of this lane's chunk inside its row, swizzle applied
+  auto a_chunk = [&](int i) {
+    const int r = (i * NW + wave) * RPI + lane / CHUNKS;
+    return ((lane % CHUNKS) ^ ((r / RPB) % CHUNKS)) << 4;
+  };
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i) {
     const int r = (i * NW + wave) * RPI + lane / CHUNKS;
-    a_voff[i] = r * (int)row_bytes + (((lane % CHUNKS) ^ ((r / RPB) % CHUNKS)) << 4);
+    a_voff[i] = r * (int)row_bytes + a_chunk(i);
   }
+  // token index of each of this lane's token-tile rows (-1 past the tile's last row)
+  auto fetch_rows = [&](const TileInfo& t, int (&tok)[GATHER ? A_LOADS : 1]) {
+#pragma unroll
+    for (int i = 0; i < (GATHER ? A_LOADS : 1); ++i) {
+      const int r = (i * NW + wave) * RPI + lane / CHUNKS;
+      tok[i] = r < t.rows ? row_map[t.row0 + r] : -1;
+    }
+  };
+  auto gather_voff = [&](const int (&tok)[GATHER ? A_LOADS : 1]) {
+#pragma unroll
+    for (int i = 0; i < (GATHER ? A_LOADS : 1); ++i) {
+      int t = tok[i];
+      while (t >= T) t -= T;  // assignment id j*T + t -> token (j < k <= 8)
+      a_voff[i] = t >= 0 ? t * (int)row_bytes + a_chunk(i) : 0x7fffffff;  // past the end of x: reads zero
+    }
+  };
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i) {
     const int r = (i * NW + wave) * RPI + lane / CHUNKS;
@@ -262,10 +285,10 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   const uint32_t b_bytes = (uint32_t)B_ROWS * row_bytes;
   auto bind_tile = [&](const TileInfo& t) {
     const size_t woff = ((size_t)t.expert * N + (size_t)t.ntile * OUT_FEAT) * K;
-    a_ptr = act + (size_t)t.row0 * K;
+    a_ptr = GATHER ? act : act + (size_t)t.row0 * K;
     b_ptr = wa + woff;
     b2_ptr = (EPI == EPI_SWIGLU ? wb : wa) + woff;
-    a_bytes = (uint32_t)t.rows * row_bytes;
+    a_bytes = (GATHER ? (uint32_t)T : (uint32_t)t.rows) * row_bytes;
   };
   // One instruction moves 64 lanes x 16 B = RPI rows of a tile; lane l lands at row l/CHUNKS, physical
   // chunk l%CHUNKS, and voff addresses the logical chunk that the swizzle maps there.  The K-step is
@@ -349,9 +372,14 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   };
 
   // ---- persistent loop over this workgroup's slots ------------------------------------------------
-  TileInfo ti;
+  TileInfo ti, nx;
+  int nx_tok[GATHER ? A_LOADS : 1];
   bool have = walk.next(offsets, E, s_pref, ti);
   if (!have) return;
+  if constexpr (GATHER) {
+    fetch_rows(ti, nx_tok);
+    gather_voff(nx_tok);
+  }
   bind_tile(ti);
   issue_prologue();
 
@@ -366,6 +394,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // Everything this wavefront has in flight (the tile's first stages; the previous tile's stores, which
     // do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // the next tile is known now; its gathered row indices travel while this tile is multiplied
+    const bool have_nx = walk.next(offsets, E, s_pref, nx);
+    if constexpr (GATHER) {
+      if (have_nx) fetch_rows(nx, nx_tok);
+    }
     read_frags(s0, s0 + A_BYTES, 0, af[0], wfr[0]);
     int kt = 0;
     if (NST == 2) {
@@ -388,7 +421,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 
     // ---- next tile: bind it and request its first stages before this tile's epilogue ---------------
     const TileInfo done = ti;
-    have = walk.next(offsets, E, s_pref, ti);
+    ti = nx;
+    have = have_nx;
+    if constexpr (GATHER) {
+      if (have) gather_voff(nx_tok);
+    }
     // every fragment read of real data finished before the last barrier; what the last sub-step read
     // afterwards is never used, so the stage buffers may be overwritten now
     if (have) {
@@ -449,7 +486,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 
 template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
-               const uint16_t* bias, const int32_t* offsets, uint16_t* out, int N, int K, hipStream_t s) {
+               const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map, int N, int K,
+               hipStream_t s) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
@@ -468,9 +506,15 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   // fewer when even the upper bound of the tile count cannot occupy every CU
   const int64_t per_xcd = ((blocks + NUM_XCD - 1) / NUM_XCD) * CU_PER_XCD;  // tiles one XCD may own
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, EPI>;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out,
-                     cfg->E, N, K);
+  // the gathering variant exists for the first GEMM's epilogues only
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, EPI, false>;
+  if constexpr (EPI != EPI_BIAS) {
+    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, EPI, true>;
+  } else {
+    if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out, row_map,
+                     cfg->T, cfg->E, N, K);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
@@ -509,29 +553,32 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
 // use narrow tiles.
 template <int EPI, int KSB, int NSB>
 int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
-                 const int32_t* offsets, uint16_t* o, int N, int K, hipStream_t s) {
+                 const int32_t* offsets, uint16_t* o, const int32_t* row_map, int N, int K, hipStream_t s) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
-    if (KSB == 64 && pick_tile_rows(cfg, N / BF) == 320)
-      return launch<320, 256, 2, 4, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, s);
-    return launch<256, 256, 2, 4, KSB, NSB, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, s);
+    // (the 320-row tile has no registers to spare for the row gather)
+    if (KSB == 64 && !row_map && pick_tile_rows(cfg, N / BF) == 320)
+      return launch<320, 256, 2, 4, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
+    return launch<256, 256, 2, 4, KSB, NSB, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, s);
+    return launch<128, 128, 2, 2, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
   else
-    return launch<128, 64, 4, 1, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, N, K, s);
+    return launch<128, 64, 4, 1, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
 }
 
 }  // namespace
 
+// row_map (nullable): row_to_assign; the token rows are then gathered from x[T, d_model] instead of read
+// from a dispatched copy.
 int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
-                          void* h, hipStream_t s) {
+                          void* h, const int32_t* row_map, hipStream_t s) {
   if (cfg->act == MOE_ACT_SWIGLU)
     return (deep_pipeline() ? gemm_any<EPI_SWIGLU, 32, 4> : gemm_any<EPI_SWIGLU, 64, 2>)(
         cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up, nullptr, offsets,
-        (uint16_t*)h, cfg->d_ff, cfg->d_model, s);
+        (uint16_t*)h, row_map, cfg->d_ff, cfg->d_model, s);
   return (deep_pipeline() ? gemm_any<EPI_GELU, 32, 4> : gemm_any<EPI_GELU, 64, 2>)(
-      cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets, (uint16_t*)h,
+      cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets, (uint16_t*)h, row_map,
       cfg->d_ff, cfg->d_model, s);
 }
 
@@ -540,7 +587,12 @@ int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const voi
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
   return (deep_pipeline() ? gemm_any<EPI_BIAS, 32, 4> : gemm_any<EPI_BIAS, 64, 2>)(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
-      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, cfg->d_model, cfg->d_ff, s);
+      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, cfg->d_model, cfg->d_ff, s);
+}
+
+// The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.
+bool gemm1_can_gather(const moe_config* cfg) {
+  return cfg->dtype == MOE_BF16 && (int64_t)cfg->T * cfg->d_model * 2 < ((int64_t)1 << 31);
 }
 
 }  // namespace moesys

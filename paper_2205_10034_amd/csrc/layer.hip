@@ -43,9 +43,11 @@ int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, c
   if ((st = mark(0)) != MOE_OK) return st;
   if ((st = launch_gate(cfg, x, w->w_router, w->b_router, topk_idx, topk_w, nullptr, s)) != MOE_OK) return st;
   if ((st = mark(1)) != MOE_OK) return st;
-  if ((st = launch_dispatch(cfg, x, topk_idx, counts, offsets, a2r, r2a, xd, scratch, s)) != MOE_OK) return st;
+  // bf16: the first GEMM gathers its rows from x through row_to_assign, so no dispatched copy is made
+  const bool gather = gemm1_can_gather(cfg);
+  if ((st = launch_dispatch(cfg, x, topk_idx, counts, offsets, a2r, r2a, gather ? nullptr : xd, scratch, s)) != MOE_OK) return st;
   if ((st = mark(2)) != MOE_OK) return st;
-  if ((st = launch_gemm1(cfg, w, xd, offsets, h, s)) != MOE_OK) return st;
+  if ((st = launch_gemm1(cfg, w, gather ? x : xd, offsets, h, gather ? r2a : nullptr, s)) != MOE_OK) return st;
   if ((st = mark(3)) != MOE_OK) return st;
   if ((st = launch_gemm2(cfg, w, h, offsets, yd, s)) != MOE_OK) return st;
   if ((st = mark(4)) != MOE_OK) return st;

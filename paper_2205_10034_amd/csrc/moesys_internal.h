@@ -18,7 +18,7 @@ inline size_t elem_size(int32_t dtype) { return dtype == MOE_BF16 ? 2 : 4; }
 int64_t max_rows(const moe_config* cfg);
 
 // Number of blocks of DISPATCH_BLOCK assignments the bookkeeping kernels use.
-constexpr int DISPATCH_BLOCK = 1024;
+constexpr int DISPATCH_BLOCK = 256;
 inline int64_t dispatch_blocks(const moe_config* cfg) {
   int64_t A = (int64_t)cfg->k * cfg->T;
   return (A + DISPATCH_BLOCK - 1) / DISPATCH_BLOCK;
@@ -29,8 +29,10 @@ int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s);
 int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx, int32_t* counts,
                         int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, hipStream_t s);
+// row_map (nullable, bf16 only): row_to_assign; xd is then x itself and the rows are gathered on the fly.
 int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
-                     void* h, hipStream_t s);
+                     void* h, const int32_t* row_map, hipStream_t s);
+bool gemm1_can_gather(const moe_config* cfg);
 int32_t launch_gemm2(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
                      void* yd, hipStream_t s);
 int32_t launch_combine(const moe_config* cfg, const void* yd, const int32_t* a2r, const float* topk_w,

@@ -215,7 +215,8 @@ def check_layer(wl, L, r, ref, tol):
     assert np.array_equal(r["expert_offsets"], ref["expert_offsets"])
     assert np.array_equal(r["assign_to_row"], ref["assign_to_row"])
     assert np.array_equal(r["row_to_assign"], ref["row_to_assign"])
-    assert np.array_equal(r["xd"], ref["xd"])
+    if wl.dtype == "f32":            # bf16: the first GEMM gathers rows from x itself, xd is not materialised
+        assert np.array_equal(r["xd"], ref["xd"])
 
 
 LAYER_CASES = [
@@ -289,7 +290,6 @@ def test_layer_forward_large_sampled():
     assert np.array_equal(r["assign_to_row"], a2r) and np.array_equal(r["row_to_assign"], r2a)
     assert (a2r < 0).any()                                   # capacity factor 1.0 drops some
     R = int(offsets[-1])
-    assert np.array_equal(r["xd"][::97], L["x"][r2a[::97] % wl.T])
     rng = np.random.default_rng(0)
     dropped_tok = np.nonzero((a2r[:wl.T] < 0) | (a2r[wl.T:] < 0))[0][:8]
     toks = np.unique(np.concatenate([rng.integers(0, wl.T, 40), dropped_tok, [0, wl.T - 1]]))
