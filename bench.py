@@ -24,6 +24,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel (grouped GEMM 1) from rocprofv3 FETCH_SIZE + WRITE_SIZE, both
+# scaled by 1.000 against the weight-transpose kernel of known size (profiles/layer_forward_gpt_hbm_traffic.txt);
+# a separate counter run, so it is a constant here and only quoted for the workload it was measured on.
+MEASURED_TRAFFIC_BYTES = {"gpt": (164009.0 + 135525.3) * 1024}
 
 
 def cpu_baseline(wl, L, budget_s=20.0):
@@ -106,7 +110,9 @@ def main():
     s = 2 if wl.dtype == "bf16" else 4
     hbm = {
         "gate": (wl.T * wl.d_model * s + 8 * wl.k * wl.T) / (stage_ms["gate"] * 1e-3) / 1e9,
-        "dispatch": ((wl.T + R) * wl.d_model * s + 12 * wl.k * wl.T) / (stage_ms["dispatch"] * 1e-3) / 1e9,
+        # bf16: routing tables only (12 B per assignment); the rows are gathered by the first GEMM
+        "dispatch": (((wl.T + R) * wl.d_model * s if wl.dtype != "bf16" else 0) + 12 * wl.k * wl.T)
+                    / (stage_ms["dispatch"] * 1e-3) / 1e9,
         "combine": ((R + wl.T) * wl.d_model * s + 8 * wl.k * wl.T) / (stage_ms["combine"] * 1e-3) / 1e9,
     }
     res = {
@@ -119,7 +125,8 @@ def main():
                    "kept_rows": R},
         "roofline": {"bound": "mfma", "kernel": f"grouped_gemm_kernel ({dom})", "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "flops_per_launch": dom_flops, "avg_launch_ms": stage_ms[dom]},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if dom == "gemm1" else None,
+                     "flops_per_launch": dom_flops, "avg_launch_ms": stage_ms[dom]},
         "stage_ms": stage_ms,
         "ffn_tflops": (flops1 + flops2) / ((stage_ms["gemm1"] + stage_ms["gemm2"]) * 1e-3) / 1e12,
         "hbm_gbs": hbm,
