@@ -30,6 +30,7 @@
 // the eight XCDs walk the same weight columns at the same time so that HBM
 // serves each weight tile once.
 #include <cstdlib>
+#include <type_traits>
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -323,52 +324,79 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 
   f32x16 acc[TB][FB];
   bf16x8 af[2][TB], wfr[2][FB];
-  auto read_frags = [&](const unsigned char* A, const unsigned char* B, int ks, bf16x8 (&a)[TB], bf16x8 (&w)[FB]) {
-#pragma unroll
-    for (int i = 0; i < TB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(A + (a_base[i] ^ (ks << 5)));
-#pragma unroll
-    for (int j = 0; j < FB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base[j] ^ (ks << 5)));
-  };
-  auto mfma_all = [&](const bf16x8 (&a)[TB], const bf16x8 (&w)[FB]) {
-#pragma unroll
-    for (int i = 0; i < TB; ++i)
-#pragma unroll
-      for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], a[i], acc[i][j], 0, 0, 0);
-  };
-  // Asks the scheduler to alternate one MFMA with one LDS read, then the remaining MFMAs.
-  auto interleave = [&]() {
-    constexpr int PAIRS = TB + FB < TB * FB ? TB + FB : TB * FB;
-#pragma unroll
-    for (int q = 0; q < PAIRS; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-    }
-    if (TB * FB > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, TB * FB - PAIRS, 0);
-  };
-
-  // One K-step on the stage in `cur`.  On entry fr[0] holds the fragments of sub-step 0 of that stage and
-  // the loads of the following NST-1 stages are in flight.  All sub-steps but the last multiply while the
-  // next sub-step's fragments are read; then every wavefront waits until its own share of the NEXT stage
-  // has landed (the younger NST-2 batches may stay in flight: loads retire in order) and until its
-  // fragment reads are done, and the workgroup meets at one barrier; the current stage's buffer is then
-  // refilled with stage kt+NST, and the last sub-step multiplies while sub-step 0 of the next stage is read.
+  // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
+  // hold at least one valid row (a partial tile - an expert's last rows - multiplies only those blocks;
+  // a wavefront with none still takes part in the loads and the barriers).
   constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS * (EPI == EPI_SWIGLU ? 2 : 1);
   constexpr int IN_FLIGHT = (NST - 2) * LOADS_PER_STAGE;  // loads allowed to be outstanding at the barrier
   static_assert(IN_FLIGHT < 64, "vmcnt is a 6-bit counter");
   // s_waitcnt immediate: vmcnt = IN_FLIGHT (bits 3:0 and 15:14), expcnt = 7 (no wait), lgkmcnt = 0
   constexpr int WAIT_IMM = (IN_FLIGHT & 15) | ((IN_FLIGHT >> 4) << 14) | (7 << 4);
-  auto step = [&](int kt, unsigned char* cur, unsigned char* nxt) {
+  auto run_tile = [&](auto tbv_tag) {
+    constexpr int TBV = decltype(tbv_tag)::value;
+    constexpr int NFB = TBV > 0 ? FB : 0;  // weight fragments are needed only if there is a token block
+    auto read_frags = [&](const unsigned char* A, const unsigned char* B, int ks, bf16x8 (&a)[TB], bf16x8 (&w)[FB]) {
 #pragma unroll
-    for (int ks = 0; ks + 1 < NSUB; ++ks) {
-      read_frags(cur, cur + A_BYTES, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
-      mfma_all(af[ks & 1], wfr[ks & 1]);
+      for (int i = 0; i < TBV; ++i) a[i] = *reinterpret_cast<const bf16x8*>(A + (a_base[i] ^ (ks << 5)));
+#pragma unroll
+      for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base[j] ^ (ks << 5)));
+    };
+    auto mfma_all = [&](const bf16x8 (&a)[TB], const bf16x8 (&w)[FB]) {
+#pragma unroll
+      for (int i = 0; i < TBV; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], a[i], acc[i][j], 0, 0, 0);
+    };
+    // Asks the scheduler to alternate one MFMA with one LDS read, then the remaining MFMAs.
+    auto interleave = [&]() {
+      constexpr int READS = TBV + NFB, MFMAS = TBV * FB;
+      constexpr int PAIRS = READS < MFMAS ? READS : MFMAS;
+#pragma unroll
+      for (int q = 0; q < PAIRS; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+      }
+      if (MFMAS > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - PAIRS, 0);
+    };
+    // One K-step on the stage in `cur`.  On entry fr[0] holds the fragments of sub-step 0 of that stage
+    // and the loads of the following NST-1 stages are in flight.  All sub-steps but the last multiply while
+    // the next sub-step's fragments are read; then every wavefront waits until its own share of the NEXT
+    // stage has landed (the younger NST-2 batches may stay in flight: loads retire in order) and until its
+    // fragment reads are done, and the workgroup meets at one barrier; the current stage's buffer is then
+    // refilled with stage kt+NST, and the last sub-step multiplies while sub-step 0 of the next stage is
+    // read.
+    auto step = [&](int kt, unsigned char* cur, unsigned char* nxt) {
+#pragma unroll
+      for (int ks = 0; ks + 1 < NSUB; ++ks) {
+        read_frags(cur, cur + A_BYTES, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
+        mfma_all(af[ks & 1], wfr[ks & 1]);
+        interleave();
+      }
+      asm volatile("s_waitcnt %0\n\ts_barrier" ::"n"(WAIT_IMM) : "memory");
+      issue_stage(kt + NST, kt + NST < KT, cur);
+      read_frags(nxt, nxt + A_BYTES, 0, af[0], wfr[0]);
+      mfma_all(af[(NSUB - 1) & 1], wfr[(NSUB - 1) & 1]);
       interleave();
+    };
+    read_frags(s0, s0 + A_BYTES, 0, af[0], wfr[0]);
+    int kt = 0;
+    if (NST == 2) {
+      for (; kt + 1 < KT; kt += 2) {
+        step(kt, s0, s1);
+        step(kt + 1, s1, s0);
+      }
+      if (kt < KT) step(kt, s0, s1);
+    } else {
+      for (; kt + 3 < KT; kt += 4) {
+        step(kt, s0, s1);
+        step(kt + 1, s1, s2);
+        step(kt + 2, s2, s3);
+        step(kt + 3, s3, s0);
+      }
+      if (kt < KT) step(kt, s0, s1);
+      if (kt + 1 < KT) step(kt + 1, s1, s2);
+      if (kt + 2 < KT) step(kt + 2, s2, s3);
     }
-    asm volatile("s_waitcnt %0\n\ts_barrier" ::"n"(WAIT_IMM) : "memory");
-    issue_stage(kt + NST, kt + NST < KT, cur);
-    read_frags(nxt, nxt + A_BYTES, 0, af[0], wfr[0]);
-    mfma_all(af[(NSUB - 1) & 1], wfr[(NSUB - 1) & 1]);
-    interleave();
   };
 
   // ---- persistent loop over this workgroup's slots ------------------------------------------------
@@ -399,24 +427,15 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     if constexpr (GATHER) {
       if (have_nx) fetch_rows(nx, nx_tok);
     }
-    read_frags(s0, s0 + A_BYTES, 0, af[0], wfr[0]);
-    int kt = 0;
-    if (NST == 2) {
-      for (; kt + 1 < KT; kt += 2) {
-        step(kt, s0, s1);
-        step(kt + 1, s1, s0);
-      }
-      if (kt < KT) step(kt, s0, s1);
-    } else {
-      for (; kt + 3 < KT; kt += 4) {
-        step(kt, s0, s1);
-        step(kt + 1, s1, s2);
-        step(kt + 2, s2, s3);
-        step(kt + 3, s3, s0);
-      }
-      if (kt < KT) step(kt, s0, s1);
-      if (kt + 1 < KT) step(kt + 1, s1, s2);
-      if (kt + 2 < KT) step(kt + 2, s2, s3);
+    // token blocks of this wavefront with at least one valid row (wave-uniform)
+    const int tbv = min(TB, max(0, (ti.rows - wt * WTOK + 31) / 32));
+    switch (tbv) {
+      case 0: run_tile(std::integral_constant<int, 0>{}); break;
+      case 1: run_tile(std::integral_constant<int, (1 < TB ? 1 : TB)>{}); break;
+      case 2: run_tile(std::integral_constant<int, (2 < TB ? 2 : TB)>{}); break;
+      case 3: run_tile(std::integral_constant<int, (3 < TB ? 3 : TB)>{}); break;
+      case 4: run_tile(std::integral_constant<int, (4 < TB ? 4 : TB)>{}); break;
+      default: run_tile(std::integral_constant<int, TB>{}); break;
     }
 
     // ---- next tile: bind it and request its first stages before this tile's epilogue ---------------
