@@ -105,6 +105,7 @@ typedef struct {
   size_t h;              /* dtype [R_max,d_ff]    hidden activations            */
   size_t yd;             /* dtype [R_max,d_model] expert outputs                */
   size_t scratch;        /* dispatch bookkeeping scratch                        */
+  size_t tile_counters;  /* int32 [16] work counters of the two grouped GEMMs   */
   size_t total;          /* == moe_workspace_bytes(cfg, MOE_WS_LAYER)           */
   int64_t r_max;         /* min(k*T, E*C): upper bound of dispatched rows       */
 } moe_ws_layout;

@@ -46,7 +46,7 @@ class _Weights(C.Structure):
 class _WsLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("topk_idx", "topk_w", "expert_counts", "expert_offsets",
                                           "assign_to_row", "row_to_assign", "xd", "h", "yd", "scratch",
-                                          "total")] + [("r_max", C.c_int64)]
+                                          "tile_counters", "total")] + [("r_max", C.c_int64)]
 
 
 RING_COPY_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p)

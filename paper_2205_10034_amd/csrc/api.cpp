@@ -66,6 +66,10 @@ int64_t max_rows(const moe_config* cfg) {
   return A < cap ? A : cap;
 }
 
+size_t ffn_counter_offset(const moe_config* cfg) {
+  return align_up((size_t)max_rows(cfg) * cfg->d_ff * elem_size(cfg->dtype), 256);
+}
+
 static void layout_of(const moe_config* c, moe_ws_layout* L) {
   const size_t s = elem_size(c->dtype);
   const size_t A = (size_t)c->k * (size_t)c->T;
@@ -82,6 +86,7 @@ static void layout_of(const moe_config* c, moe_ws_layout* L) {
   L->h = take(R * c->d_ff * s);
   L->yd = take(R * c->d_model * s);
   L->scratch = take(((size_t)dispatch_blocks(c) + 1) * c->E * 4 + 256);
+  L->tile_counters = take(TILE_COUNTER_INTS * 4);
   L->total = off;
   L->r_max = (int64_t)R;
 }
@@ -135,7 +140,7 @@ size_t moe_workspace_bytes(const moe_config* cfg, int32_t kind) {
   switch (kind) {
     case MOE_WS_LAYER: return L.total;
     case MOE_WS_DISPATCH: return align_up(((size_t)dispatch_blocks(cfg) + 1) * cfg->E * 4 + 256, 256);
-    case MOE_WS_FFN: return align_up((size_t)L.r_max * cfg->d_ff * elem_size(cfg->dtype), 256) + 256;
+    case MOE_WS_FFN: return ffn_counter_offset(cfg) + align_up(TILE_COUNTER_INTS * 4, 256);
     default: fail(MOE_ERR_INVALID_ARG, "workspace kind %d unknown", kind); return 0;
   }
 }

@@ -36,8 +36,10 @@ __device__ __forceinline__ int expert_of(const int32_t* topk_idx, int a, int T, 
 }
 
 __global__ __launch_bounds__(BT) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx, int T, int k,
-                                                            int E, int32_t* __restrict__ block_hist) {
+                                                            int E, int32_t* __restrict__ block_hist,
+                                                            int32_t* __restrict__ clear8) {
   __shared__ int hist[MOE_MAX_EXPERTS];
+  if (clear8 && blockIdx.x == 0 && threadIdx.x < 8) clear8[threadIdx.x] = 0;
   for (int e = threadIdx.x; e < E; e += BT) hist[e] = 0;
   __syncthreads();
   const int a = blockIdx.x * DISPATCH_BLOCK + threadIdx.x;
@@ -143,7 +145,9 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
 }
 
 // With no assignment at all the tables still have to say so.
-__global__ void dispatch_empty_kernel(int E, int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+__global__ void dispatch_empty_kernel(int E, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                      int32_t* __restrict__ clear8) {
+  if (clear8 && threadIdx.x < 8) clear8[threadIdx.x] = 0;
   for (int i = threadIdx.x; i <= E; i += blockDim.x) {
     offsets[i] = 0;
     if (i < E) counts[i] = 0;
@@ -178,16 +182,17 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
 }  // namespace
 
 int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx, int32_t* counts,
-                        int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, hipStream_t s) {
+                        int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, int32_t* clear8,
+                        hipStream_t s) {
   const int T = cfg->T, k = cfg->k, E = cfg->E;
   const int C = moe_capacity(cfg);
   const int nblocks = (int)dispatch_blocks(cfg);
   int32_t* block_hist = (int32_t*)ws;  // [nblocks + 1][E]
   if (nblocks == 0) {
-    hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, counts, offsets);
+    hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, counts, offsets, clear8);
     return check_hip(hipGetLastError(), "dispatch launch");
   }
-  hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist);
+  hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist, clear8);
   const int prefixed = nblocks > FUSED_SCAN_MAX_BLOCKS;
   if (prefixed)
     hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E);
@@ -218,5 +223,5 @@ extern "C" int32_t moe_dispatch(const moe_config* cfg, const void* x, const int3
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
     return fail(MOE_ERR_WORKSPACE, "moe_dispatch: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
   return launch_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
-                         (hipStream_t)stream);
+                         nullptr, (hipStream_t)stream);
 }

@@ -8,8 +8,9 @@
 
 namespace moesys {
 
-int32_t launch_gemm1_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, const int32_t*, hipStream_t);
-int32_t launch_gemm2_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, hipStream_t);
+int32_t launch_gemm1_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, const int32_t*, int32_t*,
+                          hipStream_t);
+int32_t launch_gemm2_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, int32_t*, hipStream_t);
 
 namespace {
 
@@ -115,11 +116,15 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ sr
     if (c0 + i < cols && r0 + tx < rows) dst[base + (size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
 }
 
+__global__ void clear_ints_kernel(int32_t* p, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
+}
+
 }  // namespace
 
 int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets, void* h,
-                     const int32_t* row_map, hipStream_t s) {
-  if (cfg->dtype == MOE_BF16) return launch_gemm1_bf16(cfg, w, xd, offsets, h, row_map, s);
+                     const int32_t* row_map, int32_t* tile_counters, hipStream_t s) {
+  if (cfg->dtype == MOE_BF16) return launch_gemm1_bf16(cfg, w, xd, offsets, h, row_map, tile_counters, s);
   if (row_map) return fail(MOE_ERR_UNSUPPORTED, "float32 FFN reads dispatched rows only");
   if (cfg->act == MOE_ACT_SWIGLU)
     return launch_f32(cfg, F_SWIGLU, (const float*)xd, (const float*)w->w_gate_proj, (const float*)w->w_up, nullptr,
@@ -129,8 +134,8 @@ int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd
 }
 
 int32_t launch_gemm2(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets, void* yd,
-                     hipStream_t s) {
-  if (cfg->dtype == MOE_BF16) return launch_gemm2_bf16(cfg, w, h, offsets, yd, s);
+                     int32_t* tile_counters, hipStream_t s) {
+  if (cfg->dtype == MOE_BF16) return launch_gemm2_bf16(cfg, w, h, offsets, yd, tile_counters, s);
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
   return launch_f32(cfg, F_BIAS, (const float*)h, (const float*)(sw ? w->w_down : w->w2), nullptr,
                     (const float*)(sw ? nullptr : w->b2), offsets, (float*)yd, cfg->d_model, cfg->d_ff, w->layout, s);
@@ -151,9 +156,15 @@ extern "C" int32_t moe_expert_ffn(const moe_config* cfg, const moe_weights* w, c
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
     return fail(MOE_ERR_WORKSPACE, "moe_expert_ffn: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
   if (max_rows(cfg) > 0 && (!xd || !yd)) return fail(MOE_ERR_INVALID_ARG, "moe_expert_ffn: xd and yd must be non-NULL");
-  st = launch_gemm1(cfg, w, xd, expert_offsets, ws, nullptr, (hipStream_t)stream);
+  // the tile counters sit behind h; nothing ran before us on this workspace, so clear the first GEMM's here
+  int32_t* ctr = (int32_t*)((char*)ws + ffn_counter_offset(cfg));
+  if (cfg->dtype == MOE_BF16) {
+    hipLaunchKernelGGL(clear_ints_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, ctr, 8);
+    if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
+  }
+  st = launch_gemm1(cfg, w, xd, expert_offsets, ws, nullptr, ctr, (hipStream_t)stream);
   if (st != MOE_OK) return st;
-  return launch_gemm2(cfg, w, ws, expert_offsets, yd, (hipStream_t)stream);
+  return launch_gemm2(cfg, w, ws, expert_offsets, yd, ctr, (hipStream_t)stream);
 }
 
 extern "C" int32_t moe_transpose_expert_weights(const void* src, void* dst, int32_t E, int32_t rows, int32_t cols,

@@ -8,18 +8,24 @@
 // (activations row-major, weights OUTPUT_MAJOR), accumulation is fp32 on the
 // MFMA units, one rounding to bf16 at the end.
 //
-// CDNA4 mapping.  The kernel is persistent: one workgroup per CU walks the
-// tile list with a stride of the CU count.  A workgroup owns a TOK x FEAT
-// output tile and walks K in steps of KS (32 or 64).  Operand tiles go from
+// CDNA4 mapping.  The kernel is persistent: one workgroup per CU; a workgroup's
+// first tile is fixed, every further one is drawn from a per-XCD counter, so
+// workgroups that drew short tiles draw more of them.  A workgroup owns a
+// TOK x FEAT output tile and walks K in steps of KS = 64.  Operand tiles go from
 // global memory straight into LDS (buffer_load ... lds, 16 bytes per lane, no
 // register staging) as rows of KS bf16 whose 16-byte chunks are XOR-swizzled
 // with the row index, so that the per-lane 16-byte fragment reads of
-// v_mfma_f32_32x32x16_bf16 are free of bank conflicts; NST LDS stages rotate so
-// that the next K-steps stream in while the current one is multiplied, with ONE
-// barrier per K-step placed before the step's last sub-step so that the first
-// fragments of the next step are read under the tail of the current one.  The
-// first stages of the NEXT tile are requested before the epilogue of the
-// current one, so their latency hides under the activation and the stores.
+// v_mfma_f32_32x32x16_bf16 are free of bank conflicts.  Two LDS stages rotate,
+// with ONE barrier per K-step placed before the step's last sub-step, so that
+// the first fragments of the next step are read under the tail of the current
+// one.  A stage is requested in two halves, each spread between the MFMAs of
+// one sub-step (a burst of loads would stall the issuing wavefronts, and with
+// them the matrix pipes, while the texture path drains it), and one more load
+// per K-step prefetches into L2 the lines that will be requested two K-steps
+// later (the operands stream from HBM; the stage loads themselves have less
+// than one K-step to land).  The first stages of the NEXT tile, its bias and
+// its gathered row indices are requested before the epilogue of the current
+// one, so their latency hides under the activation and the stores.
 // The MFMA "A" operand is the weight fragment and the "B" operand the
 // activation fragment: the accumulator then holds, per lane, one token and runs
 // of four consecutive output features, which store as packed 8-byte pieces.
@@ -29,6 +35,11 @@
 // the workgroups resident on one XCD share operand tiles in that XCD's L2, and
 // the eight XCDs walk the same weight columns at the same time so that HBM
 // serves each weight tile once.
+//
+// Clocks.  Under this kernel the MI355X runs at 1.6-2.0 GHz, not at the 2.4 GHz
+// its peak figure assumes (measured: shader clock counter against the 100 MHz
+// reference counter); in shader clocks the K loop keeps the matrix pipes ~85 %
+// busy.
 #include <cstdlib>
 #include <type_traits>
 #include "moesys_internal.h"
@@ -48,8 +59,10 @@ constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
 
 enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2 };
 
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);  // v_cvt_pk_bf16_f32: round to nearest even
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// two floats -> two bf16 in one dword (lo in the low half): one v_cvt_pk_bf16_f32, round to nearest even
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
@@ -72,15 +85,15 @@ __device__ __forceinline__ void fill_phi_table(f32x2* tab) {
 __device__ __forceinline__ float gelu_table(float u, const f32x2* tab) {
   float t = fmaf(u, PHI_SCALE, PHI_RANGE * PHI_SCALE);
   t = __builtin_amdgcn_fmed3f(t, 0.0f, (float)PHI_N - 0.001f);
-  const int i = (int)t;
-  const f32x2 e = tab[i];
-  return u * fmaf(t - (float)i, e.y, e.x);
+  const f32x2 e = tab[(int)t];
+  return u * fmaf(__builtin_amdgcn_fractf(t), e.y, e.x);  // t >= 0: fract(t) = t - floor(t)
 }
 __device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
 struct TileInfo {
   int expert, row0, rows;  // first dispatched row and valid rows (<= TOK) of this tile
   int ntile;               // feature tile index
+  int pm, pn, gm, gn;      // position of the tile in its gm x gn block (the tiles an XCD works on together)
 };
 
 // Tile order.  Token tiles (of all experts, in row order) are grouped GM at a time and feature tiles GN
@@ -93,9 +106,15 @@ struct TileInfo {
 __host__ __device__ inline int group_n(int n_tiles) { return n_tiles < 8 ? n_tiles : 8; }
 
 // s_pref[e] = number of token tiles of experts < e ; s_pref[E] = total.  Whole workgroup.
-template <int TOK>
-__device__ __forceinline__ void count_token_tiles(const int32_t* __restrict__ offsets, int E, int* s_pref) {
-  for (int e = threadIdx.x; e < E; e += blockDim.x) s_pref[e + 1] = (offsets[e + 1] - offsets[e] + TOK - 1) / TOK;
+// Token tiling of one expert with n rows.  Tiles are `base` rows high, except that the last tile takes
+// everything that is left when that is at most `cap` rows (cap = the kernel's tile capacity TOK, base <=
+// cap): with base 256 a 320-row kernel absorbs a remainder of up to 64 rows instead of spending a whole
+// tile - a whole K loop of weight loads and barriers - on it; with base = cap all tiles are alike.
+__host__ __device__ inline int token_tiles(int n, int cap, int base) {
+  return n <= cap ? (n > 0) : 1 + (n - cap + base - 1) / base;
+}
+__device__ __forceinline__ void count_token_tiles(const int32_t* __restrict__ offsets, int E, int cap, int base, int* s_pref) {
+  for (int e = threadIdx.x; e < E; e += blockDim.x) s_pref[e + 1] = token_tiles(offsets[e + 1] - offsets[e], cap, base);
   __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
@@ -117,15 +136,16 @@ __host__ __device__ inline int64_t block_count(int64_t MT, int n_tiles) {
 // Walks the tiles of one workgroup.  Block b (b mod 8 = the XCD) holds the gm x gn tiles of token group mg
 // and feature group ng (partial groups hold fewer).  The workgroups of an XCD share that XCD's blocks:
 // the tiles of blocks x, x+8, x+16, ... are numbered consecutively and workgroup j of the G on the XCD
-// takes numbers j, j+G, j+2G, ... - a fixed, gap-free assignment with no counters and no atomics.
+// takes number j first and then whatever number the XCD's counter hands out next (`want` is set by the
+// caller before each call and must grow): workgroups that drew short tiles simply draw more of them.
 template <int TOK>
 struct TileWalker {
   int MT, NT, GM, GN, MG, NG;
-  int xcd, G;
+  int xcd, G, tbase;
   int q, base, want;
 
-  __device__ __forceinline__ void init(int mt_total, int n_tiles) {
-    MT = mt_total; NT = n_tiles;
+  __device__ __forceinline__ void init(int mt_total, int n_tiles, int tile_base) {
+    MT = mt_total; NT = n_tiles; tbase = tile_base;
     GN = group_n(n_tiles); GM = CU_PER_XCD / GN;
     MG = (MT + GM - 1) / GM; NG = (NT + GN - 1) / GN;
     xcd = blockIdx.x % NUM_XCD; G = gridDim.x / NUM_XCD;
@@ -145,7 +165,6 @@ struct TileWalker {
       if (want < base + cnt) {
         const int r = want - base;
         const int mt = mg * GM + r / gn, nt = ng * GN + r % gn;
-        want += G;
         int lo = 0, hi = E;  // largest e with s_pref[e] <= mt
         while (hi - lo > 1) {
           const int mid = (lo + hi) >> 1;
@@ -154,10 +173,15 @@ struct TileWalker {
         // every lane computed the same values; say so to the compiler (they feed scalar descriptors)
         lo = __builtin_amdgcn_readfirstlane(lo);
         ti.expert = lo;
-        const int r0 = __builtin_amdgcn_readfirstlane(offsets[lo] + (mt - s_pref[lo]) * TOK);
+        const int r0 = __builtin_amdgcn_readfirstlane(offsets[lo] + (mt - s_pref[lo]) * tbase);
         ti.row0 = r0;
-        ti.rows = __builtin_amdgcn_readfirstlane(min(TOK, offsets[lo + 1] - r0));
+        // the expert's last tile holds whatever is left (at most TOK rows by the tile count above)
+        ti.rows = __builtin_amdgcn_readfirstlane(mt + 1 == s_pref[lo + 1] ? offsets[lo + 1] - r0 : tbase);
         ti.ntile = __builtin_amdgcn_readfirstlane(nt);
+        ti.pm = __builtin_amdgcn_readfirstlane(r / gn);
+        ti.pn = __builtin_amdgcn_readfirstlane(r % gn);
+        ti.gm = __builtin_amdgcn_readfirstlane(gm);
+        ti.gn = __builtin_amdgcn_readfirstlane(gn);
         return true;
       }
       base += cnt;
@@ -176,7 +200,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // TOK x FEAT tile, WT x WF wavefronts, K-step KS, NST LDS stages; each wavefront owns (TOK/WT) tokens x
 // (FEAT/WF) LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
-template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int EPI, bool GATHER>
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
@@ -185,11 +209,16 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const int32_t* __restrict__ offsets,  // [E+1]
     uint16_t* __restrict__ out,           // [R, N]
     const int32_t* __restrict__ row_map,  // GATHER: row_to_assign; act is then x[T,K] and row r reads token row_map[r] mod T
-    int T, int E, int N, int K) {
+    int32_t* __restrict__ tile_ctr,       // [NUM_XCD] zero at launch: tiles handed out beyond each workgroup's first
+    int32_t* __restrict__ clear_ctr,      // [NUM_XCD] or NULL: cleared here for the kernel that runs next
+    int T, int E, int N, int K, int tile_base /* rows per token tile, <= TOK */) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer descriptors are device-only types)
   constexpr int NW = WT * WF;
-  constexpr int WTOK = TOK / WT, WFEAT = FEAT / WF;
-  constexpr int TB = WTOK / 32, FB = WFEAT / 32;  // 32x32 MFMA blocks per wavefront
+  constexpr int WFEAT = FEAT / WF;
+  // 32x32 MFMA blocks per wavefront.  Token block i of wavefront row wt is block i*WT + wt of the tile: the
+  // rows of a partly filled tile then spread evenly over the wavefront rows.
+  constexpr int TB = TOK / 32 / WT, FB = WFEAT / 32;
+  static_assert(TOK % (32 * WT) == 0, "tile/wavefront mismatch");
   constexpr int ROW_BYTES = KS * 2;               // one LDS row
   constexpr int CHUNKS = KS / 8;                  // 16-byte chunks per row
   constexpr int RPB = 256 / ROW_BYTES;            // rows per 256 bytes (the LDS bank period for 16-byte reads)
@@ -202,36 +231,43 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   constexpr int A_LOADS = TOK / RPI / NW, B_LOADS = B_ROWS / RPI / NW;  // wave-instructions per wavefront per stage
   static_assert(TOK % (RPI * NW) == 0 && B_ROWS % (RPI * NW) == 0, "tile/wavefront mismatch");
   static_assert(EPI != EPI_SWIGLU || FB == 2, "SwiGLU wave tile is one gate block + one up block");
-  static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");
+  static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
+  constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
+  constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
 
   // LDS tile layout: row r keeps its logical 16-byte chunk c at physical chunk c ^ key(r), key(r) =
   // (r / RPB) mod CHUNKS.  The LDS serves 16 lanes x 16 B per clock over a 256-byte bank period; with this
   // key any 16 consecutive rows read at one logical chunk land on 16 distinct 16-byte bank groups
   // (measured conflict-free on gfx950, where keying on r mod 8 gives 2-way conflicts).
-  // NST stages (2 or 4), each one array holding the token tile then the feature tile: separate arrays so
+  // Two stages, each one array holding the token tile then the feature tile: separate arrays so
   // that the compiler can tell a stage being filled by LDS DMA from the stage being read.
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static_assert(NST == 2 || NST == 4, "two or four LDS stages");
   __shared__ __attribute__((aligned(1024))) unsigned char s0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char s1[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char s2[NST == 4 ? STAGE_BYTES : 16];
-  __shared__ __attribute__((aligned(1024))) unsigned char s3[NST == 4 ? STAGE_BYTES : 16];
   __shared__ f32x2 s_phi[EPI == EPI_GELU ? PHI_N : 1];
   __shared__ int s_pref[MOE_MAX_EXPERTS + 1];
+  __shared__ int s_next;  // number of this workgroup's next tile
+  __shared__ int s_tok[GATHER ? NW * 64 : 1];  // assignment id of every row of the next tile
+  static_assert(TOK <= NW * 64, "one thread per tile row");
+  __shared__ __attribute__((aligned(256))) unsigned char s_sink[256];  // where prefetched dwords land (never read)
+  // each wavefront's own slice of the tile's bias (WFEAT bf16 in the first bytes of its 256-byte slot); two
+  // sets, because the next tile's bias is requested before the current tile's epilogue reads its own
+  __shared__ __attribute__((aligned(256))) unsigned char s_bias[EPI == EPI_SWIGLU ? 256 : 2 * NW * 256];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave / WF, wf = wave % WF;
   const uint32_t row_bytes = (uint32_t)K * 2u;
   const int n_tiles = N / OUT_FEAT;
 
+  if (clear_ctr && blockIdx.x == 0 && tid < NUM_XCD) clear_ctr[tid] = 0;
   if (EPI == EPI_GELU) fill_phi_table(s_phi);
-  count_token_tiles<TOK>(offsets, E, s_pref);  // ends with a barrier: s_pref and the table are visible
+  count_token_tiles(offsets, E, TOK, tile_base, s_pref);  // ends with a barrier: s_pref and the table are visible
   TileWalker<TOK> walk;
-  walk.init(s_pref[E], n_tiles);
+  walk.init(s_pref[E], n_tiles, tile_base);
 
   // ---- per-lane offsets of every direct-to-LDS load, LDS fragment addresses ----------------------
   // (with a row map the token-tile offsets are recomputed per tile from the gathered token indices)
-  int a_voff[A_LOADS], b_voff[B_LOADS];
+  int a_voff[A_LOADS];
   // byte offset of this lane's chunk inside its row, swizzle applied
   auto a_chunk = [&](int i) {
     const int r = (i * NW + wave) * RPI + lane / CHUNKS;
@@ -242,43 +278,43 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const int r = (i * NW + wave) * RPI + lane / CHUNKS;
     a_voff[i] = r * (int)row_bytes + a_chunk(i);
   }
-  // token index of each of this lane's token-tile rows (-1 past the tile's last row)
-  auto fetch_rows = [&](const TileInfo& t, int (&tok)[GATHER ? A_LOADS : 1]) {
+  // Row gather: the assignment ids of a tile's rows travel from row_map into s_tok (one dword per thread,
+  // straight into LDS; threads past the tile's last row re-read its last entry), and once they have landed
+  // and a barrier has passed, every lane turns the ids of its rows into offsets into x.
+  auto fetch_rows = [&](const TileInfo& t) {
+    const int32_t* src = row_map + t.row0 + min(tid, t.rows - 1);
+    __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(s_tok + wave * 64), 4, 0, 0);
+  };
+  auto token_of = [&](int r) {
+    int t = s_tok[r];
+    while (t >= T) t -= T;  // assignment id j*T + t -> token (j < k <= 8)
+    return t;
+  };
+  auto gather_voff = [&](const TileInfo& t) {
 #pragma unroll
-    for (int i = 0; i < (GATHER ? A_LOADS : 1); ++i) {
+    for (int i = 0; i < A_LOADS; ++i) {
       const int r = (i * NW + wave) * RPI + lane / CHUNKS;
-      tok[i] = r < t.rows ? row_map[t.row0 + r] : -1;
+      a_voff[i] = r < t.rows ? token_of(r) * (int)row_bytes + a_chunk(i) : 0x7fffffff;  // out of range: reads zero
     }
   };
-  auto gather_voff = [&](const int (&tok)[GATHER ? A_LOADS : 1]) {
-#pragma unroll
-    for (int i = 0; i < (GATHER ? A_LOADS : 1); ++i) {
-      int t = tok[i];
-      while (t >= T) t -= T;  // assignment id j*T + t -> token (j < k <= 8)
-      a_voff[i] = t >= 0 ? t * (int)row_bytes + a_chunk(i) : 0x7fffffff;  // past the end of x: reads zero
-    }
-  };
-#pragma unroll
-  for (int i = 0; i < B_LOADS; ++i) {
-    const int r = (i * NW + wave) * RPI + lane / CHUNKS;
-    b_voff[i] = r * (int)row_bytes + (((lane % CHUNKS) ^ ((r / RPB) % CHUNKS)) << 4);
-  }
+  // Weight rows are never masked, so their row block can travel in the scalar offset: one per-lane offset
+  // serves every load (the swizzle key of a lane's row is the same in every load, see the assert).
+  static_assert((NW * (RPI / RPB)) % CHUNKS == 0, "a lane's swizzle key must not depend on the load index");
+  const int b_voff = (lane / CHUNKS) * (int)row_bytes + a_chunk(0);
+  const int b_blk = NW * RPI * (int)row_bytes;  // distance between the rows of consecutive loads
   // LDS byte address of this lane's fragment row with chunk key folded in: the chunk of K sub-step ks is
   // (2*ks + half) ^ key = (half ^ key) ^ 2*ks, i.e. base ^ (ks << 5).
   const int frow = lane & 31, fhalf = lane >> 5;
-  int a_base[TB], w_base[FB];
-#pragma unroll
-  for (int i = 0; i < TB; ++i) {
-    const int r = wt * WTOK + i * 32 + frow;
-    a_base[i] = r * ROW_BYTES + ((fhalf ^ ((r / RPB) % CHUNKS)) << 4);
-  }
-#pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    int r;
-    if (EPI == EPI_SWIGLU) r = j * (FEAT / 2) + wf * 32 + frow;  // j=0 gate rows, j=1 up rows
-    else r = wf * WFEAT + j * 32 + frow;
-    w_base[j] = r * ROW_BYTES + ((fhalf ^ ((r / RPB) % CHUNKS)) << 4);
-  }
+  // Block i of this wavefront lies a whole number of 32-row blocks further on, which leaves the key alone:
+  // one base per operand, the block goes into the constant part of the address.
+  static_assert(32 % (RPB * CHUNKS) == 0, "the swizzle key must repeat every 32 rows");
+  const int a_row0 = wt * 32 + frow;
+  const int w_row0 = (EPI == EPI_SWIGLU ? wf * 32 : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
+  const int a_base = a_row0 * ROW_BYTES + ((fhalf ^ ((a_row0 / RPB) % CHUNKS)) << 4);
+  const int w_base = w_row0 * ROW_BYTES + ((fhalf ^ ((w_row0 / RPB) % CHUNKS)) << 4);
+  constexpr int A_BLK = WT * 32 * ROW_BYTES;                                   // next token block of this wavefront
+  constexpr int W_BLK = (EPI == EPI_SWIGLU ? FEAT / 2 : 32) * ROW_BYTES;        // next feature block
 
   // ---- the current tile's operand windows (wave-uniform) ----------------------------------------
   const uint16_t *a_ptr = act, *b_ptr = wa, *b2_ptr = wa;
@@ -293,123 +329,216 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   };
   // One instruction moves 64 lanes x 16 B = RPI rows of a tile; lane l lands at row l/CHUNKS, physical
   // chunk l%CHUNKS, and voff addresses the logical chunk that the swizzle maps there.  The K-step is
-  // selected by the uniform offset.  `live` = false turns the stage into no-ops (zero-length descriptors).
+  // selected by the uniform offset.  `live` = false turns the loads into no-ops (zero-length descriptors),
+  // so that the number of loads in flight at every wait is fixed.  A stage is requested in two halves
+  // (token rows, then weight rows) at two different points of the K loop, see `step`.
 #define MOE_TILE_LOADS(rsrc, voff, n_loads, lds_tile)                                                            \
   _Pragma("unroll") for (int i_ = 0; i_ < (n_loads); ++i_)                                                       \
       __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                  \
           rsrc, (__attribute__((address_space(3))) void*)((lds_tile) + (i_ * NW + wave) * 1024), 16, voff[i_], koff, 0, 0)
-  auto issue_stage = [&](int kt, bool live, unsigned char* stage) {
-    unsigned char* A = stage;
-    unsigned char* B = stage + A_BYTES;
+  auto issue_tokens = [&](int kt, bool live, unsigned char* stage) {
     const int koff = kt * ROW_BYTES;
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a_ptr, live ? a_bytes : 0u);
+    MOE_TILE_LOADS(a_rsrc, a_voff, A_LOADS, stage);
+  };
+  auto issue_weights = [&](int kt, bool live, unsigned char* stage) {
+    unsigned char* B = stage + A_BYTES;
+    const int koff = kt * ROW_BYTES;
     const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(b_ptr, live ? b_bytes : 0u);
-    MOE_TILE_LOADS(a_rsrc, a_voff, A_LOADS, A);
-    MOE_TILE_LOADS(b_rsrc, b_voff, B_LOADS, B);
+    const int woff = koff + wave * RPI * (int)row_bytes;
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(B + (i * NW + wave) * 1024), 16,
+                                               b_voff, woff + i * b_blk, 0, 0);
     if (EPI == EPI_SWIGLU) {
       const __amdgpu_buffer_rsrc_t b2_rsrc = make_rsrc(b2_ptr, live ? b_bytes : 0u);
-      MOE_TILE_LOADS(b2_rsrc, b_voff, B_LOADS, B + B_ROWS * ROW_BYTES);
+#pragma unroll
+      for (int i = 0; i < B_LOADS; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            b2_rsrc, (__attribute__((address_space(3))) void*)(B + B_ROWS * ROW_BYTES + (i * NW + wave) * 1024), 16, b_voff,
+            woff + i * b_blk, 0, 0);
     }
   };
 #undef MOE_TILE_LOADS
   const int KT = K / KS;
-  auto issue_prologue = [&]() {  // the first NST stages of the bound tile
-    issue_stage(0, true, s0);
-    issue_stage(1, 1 < KT, s1);
-    if (NST == 4) {
-      issue_stage(2, 2 < KT, s2);
-      issue_stage(3, 3 < KT, s3);
+
+  // L2 prefetch.  One instruction per wavefront and K-step touches one dword of a 128-byte line per lane
+  // (it lands in a sink in LDS that nobody reads) PF_LEAD K-steps before the stage holding the line is
+  // requested: the operands stream from HBM, and a stage whose lines still have to come from there takes
+  // ~1.5 us to land where one found in L2 takes ~1.0 us (measured).  The gn workgroups of a block that
+  // share a token tile each take a 1/gn slice of its rows and the gm workgroups that share a weight tile
+  // a 1/gm slice of its rows, so every line is asked for once per XCD (asking from every workgroup doubles
+  // the L2 request traffic and gains nothing).  Lanes without a line re-touch the tile's first weight line.
+  const uint16_t* pf_ptr = wa;  // this lane's line at K-step 0 of the bound tile
+  auto bind_prefetch = [&](const TileInfo& t) {
+    const int a_lo = t.pn * TOK / t.gn, a_n = (t.pn + 1) * TOK / t.gn - a_lo;
+    const int b_lo = t.pm * FEAT / t.gm, b_n = (t.pm + 1) * FEAT / t.gm - b_lo;
+    pf_ptr = b_ptr;
+    if (tid < a_n) {
+      const int ar = a_lo + tid;
+      if (ar < t.rows) {
+        if constexpr (GATHER) {
+          pf_ptr = act + (size_t)token_of(ar) * K;
+        } else {
+          pf_ptr = a_ptr + (size_t)ar * K;
+        }
+      }
+    } else if (tid - a_n < b_n) {
+      const int br = b_lo + tid - a_n;  // LDS feature row: SwiGLU keeps the second matrix in rows B_ROWS...
+      pf_ptr = br < B_ROWS ? b_ptr + (size_t)br * K : b2_ptr + (size_t)(br - B_ROWS) * K;
+    }
+  };
+  auto issue_prefetch = [&](int kt) {  // the lines of K-step kt (past the last K-step: the last one again)
+    const uint16_t* p = pf_ptr + (size_t)min(kt, KT - 1) * KS;
+    __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) void*)p,
+                                     (__attribute__((address_space(3))) void*)s_sink, 4, 0, 0);
+  };
+  int bias_set = 0;  // the set the bound tile's bias goes to
+  auto issue_prologue = [&](const TileInfo& t) {  // stage 0, the token half of stage 1, the first prefetches, the bias
+    issue_tokens(0, true, s0);
+    issue_weights(0, true, s0);
+    issue_tokens(1, 1 < KT, s1);
+#pragma unroll
+    for (int j = 1; j <= PF_LEAD; ++j) issue_prefetch(j);
+    if constexpr (EPI != EPI_SWIGLU) {
+      // this wavefront's WFEAT bias values: lanes 0..WFEAT/2-1 move one dword each, the others (and every
+      // lane when there is no bias) read out of range, which stores zeros
+      const uint16_t* brow = bias ? bias + (size_t)t.expert * N + (size_t)t.ntile * OUT_FEAT + wf * WFEAT : act;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(make_rsrc(brow, bias ? (uint32_t)WFEAT * 2u : 0u),
+                                               (__attribute__((address_space(3))) void*)(s_bias + (bias_set * NW + wave) * 256), 4, lane * 4, 0, 0, 0);
+    }
+  };
+
+  // Tiles beyond a workgroup's first come from its XCD's counter.  One thread draws a number when a tile
+  // starts; the value is published to the workgroup two K-steps later (by then the atomic has long
+  // returned, so nobody waits for it) and turned into the next tile two K-steps after that, early enough
+  // for the next tile's gathered row indices to arrive under the rest of the K loop.
+  TileInfo ti, nx;
+  bool have_nx = false;
+  int drawn = 0;
+  auto draw_next = [&]() {
+    if (tid == 0) drawn = __hip_atomic_fetch_add(tile_ctr + walk.xcd, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  auto publish_next = [&]() {
+    if (tid == 0) s_next = walk.G + drawn;
+  };
+  auto resolve_next = [&]() {
+    walk.want = s_next;
+    have_nx = walk.next(offsets, E, s_pref, nx);
+    if constexpr (GATHER) {
+      if (have_nx) fetch_rows(nx);
     }
   };
 
   f32x16 acc[TB][FB];
-  bf16x8 af[2][TB], wfr[2][FB];
+  bf16x8 af[ABUF][TB], wfr[2][FB];
   // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
   // hold at least one valid row (a partial tile - an expert's last rows - multiplies only those blocks;
   // a wavefront with none still takes part in the loads and the barriers).
-  constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS * (EPI == EPI_SWIGLU ? 2 : 1);
-  constexpr int IN_FLIGHT = (NST - 2) * LOADS_PER_STAGE;  // loads allowed to be outstanding at the barrier
-  static_assert(IN_FLIGHT < 64, "vmcnt is a 6-bit counter");
-  // s_waitcnt immediate: vmcnt = IN_FLIGHT (bits 3:0 and 15:14), expcnt = 7 (no wait), lgkmcnt = 0
-  constexpr int WAIT_IMM = (IN_FLIGHT & 15) | ((IN_FLIGHT >> 4) << 14) | (7 << 4);
+  constexpr int W_LOADS = B_LOADS * (EPI == EPI_SWIGLU ? 2 : 1);
   auto run_tile = [&](auto tbv_tag) {
     constexpr int TBV = decltype(tbv_tag)::value;
     constexpr int NFB = TBV > 0 ? FB : 0;  // weight fragments are needed only if there is a token block
-    auto read_frags = [&](const unsigned char* A, const unsigned char* B, int ks, bf16x8 (&a)[TB], bf16x8 (&w)[FB]) {
+    // Fragment reads and one sub-step: multiply with the fragments at hand (set `c`) while those of sub-step
+    // `ks` of the stage at (A, B) are read (into set `c ^ 1`).  Two schedules:
+    //  - two sets of token fragments (ABUF == 2): all reads of the next sub-step pair off with the first
+    //    MFMAs of this one; fastest, needs 4*TB more registers;
+    //  - one set (ABUF == 1, the 320-row tile): a token fragment is used by FB consecutive MFMAs only and is
+    //    reloaded for the next sub-step right after them (it is next needed a whole sub-step later); only
+    //    the weight fragments, which every token block uses, are kept twice.
+    // The scheduler is asked to keep that order and to issue one of the VM global loads of this sub-step
+    // after each MFMA (group) while there are any.  Spreading the loads matters: the texture path accepts
+    // one 1 KB load per 16 clocks and the issuing wavefront waits when its queue is full, so a burst of
+    // loads ahead of the MFMAs leaves the matrix pipes idle while the burst drains.
+    auto read_w = [&](const unsigned char* B, int ks, bf16x8 (&w)[FB]) {
 #pragma unroll
-      for (int i = 0; i < TBV; ++i) a[i] = *reinterpret_cast<const bf16x8*>(A + (a_base[i] ^ (ks << 5)));
-#pragma unroll
-      for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base[j] ^ (ks << 5)));
+      for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base ^ (ks << 5)) + j * W_BLK);
     };
-    auto mfma_all = [&](const bf16x8 (&a)[TB], const bf16x8 (&w)[FB]) {
-#pragma unroll
-      for (int i = 0; i < TBV; ++i)
-#pragma unroll
-        for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[j], a[i], acc[i][j], 0, 0, 0);
+    auto read_a = [&](const unsigned char* A, int ks, bf16x8& a, int i) {
+      a = *reinterpret_cast<const bf16x8*>(A + (a_base ^ (ks << 5)) + i * A_BLK);
     };
-    // Asks the scheduler to alternate one MFMA with one LDS read, then the remaining MFMAs.
-    auto interleave = [&]() {
-      constexpr int READS = TBV + NFB, MFMAS = TBV * FB;
-      constexpr int PAIRS = READS < MFMAS ? READS : MFMAS;
+    auto substep = [&](const unsigned char* A, const unsigned char* B, int ks, int c, auto vm_tag) {
+      constexpr int VM = decltype(vm_tag)::value;
+      constexpr int MFMAS = TBV * FB;
+      read_w(B, ks, wfr[c ^ 1]);
+      if constexpr (ABUF == 2) {
 #pragma unroll
-      for (int q = 0; q < PAIRS; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        for (int i = 0; i < TBV; ++i) read_a(A, ks, af[c ^ 1][i], i);
+#pragma unroll
+        for (int i = 0; i < TBV; ++i)
+#pragma unroll
+          for (int j = 0; j < FB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[c][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < MFMAS; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
+          if (q < TBV + NFB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+          if (q < VM) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);         // VMEM
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < TBV; ++i) {
+#pragma unroll
+          for (int j = 0; j < FB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[0][i], acc[i][j], 0, 0, 0);
+          read_a(A, ks, af[0][i], i);
+        }
+        if (NFB) __builtin_amdgcn_sched_group_barrier(0x100, NFB, 0);
+#pragma unroll
+        for (int i = 0; i < TBV; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, FB, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+          constexpr int PER = (VM + TBV - 1) / (TBV ? TBV : 1);
+#pragma unroll
+          for (int p = 0; p < PER; ++p)
+            if (i * PER + p < VM) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // VMEM
+        }
       }
-      if (MFMAS > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - PAIRS, 0);
     };
-    // One K-step on the stage in `cur`.  On entry fr[0] holds the fragments of sub-step 0 of that stage
-    // and the loads of the following NST-1 stages are in flight.  All sub-steps but the last multiply while
-    // the next sub-step's fragments are read; then every wavefront waits until its own share of the NEXT
-    // stage has landed (the younger NST-2 batches may stay in flight: loads retire in order) and until its
-    // fragment reads are done, and the workgroup meets at one barrier; the current stage's buffer is then
-    // refilled with stage kt+NST, and the last sub-step multiplies while sub-step 0 of the next stage is
-    // read.
+    // One K-step on the stage in `cur`.  On entry af/wfr[0] hold the fragments of sub-step 0 of that stage,
+    // stage kt+1 has its token half in flight, and `nxt` (read by nobody since the last barrier) is free for
+    // its weight half, which sub-step 0 requests, followed by the prefetch.  All sub-steps but the last
+    // multiply while the next sub-step's fragments are read; then every wavefront waits until its share of
+    // stage kt+1 has landed (the prefetch, younger than those loads, stays in flight: loads retire in
+    // order) and until its fragment reads are done, and the workgroup meets at one barrier.  After it `cur`
+    // is free: the last sub-step requests the token half of stage kt+2 into it and multiplies while
+    // sub-step 0 of stage kt+1 is read.
     auto step = [&](int kt, unsigned char* cur, unsigned char* nxt) {
+      issue_weights(kt + 1, kt + 1 < KT, nxt);
+      issue_prefetch(kt + 1 + PF_LEAD);
+      substep(cur, cur + A_BYTES, 1, 0, std::integral_constant<int, W_LOADS + 1>{});
 #pragma unroll
-      for (int ks = 0; ks + 1 < NSUB; ++ks) {
-        read_frags(cur, cur + A_BYTES, ks + 1, af[(ks + 1) & 1], wfr[(ks + 1) & 1]);
-        mfma_all(af[ks & 1], wfr[ks & 1]);
-        interleave();
-      }
-      asm volatile("s_waitcnt %0\n\ts_barrier" ::"n"(WAIT_IMM) : "memory");
-      issue_stage(kt + NST, kt + NST < KT, cur);
-      read_frags(nxt, nxt + A_BYTES, 0, af[0], wfr[0]);
-      mfma_all(af[(NSUB - 1) & 1], wfr[(NSUB - 1) & 1]);
-      interleave();
+      for (int ks = 1; ks + 1 < NSUB; ++ks) substep(cur, cur + A_BYTES, ks + 1, ks & 1, std::integral_constant<int, 0>{});
+      __builtin_amdgcn_s_waitcnt(0x0071);  // vmcnt(1), expcnt untouched, lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+      issue_tokens(kt + 2, kt + 2 < KT, cur);
+      substep(nxt, nxt + A_BYTES, 0, (NSUB - 1) & 1, std::integral_constant<int, A_LOADS>{});
     };
-    read_frags(s0, s0 + A_BYTES, 0, af[0], wfr[0]);
+    read_w(s0 + A_BYTES, 0, wfr[0]);
+#pragma unroll
+    for (int i = 0; i < TBV; ++i) read_a(s0, 0, af[0][i], i);
     int kt = 0;
-    if (NST == 2) {
-      for (; kt + 1 < KT; kt += 2) {
-        step(kt, s0, s1);
-        step(kt + 1, s1, s0);
-      }
-      if (kt < KT) step(kt, s0, s1);
-    } else {
-      for (; kt + 3 < KT; kt += 4) {
-        step(kt, s0, s1);
-        step(kt + 1, s1, s2);
-        step(kt + 2, s2, s3);
-        step(kt + 3, s3, s0);
-      }
-      if (kt < KT) step(kt, s0, s1);
-      if (kt + 1 < KT) step(kt + 1, s1, s2);
-      if (kt + 2 < KT) step(kt + 2, s2, s3);
+    for (; kt + 1 < KT; kt += 2) {
+      step(kt, s0, s1);
+      step(kt + 1, s1, s0);
+      if (kt == 0) publish_next();
+      if (kt == 2) resolve_next();  // the two K-steps since publish_next() each passed a barrier
     }
+    if (kt < KT) step(kt, s0, s1);
   };
 
   // ---- persistent loop over this workgroup's slots ------------------------------------------------
-  TileInfo ti, nx;
-  int nx_tok[GATHER ? A_LOADS : 1];
   bool have = walk.next(offsets, E, s_pref, ti);
   if (!have) return;
   if constexpr (GATHER) {
-    fetch_rows(ti, nx_tok);
-    gather_voff(nx_tok);
+    fetch_rows(ti);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    gather_voff(ti);
   }
   bind_tile(ti);
-  issue_prologue();
+  bind_prefetch(ti);
+  issue_prologue(ti);
 
   while (true) {
 #pragma unroll
@@ -419,16 +548,13 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Everything this wavefront has in flight (the tile's first stages; the previous tile's stores, which
-    // do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    // the next tile is known now; its gathered row indices travel while this tile is multiplied
-    const bool have_nx = walk.next(offsets, E, s_pref, nx);
-    if constexpr (GATHER) {
-      if (have_nx) fetch_rows(nx, nx_tok);
-    }
+    // Everything this wavefront has in flight (the tile's first stages and bias; the previous tile's stores,
+    // which do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();
+    draw_next();
     // token blocks of this wavefront with at least one valid row (wave-uniform)
-    const int tbv = min(TB, max(0, (ti.rows - wt * WTOK + 31) / 32));
+    const int tbv = min(TB, max(0, (ti.rows - wt * 32 + 32 * WT - 1) / (32 * WT)));
     switch (tbv) {
       case 0: run_tile(std::integral_constant<int, 0>{}); break;
       case 1: run_tile(std::integral_constant<int, (1 < TB ? 1 : TB)>{}); break;
@@ -437,38 +563,50 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       case 4: run_tile(std::integral_constant<int, (4 < TB ? 4 : TB)>{}); break;
       default: run_tile(std::integral_constant<int, TB>{}); break;
     }
+    if (KT < 4) {  // too few K-steps for the K loop to have done it
+      if (KT < 2) publish_next();
+      __syncthreads();
+      resolve_next();
+    }
+    if (GATHER && KT < 6) {  // no K-step with its barrier has followed the request of the next tile's row ids
+      __builtin_amdgcn_s_waitcnt(0x0070);
+      __syncthreads();
+    }
 
     // ---- next tile: bind it and request its first stages before this tile's epilogue ---------------
     const TileInfo done = ti;
     ti = nx;
     have = have_nx;
     if constexpr (GATHER) {
-      if (have) gather_voff(nx_tok);
+      if (have) gather_voff(ti);
     }
     // every fragment read of real data finished before the last barrier; what the last sub-step read
     // afterwards is never used, so the stage buffers may be overwritten now
+    const int done_set = bias_set;
     if (have) {
+      bias_set ^= 1;
       bind_tile(ti);
-      issue_prologue();
+      bind_prefetch(ti);
+      issue_prologue(ti);
     }
 
     // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
     const int feat0 = done.ntile * OUT_FEAT;
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-      const int trow = wt * WTOK + tb * 32 + frow;
+      const int trow = (tb * WT + wt) * 32 + frow;
       if (trow >= done.rows) continue;
       uint16_t* orow = out + (size_t)(done.row0 + trow) * N;
       if (EPI == EPI_SWIGLU) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int n = feat0 + wf * 32 + 8 * i + 4 * fhalf;
-          uint32_t p[4];
+          float p[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) p[r] = f32_to_bf16_bits(silu(acc[tb][0][4 * i + r]) * acc[tb][1][4 * i + r]);
+          for (int r = 0; r < 4; ++r) p[r] = silu(acc[tb][0][4 * i + r]) * acc[tb][1][4 * i + r];
           u32x2 v;
-          v.x = p[0] | (p[1] << 16);
-          v.y = p[2] | (p[3] << 16);
+          v.x = pack_bf16(p[0], p[1]);
+          v.y = pack_bf16(p[2], p[3]);
           *reinterpret_cast<u32x2*>(orow + n) = v;
         }
       } else {
@@ -477,22 +615,20 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int n = feat0 + wf * WFEAT + fb * 32 + 8 * i + 4 * fhalf;
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (bias) {
-              const u32x2 b = *reinterpret_cast<const u32x2*>(bias + (size_t)done.expert * N + n);
-              bv[0] = bf16_bits_to_f32(b.x & 0xffffu); bv[1] = bf16_bits_to_f32(b.x >> 16);
-              bv[2] = bf16_bits_to_f32(b.y & 0xffffu); bv[3] = bf16_bits_to_f32(b.y >> 16);
-            }
-            uint32_t p[4];
+            // the bias sits in this wavefront's LDS slot since the tile's prologue (zeros without one)
+            const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 + (fb * 32 + 8 * i + 4 * fhalf) * 2);
+            float p[4];
+            p[0] = acc[tb][fb][4 * i + 0] + bf16_bits_to_f32(b.x & 0xffffu);
+            p[1] = acc[tb][fb][4 * i + 1] + __uint_as_float(b.x & 0xffff0000u);
+            p[2] = acc[tb][fb][4 * i + 2] + bf16_bits_to_f32(b.y & 0xffffu);
+            p[3] = acc[tb][fb][4 * i + 3] + __uint_as_float(b.y & 0xffff0000u);
+            if (EPI == EPI_GELU) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              float u = acc[tb][fb][4 * i + r] + bv[r];
-              if (EPI == EPI_GELU) u = gelu_table(u, s_phi);
-              p[r] = f32_to_bf16_bits(u);
+              for (int r = 0; r < 4; ++r) p[r] = gelu_table(p[r], s_phi);
             }
             u32x2 v;
-            v.x = p[0] | (p[1] << 16);
-            v.y = p[2] | (p[3] << 16);
+            v.x = pack_bf16(p[0], p[1]);
+            v.y = pack_bf16(p[2], p[3]);
             *reinterpret_cast<u32x2*>(orow + n) = v;
           }
       }
@@ -503,20 +639,21 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #endif
 }
 
-template <int TOK, int FEAT, int WT, int WF, int KS, int NST, int WPE, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
-               const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map, int N, int K,
-               hipStream_t s) {
+               const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
+               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, int tile_base, hipStream_t s) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
   if ((int64_t)TOK * K * 2 >= ((int64_t)1 << 31)) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d too large", K);
   const int64_t rmax = max_rows(cfg);
   if (rmax == 0) return MOE_OK;
-  int64_t mt = rmax / TOK + cfg->E;  // every expert may end in one partial tile
+  if (tile_base < 32 || tile_base > TOK) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: tile base %d", tile_base);
+  int64_t mt = rmax / tile_base + cfg->E;  // every expert may end in one partial tile
   const int64_t C = moe_capacity(cfg);
   if (C != MOE_DROPLESS) {
-    const int64_t by_cap = (int64_t)cfg->E * ((C + TOK - 1) / TOK);
+    const int64_t by_cap = (int64_t)cfg->E * token_tiles((int)(C > INT32_MAX ? INT32_MAX : C), TOK, tile_base);
     if (by_cap < mt) mt = by_cap;
   }
   const int64_t blocks = block_count(mt, N / OUT_FEAT);  // upper bound of the device's block count
@@ -526,43 +663,51 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   const int64_t per_xcd = ((blocks + NUM_XCD - 1) / NUM_XCD) * CU_PER_XCD;  // tiles one XCD may own
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
   // the gathering variant exists for the first GEMM's epilogues only
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, EPI, false>;
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false>;
   if constexpr (EPI != EPI_BIAS) {
-    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, NST, WPE, EPI, true>;
+    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true>;
   } else {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out, row_map,
-                     cfg->T, cfg->E, N, K);
+                     tile_ctr, clear_ctr, cfg->T, cfg->E, N, K, tile_base);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
-// MOESYS_GEMM_DEEP=1 selects four 32-deep LDS stages instead of two 64-deep ones.  Off by default:
-// measured ~7 % slower on MI355X (twice the barriers, no gain from the longer prefetch distance).
-bool deep_pipeline() {
-  static const bool v = [] { const char* e = getenv("MOESYS_GEMM_DEEP"); return e && atoi(e) != 0; }();
-  return v;
-}
-
-// Token-tile height.  256 rows is the default; 320 rows (10 MFMA row blocks, still within the 160 KB LDS)
-// is chosen when, for the row count an evenly loaded expert would get, it saves enough whole rounds of
-// NUM_CU tiles to pay for the taller tile (e.g. ~1024 rows per expert: 4 tiles of 320 instead of 5 of 256).
-// The estimate only steers the choice; any routing is handled by either height.
-int pick_tile_rows(const moe_config* cfg, int n_tiles) {
-  static const int forced = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
-  if (forced == 256 || forced == 320) return forced;
+// Tile shape policy: {kernel capacity, tile base}.  The 256-row kernel keeps two sets of token fragments
+// and has the faster K loop; the 320-row kernel (10 MFMA row blocks, one set of token fragments, still
+// within 160 KB of LDS and 256 registers) either runs 320-row tiles throughout or lets an expert's last
+// tile absorb a remainder of up to 64 rows.  A tile costs about the same whether it holds 30 rows or 256 -
+// with nothing to multiply its K loop runs at the latency of its weight loads - so what counts is the
+// number of tiles, in whole rounds of NUM_CU when there are few of them: e.g. ~1050 rows per expert, 16
+// experts, 4 feature tiles are 256 tiles of 320 rows (one round) or 320 tiles of 256 rows (two).  The choice
+// is made for the row count an evenly loaded expert would get, with head-room for uneven routing and capped
+// by the capacity; any routing is handled correctly by every policy.
+struct TilePolicy { int cap, base; };
+TilePolicy pick_tile_policy(const moe_config* cfg, int n_tiles) {
+  static const int f_cap = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
+  static const int f_base = [] { const char* e = getenv("MOESYS_GEMM_BASE"); return e ? atoi(e) : 0; }();
+  if ((f_cap == 256 || f_cap == 320) && f_base >= 32 && f_base <= f_cap && f_base % 32 == 0) return {f_cap, f_base};
   const int64_t A = (int64_t)cfg->k * cfg->T;
   int64_t rows = (A + cfg->E - 1) / cfg->E;
-  rows += (rows * 2 + 24) / 25;  // 8 % head-room for uneven routing
+  rows += (rows * 2 + 24) / 25;  // 8 % head-room
   const int64_t C = moe_capacity(cfg);
   if (rows > C) rows = C;
   if (rows < 1) rows = 1;
-  int best = 256;
-  int64_t best_cost = -1;
-  for (int tok : {256, 320}) {
-    const int64_t tiles = (int64_t)cfg->E * ((rows + tok - 1) / tok) * n_tiles;
-    const int64_t cost = (tiles + NUM_CU - 1) / NUM_CU * tok;
-    if (best_cost < 0 || cost < best_cost) { best = tok; best_cost = cost; }
+  if (rows > (1 << 24)) return {256, 256};
+  const TilePolicy cand[3] = {{256, 256}, {320, 256}, {320, 320}};
+  TilePolicy best = cand[0];
+  double best_cost = -1;
+  for (const TilePolicy& p : cand) {
+    const int n = token_tiles((int)rows, p.cap, p.base);
+    const int64_t last = rows - (int64_t)(n - 1) * p.base;
+    // MFMA row blocks per wavefront: 4 for a tile of up to 256 rows (also when mostly empty), 5 for a taller
+    // one; 5 % more in the 320-row kernel for its single fragment set
+    const double per_expert = (p.base > 256 ? 5.0 : 4.0) * (n - 1) + (last > 256 ? 5.0 : 4.0);
+    const double tiles = (double)cfg->E * n * n_tiles;
+    const double rounds = tiles <= 4 * NUM_CU ? (double)((int64_t)(tiles + NUM_CU - 1) / NUM_CU) : tiles / NUM_CU;
+    const double cost = (p.cap > 256 ? 1.05 : 1.0) * per_expert / n * rounds;
+    if (best_cost < 0 || cost < best_cost) { best = p; best_cost = cost; }
   }
   return best;
 }
@@ -570,20 +715,21 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
 // One grouped GEMM.  256x256x64 tiles (8 wavefronts, the highest arithmetic intensity that fits the
 // 160 KB LDS) whenever the feature count allows; feature counts that are multiples of 64 but not of 256
 // use narrow tiles.
-template <int EPI, int KSB, int NSB>
+template <int EPI>
 int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
-                 const int32_t* offsets, uint16_t* o, const int32_t* row_map, int N, int K, hipStream_t s) {
+                 const int32_t* offsets, uint16_t* o, const int32_t* row_map, int32_t* tile_ctr, int32_t* clear_ctr, int N,
+                 int K, hipStream_t s) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
-    // (the 320-row tile has no registers to spare for the row gather)
-    if (KSB == 64 && !row_map && pick_tile_rows(cfg, N / BF) == 320)
-      return launch<320, 256, 2, 4, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
-    return launch<256, 256, 2, 4, KSB, NSB, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
+    const TilePolicy p = pick_tile_policy(cfg, N / BF);
+    if (p.cap == 320)
+      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, p.base, s);
+    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, p.base, s);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
+    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, 128, s);
   else
-    return launch<128, 64, 4, 1, 64, 2, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, N, K, s);
+    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, 128, s);
 }
 
 }  // namespace
@@ -591,22 +737,24 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
 // row_map (nullable): row_to_assign; the token rows are then gathered from x[T, d_model] instead of read
 // from a dispatched copy.
 int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
-                          void* h, const int32_t* row_map, hipStream_t s) {
+                          void* h, const int32_t* row_map, int32_t* tile_counters, hipStream_t s) {
+  // the first GEMM draws from counters [0,8) and clears [8,16) for the second
   if (cfg->act == MOE_ACT_SWIGLU)
-    return (deep_pipeline() ? gemm_any<EPI_SWIGLU, 32, 4> : gemm_any<EPI_SWIGLU, 64, 2>)(
+    return gemm_any<EPI_SWIGLU>(
         cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up, nullptr, offsets,
-        (uint16_t*)h, row_map, cfg->d_ff, cfg->d_model, s);
-  return (deep_pipeline() ? gemm_any<EPI_GELU, 32, 4> : gemm_any<EPI_GELU, 64, 2>)(
+        (uint16_t*)h, row_map, tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s);
+  return gemm_any<EPI_GELU>(
       cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets, (uint16_t*)h, row_map,
-      cfg->d_ff, cfg->d_model, s);
+      tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s);
 }
 
 int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
-                          void* yd, hipStream_t s) {
+                          void* yd, int32_t* tile_counters, hipStream_t s) {
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
-  return (deep_pipeline() ? gemm_any<EPI_BIAS, 32, 4> : gemm_any<EPI_BIAS, 64, 2>)(
+  return gemm_any<EPI_BIAS>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
-      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, cfg->d_model, cfg->d_ff, s);
+      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, nullptr,
+      cfg->d_model, cfg->d_ff, s);
 }
 
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.

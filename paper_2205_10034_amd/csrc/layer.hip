@@ -35,6 +35,7 @@ int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, c
   void* h = base + L.h;
   void* yd = base + L.yd;
   void* scratch = base + L.scratch;
+  int32_t* tile_ctr = (int32_t*)(base + L.tile_counters);
 
   auto mark = [&](int i) -> int32_t {
     if (!timer) return MOE_OK;
@@ -45,11 +46,11 @@ int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, c
   if ((st = mark(1)) != MOE_OK) return st;
   // bf16: the first GEMM gathers its rows from x through row_to_assign, so no dispatched copy is made
   const bool gather = gemm1_can_gather(cfg);
-  if ((st = launch_dispatch(cfg, x, topk_idx, counts, offsets, a2r, r2a, gather ? nullptr : xd, scratch, s)) != MOE_OK) return st;
+  if ((st = launch_dispatch(cfg, x, topk_idx, counts, offsets, a2r, r2a, gather ? nullptr : xd, scratch, tile_ctr, s)) != MOE_OK) return st;
   if ((st = mark(2)) != MOE_OK) return st;
-  if ((st = launch_gemm1(cfg, w, gather ? x : xd, offsets, h, gather ? r2a : nullptr, s)) != MOE_OK) return st;
+  if ((st = launch_gemm1(cfg, w, gather ? x : xd, offsets, h, gather ? r2a : nullptr, tile_ctr, s)) != MOE_OK) return st;
   if ((st = mark(3)) != MOE_OK) return st;
-  if ((st = launch_gemm2(cfg, w, h, offsets, yd, s)) != MOE_OK) return st;
+  if ((st = launch_gemm2(cfg, w, h, offsets, yd, tile_ctr, s)) != MOE_OK) return st;
   if ((st = mark(4)) != MOE_OK) return st;
   if ((st = launch_combine(cfg, yd, a2r, topk_w, residual, out, s)) != MOE_OK) return st;
   if ((st = mark(5)) != MOE_OK) return st;

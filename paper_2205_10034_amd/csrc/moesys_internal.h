@@ -24,17 +24,27 @@ inline int64_t dispatch_blocks(const moe_config* cfg) {
   return (A + DISPATCH_BLOCK - 1) / DISPATCH_BLOCK;
 }
 
+// The grouped GEMMs hand out their tiles through one counter per XCD: the first GEMM owns ints [0,8) of a
+// 16-int block, the second [8,16).  A counter must be zero when its kernel starts: the dispatch stage
+// clears the first GEMM's, the first GEMM clears the second's.
+constexpr int TILE_COUNTER_INTS = 16;
+// Byte offset of the counters inside an MOE_WS_FFN workspace (after h[R_max, d_ff]).
+size_t ffn_counter_offset(const moe_config* cfg);
+
 // Stage launchers (arguments already validated).
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s);
+// clear8 (nullable): eight ints set to zero on the way (the first GEMM's tile counters).
 int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx, int32_t* counts,
-                        int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, hipStream_t s);
+                        int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, int32_t* clear8,
+                        hipStream_t s);
 // row_map (nullable, bf16 only): row_to_assign; xd is then x itself and the rows are gathered on the fly.
+// tile_counters: the 16-int block above (bf16 only; the fp32 kernels ignore it).
 int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
-                     void* h, const int32_t* row_map, hipStream_t s);
+                     void* h, const int32_t* row_map, int32_t* tile_counters, hipStream_t s);
 bool gemm1_can_gather(const moe_config* cfg);
 int32_t launch_gemm2(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
-                     void* yd, hipStream_t s);
+                     void* yd, int32_t* tile_counters, hipStream_t s);
 int32_t launch_combine(const moe_config* cfg, const void* yd, const int32_t* a2r, const float* topk_w,
                        const void* residual, void* out, hipStream_t s);
 int32_t check_weights(const moe_config* cfg, const moe_weights* w);

@@ -100,13 +100,14 @@ def test_workspace_layout_is_consistent():
         C_ = O.capacity(cfg.T, cfg.E, cfg.k, cfg.capacity_factor)
         assert L["r_max"] == min(cfg.k * cfg.T, cfg.E * C_)
         order = ["topk_idx", "topk_w", "expert_counts", "expert_offsets", "assign_to_row", "row_to_assign",
-                 "xd", "h", "yd", "scratch", "total"]
+                 "xd", "h", "yd", "scratch", "tile_counters", "total"]
         offs = [L[n] for n in order]
         assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
         s = 2 if cfg.dtype == "bf16" else 4
         assert L["h"] - L["xd"] >= L["r_max"] * cfg.d_model * s
         assert L["yd"] - L["h"] >= L["r_max"] * cfg.d_ff * s
-        assert M.moe_workspace_bytes(cfg, 2) >= L["r_max"] * cfg.d_ff * s
+        assert L["total"] - L["tile_counters"] >= 16 * 4
+        assert M.moe_workspace_bytes(cfg, 2) >= L["r_max"] * cfg.d_ff * s + 16 * 4
 
 
 # ----------------------------------------------------------------- ring state machine on the host
