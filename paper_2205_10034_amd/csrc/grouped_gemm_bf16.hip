@@ -105,16 +105,14 @@ struct TileInfo {
 // groups is spread over the XCDs feature group by feature group instead, to keep them equally loaded.
 __host__ __device__ inline int group_n(int n_tiles) { return n_tiles < 8 ? n_tiles : 8; }
 
+// Token tiling of one expert with n rows, for a kernel whose tile holds up to `cap` rows: the fewest tiles
+// that can hold them, ceil(n / cap), with the rows spread over them as evenly as whole units allow (a unit =
+// one 32-row MFMA block per wavefront row, the granularity at which a tile's K loop gets cheaper).  E.g. 1049
+// rows under cap 320: 17 units of 64 rows in 4 tiles of 5,4,4,4 units.
+__host__ __device__ inline int token_tiles(int n, int cap) { return (n + cap - 1) / cap; }
 // s_pref[e] = number of token tiles of experts < e ; s_pref[E] = total.  Whole workgroup.
-// Token tiling of one expert with n rows.  Tiles are `base` rows high, except that the last tile takes
-// everything that is left when that is at most `cap` rows (cap = the kernel's tile capacity TOK, base <=
-// cap): with base 256 a 320-row kernel absorbs a remainder of up to 64 rows instead of spending a whole
-// tile - a whole K loop of weight loads and barriers - on it; with base = cap all tiles are alike.
-__host__ __device__ inline int token_tiles(int n, int cap, int base) {
-  return n <= cap ? (n > 0) : 1 + (n - cap + base - 1) / base;
-}
-__device__ __forceinline__ void count_token_tiles(const int32_t* __restrict__ offsets, int E, int cap, int base, int* s_pref) {
-  for (int e = threadIdx.x; e < E; e += blockDim.x) s_pref[e + 1] = token_tiles(offsets[e + 1] - offsets[e], cap, base);
+__device__ __forceinline__ void count_token_tiles(const int32_t* __restrict__ offsets, int E, int cap, int* s_pref) {
+  for (int e = threadIdx.x; e < E; e += blockDim.x) s_pref[e + 1] = token_tiles(offsets[e + 1] - offsets[e], cap);
   __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
@@ -138,14 +136,14 @@ __host__ __device__ inline int64_t block_count(int64_t MT, int n_tiles) {
 // the tiles of blocks x, x+8, x+16, ... are numbered consecutively and workgroup j of the G on the XCD
 // takes number j first and then whatever number the XCD's counter hands out next (`want` is set by the
 // caller before each call and must grow): workgroups that drew short tiles simply draw more of them.
-template <int TOK>
+template <int TOK, int UNIT>
 struct TileWalker {
   int MT, NT, GM, GN, MG, NG;
-  int xcd, G, tbase;
+  int xcd, G;
   int q, base, want;
 
-  __device__ __forceinline__ void init(int mt_total, int n_tiles, int tile_base) {
-    MT = mt_total; NT = n_tiles; tbase = tile_base;
+  __device__ __forceinline__ void init(int mt_total, int n_tiles) {
+    MT = mt_total; NT = n_tiles;
     GN = group_n(n_tiles); GM = CU_PER_XCD / GN;
     MG = (MT + GM - 1) / GM; NG = (NT + GN - 1) / GN;
     xcd = blockIdx.x % NUM_XCD; G = gridDim.x / NUM_XCD;
@@ -173,10 +171,14 @@ struct TileWalker {
         // every lane computed the same values; say so to the compiler (they feed scalar descriptors)
         lo = __builtin_amdgcn_readfirstlane(lo);
         ti.expert = lo;
-        const int r0 = __builtin_amdgcn_readfirstlane(offsets[lo] + (mt - s_pref[lo]) * tbase);
+        // tile m of the expert's nt tiles: the units are dealt out evenly, the first `rem` tiles hold one more
+        const int e0 = offsets[lo], n_rows = offsets[lo + 1] - e0;
+        const int m = mt - s_pref[lo], nt_e = s_pref[lo + 1] - s_pref[lo];
+        const int units = (n_rows + UNIT - 1) / UNIT, per = units / nt_e, rem = units - per * nt_e;
+        const int u0 = m * per + min(m, rem), un = per + (m < rem ? 1 : 0);
+        const int r0 = __builtin_amdgcn_readfirstlane(e0 + u0 * UNIT);
         ti.row0 = r0;
-        // the expert's last tile holds whatever is left (at most TOK rows by the tile count above)
-        ti.rows = __builtin_amdgcn_readfirstlane(mt + 1 == s_pref[lo + 1] ? offsets[lo + 1] - r0 : tbase);
+        ti.rows = __builtin_amdgcn_readfirstlane(min(un * UNIT, e0 + n_rows - r0));
         ti.ntile = __builtin_amdgcn_readfirstlane(nt);
         ti.pm = __builtin_amdgcn_readfirstlane(r / gn);
         ti.pn = __builtin_amdgcn_readfirstlane(r % gn);
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const int32_t* __restrict__ row_map,  // GATHER: row_to_assign; act is then x[T,K] and row r reads token row_map[r] mod T
     int32_t* __restrict__ tile_ctr,       // [NUM_XCD] zero at launch: tiles handed out beyond each workgroup's first
     int32_t* __restrict__ clear_ctr,      // [NUM_XCD] or NULL: cleared here for the kernel that runs next
-    int T, int E, int N, int K, int tile_base /* rows per token tile, <= TOK */) {
+    int T, int E, int N, int K) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (buffer descriptors are device-only types)
   constexpr int NW = WT * WF;
   constexpr int WFEAT = FEAT / WF;
@@ -261,9 +263,9 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 
   if (clear_ctr && blockIdx.x == 0 && tid < NUM_XCD) clear_ctr[tid] = 0;
   if (EPI == EPI_GELU) fill_phi_table(s_phi);
-  count_token_tiles(offsets, E, TOK, tile_base, s_pref);  // ends with a barrier: s_pref and the table are visible
-  TileWalker<TOK> walk;
-  walk.init(s_pref[E], n_tiles, tile_base);
+  count_token_tiles(offsets, E, TOK, s_pref);  // ends with a barrier: s_pref and the table are visible
+  TileWalker<TOK, 32 * WT> walk;
+  walk.init(s_pref[E], n_tiles);
 
   // ---- per-lane offsets of every direct-to-LDS load, LDS fragment addresses ----------------------
   // (with a row map the token-tile offsets are recomputed per tile from the gathered token indices)
@@ -642,18 +644,17 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
-               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, int tile_base, hipStream_t s) {
+               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
   if ((int64_t)TOK * K * 2 >= ((int64_t)1 << 31)) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d too large", K);
   const int64_t rmax = max_rows(cfg);
   if (rmax == 0) return MOE_OK;
-  if (tile_base < 32 || tile_base > TOK) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: tile base %d", tile_base);
-  int64_t mt = rmax / tile_base + cfg->E;  // every expert may end in one partial tile
+  int64_t mt = rmax / TOK + cfg->E;  // every expert may end in one partial tile
   const int64_t C = moe_capacity(cfg);
   if (C != MOE_DROPLESS) {
-    const int64_t by_cap = (int64_t)cfg->E * token_tiles((int)(C > INT32_MAX ? INT32_MAX : C), TOK, tile_base);
+    const int64_t by_cap = (int64_t)cfg->E * token_tiles((int)(C > INT32_MAX - TOK ? INT32_MAX - TOK : C), TOK);
     if (by_cap < mt) mt = by_cap;
   }
   const int64_t blocks = block_count(mt, N / OUT_FEAT);  // upper bound of the device's block count
@@ -670,44 +671,40 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out, row_map,
-                     tile_ctr, clear_ctr, cfg->T, cfg->E, N, K, tile_base);
+                     tile_ctr, clear_ctr, cfg->T, cfg->E, N, K);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
-// Tile shape policy: {kernel capacity, tile base}.  The 256-row kernel keeps two sets of token fragments
-// and has the faster K loop; the 320-row kernel (10 MFMA row blocks, one set of token fragments, still
-// within 160 KB of LDS and 256 registers) either runs 320-row tiles throughout or lets an expert's last
-// tile absorb a remainder of up to 64 rows.  A tile costs about the same whether it holds 30 rows or 256 -
-// with nothing to multiply its K loop runs at the latency of its weight loads - so what counts is the
-// number of tiles, in whole rounds of NUM_CU when there are few of them: e.g. ~1050 rows per expert, 16
-// experts, 4 feature tiles are 256 tiles of 320 rows (one round) or 320 tiles of 256 rows (two).  The choice
-// is made for the row count an evenly loaded expert would get, with head-room for uneven routing and capped
-// by the capacity; any routing is handled correctly by every policy.
-struct TilePolicy { int cap, base; };
-TilePolicy pick_tile_policy(const moe_config* cfg, int n_tiles) {
-  static const int f_cap = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
-  static const int f_base = [] { const char* e = getenv("MOESYS_GEMM_BASE"); return e ? atoi(e) : 0; }();
-  if ((f_cap == 256 || f_cap == 320) && f_base >= 32 && f_base <= f_cap && f_base % 32 == 0) return {f_cap, f_base};
+// Tile capacity.  The 256-row kernel keeps two sets of token fragments and has the faster K loop; the
+// 320-row kernel (10 MFMA row blocks, one set of token fragments, still within 160 KB of LDS and 256
+// registers) needs fewer tiles when the rows of an expert do not fill whole 256-row tiles: e.g. ~1050 rows
+// are 4 tiles of 4-5 units (of 64 rows) under capacity 320 and 5 tiles of 3-4 units under 256, and a tile's
+// K loop does not get cheaper below ~4 units (with little to multiply it runs at the latency of its weight
+// loads).  With few tiles what counts is whole rounds of NUM_CU: 16 such experts x 4 feature tiles are 256
+// tiles (one round) or 320 (two).  The choice is made for the row count an evenly loaded expert would get,
+// with head-room for uneven routing and capped by the capacity; either kernel handles any routing.
+int pick_tile_rows(const moe_config* cfg, int n_tiles) {
+  static const int forced = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
+  if (forced == 256 || forced == 320) return forced;
   const int64_t A = (int64_t)cfg->k * cfg->T;
   int64_t rows = (A + cfg->E - 1) / cfg->E;
   rows += (rows * 2 + 24) / 25;  // 8 % head-room
   const int64_t C = moe_capacity(cfg);
   if (rows > C) rows = C;
   if (rows < 1) rows = 1;
-  if (rows > (1 << 24)) return {256, 256};
-  const TilePolicy cand[3] = {{256, 256}, {320, 256}, {320, 320}};
-  TilePolicy best = cand[0];
+  if (rows > (1 << 24)) return 256;
+  int best = 256;
   double best_cost = -1;
-  for (const TilePolicy& p : cand) {
-    const int n = token_tiles((int)rows, p.cap, p.base);
-    const int64_t last = rows - (int64_t)(n - 1) * p.base;
-    // MFMA row blocks per wavefront: 4 for a tile of up to 256 rows (also when mostly empty), 5 for a taller
-    // one; 5 % more in the 320-row kernel for its single fragment set
-    const double per_expert = (p.base > 256 ? 5.0 : 4.0) * (n - 1) + (last > 256 ? 5.0 : 4.0);
+  for (int cap : {256, 320}) {
+    const int n = token_tiles((int)rows, cap);
+    const double units = (double)((rows + 63) / 64) / n;       // per tile
+    const double per_tile = (cap > 256 ? 1.05 : 1.0) * (units < 4.0 ? 4.0 : units);
     const double tiles = (double)cfg->E * n * n_tiles;
-    const double rounds = tiles <= 4 * NUM_CU ? (double)((int64_t)(tiles + NUM_CU - 1) / NUM_CU) : tiles / NUM_CU;
-    const double cost = (p.cap > 256 ? 1.05 : 1.0) * per_expert / n * rounds;
-    if (best_cost < 0 || cost < best_cost) { best = p; best_cost = cost; }
+    // up to two rounds every workgroup's time is that of the largest tiles; beyond, the drawn tiles even out
+    const bool few = tiles <= 2 * NUM_CU;
+    const double rounds = few ? (double)((int64_t)(tiles + NUM_CU - 1) / NUM_CU) : tiles / NUM_CU;
+    const double cost = rounds * (few ? (cap > 256 ? 1.05 : 1.0) * (double)(int64_t)(units + 0.999) : per_tile);
+    if (best_cost < 0 || cost < best_cost) { best = cap; best_cost = cost; }
   }
   return best;
 }
@@ -721,15 +718,14 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
                  int K, hipStream_t s) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
-    const TilePolicy p = pick_tile_policy(cfg, N / BF);
-    if (p.cap == 320)
-      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, p.base, s);
-    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, p.base, s);
+    if (pick_tile_rows(cfg, N / BF) == 320)
+      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
+    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, 128, s);
+    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
   else
-    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, 128, s);
+    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
 }
 
 }  // namespace
