@@ -593,45 +593,50 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     }
 
     // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
+    // Lanes l and l+32 hold the two halves of the same token's 8-feature groups.  For a pair of groups
+    // (i, i+1) they trade halves (v_permlane32_swap: the upper lanes' first operand against the lower lanes'
+    // second), after which lane l owns all 8 features of group i and lane l+32 those of group i+1: one
+    // 16-byte store per lane and pair instead of two 8-byte ones.
     const int feat0 = done.ntile * OUT_FEAT;
+    auto store_pair = [&](uint16_t* orow, int n0, int i0, const float (&p)[8]) {
+      const u32x2 sx = __builtin_amdgcn_permlane32_swap(pack_bf16(p[0], p[1]), pack_bf16(p[4], p[5]), false, false);
+      const u32x2 sy = __builtin_amdgcn_permlane32_swap(pack_bf16(p[2], p[3]), pack_bf16(p[6], p[7]), false, false);
+      *reinterpret_cast<u32x4*>(orow + n0 + 8 * (i0 + fhalf)) = u32x4{sx.x, sy.x, sx.y, sy.y};
+    };
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       const int trow = (tb * WT + wt) * 32 + frow;
-      if (trow >= done.rows) continue;
+      if (trow >= done.rows) continue;  // (lanes l and l+32 share the row: they stay or leave together)
       uint16_t* orow = out + (size_t)(done.row0 + trow) * N;
       if (EPI == EPI_SWIGLU) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int n = feat0 + wf * 32 + 8 * i + 4 * fhalf;
-          float p[4];
+        for (int i0 = 0; i0 < 4; i0 += 2) {
+          float p[8];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) p[r] = silu(acc[tb][0][4 * i + r]) * acc[tb][1][4 * i + r];
-          u32x2 v;
-          v.x = pack_bf16(p[0], p[1]);
-          v.y = pack_bf16(p[2], p[3]);
-          *reinterpret_cast<u32x2*>(orow + n) = v;
+          for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][0][4 * i0 + r]) * acc[tb][1][4 * i0 + r];
+          store_pair(orow, feat0 + wf * 32, i0, p);
         }
       } else {
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int n = feat0 + wf * WFEAT + fb * 32 + 8 * i + 4 * fhalf;
-            // the bias sits in this wavefront's LDS slot since the tile's prologue (zeros without one)
-            const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 + (fb * 32 + 8 * i + 4 * fhalf) * 2);
-            float p[4];
-            p[0] = acc[tb][fb][4 * i + 0] + bf16_bits_to_f32(b.x & 0xffffu);
-            p[1] = acc[tb][fb][4 * i + 1] + __uint_as_float(b.x & 0xffff0000u);
-            p[2] = acc[tb][fb][4 * i + 2] + bf16_bits_to_f32(b.y & 0xffffu);
-            p[3] = acc[tb][fb][4 * i + 3] + __uint_as_float(b.y & 0xffff0000u);
+          for (int i0 = 0; i0 < 4; i0 += 2) {
+            float p[8];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+              // the bias sits in this wavefront's LDS slot since the tile's prologue (zeros without one)
+              const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 +
+                                                              (fb * 32 + 8 * (i0 + g) + 4 * fhalf) * 2);
+              p[4 * g + 0] = acc[tb][fb][4 * (i0 + g) + 0] + bf16_bits_to_f32(b.x & 0xffffu);
+              p[4 * g + 1] = acc[tb][fb][4 * (i0 + g) + 1] + __uint_as_float(b.x & 0xffff0000u);
+              p[4 * g + 2] = acc[tb][fb][4 * (i0 + g) + 2] + bf16_bits_to_f32(b.y & 0xffffu);
+              p[4 * g + 3] = acc[tb][fb][4 * (i0 + g) + 3] + __uint_as_float(b.y & 0xffff0000u);
+            }
             if (EPI == EPI_GELU) {
 #pragma unroll
-              for (int r = 0; r < 4; ++r) p[r] = gelu_table(p[r], s_phi);
+              for (int r = 0; r < 8; ++r) p[r] = gelu_table(p[r], s_phi);
             }
-            u32x2 v;
-            v.x = pack_bf16(p[0], p[1]);
-            v.y = pack_bf16(p[2], p[3]);
-            *reinterpret_cast<u32x2*>(orow + n) = v;
+            store_pair(orow, feat0 + wf * WFEAT + fb * 32, i0, p);
           }
       }
     }
