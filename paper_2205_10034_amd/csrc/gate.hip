@@ -430,28 +430,47 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   __syncthreads();
 
   // ---- exact recompute of the rare tokens whose ranking is within the margin -------------------
-  double* zex = part;           // [EP]
-  double* wsum = part + EP;     // [4][NE]
-  for (int tt = 0; tt < FT_TOK; ++tt) {
-    if (!s_flag[tt]) continue;  // uniform
+  // Wavefront w takes the expert groups w, w+4, ... (four experts each), its lanes stride over K; the
+  // products are exact in float64 and so is their sum up to rounding at 2^-53, far below any gap that can
+  // decide a ranking.  The flags are turned into one wave-uniform mask first (no LDS read per token).
+  uint32_t flagged = (uint32_t)__ballot(lane < FT_TOK && s_flag[lane & (FT_TOK - 1)] != 0);
+  flagged = __builtin_amdgcn_readfirstlane(flagged);
+  double* zex = part;  // [EP]
+  while (flagged) {
+    const int tt = __builtin_ctz(flagged);
+    flagged &= flagged - 1;
     const int t = t0 + tt;
-    for (int c0 = 0; c0 < E; c0 += NE) {
-      const int ne = min(NE, E - c0);
-      double acc[NE];
+    const uint16_t* xt = x + (size_t)t * d;
+    for (int g = wave; g < EP / 4; g += 4) {
+      const int e0 = g * 4;
+      if (e0 >= E) break;  // uniform
+      double a[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+      for (int i = lane; i < d; i += 64) {
+        const double xv = (double)bf16_to_f32(xt[i]);
+        const float* wp = wr + (size_t)i * E + e0;
+        float w[4];
+        if (VEC) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(wp);  // E is a multiple of 4: e0 + 3 < E
+          w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+        } else {
 #pragma unroll
-      for (int e = 0; e < NE; ++e) acc[e] = 0.0;
-      for (int i = tid; i < d; i += 256) {
-        const double xv = (double)bf16_to_f32(x[(size_t)t * d + i]);
-        const float* wrow = wr + (size_t)i * E + c0;
+          for (int j = 0; j < 4; ++j) w[j] = e0 + j < E ? wp[j] : 0.f;
+        }
 #pragma unroll
-        for (int e = 0; e < NE; ++e) acc[e] = fma(xv, (double)(e < ne ? wrow[e] : 0.f), acc[e]);
+        for (int j = 0; j < 4; ++j) a[j] = fma(xv, (double)w[j], a[j]);
       }
-      const double zsum = reduce_scatter16(acc, lane);
-      if ((lane & 3) == 0) wsum[wave * NE + ((lane >> 2) & 15)] = zsum;
-      __syncthreads();
-      if (tid < ne) zex[c0 + tid] = wsum[tid] + wsum[NE + tid] + wsum[2 * NE + tid] + wsum[3 * NE + tid] + (br ? (double)br[c0 + tid] : 0.0);
-      __syncthreads();
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
+      if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (e0 + j < E) zex[e0 + j] = a[j] + (br ? (double)br[e0 + j] : 0.0);
+      }
     }
+    __syncthreads();
     if (tid < 8) {
       double z[NPL];
 #pragma unroll
