@@ -66,6 +66,14 @@ def lib_path() -> str:
     return _LIB_PATH
 
 
+def use_library(path: str) -> None:
+    """Selects another build of the library (the phase-timing build) before the first call; diagnostics only."""
+    global _LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _LIB_PATH = path
+
+
 def lib() -> C.CDLL:
     """Loads the built library; raises if it is missing (no fallback path exists)."""
     global _lib

@@ -16,6 +16,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoesys_hip.so")
+# the same library with the grouped GEMM's phase timing compiled in (see gemm_profile.py); diagnostics only
+PROF_LIB = os.path.join(HERE, "libmoesys_hip_prof.so")
 
 SOURCES = ["api.cpp", "gate.hip", "dispatch.hip", "combine.hip", "ffn.hip", "grouped_gemm_bf16.hip",
            "layer.hip", "ring.cpp"]
@@ -27,9 +29,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, suffix: str = "", defines=()) -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + suffix + ".o")
+    cmd = [HIPCC] + FLAGS + ["-D" + d for d in defines] + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
     if r.returncode != 0:
@@ -41,14 +43,17 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        prof = ex.submit(_compile, "grouped_gemm_bf16.hip", "_prof", ("MOESYS_GEMM_PROFILE",))
         objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
-    if verbose:
-        print(f"built {LIB}")
+        prof_obj = prof.result()
+    for lib, these in ((LIB, objs), (PROF_LIB, [prof_obj if o.endswith("grouped_gemm_bf16.o") else o for o in objs])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + these
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

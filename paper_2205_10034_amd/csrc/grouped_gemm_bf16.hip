@@ -44,7 +44,19 @@
 #include <type_traits>
 #include "moesys_internal.h"
 
+// Optional phase timing, compiled in with -DMOESYS_GEMM_PROFILE (a separate library, never the product
+// build): every wavefront sums the shader clocks it spends between its K-step barriers, waiting for its
+// own loads, waiting at the barriers and in the epilogues, and reads the 100 MHz reference counter at both
+// ends, which gives the shader clock frequency the kernel actually ran at.  moe_gemm_profile_set() points
+// the kernels at a buffer of PROF_SLOTS uint64 per wavefront (first GEMM first, second GEMM behind it).
+#ifdef MOESYS_GEMM_PROFILE
+#define MOE_PROF(...) __VA_ARGS__
+#else
+#define MOE_PROF(...)
+#endif
+
 namespace moesys {
+MOE_PROF(__device__ unsigned long long* g_gemm_prof = nullptr; constexpr int PROF_SLOTS = 16;)
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -432,6 +444,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     }
   };
 
+  MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0; } pf = {};
+           pf.c0 = __builtin_readcyclecounter(); pf.r0 = __builtin_amdgcn_s_memrealtime();)
   f32x16 acc[TB][FB];
   bf16x8 af[ABUF][TB], wfr[2][FB];
   // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
@@ -511,8 +525,12 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       substep(cur, cur + A_BYTES, 1, 0, std::integral_constant<int, W_LOADS + 1>{});
 #pragma unroll
       for (int ks = 1; ks + 1 < NSUB; ++ks) substep(cur, cur + A_BYTES, ks + 1, ks & 1, std::integral_constant<int, 0>{});
+      MOE_PROF(__builtin_amdgcn_s_waitcnt(0xc07f); const unsigned long long t_a = __builtin_readcyclecounter();)
       __builtin_amdgcn_s_waitcnt(0x0071);  // vmcnt(1), expcnt untouched, lgkmcnt(0)
+      MOE_PROF(const unsigned long long t_b = __builtin_readcyclecounter();)
       __builtin_amdgcn_s_barrier();
+      MOE_PROF(const unsigned long long t_c = __builtin_readcyclecounter(); pf.comp += t_a - pf.last; pf.vm += t_b - t_a;
+               pf.bar += t_c - t_b; pf.last = t_c; ++pf.steps;)
       issue_tokens(kt + 2, kt + 2 < KT, cur);
       substep(nxt, nxt + A_BYTES, 0, (NSUB - 1) & 1, std::integral_constant<int, A_LOADS>{});
     };
@@ -553,7 +571,10 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // Everything this wavefront has in flight (the tile's first stages and bias; the previous tile's stores,
     // which do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
     __builtin_amdgcn_s_waitcnt(0x0070);
+    MOE_PROF({ const unsigned long long t = __builtin_readcyclecounter(); if (pf.tiles) pf.epi += t - pf.last; pf.last = t; })
     __builtin_amdgcn_s_barrier();
+    MOE_PROF({ const unsigned long long t = __builtin_readcyclecounter(); if (pf.tiles) pf.tbar += t - pf.last; else pf.start = t - pf.c0;
+               pf.last = t; ++pf.tiles; })
     draw_next();
     // token blocks of this wavefront with at least one valid row (wave-uniform)
     const int tbv = min(TB, max(0, (ti.rows - wt * 32 + 32 * WT - 1) / (32 * WT)));
@@ -643,6 +664,12 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     if (!have) break;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only zero-length loads and stores remain; retire them
+  MOE_PROF(if (g_gemm_prof && lane == 0) {
+    unsigned long long* o = g_gemm_prof + ((size_t)(EPI == EPI_BIAS ? NUM_CU : 0) * 8 + (size_t)blockIdx.x * NW + wave) * PROF_SLOTS;
+    const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+    o[0] = pf.comp; o[1] = pf.vm; o[2] = pf.bar; o[3] = pf.steps; o[4] = pf.epi; o[5] = pf.tiles; o[6] = c1 - pf.last;
+    o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1;
+  })
 #endif
 }
 
@@ -764,3 +791,10 @@ bool gemm1_can_gather(const moe_config* cfg) {
 }
 
 }  // namespace moesys
+
+#ifdef MOESYS_GEMM_PROFILE
+// buf: device, 2 * 256 * 8 * 16 uint64, zeroed by the caller; NULL switches the recording off.
+extern "C" int32_t moe_gemm_profile_set(unsigned long long* buf) {
+  return moesys::check_hip(hipMemcpyToSymbol(HIP_SYMBOL(moesys::g_gemm_prof), &buf, sizeof(buf)), "hipMemcpyToSymbol");
+}
+#endif
