@@ -105,7 +105,8 @@ __device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcp
 struct TileInfo {
   int expert, row0, rows;  // first dispatched row and valid rows (<= TOK) of this tile
   int ntile;               // feature tile index
-  int pm, pn, gm, gn;      // position of the tile in its gm x gn block (the tiles an XCD works on together)
+  int pm, gm;              // this tile is number pm of the gm tiles of its block that use the same weight tile
+  int pn, gn;              // ... and number pn of the gn that use the same token tile
 };
 
 // Tile order.  Token tiles (of all experts, in row order) are grouped GM at a time and feature tiles GN
@@ -192,9 +193,12 @@ struct TileWalker {
         ti.row0 = r0;
         ti.rows = __builtin_amdgcn_readfirstlane(min(un * UNIT, e0 + n_rows - r0));
         ti.ntile = __builtin_amdgcn_readfirstlane(nt);
-        ti.pm = __builtin_amdgcn_readfirstlane(r / gn);
+        // who shares this tile's operands: the gn feature tiles of the block share the token tile; the weight
+        // tile is shared by those of the block's token tiles that belong to the same expert
+        const int m_lo = max(mg * GM, s_pref[lo]), m_hi = min(mg * GM + gm, s_pref[lo + 1]);
+        ti.pm = __builtin_amdgcn_readfirstlane(mt - m_lo);
+        ti.gm = __builtin_amdgcn_readfirstlane(m_hi - m_lo);
         ti.pn = __builtin_amdgcn_readfirstlane(r % gn);
-        ti.gm = __builtin_amdgcn_readfirstlane(gm);
         ti.gn = __builtin_amdgcn_readfirstlane(gn);
         return true;
       }
@@ -248,6 +252,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
   constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
   constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
+  constexpr int PF_MIN_KT = 64;            // shortest K loop (in K-steps) that prefetches, see bind_prefetch
 
   // LDS tile layout: row r keeps its logical 16-byte chunk c at physical chunk c ^ key(r), key(r) =
   // (r / RPB) mod CHUNKS.  The LDS serves 16 lanes x 16 B per clock over a 256-byte bank period; with this
@@ -383,11 +388,16 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // share a token tile each take a 1/gn slice of its rows and the gm workgroups that share a weight tile
   // a 1/gm slice of its rows, so every line is asked for once per XCD (asking from every workgroup doubles
   // the L2 request traffic and gains nothing).  Lanes without a line re-touch the tile's first weight line.
+  // Measured on MI355X, the prefetch pays only where the K loop is long and its operands are shared (second
+  // GEMM of the large SwiGLU workload +3.5 %, of the GPT-style one +2 %); with K of 1024-2048 or with weight
+  // tiles that no other workgroup reads (few rows per expert: the kernel is then bound by HBM, not by
+  // latency) it costs 5-20 %, so short K loops do not prefetch and unshared tiles are left out.
   const uint16_t* pf_ptr = wa;  // this lane's line at K-step 0 of the bound tile
   auto bind_prefetch = [&](const TileInfo& t) {
-    const int a_lo = t.pn * TOK / t.gn, a_n = (t.pn + 1) * TOK / t.gn - a_lo;
-    const int b_lo = t.pm * FEAT / t.gm, b_n = (t.pm + 1) * FEAT / t.gm - b_lo;
+    const int a_lo = t.pn * TOK / t.gn, a_n = t.gn > 1 ? (t.pn + 1) * TOK / t.gn - a_lo : 0;
+    const int b_lo = t.pm * FEAT / t.gm, b_n = t.gm > 1 ? (t.pm + 1) * FEAT / t.gm - b_lo : 0;
     pf_ptr = b_ptr;
+    if (KT < PF_MIN_KT) return;
     if (tid < a_n) {
       const int ar = a_lo + tid;
       if (ar < t.rows) {
