@@ -98,6 +98,17 @@ def main():
         stage += np.array(timer.read())
     stage /= args.steps
     stage_ms = dict(zip(M.STAGE_NAMES, [float(v) for v in stage]))
+    # the same with cold caches: 1 GiB streamed through L2 and the 256 MB last-level cache before every step
+    # (consecutive steps otherwise find part of x, h and yd still cached)
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cold = np.zeros(len(M.STAGE_NAMES))
+    n_cold = min(20, args.steps)
+    for _ in range(n_cold):
+        flush.fill_(1)
+        M.moe_layer_forward_timed(cfg, W, x, None, out, ws, timer, stream)
+        cold += np.array(timer.read())
+    cold /= max(n_cold, 1)
+    del flush
 
     lay = M.moe_workspace_layout(cfg)
     R = int(ws_view(ws, lay["expert_offsets"], cfg.E + 1, torch.int32)[-1].item())
@@ -128,6 +139,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if dom == "gemm1" else None,
                      "flops_per_launch": dom_flops, "avg_launch_ms": stage_ms[dom]},
         "stage_ms": stage_ms,
+        "stage_ms_cold_caches": dict(zip(M.STAGE_NAMES, [float(v) for v in cold])),
         "ffn_tflops": (flops1 + flops2) / ((stage_ms["gemm1"] + stage_ms["gemm2"]) * 1e-3) / 1e12,
         "hbm_gbs": hbm,
         "hbm_frac": {k: v / HBM_PEAK_GBS for k, v in hbm.items()},
