@@ -238,6 +238,26 @@ def test_single_expert_is_dense_ffn(act):
 
 
 @pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_expert_rows_square_matrices_bruteforce(act):
+    """d_model == d_ff, where a transposed matrix would go unnoticed by shapes: plain loops over indices."""
+    wl, L = tiny(T=3, d=4, f=4, E=2, k=1, act=act, seed=11)
+    x = L["x"].astype(np.float64)
+    for e in range(2):
+        got = O.expert_rows_ffn(x, e, L, act)
+        for t in range(3):
+            if act == "gelu":
+                hidden = [sum(x[t, i] * float(L["w1"][e][i, n]) for i in range(4)) + float(L["b1"][e][n]) for n in range(4)]
+                hidden = [0.5 * u * (1.0 + math.erf(u / math.sqrt(2.0))) for u in hidden]
+                want = [sum(hidden[n] * float(L["w2"][e][n, o]) for n in range(4)) + float(L["b2"][e][o]) for o in range(4)]
+            else:
+                g = [sum(x[t, i] * float(L["w_gate_proj"][e][i, n]) for i in range(4)) for n in range(4)]
+                u = [sum(x[t, i] * float(L["w_up"][e][i, n]) for i in range(4)) for n in range(4)]
+                hidden = [gg / (1.0 + math.exp(-gg)) * uu for gg, uu in zip(g, u)]
+                want = [sum(hidden[n] * float(L["w_down"][e][n, o]) for n in range(4)) for o in range(4)]
+            assert np.allclose(got[t], want, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
 def test_k_equals_E_is_full_softmax_mixture(act):
     wl, L = tiny(T=12, d=8, f=20, E=3, k=3, act=act, seed=11)
     r = O.layer_forward(L["x"], L, E=3, k=3, capacity_factor=0.0, renormalize=True, act=act)
