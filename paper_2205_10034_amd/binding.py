@@ -80,6 +80,9 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2205_10034_amd.build`")
+        # torch brings its own copy of the HIP runtime; it has to be the first one in the process, so that
+        # this library binds to the same runtime (and the same device context) as the tensors it is handed
+        import torch  # noqa: F401
         L = C.CDLL(_LIB_PATH)
         L.moe_status_string.restype = C.c_char_p
         L.moe_status_string.argtypes = [C.c_int32]

@@ -45,9 +45,11 @@ def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as ex:
         prof = ex.submit(_compile, "grouped_gemm_bf16.hip", "_prof", ("MOESYS_GEMM_PROFILE",))
+        peaks = ex.submit(_compile, "peaks.hip")  # machine peaks: diagnostics, linked into the timing build only
         objs = list(ex.map(_compile, SOURCES))
-        prof_obj = prof.result()
-    for lib, these in ((LIB, objs), (PROF_LIB, [prof_obj if o.endswith("grouped_gemm_bf16.o") else o for o in objs])):
+        prof_obj, peaks_obj = prof.result(), peaks.result()
+    prof_objs = [prof_obj if o.endswith("grouped_gemm_bf16.o") else o for o in objs] + [peaks_obj]
+    for lib, these in ((LIB, objs), (PROF_LIB, prof_objs)):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + these
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

@@ -1,0 +1,125 @@
+// Measured peaks of the machine, for the denominators quoted next to the kernels' numbers: a streaming
+// copy and a streaming read (HBM), a loop of nothing but bf16 MFMAs (matrix pipes, with the shader clock it
+// ran at) and conflict-free 16-byte LDS reads.  Diagnostics only: part of the phase-timing build of the
+// library, never of the product library; it allocates its own buffers.
+#include "moesys_internal.h"
+
+namespace moesys {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, size_t n, unsigned* out) {
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) acc |= src[i];
+  if ((acc.x | acc.y | acc.z | acc.w) == 0x12345u) out[0] = 1;  // never true for the zero-filled buffer; keeps the loads
+}
+
+// 8 independent accumulators per wavefront; clocks[0..1] of block 0 = shader clocks and 100 MHz ticks of the loop
+__global__ __launch_bounds__(512) void mfma_kernel(int iters, float* out, unsigned long long* clocks) {
+  f32x16 acc[8];
+  for (int i = 0; i < 8; ++i)
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  bf16x8 a, b;
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(float)(threadIdx.x & 3); b[i] = (__bf16)1.0f; }
+  const unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0;
+  for (int i = 0; i < 8; ++i) s += acc[i][0];
+  const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  if (s == 12345.f) out[0] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) { clocks[0] = c1 - c0; clocks[1] = r1 - r0; }
+}
+
+// every lane reads 16 bytes; rows of 128 bytes with the 16-byte chunk XOR-ed with (row/2) mod 8: the
+// layout of the GEMM's operand tiles, free of bank conflicts
+__global__ __launch_bounds__(512) void lds_kernel(int iters, unsigned* out, unsigned long long* clocks) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[65536];
+  for (int i = threadIdx.x; i < 65536 / 4; i += blockDim.x) ((unsigned*)smem)[i] = i;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, r = lane & 31, c = lane >> 5;
+  const int base = r * 128 + ((c ^ ((r >> 1) & 7)) << 4);
+  u32x4 acc = {0, 0, 0, 0};
+  const unsigned long long c0 = __builtin_readcyclecounter();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc += *reinterpret_cast<const u32x4*>(smem + ((base + j * 4096) & 65535));
+    asm volatile("" ::: "memory");
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter();
+  if (acc.x + acc.y + acc.z + acc.w == 0x12345u) out[0] = 1;
+  if (blockIdx.x == 0 && threadIdx.x == 0) clocks[2] = c1 - c0;
+}
+
+}  // namespace
+}  // namespace moesys
+
+using namespace moesys;
+
+// out (host, 6 doubles): copy GB/s (read + written bytes), read GB/s, MFMA TFLOP/s, shader clock of the MFMA
+// loop in MHz, LDS read bytes per shader clock per CU, number of CUs.
+extern "C" int32_t moe_hw_peaks(double* out) {
+  if (!out) return fail(MOE_ERR_INVALID_ARG, "moe_hw_peaks: out is NULL");
+  hipDeviceProp_t prop;
+  int32_t st;
+  if ((st = check_hip(hipGetDeviceProperties(&prop, 0), "hipGetDeviceProperties")) != MOE_OK) return st;
+  const int cus = prop.multiProcessorCount;
+  const size_t bytes = (size_t)1 << 30, n = bytes / 16;
+  void *src = nullptr, *dst = nullptr, *small = nullptr;
+  if ((st = check_hip(hipMalloc(&src, bytes), "hipMalloc")) != MOE_OK) return st;
+  if ((st = check_hip(hipMalloc(&dst, bytes), "hipMalloc")) != MOE_OK) return st;
+  if ((st = check_hip(hipMalloc(&small, 4096), "hipMalloc")) != MOE_OK) return st;
+  hipMemset(src, 0, bytes);
+  hipMemset(small, 0, 4096);
+  hipEvent_t e0, e1;
+  hipEventCreate(&e0);
+  hipEventCreate(&e1);
+  float ms = 0.f;
+  const int reps = 10;
+  hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)dst, n);
+  hipEventRecord(e0, 0);
+  for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)dst, n);
+  hipEventRecord(e1, 0);
+  hipEventSynchronize(e1);
+  hipEventElapsedTime(&ms, e0, e1);
+  out[0] = 2.0 * bytes * reps / (ms * 1e-3) / 1e9;
+  hipLaunchKernelGGL(read_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, n, (unsigned*)small);
+  hipEventRecord(e0, 0);
+  for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(read_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, n, (unsigned*)small);
+  hipEventRecord(e1, 0);
+  hipEventSynchronize(e1);
+  hipEventElapsedTime(&ms, e0, e1);
+  out[1] = (double)bytes * reps / (ms * 1e-3) / 1e9;
+  unsigned long long* clocks = (unsigned long long*)((char*)small + 1024);
+  const int iters = 20000;
+  hipLaunchKernelGGL(mfma_kernel, dim3(cus), dim3(512), 0, 0, 100, (float*)small, clocks);
+  hipEventRecord(e0, 0);
+  hipLaunchKernelGGL(mfma_kernel, dim3(cus), dim3(512), 0, 0, iters, (float*)small, clocks);
+  hipEventRecord(e1, 0);
+  hipEventSynchronize(e1);
+  hipEventElapsedTime(&ms, e0, e1);
+  out[2] = (double)cus * 8 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12;
+  const int lds_iters = 4000;
+  hipLaunchKernelGGL(lds_kernel, dim3(cus), dim3(512), 0, 0, lds_iters, (unsigned*)small, clocks);
+  unsigned long long h[3] = {0, 0, 0};
+  st = check_hip(hipMemcpy(h, clocks, sizeof(h), hipMemcpyDeviceToHost), "hipMemcpy");
+  out[3] = h[1] ? (double)h[0] / (double)h[1] * 100.0 : 0.0;
+  out[4] = h[2] ? 512.0 * 16 * 8 * lds_iters / (double)h[2] : 0.0;
+  out[5] = cus;
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  hipFree(src);
+  hipFree(dst);
+  hipFree(small);
+  if (st != MOE_OK) return st;
+  return check_hip(hipGetLastError(), "moe_hw_peaks");
+}
