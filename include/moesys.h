@@ -189,6 +189,9 @@ int32_t moe_combine(const moe_config* cfg, const void* yd, const int32_t* assign
 
 /* gate -> dispatch -> expert FFN -> combine on one stream with one workspace
  * (moe_workspace_bytes(cfg, MOE_WS_LAYER); layout from moe_workspace_layout).
+ * The workspace need not be cleared; it serves one call at a time (calls that
+ * overlap on the device need a workspace each).  Nothing is allocated and the
+ * device is never synchronised, so the call can be captured in a HIP graph.
  * x device [T,d_model]; residual device [T,d_model] or NULL; out device
  * [T,d_model] (may alias residual, must not alias x unless residual == x). */
 int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const void* x,

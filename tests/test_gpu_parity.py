@@ -311,3 +311,55 @@ def test_determinism():
     a = run_layer(cfg, W, x)["out_tensor"]
     b = run_layer(cfg, W, x)["out_tensor"]
     assert torch.equal(a, b)
+
+
+def test_layer_forward_does_not_need_a_cleared_workspace():
+    """Nothing in the workspace has to be zero (or anything else) on entry: random bytes, and the leftovers of
+    a call with a different routing, give the same bits as a cleared workspace."""
+    wl = small("gpt", T=2048, E=8)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    want = run_layer(cfg, W, x)["out_tensor"]
+    ws = alloc_ws(cfg)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    ws.copy_(torch.randint(0, 256, ws.shape, dtype=torch.uint8, device="cuda", generator=g))
+    out = torch.empty_like(x)
+    M.moe_layer_forward(cfg, W, x, None, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    x2 = to_dev(make_layer(wl.scaled(seed=wl.seed + 7))["x"], wl.dtype)   # other tokens, other routing
+    M.moe_layer_forward(cfg, W, x2, None, out, ws)
+    M.moe_layer_forward(cfg, W, x, None, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+
+
+def test_layer_forward_in_a_hip_graph():
+    """The call allocates nothing and never synchronises, so it can be captured; every replay (with eager
+    work and synchronisations in between) gives the eager result bit for bit."""
+    wl = small("gpt", T=2048, E=8)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    want = run_layer(cfg, W, x)["out_tensor"]
+    ws = alloc_ws(cfg)
+    out = torch.zeros_like(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        M.moe_layer_forward(cfg, W, x, None, out, ws, side)      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        M.moe_layer_forward(cfg, W, x, None, out, ws, torch.cuda.current_stream())
+    for rep in range(4):
+        out.fill_(float("nan"))
+        ws.fill_(rep)                       # eager work between the replays; the workspace content must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep} differs from the eager result"
