@@ -64,6 +64,10 @@ def main():
         run_case(rows, "gelu", 256, 512, 100 + i)
     run_case(ROW_SETS[0], "swiglu", 256, 256, 200)
     run_case(ROW_SETS[1], "gelu", 192, 320, 201)   # narrow-tile kernels
+    # K loops of one to five K-steps (the next tile is then resolved outside the K loop), wide and narrow tiles
+    for i, (d_model, d_ff) in enumerate([(64, 256), (256, 64), (128, 256), (192, 256), (320, 256), (64, 64)]):
+        run_case(ROW_SETS[0], "gelu", d_model, d_ff, 300 + i)
+    run_case(ROW_SETS[2], "swiglu", 64, 128, 310)
     return 0
 
 
