@@ -216,8 +216,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 }
 #endif
 
-// TOK x FEAT tile, WT x WF wavefronts, K-step KS, NST LDS stages; each wavefront owns (TOK/WT) tokens x
-// (FEAT/WF) LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
+// TOK x FEAT tile, WT x WF wavefronts, K-step KS, two LDS stages; each wavefront owns TOK/WT tokens (every
+// WT-th 32-row block) x FEAT/WF LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
 template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
