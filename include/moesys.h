@@ -103,7 +103,8 @@ typedef struct {
   size_t xd;             /* dtype [R_max,d_model] dispatched rows (MOE_F32 only: the
                             bf16 FFN gathers its rows from x through row_to_assign) */
   size_t h;              /* dtype [R_max,d_ff]    hidden activations            */
-  size_t yd;             /* dtype [R_max,d_model] expert outputs                */
+  size_t yd;             /* dtype [R_max,d_model] expert outputs (not written when k == 1
+                            in MOE_BF16: the second GEMM then writes `out` itself)    */
   size_t scratch;        /* dispatch bookkeeping scratch                        */
   size_t tile_counters;  /* int32 [16] work counters of the two grouped GEMMs   */
   size_t total;          /* == moe_workspace_bytes(cfg, MOE_WS_LAYER)           */
@@ -193,7 +194,13 @@ int32_t moe_combine(const moe_config* cfg, const void* yd, const int32_t* assign
  * overlap on the device need a workspace each).  Nothing is allocated and the
  * device is never synchronised, so the call can be captured in a HIP graph.
  * x device [T,d_model]; residual device [T,d_model] or NULL; out device
- * [T,d_model] (may alias residual, must not alias x unless residual == x). */
+ * [T,d_model] (may alias residual, must not alias x unless residual == x).
+ * Fusions inside the call (MOE_BF16): the first GEMM gathers its rows from x
+ * through row_to_assign, so no dispatched copy xd is made; with k == 1 the
+ * second GEMM scales each row by its gate weight, adds the residual in fp32
+ * and stores it at its token's place in `out` (one rounding; no yd, and the
+ * combine stage only fills the rows of dropped tokens) -- the kernel fusion
+ * the paper asks for in Section 3.3.1. */
 int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const void* x,
                           const void* residual, void* out, void* ws, size_t ws_bytes, void* stream);
 

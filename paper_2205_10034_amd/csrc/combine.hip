@@ -75,7 +75,26 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
   }
 }
 
+// k = 1: rows of the tokens whose assignment was dropped (the others are written by the second GEMM).
+__global__ __launch_bounds__(256) void fill_dropped_kernel(const int32_t* __restrict__ a2r, const uint4* residual, uint4* out,
+                                                           int T, int row_vec) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T || a2r[t] >= 0) return;
+  if (residual == out) return;  // in place: the row already holds its residual
+  for (int v = lane; v < row_vec; v += 64)
+    out[(size_t)t * row_vec + v] = residual ? residual[(size_t)t * row_vec + v] : uint4{0u, 0u, 0u, 0u};
+}
+
 }  // namespace
+
+int32_t launch_fill_dropped(const moe_config* cfg, const int32_t* a2r, const void* residual, void* out, hipStream_t s) {
+  if (cfg->T == 0) return MOE_OK;
+  const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
+  hipLaunchKernelGGL(fill_dropped_kernel, dim3((cfg->T + 3) / 4), dim3(256), 0, s, a2r, (const uint4*)residual, (uint4*)out,
+                     cfg->T, row_vec);
+  return check_hip(hipGetLastError(), "fill launch");
+}
 
 int32_t launch_combine(const moe_config* cfg, const void* yd, const int32_t* a2r, const float* topk_w,
                        const void* residual, void* out, hipStream_t s) {

@@ -11,6 +11,8 @@ namespace moesys {
 int32_t launch_gemm1_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, const int32_t*, int32_t*,
                           hipStream_t);
 int32_t launch_gemm2_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, void*, int32_t*, hipStream_t);
+int32_t launch_gemm2_combine_bf16(const moe_config*, const moe_weights*, const void*, const int32_t*, const int32_t*,
+                                  const float*, const void*, void*, int32_t*, hipStream_t);
 
 namespace {
 
@@ -139,6 +141,17 @@ int32_t launch_gemm2(const moe_config* cfg, const moe_weights* w, const void* h,
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
   return launch_f32(cfg, F_BIAS, (const float*)h, (const float*)(sw ? w->w_down : w->w2), nullptr,
                     (const float*)(sw ? nullptr : w->b2), offsets, (float*)yd, cfg->d_model, cfg->d_ff, w->layout, s);
+}
+
+// With one expert per token a dispatched row is the only term of its token's output, so the second GEMM can
+// finish the combine itself (bf16 only).
+bool gemm2_can_combine(const moe_config* cfg) { return cfg->dtype == MOE_BF16 && cfg->k == 1; }
+
+int32_t launch_gemm2_combine(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
+                             const int32_t* r2a, const float* topk_w, const void* residual, void* out,
+                             int32_t* tile_counters, hipStream_t s) {
+  if (!gemm2_can_combine(cfg)) return fail(MOE_ERR_UNSUPPORTED, "combine in the second GEMM needs bf16 and k = 1");
+  return launch_gemm2_combine_bf16(cfg, w, h, offsets, r2a, topk_w, residual, out, tile_counters, s);
 }
 
 }  // namespace moesys

@@ -69,7 +69,9 @@ constexpr int NUM_XCD = 8;
 constexpr int CU_PER_XCD = 32;
 constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
 
-enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2 };
+// EPI_COMBINE: the second GEMM with the top-1 combine folded in: row r goes to token row_map[r] as
+// residual + gate weight * (product + bias), rounded once.
+enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // two floats -> two bf16 in one dword (lo in the low half): one v_cvt_pk_bf16_f32, round to nearest even
@@ -225,8 +227,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ wb,      // [E, N, K]   (Wu, SwiGLU only)
     const uint16_t* __restrict__ bias,    // [E, N] or NULL
     const int32_t* __restrict__ offsets,  // [E+1]
-    uint16_t* __restrict__ out,           // [R, N]
+    uint16_t* out,                        // [R, N]; EPI_COMBINE: [T, N], may be the residual itself
     const int32_t* __restrict__ row_map,  // GATHER: row_to_assign; act is then x[T,K] and row r reads token row_map[r] mod T
+                                          // EPI_COMBINE: row_to_assign with k = 1, i.e. the token of every row
+    const float* __restrict__ gate_w,     // EPI_COMBINE: [T] gate weight of every token
+    const uint16_t* residual,             // EPI_COMBINE: [T, N] or NULL
     int32_t* __restrict__ tile_ctr,       // [NUM_XCD] zero at launch: tiles handed out beyond each workgroup's first
     int32_t* __restrict__ clear_ctr,      // [NUM_XCD] or NULL: cleared here for the kernel that runs next
     int T, int E, int N, int K) {
@@ -272,6 +277,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // each wavefront's own slice of the tile's bias (WFEAT bf16 in the first bytes of its 256-byte slot); two
   // sets, because the next tile's bias is requested before the current tile's epilogue reads its own
   __shared__ __attribute__((aligned(256))) unsigned char s_bias[EPI == EPI_SWIGLU ? 256 : 2 * NW * 256];
+  // EPI_COMBINE: the token of every row of the tile, two sets like the bias
+  __shared__ int s_rowtok[EPI == EPI_COMBINE ? 2 * NW * 64 : 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wt = wave / WF, wf = wave % WF;
@@ -430,6 +437,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       const uint16_t* brow = bias ? bias + (size_t)t.expert * N + (size_t)t.ntile * OUT_FEAT + wf * WFEAT : act;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(make_rsrc(brow, bias ? (uint32_t)WFEAT * 2u : 0u),
                                                (__attribute__((address_space(3))) void*)(s_bias + (bias_set * NW + wave) * 256), 4, lane * 4, 0, 0, 0);
+    }
+    if constexpr (EPI == EPI_COMBINE) {  // one row id per thread, threads past the last row re-read it
+      const int32_t* src = row_map + t.row0 + min(tid, t.rows - 1);
+      __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(s_rowtok + (bias_set * NW + wave) * 64), 4, 0, 0);
     }
   };
 
@@ -634,11 +646,21 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       const u32x2 sy = __builtin_amdgcn_permlane32_swap(pack_bf16(p[2], p[3]), pack_bf16(p[6], p[7]), false, false);
       *reinterpret_cast<u32x4*>(orow + n0 + 8 * (i0 + fhalf)) = u32x4{sx.x, sy.x, sx.y, sy.y};
     };
+    int row_tok[TB];   // EPI_COMBINE: token and gate weight of this lane's row in every token block
+    float row_gw[TB];
+    if constexpr (EPI == EPI_COMBINE) {
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) {
+        row_tok[tb] = s_rowtok[done_set * NW * 64 + min((tb * WT + wt) * 32 + frow, done.rows - 1)];
+        row_gw[tb] = gate_w[row_tok[tb]];
+      }
+    }
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       const int trow = (tb * WT + wt) * 32 + frow;
       if (trow >= done.rows) continue;  // (lanes l and l+32 share the row: they stay or leave together)
-      uint16_t* orow = out + (size_t)(done.row0 + trow) * N;
+      const size_t orow_idx = EPI == EPI_COMBINE ? (size_t)row_tok[tb] : (size_t)(done.row0 + trow);
+      uint16_t* orow = out + orow_idx * N;
       if (EPI == EPI_SWIGLU) {
 #pragma unroll
         for (int i0 = 0; i0 < 4; i0 += 2) {
@@ -667,6 +689,20 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #pragma unroll
               for (int r = 0; r < 8; ++r) p[r] = gelu_table(p[r], s_phi);
             }
+            if constexpr (EPI == EPI_COMBINE) {
+              // before the lanes trade halves: this lane's 4 + 4 features of the residual row
+#pragma unroll
+              for (int g = 0; g < 2; ++g) {
+                u32x2 rv = {0u, 0u};
+                if (residual)
+                  rv = *reinterpret_cast<const u32x2*>(residual + orow_idx * N + feat0 + wf * WFEAT + fb * 32 +
+                                                       8 * (i0 + g) + 4 * fhalf);
+                p[4 * g + 0] = __builtin_fmaf(row_gw[tb], p[4 * g + 0], bf16_bits_to_f32(rv.x & 0xffffu));
+                p[4 * g + 1] = __builtin_fmaf(row_gw[tb], p[4 * g + 1], __uint_as_float(rv.x & 0xffff0000u));
+                p[4 * g + 2] = __builtin_fmaf(row_gw[tb], p[4 * g + 2], bf16_bits_to_f32(rv.y & 0xffffu));
+                p[4 * g + 3] = __builtin_fmaf(row_gw[tb], p[4 * g + 3], __uint_as_float(rv.y & 0xffff0000u));
+              }
+            }
             store_pair(orow, feat0 + wf * WFEAT + fb * 32, i0, p);
           }
       }
@@ -675,7 +711,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only zero-length loads and stores remain; retire them
   MOE_PROF(if (g_gemm_prof && lane == 0) {
-    unsigned long long* o = g_gemm_prof + ((size_t)(EPI == EPI_BIAS ? NUM_CU : 0) * 8 + (size_t)blockIdx.x * NW + wave) * PROF_SLOTS;
+    unsigned long long* o = g_gemm_prof + ((size_t)(EPI >= EPI_BIAS ? NUM_CU : 0) * 8 + (size_t)blockIdx.x * NW + wave) * PROF_SLOTS;
     const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
     o[0] = pf.comp; o[1] = pf.vm; o[2] = pf.bar; o[3] = pf.steps; o[4] = pf.epi; o[5] = pf.tiles; o[6] = c1 - pf.last;
     o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1;
@@ -686,7 +722,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
-               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s) {
+               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s, const float* gate_w = nullptr,
+               const uint16_t* residual = nullptr) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
@@ -707,13 +744,15 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
   // the gathering variant exists for the first GEMM's epilogues only
   auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false>;
-  if constexpr (EPI != EPI_BIAS) {
+  if constexpr (EPI == EPI_GELU || EPI == EPI_SWIGLU) {
     if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true>;
-  } else {
+  } else if constexpr (EPI == EPI_BIAS) {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
+  } else {
+    if (!row_map || !gate_w || cfg->k != 1) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: combine epilogue needs k = 1, row map and gate weights");
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out, row_map,
-                     tile_ctr, clear_ctr, cfg->T, cfg->E, N, K);
+                     gate_w, residual, tile_ctr, clear_ctr, cfg->T, cfg->E, N, K);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
@@ -757,17 +796,17 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
 template <int EPI>
 int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
                  const int32_t* offsets, uint16_t* o, const int32_t* row_map, int32_t* tile_ctr, int32_t* clear_ctr, int N,
-                 int K, hipStream_t s) {
+                 int K, hipStream_t s, const float* gate_w = nullptr, const uint16_t* residual = nullptr) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
     if (pick_tile_rows(cfg, N / BF) == 320)
-      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
-    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
+      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
+    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
+    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
   else
-    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s);
+    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
 }
 
 }  // namespace
@@ -793,6 +832,18 @@ int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const voi
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
       (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, nullptr,
       cfg->d_model, cfg->d_ff, s);
+}
+
+// The second GEMM with the top-1 combine in its epilogue: out[T, d_model] rows of the tokens that kept their
+// expert are written here, the others by the caller.
+int32_t launch_gemm2_combine_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
+                                  const int32_t* row_to_assign, const float* topk_w, const void* residual, void* out,
+                                  int32_t* tile_counters, hipStream_t s) {
+  const bool sw = cfg->act == MOE_ACT_SWIGLU;
+  return gemm_any<EPI_COMBINE>(
+      cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
+      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)out, row_to_assign, tile_counters + NUM_XCD, nullptr,
+      cfg->d_model, cfg->d_ff, s, topk_w, (const uint16_t*)residual);
 }
 
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.

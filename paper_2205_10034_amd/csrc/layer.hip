@@ -50,9 +50,19 @@ int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, c
   if ((st = mark(2)) != MOE_OK) return st;
   if ((st = launch_gemm1(cfg, w, gather ? x : xd, offsets, h, gather ? r2a : nullptr, tile_ctr, s)) != MOE_OK) return st;
   if ((st = mark(3)) != MOE_OK) return st;
-  if ((st = launch_gemm2(cfg, w, h, offsets, yd, tile_ctr, s)) != MOE_OK) return st;
-  if ((st = mark(4)) != MOE_OK) return st;
-  if ((st = launch_combine(cfg, yd, a2r, topk_w, residual, out, s)) != MOE_OK) return st;
+  if (gemm2_can_combine(cfg)) {
+    // one expert per token: the second GEMM scales each row by its gate weight, adds the residual and writes
+    // it to its token's place; what is left of the combine stage are the rows of dropped tokens
+    if ((st = launch_gemm2_combine(cfg, w, h, offsets, r2a, topk_w, residual, out, tile_ctr, s)) != MOE_OK) return st;
+    if ((st = mark(4)) != MOE_OK) return st;
+    const int64_t C = moe_capacity(cfg);  // an expert gets at most T rows: no drops unless C is smaller
+    if (C != MOE_DROPLESS && C < cfg->T)
+      if ((st = launch_fill_dropped(cfg, a2r, residual, out, s)) != MOE_OK) return st;
+  } else {
+    if ((st = launch_gemm2(cfg, w, h, offsets, yd, tile_ctr, s)) != MOE_OK) return st;
+    if ((st = mark(4)) != MOE_OK) return st;
+    if ((st = launch_combine(cfg, yd, a2r, topk_w, residual, out, s)) != MOE_OK) return st;
+  }
   if ((st = mark(5)) != MOE_OK) return st;
   if (timer) timer->recorded = true;
   return MOE_OK;

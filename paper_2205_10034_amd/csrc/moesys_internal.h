@@ -45,6 +45,14 @@ int32_t launch_gemm1(const moe_config* cfg, const moe_weights* w, const void* xd
 bool gemm1_can_gather(const moe_config* cfg);
 int32_t launch_gemm2(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
                      void* yd, int32_t* tile_counters, hipStream_t s);
+// k = 1, bf16: the second GEMM writes out[t] = residual[t] + topk_w[t] * FFN row for every token that kept its
+// expert; launch_fill_dropped writes the others (residual[t], or zero).  Together they replace
+// launch_gemm2 + launch_combine and the dispatched-order output yd.
+bool gemm2_can_combine(const moe_config* cfg);
+int32_t launch_gemm2_combine(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
+                             const int32_t* r2a, const float* topk_w, const void* residual, void* out,
+                             int32_t* tile_counters, hipStream_t s);
+int32_t launch_fill_dropped(const moe_config* cfg, const int32_t* a2r, const void* residual, void* out, hipStream_t s);
 int32_t launch_combine(const moe_config* cfg, const void* yd, const int32_t* a2r, const float* topk_w,
                        const void* residual, void* out, hipStream_t s);
 int32_t check_weights(const moe_config* cfg, const moe_weights* w);
