@@ -96,11 +96,20 @@ __device__ __forceinline__ void fill_phi_table(f32x2* tab) {
     tab[i] = f32x2{p0, p1 - p0};
   }
 }
-__device__ __forceinline__ float gelu_table(float u, const f32x2* tab) {
-  float t = fmaf(u, PHI_SCALE, PHI_RANGE * PHI_SCALE);
-  t = __builtin_amdgcn_fmed3f(t, 0.0f, (float)PHI_N - 0.001f);
-  const f32x2 e = tab[(int)t];
-  return u * fmaf(__builtin_amdgcn_fractf(t), e.y, e.x);  // t >= 0: fract(t) = t - floor(t)
+// B values at a time, in three passes: table positions, the B table reads back to back, the
+// interpolations.  (One value at a time the compiler waits for every read before it starts the next
+// value, and the epilogue then runs at the latency of the LDS instead of at the rate of the vector ALU.)
+template <int B>
+__device__ __forceinline__ void gelu_table_n(float* u, const f32x2* tab) {
+  float t[B];
+  f32x2 e[B];
+#pragma unroll
+  for (int r = 0; r < B; ++r)
+    t[r] = __builtin_amdgcn_fmed3f(fmaf(u[r], PHI_SCALE, PHI_RANGE * PHI_SCALE), 0.0f, (float)PHI_N - 0.001f);
+#pragma unroll
+  for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
+#pragma unroll
+  for (int r = 0; r < B; ++r) u[r] *= fmaf(__builtin_amdgcn_fractf(t[r]), e[r].y, e[r].x);  // t >= 0: fract(t) = t - floor(t)
 }
 __device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
@@ -686,8 +695,9 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
               p[4 * g + 3] = acc[tb][fb][4 * (i0 + g) + 3] + __uint_as_float(b.y & 0xffff0000u);
             }
             if (EPI == EPI_GELU) {
+              constexpr int GB = TOK > 256 ? 4 : 8;  // (8 at a time spills in the 320-row kernel)
 #pragma unroll
-              for (int r = 0; r < 8; ++r) p[r] = gelu_table(p[r], s_phi);
+              for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, s_phi);
             }
             if constexpr (EPI == EPI_COMBINE) {
               // before the lanes trade halves: this lane's 4 + 4 features of the residual row
