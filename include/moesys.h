@@ -276,6 +276,34 @@ int32_t moe_ring_release(moe_ring* r, int32_t layer, void* compute_stream);
 int32_t moe_ring_stats(moe_ring* r, uint64_t* bytes_copied, uint64_t* copies, double* copy_ms);
 int32_t moe_ring_destroy(moe_ring* r);
 
+/* ---- frequency-based expert cache (Algorithm 2, Section 3.2.2) ----------- */
+/*
+ * Host-side policy deciding which items (experts, numbered by the caller, e.g.
+ * layer*E + e) occupy the `slots` slots of a pool in the faster memory.  It is
+ * the paper's LFU-like scheduling of sparse parameters one tier up (pinned
+ * host memory -> HBM instead of SSD -> CPU memory): a request of a cached item
+ * adds one to its hit count; a new item takes a free slot, or with the pool
+ * full the slot of the item with the lowest hit count among those whose count
+ * is >= threshold (none such: the lowest count overall; ties: cached
+ * earliest); after every decay_steps requests all counts are multiplied by
+ * beta.  Items requested since the last moe_expert_cache_begin_batch are
+ * never evicted (one layer's experts are needed together); MOE_ERR_STATE if
+ * that leaves no slot.  No GPU call is made: the caller moves the data.
+ */
+typedef struct moe_expert_cache moe_expert_cache;
+int32_t moe_expert_cache_create(moe_expert_cache** out, int32_t slots, float threshold, float beta,
+                                int32_t decay_steps);
+int32_t moe_expert_cache_destroy(moe_expert_cache* c);
+int32_t moe_expert_cache_begin_batch(moe_expert_cache* c);
+/* One request.  *slot: where `item` (>= 0) now lives; *hit (nullable): 1 if it
+ * was cached already; *evicted (nullable): the item that lost its slot, or -1. */
+int32_t moe_expert_cache_schedule(moe_expert_cache* c, int64_t item, int32_t* slot, int32_t* hit,
+                                  int64_t* evicted);
+/* *slot = -1 and *hits = 0 if `item` is not cached (nullable outputs). */
+int32_t moe_expert_cache_lookup(const moe_expert_cache* c, int64_t item, int32_t* slot, double* hits);
+int32_t moe_expert_cache_stats(const moe_expert_cache* c, uint64_t* hits, uint64_t* misses,
+                               uint64_t* evictions);
+
 #ifdef __cplusplus
 }
 #endif

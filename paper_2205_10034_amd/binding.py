@@ -110,6 +110,13 @@ def lib() -> C.CDLL:
         L.moe_ring_release.argtypes = [vp, C.c_int32, vp]
         L.moe_ring_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
         L.moe_ring_destroy.argtypes = [vp]
+        L.moe_expert_cache_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_float, C.c_float, C.c_int32]
+        L.moe_expert_cache_destroy.argtypes = [vp]
+        L.moe_expert_cache_begin_batch.argtypes = [vp]
+        L.moe_expert_cache_schedule.argtypes = [vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                                C.POINTER(C.c_int64)]
+        L.moe_expert_cache_lookup.argtypes = [vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+        L.moe_expert_cache_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         _lib = L
     return _lib
 
@@ -299,6 +306,47 @@ class Ring:
     def close(self):
         if self.h:
             lib().moe_ring_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class ExpertCache:
+    """moe_expert_cache_* wrapper: the frequency-based residency policy (host only)."""
+
+    def __init__(self, slots: int, threshold: float, beta: float, decay_steps: int):
+        self.h = C.c_void_p()
+        _check(lib().moe_expert_cache_create(C.byref(self.h), slots, threshold, beta, decay_steps),
+               "moe_expert_cache_create")
+
+    def begin_batch(self) -> None:
+        _check(lib().moe_expert_cache_begin_batch(self.h), "moe_expert_cache_begin_batch")
+
+    def schedule(self, item: int):
+        """-> (slot, hit, evicted item or -1)"""
+        slot, hit, gone = C.c_int32(), C.c_int32(), C.c_int64()
+        _check(lib().moe_expert_cache_schedule(self.h, item, C.byref(slot), C.byref(hit), C.byref(gone)),
+               "moe_expert_cache_schedule")
+        return slot.value, bool(hit.value), gone.value
+
+    def lookup(self, item: int):
+        """-> (slot or -1, hit count)"""
+        slot, hits = C.c_int32(), C.c_double()
+        _check(lib().moe_expert_cache_lookup(self.h, item, C.byref(slot), C.byref(hits)), "moe_expert_cache_lookup")
+        return slot.value, hits.value
+
+    def stats(self):
+        h, m, e = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        _check(lib().moe_expert_cache_stats(self.h, C.byref(h), C.byref(m), C.byref(e)), "moe_expert_cache_stats")
+        return {"hits": h.value, "misses": m.value, "evictions": e.value}
+
+    def close(self):
+        if self.h:
+            lib().moe_expert_cache_destroy(self.h)
             self.h = C.c_void_p()
 
     def __del__(self):

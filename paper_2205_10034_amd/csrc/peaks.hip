@@ -78,35 +78,35 @@ extern "C" int32_t moe_hw_peaks(double* out) {
   if ((st = check_hip(hipMalloc(&src, bytes), "hipMalloc")) != MOE_OK) return st;
   if ((st = check_hip(hipMalloc(&dst, bytes), "hipMalloc")) != MOE_OK) return st;
   if ((st = check_hip(hipMalloc(&small, 4096), "hipMalloc")) != MOE_OK) return st;
-  hipMemset(src, 0, bytes);
-  hipMemset(small, 0, 4096);
+  (void)hipMemset(src, 0, bytes);
+  (void)hipMemset(small, 0, 4096);
   hipEvent_t e0, e1;
-  hipEventCreate(&e0);
-  hipEventCreate(&e1);
+  (void)hipEventCreate(&e0);
+  (void)hipEventCreate(&e1);
   float ms = 0.f;
   const int reps = 10;
   hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)dst, n);
-  hipEventRecord(e0, 0);
+  (void)hipEventRecord(e0, 0);
   for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)dst, n);
-  hipEventRecord(e1, 0);
-  hipEventSynchronize(e1);
-  hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventRecord(e1, 0);
+  (void)hipEventSynchronize(e1);
+  (void)hipEventElapsedTime(&ms, e0, e1);
   out[0] = 2.0 * bytes * reps / (ms * 1e-3) / 1e9;
   hipLaunchKernelGGL(read_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, n, (unsigned*)small);
-  hipEventRecord(e0, 0);
+  (void)hipEventRecord(e0, 0);
   for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(read_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, n, (unsigned*)small);
-  hipEventRecord(e1, 0);
-  hipEventSynchronize(e1);
-  hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventRecord(e1, 0);
+  (void)hipEventSynchronize(e1);
+  (void)hipEventElapsedTime(&ms, e0, e1);
   out[1] = (double)bytes * reps / (ms * 1e-3) / 1e9;
   unsigned long long* clocks = (unsigned long long*)((char*)small + 1024);
   const int iters = 20000;
   hipLaunchKernelGGL(mfma_kernel, dim3(cus), dim3(512), 0, 0, 100, (float*)small, clocks);
-  hipEventRecord(e0, 0);
+  (void)hipEventRecord(e0, 0);
   hipLaunchKernelGGL(mfma_kernel, dim3(cus), dim3(512), 0, 0, iters, (float*)small, clocks);
-  hipEventRecord(e1, 0);
-  hipEventSynchronize(e1);
-  hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventRecord(e1, 0);
+  (void)hipEventSynchronize(e1);
+  (void)hipEventElapsedTime(&ms, e0, e1);
   out[2] = (double)cus * 8 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12;
   const int lds_iters = 4000;
   hipLaunchKernelGGL(lds_kernel, dim3(cus), dim3(512), 0, 0, lds_iters, (unsigned*)small, clocks);
@@ -115,11 +115,11 @@ extern "C" int32_t moe_hw_peaks(double* out) {
   out[3] = h[1] ? (double)h[0] / (double)h[1] * 100.0 : 0.0;
   out[4] = h[2] ? 512.0 * 16 * 8 * lds_iters / (double)h[2] : 0.0;
   out[5] = cus;
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
-  hipFree(src);
-  hipFree(dst);
-  hipFree(small);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(src);
+  (void)hipFree(dst);
+  (void)hipFree(small);
   if (st != MOE_OK) return st;
   return check_hip(hipGetLastError(), "moe_hw_peaks");
 }
