@@ -77,7 +77,14 @@ typedef struct {
  *   INPUT_MAJOR : w1,w_gate_proj,w_up [E,d_model,d_ff];  w2,w_down [E,d_ff,d_model]
  *   OUTPUT_MAJOR: w1,w_gate_proj,w_up [E,d_ff,d_model];  w2,w_down [E,d_model,d_ff]
  * b1 [E,d_ff], b2 [E,d_model] in the activation dtype.
- * w_router [d_model,E] and b_router [E] (nullable) are float32. */
+ * w_router [d_model,E] and b_router [E] (nullable) are float32.
+ * expert_elem_offset (nullable; MOE_BF16 only): device int64 [E].  When given,
+ * the experts are not one [E,...] array each: expert e's matrices and biases
+ * start expert_elem_offset[e] elements after the respective base pointer (the
+ * same offset for all of them), e.g. one blob per expert in a pool of slots
+ * with w1 = pool, w2 = pool + d_ff*d_model, b1 = pool + 2*d_ff*d_model, ...
+ * Offsets must be multiples of 8 elements.  Only experts that own rows are
+ * dereferenced. */
 typedef struct {
   const void* w1;
   const void* b1;
@@ -89,6 +96,7 @@ typedef struct {
   const float* w_router;
   const float* b_router;
   int32_t layout; /* moe_layout of the expert matrices */
+  const int64_t* expert_elem_offset;
 } moe_weights;
 
 /* Byte offsets of every intermediate inside the workspace of moe_layer_forward
@@ -202,6 +210,19 @@ int32_t moe_combine(const moe_config* cfg, const void* yd, const int32_t* assign
  * combine stage only fills the rows of dropped tokens) -- the kernel fusion
  * the paper asks for in Section 3.3.1. */
 int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const void* x,
+                          const void* residual, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/* The two halves of moe_layer_forward, for callers that have to look at the
+ * routing before the experts run (e.g. to bring the activated experts'
+ * parameters into HBM first, see moe_expert_pool_*): moe_layer_route runs
+ * gate and dispatch bookkeeping into the workspace (w->w_router, w->b_router
+ * are the only weights read); moe_layer_experts runs expert FFN and combine
+ * from what moe_layer_route left in the same workspace.  Same arguments,
+ * workspace and rules as moe_layer_forward; calling one after the other is
+ * moe_layer_forward. */
+int32_t moe_layer_route(const moe_config* cfg, const moe_weights* w, const void* x, void* ws,
+                        size_t ws_bytes, void* stream);
+int32_t moe_layer_experts(const moe_config* cfg, const moe_weights* w, const void* x,
                           const void* residual, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /* Same as moe_layer_forward, additionally recording HIP events on `stream`

@@ -40,7 +40,8 @@ class _Config(C.Structure):
 class _Weights(C.Structure):
     _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p),
                 ("w_gate_proj", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
-                ("w_router", C.c_void_p), ("b_router", C.c_void_p), ("layout", C.c_int32)]
+                ("w_router", C.c_void_p), ("b_router", C.c_void_p), ("layout", C.c_int32),
+                ("expert_elem_offset", C.c_void_p)]
 
 
 class _WsLayout(C.Structure):
@@ -99,6 +100,8 @@ def lib() -> C.CDLL:
         L.moe_expert_ffn.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
         L.moe_combine.argtypes = [C.POINTER(_Config)] + [vp] * 6
         L.moe_layer_forward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
+        L.moe_layer_route.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, C.c_size_t, vp]
+        L.moe_layer_experts.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
         L.moe_layer_forward_timed.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp, vp]
         L.moe_timer_create.argtypes = [C.POINTER(vp)]
         L.moe_timer_destroy.argtypes = [vp]
@@ -176,7 +179,8 @@ class Weights:
         g = lambda n: _ptr(self.tensors.get(n))
         self.c = _Weights(g("w1"), g("b1"), g("w2"), g("b2"), g("w_gate_proj"), g("w_up"), g("w_down"),
                           g("w_router"), g("b_router"),
-                          MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR)
+                          MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR,
+                          g("expert_elem_offset"))
 
 
 def moe_capacity(cfg: MoEConfig) -> int:
@@ -234,6 +238,20 @@ def moe_layer_forward(cfg, weights: Weights, x, residual, out, ws, stream=None):
     _check(lib().moe_layer_forward(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_forward")
+
+
+def moe_layer_route(cfg, weights: Weights, x, ws, stream=None):
+    c = cfg.c()
+    _check(lib().moe_layer_route(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(ws),
+                                 ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "moe_layer_route")
+
+
+def moe_layer_experts(cfg, weights: Weights, x, residual, out, ws, stream=None):
+    c = cfg.c()
+    _check(lib().moe_layer_experts(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
+                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "moe_layer_experts")
 
 
 class StageTimer:

@@ -103,6 +103,8 @@ int32_t check_weights(const moe_config* cfg, const moe_weights* w) {
   }
   if (cfg->dtype == MOE_BF16 && w->layout != MOE_LAYOUT_OUTPUT_MAJOR)
     return fail(MOE_ERR_UNSUPPORTED, "bf16 experts must be MOE_LAYOUT_OUTPUT_MAJOR (use moe_transpose_expert_weights once)");
+  if (w->expert_elem_offset && cfg->dtype != MOE_BF16)
+    return fail(MOE_ERR_UNSUPPORTED, "per-expert offsets (expert_elem_offset) are supported for bf16 experts only");
   return MOE_OK;
 }
 

@@ -241,6 +241,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
                                           // EPI_COMBINE: row_to_assign with k = 1, i.e. the token of every row
     const float* __restrict__ gate_w,     // EPI_COMBINE: [T] gate weight of every token
     const uint16_t* residual,             // EPI_COMBINE: [T, N] or NULL
+    const int64_t* __restrict__ eoff,     // [E] or NULL: expert e's weights (and bias) start eoff[e] elements after
+                                          // wa/wb (bias) instead of e*N*K (e*N)
     int32_t* __restrict__ tile_ctr,       // [NUM_XCD] zero at launch: tiles handed out beyond each workgroup's first
     int32_t* __restrict__ clear_ctr,      // [NUM_XCD] or NULL: cleared here for the kernel that runs next
     int T, int E, int N, int K) {
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   uint32_t a_bytes = 0;
   const uint32_t b_bytes = (uint32_t)B_ROWS * row_bytes;
   auto bind_tile = [&](const TileInfo& t) {
-    const size_t woff = ((size_t)t.expert * N + (size_t)t.ntile * OUT_FEAT) * K;
+    const size_t woff = (eoff ? (size_t)eoff[t.expert] : (size_t)t.expert * N * K) + (size_t)t.ntile * OUT_FEAT * K;
     a_ptr = GATHER ? act : act + (size_t)t.row0 * K;
     b_ptr = wa + woff;
     b2_ptr = (EPI == EPI_SWIGLU ? wb : wa) + woff;
@@ -443,7 +445,9 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     if constexpr (EPI != EPI_SWIGLU) {
       // this wavefront's WFEAT bias values: lanes 0..WFEAT/2-1 move one dword each, the others (and every
       // lane when there is no bias) read out of range, which stores zeros
-      const uint16_t* brow = bias ? bias + (size_t)t.expert * N + (size_t)t.ntile * OUT_FEAT + wf * WFEAT : act;
+      const uint16_t* brow = bias ? bias + (eoff ? (size_t)eoff[t.expert] : (size_t)t.expert * N) +
+                                        (size_t)t.ntile * OUT_FEAT + wf * WFEAT
+                                  : act;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(make_rsrc(brow, bias ? (uint32_t)WFEAT * 2u : 0u),
                                                (__attribute__((address_space(3))) void*)(s_bias + (bias_set * NW + wave) * 256), 4, lane * 4, 0, 0, 0);
     }
@@ -732,8 +736,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
-               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s, const float* gate_w = nullptr,
-               const uint16_t* residual = nullptr) {
+               int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s, const int64_t* eoff,
+               const float* gate_w = nullptr, const uint16_t* residual = nullptr) {
   constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
@@ -762,7 +766,7 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
     if (!row_map || !gate_w || cfg->k != 1) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: combine epilogue needs k = 1, row map and gate weights");
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WT * WF * 64), 0, s, act, wa, wb, bias, offsets, out, row_map,
-                     gate_w, residual, tile_ctr, clear_ctr, cfg->T, cfg->E, N, K);
+                     gate_w, residual, eoff, tile_ctr, clear_ctr, cfg->T, cfg->E, N, K);
   return check_hip(hipGetLastError(), "grouped GEMM launch");
 }
 
@@ -806,17 +810,18 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
 template <int EPI>
 int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
                  const int32_t* offsets, uint16_t* o, const int32_t* row_map, int32_t* tile_ctr, int32_t* clear_ctr, int N,
-                 int K, hipStream_t s, const float* gate_w = nullptr, const uint16_t* residual = nullptr) {
+                 int K, hipStream_t s, const int64_t* eoff, const float* gate_w = nullptr,
+                 const uint16_t* residual = nullptr) {
   constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
     if (pick_tile_rows(cfg, N / BF) == 320)
-      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
-    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
+      return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
+    return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
   }
   if constexpr (EPI == EPI_SWIGLU)
-    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
+    return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
   else
-    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, gate_w, residual);
+    return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
 }
 
 }  // namespace
@@ -829,10 +834,10 @@ int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const voi
   if (cfg->act == MOE_ACT_SWIGLU)
     return gemm_any<EPI_SWIGLU>(
         cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up, nullptr, offsets,
-        (uint16_t*)h, row_map, tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s);
+        (uint16_t*)h, row_map, tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s, w->expert_elem_offset);
   return gemm_any<EPI_GELU>(
       cfg, (const uint16_t*)xd, (const uint16_t*)w->w1, nullptr, (const uint16_t*)w->b1, offsets, (uint16_t*)h, row_map,
-      tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s);
+      tile_counters, tile_counters + NUM_XCD, cfg->d_ff, cfg->d_model, s, w->expert_elem_offset);
 }
 
 int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
@@ -841,7 +846,7 @@ int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const voi
   return gemm_any<EPI_BIAS>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
       (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, nullptr,
-      cfg->d_model, cfg->d_ff, s);
+      cfg->d_model, cfg->d_ff, s, w->expert_elem_offset);
 }
 
 // The second GEMM with the top-1 combine in its epilogue: out[T, d_model] rows of the tokens that kept their
@@ -853,7 +858,7 @@ int32_t launch_gemm2_combine_bf16(const moe_config* cfg, const moe_weights* w, c
   return gemm_any<EPI_COMBINE>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
       (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)out, row_to_assign, tile_counters + NUM_XCD, nullptr,
-      cfg->d_model, cfg->d_ff, s, topk_w, (const uint16_t*)residual);
+      cfg->d_model, cfg->d_ff, s, w->expert_elem_offset, topk_w, (const uint16_t*)residual);
 }
 
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.

@@ -11,61 +11,103 @@ struct moe_timer {
 namespace moesys {
 namespace {
 
-int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, const void* residual, void* out,
-                   void* ws, size_t ws_bytes, hipStream_t s, moe_timer* timer) {
+struct Segments {
+  int32_t *topk_idx, *counts, *offsets, *a2r, *r2a, *tile_ctr;
+  float* topk_w;
+  void *xd, *h, *yd, *scratch;
+};
+
+// Validates what both halves of the layer need and resolves the workspace segments.
+int32_t open_workspace(const char* who, const moe_config* cfg, const moe_weights* w, const void* x, void* ws,
+                       size_t ws_bytes, Segments* sg) {
   int32_t st = moe_config_check(cfg);
   if (st != MOE_OK) return st;
-  st = check_weights(cfg, w);
-  if (st != MOE_OK) return st;
-  if (!w->w_router) return fail(MOE_ERR_INVALID_ARG, "moe_layer_forward: w_router is NULL");
-  if (cfg->T > 0 && (!x || !out)) return fail(MOE_ERR_INVALID_ARG, "moe_layer_forward: x and out must be non-NULL");
-  if (out == x && residual != x) return fail(MOE_ERR_INVALID_ARG, "moe_layer_forward: out aliases x");
+  if (!w) return fail(MOE_ERR_INVALID_ARG, "%s: weights is NULL", who);
+  if (cfg->T > 0 && !x) return fail(MOE_ERR_INVALID_ARG, "%s: x must be non-NULL", who);
   moe_ws_layout L;
   moe_workspace_layout(cfg, &L);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < L.total)
-    return fail(MOE_ERR_WORKSPACE, "moe_layer_forward: workspace needs %zu bytes, 256-byte aligned (got %zu)", L.total, ws_bytes);
+    return fail(MOE_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned (got %zu)", who, L.total, ws_bytes);
   char* base = (char*)ws;
-  int32_t* topk_idx = (int32_t*)(base + L.topk_idx);
-  float* topk_w = (float*)(base + L.topk_w);
-  int32_t* counts = (int32_t*)(base + L.expert_counts);
-  int32_t* offsets = (int32_t*)(base + L.expert_offsets);
-  int32_t* a2r = (int32_t*)(base + L.assign_to_row);
-  int32_t* r2a = (int32_t*)(base + L.row_to_assign);
-  void* xd = base + L.xd;
-  void* h = base + L.h;
-  void* yd = base + L.yd;
-  void* scratch = base + L.scratch;
-  int32_t* tile_ctr = (int32_t*)(base + L.tile_counters);
+  sg->topk_idx = (int32_t*)(base + L.topk_idx);
+  sg->topk_w = (float*)(base + L.topk_w);
+  sg->counts = (int32_t*)(base + L.expert_counts);
+  sg->offsets = (int32_t*)(base + L.expert_offsets);
+  sg->a2r = (int32_t*)(base + L.assign_to_row);
+  sg->r2a = (int32_t*)(base + L.row_to_assign);
+  sg->xd = base + L.xd;
+  sg->h = base + L.h;
+  sg->yd = base + L.yd;
+  sg->scratch = base + L.scratch;
+  sg->tile_ctr = (int32_t*)(base + L.tile_counters);
+  return MOE_OK;
+}
 
-  auto mark = [&](int i) -> int32_t {
-    if (!timer) return MOE_OK;
-    return check_hip(hipEventRecord(timer->ev[i], s), "hipEventRecord");
-  };
-  if ((st = mark(0)) != MOE_OK) return st;
-  if ((st = launch_gate(cfg, x, w->w_router, w->b_router, topk_idx, topk_w, nullptr, s)) != MOE_OK) return st;
-  if ((st = mark(1)) != MOE_OK) return st;
+int32_t mark(moe_timer* timer, int i, hipStream_t s) {
+  if (!timer) return MOE_OK;
+  return check_hip(hipEventRecord(timer->ev[i], s), "hipEventRecord");
+}
+
+// gate -> dispatch bookkeeping (and, on the fp32 path, the dispatched copy)
+int32_t route_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* x, void* ws,
+                   size_t ws_bytes, hipStream_t s, moe_timer* timer) {
+  Segments sg;
+  int32_t st = open_workspace(who, cfg, w, x, ws, ws_bytes, &sg);
+  if (st != MOE_OK) return st;
+  if (!w->w_router) return fail(MOE_ERR_INVALID_ARG, "%s: w_router is NULL", who);
+  if ((st = mark(timer, 0, s)) != MOE_OK) return st;
+  if ((st = launch_gate(cfg, x, w->w_router, w->b_router, sg.topk_idx, sg.topk_w, nullptr, s)) != MOE_OK) return st;
+  if ((st = mark(timer, 1, s)) != MOE_OK) return st;
   // bf16: the first GEMM gathers its rows from x through row_to_assign, so no dispatched copy is made
   const bool gather = gemm1_can_gather(cfg);
-  if ((st = launch_dispatch(cfg, x, topk_idx, counts, offsets, a2r, r2a, gather ? nullptr : xd, scratch, tile_ctr, s)) != MOE_OK) return st;
-  if ((st = mark(2)) != MOE_OK) return st;
-  if ((st = launch_gemm1(cfg, w, gather ? x : xd, offsets, h, gather ? r2a : nullptr, tile_ctr, s)) != MOE_OK) return st;
-  if ((st = mark(3)) != MOE_OK) return st;
+  if ((st = launch_dispatch(cfg, x, sg.topk_idx, sg.counts, sg.offsets, sg.a2r, sg.r2a, gather ? nullptr : sg.xd,
+                            sg.scratch, sg.tile_ctr, s)) != MOE_OK)
+    return st;
+  return mark(timer, 2, s);
+}
+
+// expert FFN -> combine, from the routing tables in the workspace
+int32_t experts_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* x, const void* residual,
+                     void* out, void* ws, size_t ws_bytes, hipStream_t s, moe_timer* timer) {
+  Segments sg;
+  int32_t st = open_workspace(who, cfg, w, x, ws, ws_bytes, &sg);
+  if (st != MOE_OK) return st;
+  if ((st = check_weights(cfg, w)) != MOE_OK) return st;
+  if (cfg->T > 0 && !out) return fail(MOE_ERR_INVALID_ARG, "%s: out must be non-NULL", who);
+  if (out == x && residual != x) return fail(MOE_ERR_INVALID_ARG, "%s: out aliases x", who);
+  const bool gather = gemm1_can_gather(cfg);
+  if ((st = launch_gemm1(cfg, w, gather ? x : sg.xd, sg.offsets, sg.h, gather ? sg.r2a : nullptr, sg.tile_ctr, s)) != MOE_OK)
+    return st;
+  if ((st = mark(timer, 3, s)) != MOE_OK) return st;
   if (gemm2_can_combine(cfg)) {
     // one expert per token: the second GEMM scales each row by its gate weight, adds the residual and writes
     // it to its token's place; what is left of the combine stage are the rows of dropped tokens
-    if ((st = launch_gemm2_combine(cfg, w, h, offsets, r2a, topk_w, residual, out, tile_ctr, s)) != MOE_OK) return st;
-    if ((st = mark(4)) != MOE_OK) return st;
+    if ((st = launch_gemm2_combine(cfg, w, sg.h, sg.offsets, sg.r2a, sg.topk_w, residual, out, sg.tile_ctr, s)) != MOE_OK)
+      return st;
+    if ((st = mark(timer, 4, s)) != MOE_OK) return st;
     const int64_t C = moe_capacity(cfg);  // an expert gets at most T rows: no drops unless C is smaller
     if (C != MOE_DROPLESS && C < cfg->T)
-      if ((st = launch_fill_dropped(cfg, a2r, residual, out, s)) != MOE_OK) return st;
+      if ((st = launch_fill_dropped(cfg, sg.a2r, residual, out, s)) != MOE_OK) return st;
   } else {
-    if ((st = launch_gemm2(cfg, w, h, offsets, yd, tile_ctr, s)) != MOE_OK) return st;
-    if ((st = mark(4)) != MOE_OK) return st;
-    if ((st = launch_combine(cfg, yd, a2r, topk_w, residual, out, s)) != MOE_OK) return st;
+    if ((st = launch_gemm2(cfg, w, sg.h, sg.offsets, sg.yd, sg.tile_ctr, s)) != MOE_OK) return st;
+    if ((st = mark(timer, 4, s)) != MOE_OK) return st;
+    if ((st = launch_combine(cfg, sg.yd, sg.a2r, sg.topk_w, residual, out, s)) != MOE_OK) return st;
   }
-  if ((st = mark(5)) != MOE_OK) return st;
+  if ((st = mark(timer, 5, s)) != MOE_OK) return st;
   if (timer) timer->recorded = true;
   return MOE_OK;
+}
+
+int32_t layer_impl(const moe_config* cfg, const moe_weights* w, const void* x, const void* residual, void* out,
+                   void* ws, size_t ws_bytes, hipStream_t s, moe_timer* timer) {
+  // everything is validated before anything is launched
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if ((st = check_weights(cfg, w)) != MOE_OK) return st;
+  if (cfg->T > 0 && (!x || !out)) return fail(MOE_ERR_INVALID_ARG, "moe_layer_forward: x and out must be non-NULL");
+  if (out == x && residual != x) return fail(MOE_ERR_INVALID_ARG, "moe_layer_forward: out aliases x");
+  if ((st = route_impl("moe_layer_forward", cfg, w, x, ws, ws_bytes, s, timer)) != MOE_OK) return st;
+  return experts_impl("moe_layer_forward", cfg, w, x, residual, out, ws, ws_bytes, s, timer);
 }
 
 }  // namespace
@@ -78,6 +120,16 @@ extern "C" {
 int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const void* x, const void* residual,
                           void* out, void* ws, size_t ws_bytes, void* stream) {
   return layer_impl(cfg, w, x, residual, out, ws, ws_bytes, (hipStream_t)stream, nullptr);
+}
+
+int32_t moe_layer_route(const moe_config* cfg, const moe_weights* w, const void* x, void* ws, size_t ws_bytes,
+                        void* stream) {
+  return route_impl("moe_layer_route", cfg, w, x, ws, ws_bytes, (hipStream_t)stream, nullptr);
+}
+
+int32_t moe_layer_experts(const moe_config* cfg, const moe_weights* w, const void* x, const void* residual,
+                          void* out, void* ws, size_t ws_bytes, void* stream) {
+  return experts_impl("moe_layer_experts", cfg, w, x, residual, out, ws, ws_bytes, (hipStream_t)stream, nullptr);
 }
 
 int32_t moe_layer_forward_timed(const moe_config* cfg, const moe_weights* w, const void* x, const void* residual,

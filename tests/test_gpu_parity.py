@@ -12,7 +12,7 @@ import paper_2205_10034_amd as M
 from oracle import moe_oracle as O
 from workloads import WORKLOADS, make_layer
 
-from gpu_util import alloc_ws, rel_fro, run_layer, tdtype, to_dev, to_np, upload_weights
+from gpu_util import alloc_ws, rel_fro, run_layer, tdtype, to_dev, to_np, upload_weights, ws_view
 
 pytestmark = pytest.mark.gpu
 
@@ -343,6 +343,58 @@ def test_layer_forward_top1_writes_every_token(with_bias):
     got = to_np(out)
     assert np.array_equal(got[dropped], res_np[dropped])
     assert rel_fro(got, ref["out"] + res_np) < BF16_TOL
+
+
+@pytest.mark.parametrize("name,kw", [("gpt", dict(T=1500, E=8)), ("gpt", dict(T=40, E=16, k=2, capacity_factor=0.0)),
+                                     ("skew", dict(T=2000)), ("large", dict(T=900, d_model=512, d_ff=1024, E=4)),
+                                     ("ring", dict(T=64, d_model=512, d_ff=1024, E=64, capacity_factor=0.0))],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_layer_with_experts_scattered_over_a_pool(name, kw):
+    """Route, then experts, with every expert's parameters in its own slot of a pool (shuffled slots, one
+    offset per expert): bit-identical to moe_layer_forward on the [E, ...] arrays."""
+    wl = small(name, **kw)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    want = run_layer(cfg, W, x)
+    E, d, f = wl.E, wl.d_model, wl.d_ff
+    names = ["w1", "w2", "b1", "b2"] if wl.act == "gelu" else ["w_gate_proj", "w_up", "w_down"]
+    parts = [W.tensors[n] for n in names if n in W.tensors]
+    sizes = [p[0].numel() for p in parts]
+    stride = (sum(sizes) + 127) // 128 * 128
+    n_slots = E + 3
+    pool = torch.full((n_slots * stride,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    rng = np.random.default_rng(5)
+    slot_of = rng.permutation(n_slots)[:E]
+    counts = want["expert_counts"]
+    for e in range(E):
+        if counts[e] == 0:
+            continue                                   # an expert without rows needs no slot at all
+        o = int(slot_of[e]) * stride
+        for p_, n in zip(parts, sizes):
+            pool[o:o + n] = p_[e].reshape(-1)
+            o += n
+    offs = torch.tensor([int(slot_of[e]) * stride if counts[e] else 0 for e in range(E)], dtype=torch.int64, device="cuda")
+    t = {"w_router": W.tensors["w_router"], "expert_elem_offset": offs}
+    if "b_router" in W.tensors:
+        t["b_router"] = W.tensors["b_router"]
+    base = pool.data_ptr()
+    o = 0
+    for n_, size in zip([n for n in names if n in W.tensors], sizes):
+        t[n_] = base + 2 * o
+        o += size
+    Wp = M.Weights(t)
+    ws = alloc_ws(cfg)
+    out = torch.full_like(x, float("nan"))
+    M.moe_layer_route(cfg, Wp, x, ws)
+    torch.cuda.synchronize()
+    lay = M.moe_workspace_layout(cfg)
+    got_counts = ws_view(ws, lay["expert_counts"], E, torch.int32).cpu().numpy()
+    assert np.array_equal(got_counts, counts)          # what a caller reads before it places the experts
+    M.moe_layer_experts(cfg, Wp, x, None, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want["out_tensor"])
 
 
 def test_determinism():
