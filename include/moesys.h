@@ -325,6 +325,39 @@ int32_t moe_expert_cache_lookup(const moe_expert_cache* c, int64_t item, int32_t
 int32_t moe_expert_cache_stats(const moe_expert_cache* c, uint64_t* hits, uint64_t* misses,
                                uint64_t* evictions);
 
+/* ---- pool of expert slots fed from pinned host memory -------------------- */
+/*
+ * Offloading at expert granularity, for steps with few tokens: every expert's
+ * parameter blob (any layout the caller's moe_weights base pointers and one
+ * offset per expert can describe, e.g. [W1 | W2 | b1 | b2]) lives in pinned
+ * host memory; dev_pool (device, 256-byte aligned) is cut into pool_bytes /
+ * slot_bytes slots, managed by the frequency-based policy above with item
+ * layer*E + e.  moe_expert_pool_prepare, called between moe_layer_route and
+ * moe_layer_experts of `layer`:
+ *   - reads the E per-expert counts from counts_dev (device; the workspace's
+ *     expert_counts) and waits for compute_stream, because the host needs them;
+ *   - schedules every expert with a count > 0 (ascending e, one batch), copies
+ *     the blobs of the misses into their slots on the copy stream and makes
+ *     compute_stream wait for those copies;
+ *   - writes, through compute_stream, the table dev_offsets (device int64 [E])
+ *     of slot offsets in elements of elem_bytes (0 for experts without rows),
+ *     to be used as moe_weights.expert_elem_offset.
+ * The pool keeps host_blobs' pointers ([n_layers*E], each blob_bytes long,
+ * pinned) and dev_pool; the caller keeps them alive.  copy_stream NULL = a
+ * stream of its own (default priority).  One pool serves one compute stream.
+ */
+typedef struct moe_expert_pool moe_expert_pool;
+int32_t moe_expert_pool_create(void* dev_pool, size_t pool_bytes, size_t slot_bytes,
+                               const void* const* host_blobs, int32_t n_layers, int32_t E,
+                               size_t blob_bytes, float threshold, float beta, int32_t decay_steps,
+                               void* copy_stream, moe_expert_pool** out);
+int32_t moe_expert_pool_prepare(moe_expert_pool* p, int32_t layer, const int32_t* counts_dev,
+                                int32_t elem_bytes, int64_t* dev_offsets, void* compute_stream);
+/* Totals since creation (nullable outputs). */
+int32_t moe_expert_pool_stats(const moe_expert_pool* p, uint64_t* bytes_copied, uint64_t* copies,
+                              uint64_t* hits, uint64_t* misses, uint64_t* evictions);
+int32_t moe_expert_pool_destroy(moe_expert_pool* p);
+
 #ifdef __cplusplus
 }
 #endif

@@ -120,6 +120,11 @@ def lib() -> C.CDLL:
                                                 C.POINTER(C.c_int64)]
         L.moe_expert_cache_lookup.argtypes = [vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.moe_expert_cache_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
+                                             C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
+        L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
+        L.moe_expert_pool_stats.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 5
+        L.moe_expert_pool_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -365,6 +370,40 @@ class ExpertCache:
     def close(self):
         if self.h:
             lib().moe_expert_cache_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class ExpertPool:
+    """moe_expert_pool_* wrapper.  ``host_blobs``: pinned host tensors, one per (layer, expert), layer-major."""
+
+    def __init__(self, dev_pool, slot_bytes: int, host_blobs: Sequence, n_layers: int, E: int, blob_bytes: int,
+                 threshold: float, beta: float, decay_steps: int, copy_stream=None):
+        self._keep = (dev_pool, list(host_blobs), copy_stream)
+        ptrs = (C.c_void_p * len(host_blobs))(*[h.data_ptr() for h in host_blobs])
+        self.h = C.c_void_p()
+        cs = None if copy_stream is None else copy_stream.cuda_stream
+        _check(lib().moe_expert_pool_create(dev_pool.data_ptr(), dev_pool.numel() * dev_pool.element_size(), slot_bytes,
+                                            ptrs, n_layers, E, blob_bytes, threshold, beta, decay_steps, cs,
+                                            C.byref(self.h)), "moe_expert_pool_create")
+
+    def prepare(self, layer: int, counts_dev, elem_bytes: int, dev_offsets, compute_stream=None) -> None:
+        _check(lib().moe_expert_pool_prepare(self.h, layer, _ptr(counts_dev), elem_bytes, _ptr(dev_offsets),
+                                             _stream(compute_stream)), "moe_expert_pool_prepare")
+
+    def stats(self):
+        v = [C.c_uint64() for _ in range(5)]
+        _check(lib().moe_expert_pool_stats(self.h, *[C.byref(x) for x in v]), "moe_expert_pool_stats")
+        return dict(zip(("bytes_copied", "copies", "hits", "misses", "evictions"), [x.value for x in v]))
+
+    def close(self):
+        if self.h:
+            lib().moe_expert_pool_destroy(self.h)
             self.h = C.c_void_p()
 
     def __del__(self):

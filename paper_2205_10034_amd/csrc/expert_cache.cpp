@@ -139,3 +139,137 @@ int32_t moe_expert_cache_stats(const moe_expert_cache* c, uint64_t* hits, uint64
 }
 
 }  // extern "C"
+
+// ---- the pool: policy + data movement ------------------------------------------------------------
+//
+// All experts' parameter blobs (one per layer and expert) stay in pinned host memory; a region of HBM is cut
+// into slots of one blob each.  Before a layer's experts run, the caller hands over the per-expert row
+// counts that the routing left on the device; every expert with rows is scheduled through the policy above
+// (in ascending expert order, as one batch), the blobs of the misses are copied into their slots on the copy
+// stream, the compute stream is made to wait for them, and the table of the experts' offsets inside the
+// pool is written for the kernels (moe_weights.expert_elem_offset).  Traffic is proportional to the
+// activated experts that are not yet resident, not to the layer: the case the ring of whole layers
+// (Section 3.3.2) handles worst, few tokens per step.
+//
+// Reading the counts needs the host to wait for the compute stream, so by the time slots are reassigned
+// every kernel that read them has finished; copies follow each other on the one copy stream.
+struct moe_expert_pool {
+  moe_expert_cache* policy;
+  char* dev_pool;
+  size_t slot_bytes, blob_bytes;
+  int32_t n_layers, E;
+  std::vector<const void*> host;   // [n_layers * E]
+  hipStream_t copy_stream;
+  bool own_stream;
+  hipEvent_t copied;
+  int32_t* counts_host;            // pinned [E]
+  int64_t* offsets_host;           // pinned [E]
+  uint64_t bytes_copied, copies;
+};
+
+extern "C" {
+
+int32_t moe_expert_pool_create(void* dev_pool, size_t pool_bytes, size_t slot_bytes, const void* const* host_blobs,
+                               int32_t n_layers, int32_t E, size_t blob_bytes, float threshold, float beta,
+                               int32_t decay_steps, void* copy_stream, moe_expert_pool** out) {
+  if (!out || !dev_pool || !host_blobs) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_create: NULL argument");
+  if (n_layers < 1 || E < 1 || E > MOE_MAX_EXPERTS || blob_bytes == 0 || slot_bytes < blob_bytes || (slot_bytes & 255) ||
+      ((uintptr_t)dev_pool & 255))
+    return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_create: need n_layers, E >= 1, blob_bytes <= slot_bytes, "
+                                     "slot_bytes and dev_pool multiples of 256");
+  const size_t slots = pool_bytes / slot_bytes;
+  if (slots < 1 || slots > (size_t)INT32_MAX) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_create: pool holds %zu slots", slots);
+  for (int64_t i = 0; i < (int64_t)n_layers * E; ++i)
+    if (!host_blobs[i]) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_create: host_blobs[%lld] is NULL", (long long)i);
+  moe_expert_pool* p = new (std::nothrow) moe_expert_pool();
+  if (!p) return fail(MOE_ERR_HIP, "moe_expert_pool_create: out of host memory");
+  p->policy = nullptr;
+  p->copy_stream = nullptr;
+  p->own_stream = false;
+  p->copied = nullptr;
+  p->counts_host = nullptr;
+  p->offsets_host = nullptr;
+  int32_t st = moe_expert_cache_create(&p->policy, (int32_t)slots, threshold, beta, decay_steps);
+  if (st == MOE_OK) {
+    p->dev_pool = (char*)dev_pool;
+    p->slot_bytes = slot_bytes;
+    p->blob_bytes = blob_bytes;
+    p->n_layers = n_layers;
+    p->E = E;
+    p->host.assign(host_blobs, host_blobs + (size_t)n_layers * E);
+    p->bytes_copied = p->copies = 0;
+    if (copy_stream) {
+      p->copy_stream = (hipStream_t)copy_stream;
+    } else {
+      st = check_hip(hipStreamCreateWithFlags(&p->copy_stream, hipStreamNonBlocking), "hipStreamCreate");
+      p->own_stream = st == MOE_OK;
+    }
+  }
+  if (st == MOE_OK) st = check_hip(hipEventCreateWithFlags(&p->copied, hipEventDisableTiming), "hipEventCreate");
+  if (st == MOE_OK) st = check_hip(hipHostMalloc((void**)&p->counts_host, sizeof(int32_t) * E, hipHostMallocDefault), "hipHostMalloc");
+  if (st == MOE_OK) st = check_hip(hipHostMalloc((void**)&p->offsets_host, sizeof(int64_t) * E, hipHostMallocDefault), "hipHostMalloc");
+  if (st != MOE_OK) {
+    moe_expert_pool_destroy(p);
+    return st;
+  }
+  *out = p;
+  return MOE_OK;
+}
+
+int32_t moe_expert_pool_destroy(moe_expert_pool* p) {
+  if (!p) return MOE_OK;
+  if (p->copy_stream) (void)hipStreamSynchronize(p->copy_stream);
+  if (p->copied) (void)hipEventDestroy(p->copied);
+  if (p->own_stream && p->copy_stream) (void)hipStreamDestroy(p->copy_stream);
+  if (p->counts_host) (void)hipHostFree(p->counts_host);
+  if (p->offsets_host) (void)hipHostFree(p->offsets_host);
+  moe_expert_cache_destroy(p->policy);
+  delete p;
+  return MOE_OK;
+}
+
+int32_t moe_expert_pool_prepare(moe_expert_pool* p, int32_t layer, const int32_t* counts_dev, int32_t elem_bytes,
+                                int64_t* dev_offsets, void* compute_stream) {
+  if (!p || !counts_dev || !dev_offsets) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_prepare: NULL argument");
+  if (layer < 0 || layer >= p->n_layers) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_prepare: layer %d of %d", layer, p->n_layers);
+  if ((elem_bytes != 2 && elem_bytes != 4) || p->slot_bytes % ((size_t)elem_bytes * 8))
+    return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_prepare: elem_bytes must be 2 or 4 and divide the slot size into multiples of 8");
+  hipStream_t cs = (hipStream_t)compute_stream;
+  int32_t st = check_hip(hipMemcpyAsync(p->counts_host, counts_dev, sizeof(int32_t) * p->E, hipMemcpyDeviceToHost, cs), "hipMemcpyAsync(counts)");
+  if (st != MOE_OK) return st;
+  // the host needs the counts; everything enqueued before on the compute stream has finished after this
+  if ((st = check_hip(hipStreamSynchronize(cs), "hipStreamSynchronize")) != MOE_OK) return st;
+  if ((st = moe_expert_cache_begin_batch(p->policy)) != MOE_OK) return st;
+  bool any_copy = false;
+  for (int32_t e = 0; e < p->E; ++e) {
+    p->offsets_host[e] = 0;
+    if (p->counts_host[e] <= 0) continue;
+    int32_t slot = -1, hit = 0;
+    if ((st = moe_expert_cache_schedule(p->policy, (int64_t)layer * p->E + e, &slot, &hit, nullptr)) != MOE_OK) return st;
+    p->offsets_host[e] = (int64_t)((size_t)slot * p->slot_bytes / (size_t)elem_bytes);
+    if (!hit) {
+      st = check_hip(hipMemcpyAsync(p->dev_pool + (size_t)slot * p->slot_bytes, p->host[(size_t)layer * p->E + e],
+                                    p->blob_bytes, hipMemcpyHostToDevice, p->copy_stream), "hipMemcpyAsync(expert)");
+      if (st != MOE_OK) return st;
+      p->bytes_copied += p->blob_bytes;
+      ++p->copies;
+      any_copy = true;
+    }
+  }
+  if (any_copy) {
+    if ((st = check_hip(hipEventRecord(p->copied, p->copy_stream), "hipEventRecord")) != MOE_OK) return st;
+    if ((st = check_hip(hipStreamWaitEvent(cs, p->copied, 0), "hipStreamWaitEvent")) != MOE_OK) return st;
+  }
+  return check_hip(hipMemcpyAsync(dev_offsets, p->offsets_host, sizeof(int64_t) * p->E, hipMemcpyHostToDevice, cs), "hipMemcpyAsync(offsets)");
+}
+
+int32_t moe_expert_pool_stats(const moe_expert_pool* p, uint64_t* bytes_copied, uint64_t* copies, uint64_t* hits,
+                              uint64_t* misses, uint64_t* evictions) {
+  if (!p) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_stats: pool is NULL");
+  if (bytes_copied) *bytes_copied = p->bytes_copied;
+  if (copies) *copies = p->copies;
+  return moe_expert_cache_stats(p->policy, hits, misses, evictions);
+}
+
+}  // extern "C"
+

@@ -1,0 +1,126 @@
+"""Offloading at expert granularity on the GPU: a stack of MoE layers whose expert parameters live in
+pinned host memory, one blob per (layer, expert), and are brought into a small pool of HBM slots only when
+the routing of a step activates them (policy: Algorithm 2 of Section 3.2.2, one memory tier up).
+
+Checks: the stack run through the pool is bit-identical to the same stack with every parameter resident;
+hits, misses, evictions and bytes copied equal what the policy oracle predicts for the routing that was
+observed; a pool smaller than one layer's activated experts is refused, not overrun.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2205_10034_amd as M
+from oracle.expert_cache_oracle import SparseParameterCache
+from workloads import WORKLOADS, make_ring_stack
+
+from gpu_util import alloc_ws, to_dev, upload_weights, ws_view
+
+pytestmark = pytest.mark.gpu
+
+
+def expert_blobs(W, e_count):
+    """Per expert: [w1 | w2 | b1 | b2] (bf16, output-major matrices) in pinned host memory."""
+    parts = [W.tensors[n] for n in ("w1", "w2", "b1", "b2")]
+    sizes = [p[0].numel() for p in parts]
+    blobs = []
+    for e in range(e_count):
+        b = torch.empty(sum(sizes), dtype=torch.bfloat16, pin_memory=True)
+        o = 0
+        for p, n in zip(parts, sizes):
+            b[o:o + n] = p[e].reshape(-1).cpu()
+            o += n
+        blobs.append(b)
+    return blobs, sizes
+
+
+@pytest.mark.parametrize("T,slots,steps", [(24, 10, 6), (3, 16, 12), (64, 13, 4)])
+def test_pool_stack_matches_resident_and_policy_oracle(T, slots, steps):
+    N, thr, beta, K = 3, 2.0, 0.5, 7
+    wl = WORKLOADS["ring"].scaled(T=T, d_model=256, d_ff=512, E=8, capacity_factor=0.0)
+    print(f"pool stack T={T} slots={slots} steps={steps} {wl}", flush=True)
+    _, layers = make_ring_stack(wl, N)
+    for i, L in enumerate(layers):                         # biases, so that their offsets are exercised too
+        r = np.random.default_rng(100 + i)
+        L["b1"] = np.asarray(to_dev(r.standard_normal((wl.E, wl.d_ff)).astype(np.float32) * 0.1, "bf16").float().cpu())
+        L["b2"] = np.asarray(to_dev(r.standard_normal((wl.E, wl.d_model)).astype(np.float32) * 0.1, "bf16").float().cpu())
+    cfg = M.MoEConfig.from_workload(wl)
+    Ws = [upload_weights(L, wl.dtype) for L in layers]
+    host, sizes = [], None
+    for W in Ws:
+        b, sizes = expert_blobs(W, wl.E)
+        host += b
+    blob_elems = sum(sizes)
+    slot_bytes = (blob_elems * 2 + 255) // 256 * 256
+    dev_pool = torch.full((slots * slot_bytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    pool = M.ExpertPool(dev_pool, slot_bytes, host, N, wl.E, blob_elems * 2, thr, beta, K)
+    offs = torch.zeros(wl.E, dtype=torch.int64, device="cuda")
+    base = dev_pool.data_ptr()
+    ref_policy = SparseParameterCache(slots, thr, beta, K)
+    want_copies = want_hits = want_evictions = 0
+    ws = alloc_ws(cfg)
+    lay = M.moe_workspace_layout(cfg)
+    counts_dev = ws_view(ws, lay["expert_counts"], wl.E, torch.int32)
+    rng = np.random.default_rng(9)
+    for step in range(steps):
+        x = to_dev(rng.standard_normal((T, wl.d_model)).astype(np.float32), wl.dtype)
+        x_ref = x.clone()
+        for l in range(N):
+            # resident reference
+            nxt_ref = torch.empty_like(x_ref)
+            M.moe_layer_forward(cfg, Ws[l], x_ref, x_ref, nxt_ref, alloc_ws(cfg))
+            # through the pool
+            t = {"w_router": Ws[l].tensors["w_router"], "expert_elem_offset": offs, "w1": base,
+                 "w2": base + 2 * sizes[0], "b1": base + 2 * (sizes[0] + sizes[1]),
+                 "b2": base + 2 * (sizes[0] + sizes[1] + sizes[2])}
+            Wp = M.Weights(t)
+            M.moe_layer_route(cfg, Wp, x, ws)
+            pool.prepare(l, counts_dev, 2, offs)
+            nxt = torch.empty_like(x)
+            M.moe_layer_experts(cfg, Wp, x, x, nxt, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(nxt, nxt_ref), f"step {step} layer {l}"
+            counts = counts_dev.cpu().numpy()
+            ref_policy.begin_batch()
+            for e in range(wl.E):
+                if counts[e] > 0:
+                    slot, hit, gone = ref_policy.schedule(l * wl.E + e)
+                    want_hits += hit
+                    want_copies += not hit
+                    want_evictions += gone is not None
+                    assert int(offs[e].item()) == slot * slot_bytes // 2
+            x, x_ref = nxt, nxt_ref
+    st = pool.stats()
+    print(st, flush=True)
+    assert st == {"bytes_copied": want_copies * blob_elems * 2, "copies": want_copies, "hits": want_hits,
+                  "misses": want_copies, "evictions": want_evictions}
+    assert want_evictions > 0 and (want_hits > 0 or T >= 8)   # (T >= 8 activates every expert: a cyclic sweep, no hits)
+    pool.close()
+
+
+def test_pool_smaller_than_one_layers_experts_is_refused():
+    wl = WORKLOADS["ring"].scaled(T=64, d_model=256, d_ff=512, E=8, capacity_factor=0.0)
+    _, layers = make_ring_stack(wl, 1)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(layers[0], wl.dtype)
+    parts = [W.tensors[n] for n in ("w1", "w2")]
+    blob_elems = sum(p[0].numel() for p in parts)
+    host = []
+    for e in range(wl.E):
+        b = torch.empty(blob_elems, dtype=torch.bfloat16, pin_memory=True)
+        b[:parts[0][0].numel()] = parts[0][e].reshape(-1).cpu()
+        b[parts[0][0].numel():] = parts[1][e].reshape(-1).cpu()
+        host.append(b)
+    slot_bytes = blob_elems * 2
+    dev_pool = torch.zeros(3 * slot_bytes // 2, dtype=torch.bfloat16, device="cuda")      # 3 slots, 8 experts
+    pool = M.ExpertPool(dev_pool, slot_bytes, host, 1, wl.E, slot_bytes, 1.0, 1.0, 100)
+    x = to_dev(np.random.default_rng(0).standard_normal((wl.T, wl.d_model)).astype(np.float32), wl.dtype)
+    ws = alloc_ws(cfg)
+    lay = M.moe_workspace_layout(cfg)
+    offs = torch.zeros(wl.E, dtype=torch.int64, device="cuda")
+    M.moe_layer_route(cfg, W, x, ws)
+    with pytest.raises(M.MoEError) as e:
+        pool.prepare(0, ws_view(ws, lay["expert_counts"], wl.E, torch.int32), 2, offs)
+    assert "current batch" in str(e.value)
+    torch.cuda.synchronize()
+    pool.close()
