@@ -229,7 +229,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 // TOK x FEAT tile, WT x WF wavefronts, K-step KS, two LDS stages; each wavefront owns TOK/WT tokens (every
 // WT-th 32-row block) x FEAT/WF LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
-template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER>
+// HASB = false: the caller passed no bias; its staging and the two vector instructions per element that add it
+// are compiled out (SwiGLU never has one).
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER, bool HASB>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   __shared__ __attribute__((aligned(256))) unsigned char s_sink[256];  // where prefetched dwords land (never read)
   // each wavefront's own slice of the tile's bias (WFEAT bf16 in the first bytes of its 256-byte slot); two
   // sets, because the next tile's bias is requested before the current tile's epilogue reads its own
-  __shared__ __attribute__((aligned(256))) unsigned char s_bias[EPI == EPI_SWIGLU ? 256 : 2 * NW * 256];
+  __shared__ __attribute__((aligned(256))) unsigned char s_bias[HASB ? 2 * NW * 256 : 256];
   // EPI_COMBINE: the token of every row of the tile, two sets like the bias
   __shared__ int s_rowtok[EPI == EPI_COMBINE ? 2 * NW * 64 : 1];
 
@@ -442,13 +444,12 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     issue_tokens(1, 1 < KT, s1);
 #pragma unroll
     for (int j = 1; j <= PF_LEAD; ++j) issue_prefetch(j);
-    if constexpr (EPI != EPI_SWIGLU) {
-      // this wavefront's WFEAT bias values: lanes 0..WFEAT/2-1 move one dword each, the others (and every
-      // lane when there is no bias) read out of range, which stores zeros
-      const uint16_t* brow = bias ? bias + (eoff ? (size_t)eoff[t.expert] : (size_t)t.expert * N) +
-                                        (size_t)t.ntile * OUT_FEAT + wf * WFEAT
-                                  : act;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(make_rsrc(brow, bias ? (uint32_t)WFEAT * 2u : 0u),
+    if constexpr (HASB) {
+      // this wavefront's WFEAT bias values: lanes 0..WFEAT/2-1 move one dword each, the others read out of
+      // range, which stores zeros
+      const uint16_t* brow = bias + (eoff ? (size_t)eoff[t.expert] : (size_t)t.expert * N) +
+                             (size_t)t.ntile * OUT_FEAT + wf * WFEAT;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(make_rsrc(brow, (uint32_t)WFEAT * 2u),
                                                (__attribute__((address_space(3))) void*)(s_bias + (bias_set * NW + wave) * 256), 4, lane * 4, 0, 0, 0);
     }
     if constexpr (EPI == EPI_COMBINE) {  // one row id per thread, threads past the last row re-read it
@@ -690,13 +691,18 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             float p[8];
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
-              // the bias sits in this wavefront's LDS slot since the tile's prologue (zeros without one)
-              const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 +
-                                                              (fb * 32 + 8 * (i0 + g) + 4 * fhalf) * 2);
-              p[4 * g + 0] = acc[tb][fb][4 * (i0 + g) + 0] + bf16_bits_to_f32(b.x & 0xffffu);
-              p[4 * g + 1] = acc[tb][fb][4 * (i0 + g) + 1] + __uint_as_float(b.x & 0xffff0000u);
-              p[4 * g + 2] = acc[tb][fb][4 * (i0 + g) + 2] + bf16_bits_to_f32(b.y & 0xffffu);
-              p[4 * g + 3] = acc[tb][fb][4 * (i0 + g) + 3] + __uint_as_float(b.y & 0xffff0000u);
+              if constexpr (HASB) {
+                // the bias sits in this wavefront's LDS slot since the tile's prologue
+                const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 +
+                                                                (fb * 32 + 8 * (i0 + g) + 4 * fhalf) * 2);
+                p[4 * g + 0] = acc[tb][fb][4 * (i0 + g) + 0] + bf16_bits_to_f32(b.x & 0xffffu);
+                p[4 * g + 1] = acc[tb][fb][4 * (i0 + g) + 1] + __uint_as_float(b.x & 0xffff0000u);
+                p[4 * g + 2] = acc[tb][fb][4 * (i0 + g) + 2] + bf16_bits_to_f32(b.y & 0xffffu);
+                p[4 * g + 3] = acc[tb][fb][4 * (i0 + g) + 3] + __uint_as_float(b.y & 0xffff0000u);
+              } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) p[4 * g + q] = acc[tb][fb][4 * (i0 + g) + q];
+              }
             }
             if (EPI == EPI_GELU) {
               constexpr int GB = TOK > 256 ? 4 : 8;  // (8 at a time spills in the 320-row kernel)
@@ -757,9 +763,17 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   const int64_t per_xcd = ((blocks + NUM_XCD - 1) / NUM_XCD) * CU_PER_XCD;  // tiles one XCD may own
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
   // the gathering variant exists for the first GEMM's epilogues only
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false>;
-  if constexpr (EPI == EPI_GELU || EPI == EPI_SWIGLU) {
-    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true>;
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, false>;
+  if constexpr (EPI == EPI_SWIGLU) {
+    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
+  } else {
+    if (bias) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, true>;
+  }
+  if constexpr (EPI == EPI_GELU) {
+    if (row_map)
+      kern = bias ? grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, true>
+                  : grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
+  } else if constexpr (EPI == EPI_SWIGLU) {
   } else if constexpr (EPI == EPI_BIAS) {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
   } else {
