@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (grouped GEMM 1) from rocprofv3 FETCH_SIZE + WRITE_SIZE, both
 # scaled by 1.000 against the weight-transpose kernel of known size (profiles/layer_forward_gpt_hbm_traffic.txt);
 # a separate counter run, so it is a constant here and only quoted for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"gpt": (151330.5 + 132885.6) * 1024}
+MEASURED_TRAFFIC_BYTES = {"gpt": (151107.6 + 132461.0) * 1024}
 
 
 def cpu_baseline(wl, L, budget_s=20.0):
