@@ -28,18 +28,18 @@ ROW_SETS = [
 ]
 
 
-def run_case(rows, act, d_model, d_ff, seed):
+def run_case(rows, act, d_model, d_ff, seed, bias=True):
     E = len(rows)
     R = int(sum(rows))
     # a config whose capacity admits these counts: dropless, T*k = R
     wl = WORKLOADS["gpt"].scaled(T=max(R, 1), E=E, k=1, d_model=d_model, d_ff=d_ff, act=act, capacity_factor=0.0,
                                  seed=seed)
-    L = make_layer(wl, with_bias=True)
+    L = make_layer(wl, with_bias=bias)
     cfg = M.MoEConfig.from_workload(wl)
     offsets_np = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
     xd_np = L["x"][:R]
     ref = O.expert_ffn(xd_np.astype(np.float64), offsets_np, L, act)
-    W = upload_weights(L, "bf16")
+    W = upload_weights(L, "bf16", nullable_bias=True)      # zero biases travel as NULL pointers
     xd = to_dev(xd_np, "bf16")
     yd = torch.full((max(R, 1), d_model), float("nan"), dtype=tdtype("bf16"), device="cuda")
     ws = alloc_ws(cfg, 2)
@@ -55,7 +55,7 @@ def run_case(rows, act, d_model, d_ff, seed):
             if hi > lo:
                 err = rel_fro(got[lo:hi], ref[lo:hi])
                 assert err < 1e-2, f"rows {rows} {act} expert {e} ({hi - lo} rows) rel err {err} (call {rep})"
-    print(f"ok rows={rows} act={act} d={d_model} f={d_ff}", flush=True)
+    print(f"ok rows={rows} act={act} d={d_model} f={d_ff} bias={bias}", flush=True)
 
 
 def main():
@@ -68,6 +68,10 @@ def main():
     for i, (d_model, d_ff) in enumerate([(64, 256), (256, 64), (128, 256), (192, 256), (320, 256), (64, 64)]):
         run_case(ROW_SETS[0], "gelu", d_model, d_ff, 300 + i)
     run_case(ROW_SETS[2], "swiglu", 64, 128, 310)
+    # without biases (NULL pointers): the kernels compiled without the bias staging
+    run_case(ROW_SETS[0], "gelu", 256, 512, 320, bias=False)
+    run_case(ROW_SETS[1], "gelu", 192, 320, 321, bias=False)
+    run_case(ROW_SETS[0], "gelu", 64, 256, 322, bias=False)
     return 0
 
 
