@@ -313,6 +313,35 @@ def test_layer_forward_large_sampled():
         assert rel_fro(r["out"][t], ref[i]) < 3 * BF16_TOL
 
 
+def test_layer_forward_ring_layer_full_size_sampled():
+    """One layer of the ring workload at full size (4096 x 2048 x 8192, 64 experts, ~128 rows per expert:
+    the weight-streaming regime of the grouped GEMMs): routing compared in full, outputs on sampled tokens."""
+    wl = WORKLOADS["ring"]
+    print(f"full-size layer {wl}", flush=True)
+    L = make_layer(wl)
+    cfg = M.MoEConfig.from_workload(wl)
+    p, idx, w = O.gate(L["x"], L["w_router"], L["b_router"], wl.k, wl.renormalize)
+    C = O.capacity(wl.T, wl.E, wl.k, wl.capacity_factor)
+    counts, offsets, a2r, r2a = O.dispatch_plan(idx, wl.E, C)
+    W = upload_weights(L, wl.dtype, nullable_bias=True)
+    r = run_layer(cfg, W, to_dev(L["x"], wl.dtype))
+    assert np.array_equal(r["topk_idx"], idx) and np.allclose(r["topk_w"], w, rtol=GATE_RTOL, atol=0)
+    assert np.array_equal(r["expert_counts"], counts) and np.array_equal(r["expert_offsets"], offsets)
+    assert np.array_equal(r["assign_to_row"], a2r) and np.array_equal(r["row_to_assign"], r2a)
+    rng = np.random.default_rng(1)
+    smallest, largest = int(np.argmin(counts)), int(np.argmax(counts))
+    edge = [int(r2a[offsets[e]]) % wl.T for e in (smallest, largest) if counts[e]] + \
+           [int(r2a[offsets[e + 1] - 1]) % wl.T for e in (smallest, largest) if counts[e]]
+    toks = np.unique(np.concatenate([rng.integers(0, wl.T, 60), edge, [0, wl.T - 1]]))
+    plan = dict(topk_idx=idx, topk_w=w, assign_to_row=a2r)
+    ref = O.sampled_tokens_forward(L["x"], L, plan, toks, act=wl.act)
+    err = rel_fro(r["out"][toks], ref)
+    print(f"ring layer: rows per expert {int(counts.min())}..{int(counts.max())} sampled rel fro {err:.3e}", flush=True)
+    assert err < BF16_TOL
+    for i, t in enumerate(toks):
+        assert rel_fro(r["out"][t], ref[i]) < 3 * BF16_TOL
+
+
 @pytest.mark.parametrize("with_bias", [False, True])
 def test_layer_forward_top1_writes_every_token(with_bias):
     """k = 1 in bf16: kept tokens are written by the second GEMM's epilogue and dropped ones by the fill
