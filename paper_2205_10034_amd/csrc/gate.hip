@@ -269,17 +269,25 @@ __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E,
   return close;
 }
 
-// EB = number of 16-expert blocks (E <= 16*EB).  One workgroup = 16 tokens (one MFMA token tile); its four
-// wavefronts split the K range chunk by chunk and meet once, to add their partial logits.  VEC: the router
-// weights can be read four experts at a time (E a multiple of 4, 16-byte aligned base).
+// EB = number of 16-expert blocks (E <= 16*EB).  One workgroup = 16 tokens (one MFMA token tile); its NWV
+// wavefronts split the K range chunk by chunk and meet once, to add their partial logits.  A wavefront
+// works through a chunk one expert block at a time, re-using one staging area of 16 experts (its LDS
+// operations execute in order), so that eight wavefronts fit where the router is wide: with 64 experts a
+// wavefront's chain of split, stage and multiply is four times as long as with 16, and the kernel's time
+// is the length of that chain.  VEC: the router weights can be read four experts at a time (E a multiple
+// of 4, 16-byte aligned base).
+template <int EB>
+constexpr int gate_waves() { return EB == 1 ? 4 : 8; }
+
 template <int EB, bool VEC>
-__global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
+__global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
                                                         const float* __restrict__ br, int T, int d, int E, int k,
                                                         int renorm, int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_w, float* __restrict__ probs) {
   constexpr int EP = EB * 16;
   constexpr int NPL = EP / 8;                    // logits per lane in the 8-lane finalisation groups
-  constexpr int W_WAVE_BYTES = 3 * EP * FT_ROW;  // one wavefront's hi/mid/lo chunk
+  constexpr int NWV = gate_waves<EB>();
+  constexpr int W_WAVE_BYTES = 3 * 16 * FT_ROW;  // one wavefront's hi/mid/lo pieces of one expert block's chunk
   constexpr int PF = EB == 1 ? 4 : 2;            // chunks in flight per wavefront (register-staged)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_flag[FT_TOK];
@@ -298,6 +306,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
     for (int r = 0; r < 4; ++r) zacc[b][r] = 0.0;
 
   // router-weight micro-tiles of this lane: 4 consecutive k x 4 consecutive experts each
+  // (micro-tile m of a lane belongs to expert block m: expert group m*4 + lane%4, K group lane/4)
   constexpr int MT_PER_LANE = (FT_KC / 4) * (EP / 4) / 64;  // = EB
   const int n_chunks = d / FT_KC;
 
@@ -312,7 +321,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
     xa[s_][0] = *reinterpret_cast<const u32x4*>(xrow + k0_);                                            \
     xa[s_][1] = *reinterpret_cast<const u32x4*>(xrow + k0_ + 8);                                        \
     _Pragma("unroll") for (int m = 0; m < MT_PER_LANE; ++m) {                                           \
-      const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);                             \
+      const int eg = m * 4 + (lane & 3), kg = lane >> 2;                                                \
       _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
         const float* wp = wr + (size_t)(k0_ + kg * 4 + i) * E;                                          \
         if (VEC) {                                                                                      \
@@ -331,21 +340,25 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
     }                                                                                                   \
   }
 
-  // chunks wave, wave+4, ...  The LDS staging area is private to the wavefront and LDS operations of one
+  // chunks wave, wave+NWV, ...  The LDS staging area is private to the wavefront and LDS operations of one
   // wavefront execute in order, so no barrier is needed inside this loop.
 #pragma unroll
-  for (int s = 0; s < PF; ++s) GATE_LOAD_STAGE(s, wave + 4 * s)
-  for (int base = wave; base < n_chunks; base += 4 * PF) {
+  for (int s = 0; s < PF; ++s) GATE_LOAD_STAGE(s, wave + NWV * s)
+  for (int base = wave; base < n_chunks; base += NWV * PF) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
-      const int c = base + 4 * s;
+      const int c = base + NWV * s;
       const bool live = c < n_chunks;  // uniform
       bf16x8 xb[2];
+      f32x4 acc[EB];
       if (live) {
-        // split this chunk's router weights into three bf16 pieces and stage them K-contiguous per expert
+        xb[0] = __builtin_bit_cast(bf16x8, xa[s][0]);
+        xb[1] = __builtin_bit_cast(bf16x8, xa[s][1]);
+        // one expert block at a time: split its router weights into three bf16 pieces, stage them
+        // K-contiguous per expert, multiply
 #pragma unroll
         for (int m = 0; m < MT_PER_LANE; ++m) {
-          const int mt = m * 64 + lane, eg = mt % (EP / 4), kg = mt / (EP / 4);
+          const int egl = lane & 3, kg = lane >> 2;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             uint32_t hi[4], mid[4], lo[4];
@@ -358,39 +371,33 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
               const float r2 = r1 - __uint_as_float(mid[i] << 16);
               lo[i] = bf16_bits_rne(r2);
             }
-            unsigned char* row = wl + (eg * 4 + j) * FT_ROW + kg * 8;
+            unsigned char* row = wl + (egl * 4 + j) * FT_ROW + kg * 8;
             u32x2 v;
             v.x = hi[0] | (hi[1] << 16); v.y = hi[2] | (hi[3] << 16);
             *reinterpret_cast<u32x2*>(row) = v;
             v.x = mid[0] | (mid[1] << 16); v.y = mid[2] | (mid[3] << 16);
-            *reinterpret_cast<u32x2*>(row + EP * FT_ROW) = v;
+            *reinterpret_cast<u32x2*>(row + 16 * FT_ROW) = v;
             v.x = lo[0] | (lo[1] << 16); v.y = lo[2] | (lo[3] << 16);
-            *reinterpret_cast<u32x2*>(row + 2 * EP * FT_ROW) = v;
+            *reinterpret_cast<u32x2*>(row + 2 * 16 * FT_ROW) = v;
           }
-        }
-        xb[0] = __builtin_bit_cast(bf16x8, xa[s][0]);
-        xb[1] = __builtin_bit_cast(bf16x8, xa[s][1]);
-      }
-      GATE_LOAD_STAGE(s, c + 4 * PF)  // refill this register stage
-      if (live) {
-        asm volatile("" ::: "memory");  // keep the LDS reads below the LDS writes above (same wavefront: in order)
-        f32x4 acc[EB];
+          asm volatile("" ::: "memory");  // keep the LDS reads below the LDS writes above (same wavefront: in order)
+          acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int b = 0; b < EB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int p = 0; p < 3; ++p)
-#pragma unroll
-            for (int b = 0; b < EB; ++b) {
-              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * EP + b * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
-              acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[s2], acc[b], 0, 0, 0);
+            for (int p = 0; p < 3; ++p) {
+              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
+              acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[s2], acc[m], 0, 0, 0);
             }
+          asm volatile("" ::: "memory");  // ... and the next block's writes below these reads
+        }
+      }
+      GATE_LOAD_STAGE(s, c + NWV * PF)  // refill this register stage
+      if (live) {
 #pragma unroll
         for (int b = 0; b < EB; ++b)
 #pragma unroll
           for (int r = 0; r < 4; ++r) zacc[b][r] += (double)acc[b][r];
-        asm volatile("" ::: "memory");
       }
     }
   }
@@ -398,7 +405,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   __syncthreads();  // every wavefront is done with its staging area
 
   // ---- cross-wavefront sum of the partial logits (float64) and per-token finalisation ------------
-  double* part = reinterpret_cast<double*>(smem);  // [4][EP][FT_TOK]
+  double* part = reinterpret_cast<double*>(smem);  // [NWV][EP][FT_TOK]
 #pragma unroll
   for (int b = 0; b < EB; ++b)
 #pragma unroll
@@ -415,7 +422,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
       if (e < E) {
         v = part[(size_t)e * FT_TOK + tok];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) v += part[((size_t)w * EP + e) * FT_TOK + tok];
+        for (int w = 1; w < NWV; ++w) v += part[((size_t)w * EP + e) * FT_TOK + tok];
         if (br) v += (double)br[e];
       }
       z[i] = v;
@@ -430,45 +437,59 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   __syncthreads();
 
   // ---- exact recompute of the rare tokens whose ranking is within the margin -------------------
-  // Wavefront w takes the expert groups w, w+4, ... (four experts each), its lanes stride over K; the
-  // products are exact in float64 and so is their sum up to rounding at 2^-53, far below any gap that can
-  // decide a ranking.  The flags are turned into one wave-uniform mask first (no LDS read per token).
+  // Each wavefront takes a contiguous K range; a load instruction covers whole router rows (lane = expert
+  // quad + row slot), so that it is coalesced and many of them can be in flight: a token flagged in one
+  // workgroup delays the whole kernel by the time this takes.  The products are exact in float64 and so is
+  // their sum up to rounding at 2^-53, far below any gap that can decide a ranking.  The flags are turned
+  // into one wave-uniform mask first (no LDS read per token).
   uint32_t flagged = (uint32_t)__ballot(lane < FT_TOK && s_flag[lane & (FT_TOK - 1)] != 0);
   flagged = __builtin_amdgcn_readfirstlane(flagged);
-  double* zex = part;  // [EP]
+  constexpr int QN = EP / 4;    // expert quads per router row
+  constexpr int RPI = 64 / QN;  // router rows per load instruction of a wavefront
+  double* zpart = part;         // [NWV][EP]
+  double* zex = part + NWV * EP;  // [EP]
+  const int q = lane % QN, rs = lane / QN;
+  const int rows_per_wave = d / NWV;  // d is a multiple of 64: a whole number of load instructions
+  const bool qlive = q * 4 < E;
   while (flagged) {
     const int tt = __builtin_ctz(flagged);
     flagged &= flagged - 1;
     const int t = t0 + tt;
     const uint16_t* xt = x + (size_t)t * d;
-    for (int g = wave; g < EP / 4; g += 4) {
-      const int e0 = g * 4;
-      if (e0 >= E) break;  // uniform
-      double a[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-      for (int i = lane; i < d; i += 64) {
-        const double xv = (double)bf16_to_f32(xt[i]);
-        const float* wp = wr + (size_t)i * E + e0;
-        float w[4];
-        if (VEC) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(wp);  // E is a multiple of 4: e0 + 3 < E
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    const int r_end = (wave + 1) * rows_per_wave;
+#pragma unroll 8
+    for (int r = wave * rows_per_wave + rs; r < r_end; r += RPI) {
+      const double xv = (double)bf16_to_f32(xt[r]);
+      const float* wp = wr + (size_t)r * E + q * 4;
+      float w[4] = {0.f, 0.f, 0.f, 0.f};
+      if (VEC) {
+        if (qlive) {  // E is a multiple of 4: q*4 + 3 < E
+          const f32x4 v = *reinterpret_cast<const f32x4*>(wp);
           w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) w[j] = e0 + j < E ? wp[j] : 0.f;
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = fma(xv, (double)w[j], a[j]);
-      }
-#pragma unroll
-      for (int m = 32; m >= 1; m >>= 1)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
-      if (lane == 0) {
+      } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          if (e0 + j < E) zex[e0 + j] = a[j] + (br ? (double)br[e0 + j] : 0.0);
+          if (q * 4 + j < E) w[j] = wp[j];
       }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a[j] = fma(xv, (double)w[j], a[j]);
+    }
+#pragma unroll
+    for (int m = QN; m < 64; m <<= 1)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
+    if (rs == 0) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) zpart[wave * EP + q * 4 + j] = a[j];
+    }
+    __syncthreads();
+    if (tid < E) {
+      double v = zpart[tid];
+#pragma unroll
+      for (int w = 1; w < NWV; ++w) v += zpart[w * EP + tid];
+      zex[tid] = v + (br ? (double)br[tid] : 0.0);
     }
     __syncthreads();
     if (tid < 8) {
@@ -486,8 +507,9 @@ template <int EB>
 int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   constexpr int EP = EB * 16;
-  const size_t w_bytes = (size_t)4 * 3 * EP * FT_ROW;
-  const size_t z_bytes = (size_t)4 * EP * FT_TOK * sizeof(double) + 256;
+  constexpr int NWV = gate_waves<EB>();
+  const size_t w_bytes = (size_t)NWV * 3 * 16 * FT_ROW;
+  const size_t z_bytes = (size_t)NWV * EP * FT_TOK * sizeof(double) + 256;
   const size_t shmem = w_bytes > z_bytes ? w_bytes : z_bytes;
   const bool vec = cfg->E % 4 == 0 && ((uintptr_t)w_router & 15) == 0;
   auto kern = vec ? gate_mfma_kernel<EB, true> : gate_mfma_kernel<EB, false>;
@@ -495,7 +517,7 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
   }
-  hipLaunchKernelGGL(kern, dim3((cfg->T + FT_TOK - 1) / FT_TOK), dim3(256), shmem, s, (const uint16_t*)x, w_router,
+  hipLaunchKernelGGL(kern, dim3((cfg->T + FT_TOK - 1) / FT_TOK), dim3(NWV * 64), shmem, s, (const uint16_t*)x, w_router,
                      b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
   return check_hip(hipGetLastError(), "gate launch");
 }
