@@ -297,6 +297,19 @@ int32_t moe_ring_release(moe_ring* r, int32_t layer, void* compute_stream);
 int32_t moe_ring_stats(moe_ring* r, uint64_t* bytes_copied, uint64_t* copies, double* copy_ms);
 int32_t moe_ring_destroy(moe_ring* r);
 
+/* ---- backward pass (first piece) ------------------------------------------ */
+/* Weight-gradient product of the expert FFN's backward pass (the paper is a
+ * training system, Section 3.2, and leaves the kernels open): for every expert e
+ *   c[e, n1, n2] = sum over r in [expert_offsets[e], expert_offsets[e+1]) of a[r, n1] * b[r, n2]
+ * e.g. dW2_e = d_y_e^T h_e (a = d_y [R,d_model], b = h [R,d_ff]) and dW1_e = d_u_e^T xd_e for
+ * OUTPUT_MAJOR weights.  a device bf16 [R,N1], b device bf16 [R,N2], c device float32
+ * [E,N1,N2] (overwritten; zero for an expert without rows); expert_offsets is read on
+ * the device; max_rows_per_expert is the caller's bound of any expert's row count (only
+ * used to check that an expert's operand block stays below 2 GiB).  N1 and N2 must be
+ * multiples of 256 (MOE_ERR_UNSUPPORTED otherwise). */
+int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
+                         int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert, void* stream);
+
 /* ---- frequency-based expert cache (Algorithm 2, Section 3.2.2) ----------- */
 /*
  * Host-side policy deciding which items (experts, numbered by the caller, e.g.

@@ -1,8 +1,7 @@
 """CPU oracle for the backward pass of the sparsely-gated MoE layer (TEST INFRASTRUCTURE).
 
-This file is the checker, not the product: only ``tests/`` may import it.  No GPU
-kernel of the backward pass exists yet; the oracle is written and pinned first so that
-they can be built against it.
+This file is the checker, not the product: only ``tests/`` may import it.  It was
+written and pinned before any backward kernel, so that they can be built against it.
 
 What it computes.  The paper is mainly a training system (Section 3.2) but, as for the
 forward pass, never writes the layer's equations; the backward pass is the chain rule
@@ -30,9 +29,9 @@ experts.  Expert matrices are input-major ([E, in, out]) as in the forward oracl
 Pins (tests/test_backward_oracle_pins.py): central differences of the forward oracle
 along random directions in every input and parameter (the step is small enough that
 the routing does not change, which the test checks); torch's autograd in float64 on a
-dense re-expression of the layer with the routing fixed; the special cases E = 1
-(a dense FFN: gate gradients vanish) and k = E without capacity (a full softmax
-mixture).  No function here is "parity unpinned".
+dense re-expression of the layer with the routing fixed; the special case E = 1 (a
+dense FFN: gate gradients vanish); the weight-gradient product by brute force and
+against the layer's own dW2.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -144,3 +143,17 @@ def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, 
     grads["topk_w"] = d_w
     grads["logits"] = d_z
     return grads
+
+
+def expert_wgrad(a: np.ndarray, b: np.ndarray, offsets: np.ndarray) -> np.ndarray:
+    """c[e] = a[rows of e]^T b[rows of e]: the weight-gradient products of the expert FFN above
+    (dW2_e = h_e^T d_y_e, dW1_e = xd_e^T d_u_e and their transposes), one matmul per expert."""
+    E = len(offsets) - 1
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    c = np.zeros((E, a.shape[1], b.shape[1]), dtype=np.float64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            c[e] = np.matmul(a[lo:hi].T, b[lo:hi])
+    return c

@@ -120,6 +120,7 @@ def lib() -> C.CDLL:
                                                 C.POINTER(C.c_int64)]
         L.moe_expert_cache_lookup.argtypes = [vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.moe_expert_cache_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
         L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
@@ -257,6 +258,13 @@ def moe_layer_experts(cfg, weights: Weights, x, residual, out, ws, stream=None):
     _check(lib().moe_layer_experts(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_experts")
+
+
+def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None):
+    """c[e] = a[rows of e]^T @ b[rows of e]; a [R,N1], b [R,N2] bf16, c [E,N1,N2] float32."""
+    E, N1, N2 = c.shape
+    _check(lib().moe_expert_wgrad(_ptr(a), _ptr(b), _ptr(expert_offsets), _ptr(c), E, N1, N2, max_rows_per_expert,
+                                  _stream(stream)), "moe_expert_wgrad")
 
 
 class StageTimer:

@@ -135,6 +135,35 @@ def pin_single_expert_is_a_dense_ffn(_c=None):
         assert np.allclose(t[n].grad.numpy(), g[n][0], rtol=1e-10, atol=1e-12)
 
 
+def test_expert_wgrad_bruteforce_and_against_layer_backward():
+    r = np.random.default_rng(8)
+    offsets = np.array([0, 3, 3, 4, 9])
+    A, Bm = r.standard_normal((9, 5)), r.standard_normal((9, 4))
+    got = B.expert_wgrad(A, Bm, offsets)
+    for e in range(4):
+        for i in range(5):
+            for j in range(4):
+                want = sum(A[t, i] * Bm[t, j] for t in range(offsets[e], offsets[e + 1]))
+                assert abs(got[e, i, j] - want) < 1e-12
+    assert not got[1].any()
+    # the layer's own weight gradients are such products: dW2_e (input-major [f, d]) = h_e^T d_y_e
+    c = CASES[0]
+    x, W, res, G = make(c, 5)
+    g = B.layer_backward(x, W, G, residual=res, **kw(c))
+    fw = F.layer_forward(x, W, residual=res, **kw(c))
+    T, k = fw["topk_w"].shape
+    d_y = np.zeros_like(fw["yd"])
+    for j in range(k):
+        rows = fw["assign_to_row"][j * T:(j + 1) * T]
+        keep = rows >= 0
+        d_y[rows[keep]] = fw["topk_w"][keep, j][:, None] * G[keep]
+    h = np.zeros((fw["xd"].shape[0], c["f"]))
+    for e in range(c["E"]):
+        lo, hi = fw["expert_offsets"][e], fw["expert_offsets"][e + 1]
+        h[lo:hi] = F.gelu(fw["xd"][lo:hi] @ W["w1"][e] + W["b1"][e])
+    assert np.allclose(B.expert_wgrad(h, d_y, fw["expert_offsets"]), g["w2"], rtol=1e-12, atol=1e-12)
+
+
 PINS = [pin_central_differences, pin_torch_autograd]
 
 
