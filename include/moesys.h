@@ -298,6 +298,16 @@ int32_t moe_ring_stats(moe_ring* r, uint64_t* bytes_copied, uint64_t* copies, do
 int32_t moe_ring_destroy(moe_ring* r);
 
 /* ---- backward pass (first piece) ------------------------------------------ */
+/* Backward of moe_combine for the gradient d_out [T,d_model] of its output: for every kept
+ * choice (t,j) with row r = assign_to_row[j*T+t]
+ *   d_yd[r] = topk_w[t,j] * d_out[t]   (cfg.dtype, one rounding)
+ *   d_topk_w[t,j] = <d_out[t], yd[r]>  (float32, fp32 accumulation; 0 for a dropped choice)
+ * The gradient of the residual is d_out itself.  All pointers device; yd, d_yd [R_max,d_model]
+ * (rows beyond the kept ones are not touched); d_topk_w [T,k]. */
+int32_t moe_combine_backward(const moe_config* cfg, const void* d_out, const void* yd,
+                             const int32_t* assign_to_row, const float* topk_w, void* d_yd,
+                             float* d_topk_w, void* stream);
+
 /* Weight-gradient product of the expert FFN's backward pass (the paper is a
  * training system, Section 3.2, and leaves the kernels open): for every expert e
  *   c[e, n1, n2] = sum over r in [expert_offsets[e], expert_offsets[e+1]) of a[r, n1] * b[r, n2]
@@ -309,6 +319,24 @@ int32_t moe_ring_destroy(moe_ring* r);
  * multiples of 256 (MOE_ERR_UNSUPPORTED otherwise). */
 int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
                          int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert, void* stream);
+
+/* Backward of moe_expert_ffn for GELU experts in MOE_BF16, given d_yd [R_max,d_model]:
+ *   d_xd [R_max,d_model] (cfg.dtype), d_w1 [E,d_ff,d_model], d_b1 [E,d_ff], d_w2 [E,d_model,d_ff],
+ *   d_b2 [E,d_model] (float32, OUTPUT_MAJOR like the weights; overwritten; the bias gradients are
+ *   required exactly when w has the bias).
+ * w holds the OUTPUT_MAJOR weights of the forward pass; w1_input_major [E,d_model,d_ff] and
+ * w2_input_major [E,d_ff,d_model] are their transposed copies (moe_transpose_expert_weights),
+ * on which the input gradients are plain grouped products.  xd [R_max,d_model] and
+ * h [R_max,d_ff] are the forward pass's dispatched rows and hidden activations (for
+ * moe_layer_forward: gather xd with moe_dispatch; h is in the workspace); the
+ * pre-activations are recomputed.  ws: moe_expert_ffn_backward_workspace_bytes(cfg), 256-byte
+ * aligned.  d_model and d_ff must be multiples of 256.  All pointers device. */
+size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg);
+int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
+                                const void* w2_input_major, const void* xd, const void* h,
+                                const void* d_yd, const int32_t* expert_offsets, void* d_xd,
+                                float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
+                                size_t ws_bytes, void* stream);
 
 /* ---- frequency-based expert cache (Algorithm 2, Section 3.2.2) ----------- */
 /*

@@ -53,29 +53,14 @@ def silu_grad(v: np.ndarray) -> np.ndarray:
     return s * (1.0 + v * (1.0 - s))
 
 
-def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, capacity_factor: float,
-                   renormalize: bool, act: str, residual: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
-    """Gradients of sum(out * d_out) with respect to x, the residual and every parameter."""
-    x = np.asarray(x, dtype=np.float64)
-    G = np.asarray(d_out, dtype=np.float64)
-    T, d = x.shape
-    fw = F.layer_forward(x, weights, E=E, k=k, capacity_factor=capacity_factor, renormalize=renormalize, act=act,
-                         residual=residual)
-    p, idx, w = fw["probs"], fw["topk_idx"], fw["topk_w"]
-    a2r, offsets, xd, yd = fw["assign_to_row"], fw["expert_offsets"], fw["xd"], fw["yd"]
-    R = xd.shape[0]
-    grads: Dict[str, np.ndarray] = {"residual": G.copy()}
-
-    # combine
-    d_y = np.zeros((R, d))
-    d_w = np.zeros((T, k))
-    for j in range(k):
-        rows = a2r[j * T:(j + 1) * T].astype(np.int64)
-        keep = rows >= 0
-        d_y[rows[keep]] = w[keep, j][:, None] * G[keep]
-        d_w[keep, j] = np.sum(G[keep] * yd[rows[keep]], axis=1)
-
-    # expert FFN
+def expert_ffn_backward(xd, offsets, weights: Dict[str, np.ndarray], d_y, act: str) -> Dict[str, np.ndarray]:
+    """Gradients of the per-expert FFN for the gradient d_y of its output rows: "xd" and one entry per
+    parameter present in ``weights`` (input-major, like the parameters)."""
+    xd = np.asarray(xd, dtype=np.float64)
+    d_y = np.asarray(d_y, dtype=np.float64)
+    E = len(offsets) - 1
+    R, d = xd.shape
+    grads: Dict[str, np.ndarray] = {}
     d_xd = np.zeros((R, d))
     names = ("w1", "b1", "w2", "b2") if act == "gelu" else ("w_gate_proj", "w_up", "w_down")
     for n in names:
@@ -114,6 +99,36 @@ def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, 
             d_xd[lo:hi] = np.matmul(d_g, wg.T) + np.matmul(d_u, wu.T)
         else:
             raise ValueError(act)
+    grads["xd"] = d_xd
+    return grads
+
+
+def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, capacity_factor: float,
+                   renormalize: bool, act: str, residual: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Gradients of sum(out * d_out) with respect to x, the residual and every parameter."""
+    x = np.asarray(x, dtype=np.float64)
+    G = np.asarray(d_out, dtype=np.float64)
+    T, d = x.shape
+    fw = F.layer_forward(x, weights, E=E, k=k, capacity_factor=capacity_factor, renormalize=renormalize, act=act,
+                         residual=residual)
+    p, idx, w = fw["probs"], fw["topk_idx"], fw["topk_w"]
+    a2r, offsets, xd, yd = fw["assign_to_row"], fw["expert_offsets"], fw["xd"], fw["yd"]
+    R = xd.shape[0]
+    grads: Dict[str, np.ndarray] = {"residual": G.copy()}
+
+    # combine
+    d_y = np.zeros((R, d))
+    d_w = np.zeros((T, k))
+    for j in range(k):
+        rows = a2r[j * T:(j + 1) * T].astype(np.int64)
+        keep = rows >= 0
+        d_y[rows[keep]] = w[keep, j][:, None] * G[keep]
+        d_w[keep, j] = np.sum(G[keep] * yd[rows[keep]], axis=1)
+
+    # expert FFN
+    ffn = expert_ffn_backward(xd, offsets, weights, d_y, act)
+    d_xd = ffn.pop("xd")
+    grads.update(ffn)
 
     # dispatch
     d_x = np.zeros((T, d))

@@ -120,6 +120,10 @@ def lib() -> C.CDLL:
                                                 C.POINTER(C.c_int64)]
         L.moe_expert_cache_lookup.argtypes = [vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.moe_expert_cache_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.moe_combine_backward.argtypes = [C.POINTER(_Config)] + [vp] * 7
+        L.moe_expert_ffn_backward_workspace_bytes.restype = C.c_size_t
+        L.moe_expert_ffn_backward_workspace_bytes.argtypes = [C.POINTER(_Config)]
+        L.moe_expert_ffn_backward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 12 + [C.c_size_t, vp]
         L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
@@ -258,6 +262,26 @@ def moe_layer_experts(cfg, weights: Weights, x, residual, out, ws, stream=None):
     _check(lib().moe_layer_experts(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_experts")
+
+
+def moe_combine_backward(cfg, d_out, yd, assign_to_row, topk_w, d_yd, d_topk_w, stream=None):
+    c = cfg.c()
+    _check(lib().moe_combine_backward(C.byref(c), _ptr(d_out), _ptr(yd), _ptr(assign_to_row), _ptr(topk_w), _ptr(d_yd),
+                                      _ptr(d_topk_w), _stream(stream)), "moe_combine_backward")
+
+
+def moe_expert_ffn_backward_workspace_bytes(cfg) -> int:
+    c = cfg.c()
+    return lib().moe_expert_ffn_backward_workspace_bytes(C.byref(c))
+
+
+def moe_expert_ffn_backward(cfg, weights: Weights, w1_input_major, w2_input_major, xd, h, d_yd, expert_offsets, d_xd,
+                            d_w1, d_b1, d_w2, d_b2, ws, stream=None):
+    c = cfg.c()
+    _check(lib().moe_expert_ffn_backward(C.byref(c), C.byref(weights.c), _ptr(w1_input_major), _ptr(w2_input_major),
+                                         _ptr(xd), _ptr(h), _ptr(d_yd), _ptr(expert_offsets), _ptr(d_xd), _ptr(d_w1),
+                                         _ptr(d_b1), _ptr(d_w2), _ptr(d_b2), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)), "moe_expert_ffn_backward")
 
 
 def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None):

@@ -875,6 +875,15 @@ int32_t launch_gemm2_combine_bf16(const moe_config* cfg, const moe_weights* w, c
       cfg->d_model, cfg->d_ff, s, w->expert_elem_offset, topk_w, (const uint16_t*)residual);
 }
 
+// A plain grouped product out[r, n] = sum_k act[r, k] * w_e[n, k] (+ bias_e[n]) with the second GEMM's kernel:
+// what the backward pass needs for its input gradients (on the weights' transposed copies) and for
+// recomputing the pre-activations.  counters8: eight zeroed ints.
+int32_t launch_grouped_matmul_bf16(const moe_config* cfg, const void* act, const void* w, const void* bias,
+                                   const int32_t* offsets, void* out, int N, int K, int32_t* counters8, hipStream_t s) {
+  return gemm_any<EPI_BIAS>(cfg, (const uint16_t*)act, (const uint16_t*)w, nullptr, (const uint16_t*)bias, offsets,
+                            (uint16_t*)out, nullptr, counters8, nullptr, N, K, s, nullptr);
+}
+
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.
 bool gemm1_can_gather(const moe_config* cfg) {
   return cfg->dtype == MOE_BF16 && (int64_t)cfg->T * cfg->d_model * 2 < ((int64_t)1 << 31);

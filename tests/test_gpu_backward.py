@@ -1,0 +1,98 @@
+"""Backward pass pieces on the GPU against the backward oracle: the combine's backward and the expert FFN's
+backward (input gradient, weight and bias gradients) on the forward pass's own routing."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2205_10034_amd as M
+from oracle import moe_backward_oracle as B
+from oracle import moe_oracle as O
+from workloads import WORKLOADS, make_layer
+
+from gpu_util import alloc_ws, rel_fro, to_dev, to_np, upload_weights
+
+pytestmark = pytest.mark.gpu
+
+
+def forward_pieces(wl, L, W, x):
+    """gate -> dispatch (with the gathered rows) -> expert FFN through the C ABI; returns the device buffers."""
+    cfg = M.MoEConfig.from_workload(wl)
+    A = wl.k * wl.T
+    idx = torch.empty(wl.T, wl.k, dtype=torch.int32, device="cuda")
+    w = torch.empty(wl.T, wl.k, dtype=torch.float32, device="cuda")
+    M.moe_gate(cfg, x, W.tensors["w_router"], W.tensors.get("b_router"), idx, w)
+    counts = torch.empty(wl.E, dtype=torch.int32, device="cuda")
+    offsets = torch.empty(wl.E + 1, dtype=torch.int32, device="cuda")
+    a2r = torch.empty(A, dtype=torch.int32, device="cuda")
+    r2a = torch.empty(A, dtype=torch.int32, device="cuda")
+    lay = M.moe_workspace_layout(cfg)
+    xd = torch.zeros(max(lay["r_max"], 1), wl.d_model, dtype=torch.bfloat16, device="cuda")
+    M.moe_dispatch(cfg, x, idx, counts, offsets, a2r, r2a, xd, alloc_ws(cfg, 1))
+    yd = torch.zeros_like(xd)
+    ws_ffn = alloc_ws(cfg, 2)
+    M.moe_expert_ffn(cfg, W, xd, offsets, yd, ws_ffn)
+    torch.cuda.synchronize()
+    h = ws_ffn[:lay["r_max"] * wl.d_ff * 2].view(torch.bfloat16).reshape(lay["r_max"], wl.d_ff)
+    return cfg, dict(idx=idx, w=w, offsets=offsets, a2r=a2r, xd=xd, yd=yd, h=h, r_max=lay["r_max"])
+
+
+@pytest.mark.parametrize("kw", [dict(T=700, E=4, d_model=256, d_ff=512), dict(T=1500, E=8, d_model=512, d_ff=256, capacity_factor=0.6),
+                                dict(T=96, E=16, d_model=256, d_ff=256, k=1, capacity_factor=0.0)],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_combine_and_expert_ffn_backward(kw):
+    wl = WORKLOADS["gpt"].scaled(**kw)
+    print(f"backward case {wl}", flush=True)
+    L = make_layer(wl, with_bias=True)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    cfg, fw = forward_pieces(wl, L, W, x)
+    ref_fw = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor, renormalize=wl.renormalize,
+                             act=wl.act)
+    assert np.array_equal(fw["a2r"].cpu().numpy(), ref_fw["assign_to_row"])
+    R = int(ref_fw["expert_offsets"][-1])
+    rng = np.random.default_rng(3)
+    G_np = to_np(to_dev(rng.standard_normal(L["x"].shape).astype(np.float32), wl.dtype))
+    G = to_dev(G_np, wl.dtype)
+
+    # ---- combine backward (fed the GPU's own yd and gate weights, like the oracle below)
+    d_yd = torch.full_like(fw["yd"], float("nan"))
+    d_w = torch.full((wl.T, wl.k), float("nan"), dtype=torch.float32, device="cuda")
+    M.moe_combine_backward(cfg, G, fw["yd"], fw["a2r"], fw["w"], d_yd, d_w)
+    torch.cuda.synchronize()
+    yd_np, w_np = to_np(fw["yd"]), fw["w"].cpu().numpy()
+    a2r = ref_fw["assign_to_row"]
+    ref_dy = np.zeros((R, wl.d_model))
+    ref_dw = np.zeros((wl.T, wl.k))
+    for j in range(wl.k):
+        rows = a2r[j * wl.T:(j + 1) * wl.T]
+        keep = rows >= 0
+        ref_dy[rows[keep]] = w_np[keep, j][:, None].astype(np.float64) * G_np[keep]
+        ref_dw[keep, j] = np.sum(G_np[keep].astype(np.float64) * yd_np[rows[keep]], axis=1)
+    assert rel_fro(to_np(d_yd[:R]), ref_dy) < 4e-3          # one bf16 rounding
+    assert np.allclose(d_w.cpu().numpy(), ref_dw, rtol=1e-4, atol=1e-4)
+    assert (d_w.cpu().numpy()[a2r.reshape(wl.k, wl.T).T < 0] == 0).all()
+
+    # ---- expert FFN backward: the oracle gets the rows and the upstream gradient the GPU used
+    w1_im, w2_im = to_dev(L["w1"], wl.dtype), to_dev(L["w2"], wl.dtype)         # input-major, as generated
+    d_xd = torch.full_like(fw["xd"], float("nan"))
+    d_w1 = torch.full((wl.E, wl.d_ff, wl.d_model), float("nan"), dtype=torch.float32, device="cuda")
+    d_w2 = torch.full((wl.E, wl.d_model, wl.d_ff), float("nan"), dtype=torch.float32, device="cuda")
+    d_b1 = torch.full((wl.E, wl.d_ff), float("nan"), dtype=torch.float32, device="cuda")
+    d_b2 = torch.full((wl.E, wl.d_model), float("nan"), dtype=torch.float32, device="cuda")
+    nws = M.moe_expert_ffn_backward_workspace_bytes(cfg)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        M.moe_expert_ffn_backward(cfg, W, w1_im, w2_im, fw["xd"], fw["h"], d_yd, fw["offsets"], d_xd, d_w1, d_b1, d_w2,
+                                  d_b2, ws)
+        torch.cuda.synchronize()
+        ref = B.expert_ffn_backward(to_np(fw["xd"][:R]), ref_fw["expert_offsets"], L, to_np(d_yd[:R]), wl.act)
+        errs = {
+            "xd": rel_fro(to_np(d_xd[:R]), ref["xd"]),
+            "w1": rel_fro(d_w1.cpu().numpy().transpose(0, 2, 1), ref["w1"]),
+            "w2": rel_fro(d_w2.cpu().numpy().transpose(0, 2, 1), ref["w2"]),
+            "b1": rel_fro(d_b1.cpu().numpy(), ref["b1"]),
+            "b2": rel_fro(d_b2.cpu().numpy(), ref["b2"]),
+        }
+        print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        assert all(v < 1e-2 for v in errs.values()), errs
+        assert errs["b2"] < 1e-5 and errs["w2"] < 6e-3      # exact products of the stored bf16 operands (h is the GPU's rounding of gelu)
