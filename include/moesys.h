@@ -338,6 +338,24 @@ int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, con
                                 float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
                                 size_t ws_bytes, void* stream);
 
+/* Backward of moe_layer_forward (GELU experts, MOE_BF16, E <= 64) for the gradient d_out
+ * [T,d_model] of its output, with the routing of the forward pass held fixed:
+ *   d_x [T,d_model] (cfg.dtype) = add_to_d_x (nullable; e.g. d_out when the layer ran with
+ *       residual == x) + the experts' path (through dispatch) + the gate's path, one rounding;
+ *   d_w_router [d_model,E], d_b_router [E] (float32; the latter required iff w->b_router);
+ *   d_w1, d_b1, d_w2, d_b2 as in moe_expert_ffn_backward.
+ * The gradient of the residual input is d_out itself.  fwd_ws is the workspace that
+ * moe_layer_forward (or route + experts) left for the same cfg, x and w: its routing
+ * tables and hidden activations are read; the gate is run again for the probabilities and
+ * the pre-activations are recomputed.  ws: moe_layer_backward_workspace_bytes(cfg),
+ * 256-byte aligned; nothing is allocated and the device is not synchronised. */
+size_t moe_layer_backward_workspace_bytes(const moe_config* cfg);
+int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
+                           const void* w2_input_major, const void* x, const void* d_out,
+                           const void* add_to_d_x, const void* fwd_ws, size_t fwd_ws_bytes, void* d_x,
+                           float* d_w_router, float* d_b_router, float* d_w1, float* d_b1,
+                           float* d_w2, float* d_b2, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- frequency-based expert cache (Algorithm 2, Section 3.2.2) ----------- */
 /*
  * Host-side policy deciding which items (experts, numbered by the caller, e.g.

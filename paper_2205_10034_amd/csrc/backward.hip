@@ -10,6 +10,7 @@
 
 namespace moesys {
 
+int32_t launch_gather_rows(const moe_config*, const void*, const int32_t*, void*, hipStream_t);
 int32_t launch_grouped_matmul_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, void*, int, int,
                                    int32_t*, hipStream_t);
 int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, int, int, int, int64_t, hipStream_t);
@@ -69,6 +70,128 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const uint4* __restrict_
       out[(size_t)e * N + blockIdx.x * 512 + c] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
 
+// ---- gate ----------------------------------------------------------------------------------------
+// d_z[t, e] = p[t,e] * (d_p[t,e] - sum_e' d_p[t,e'] p[t,e']), where d_p is zero off the k selected experts and
+// there d_p = (d_w_j - sum_i d_w_i w_i) / S with S = sum of the selected probabilities if the weights are
+// renormalised, d_p = d_w_j otherwise.  One wavefront per token, lanes over the experts.
+__global__ __launch_bounds__(256) void gate_dlogits_kernel(const float* __restrict__ probs, const int32_t* __restrict__ topk_idx,
+                                                           const float* __restrict__ topk_w, const float* __restrict__ d_topk_w,
+                                                           float* __restrict__ d_z, int T, int E, int k, int renorm) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float S = 0.f, common = 0.f;
+  for (int j = 0; j < k; ++j) {
+    S += probs[(size_t)t * E + topk_idx[(size_t)t * k + j]];
+    common += d_topk_w[(size_t)t * k + j] * topk_w[(size_t)t * k + j];
+  }
+  float s = 0.f;  // sum over the selected experts of d_p * p
+  for (int j = 0; j < k; ++j) {
+    const float dp = renorm ? (d_topk_w[(size_t)t * k + j] - common) / S : d_topk_w[(size_t)t * k + j];
+    s += dp * probs[(size_t)t * E + topk_idx[(size_t)t * k + j]];
+  }
+  for (int e = lane; e < E; e += 64) {
+    float dp = 0.f;
+    for (int j = 0; j < k; ++j)
+      if (topk_idx[(size_t)t * k + j] == e) dp = renorm ? (d_topk_w[(size_t)t * k + j] - common) / S : d_topk_w[(size_t)t * k + j];
+    d_z[(size_t)t * E + e] = probs[(size_t)t * E + e] * (dp - s);
+  }
+}
+
+// out[e] = sum_t d_z[t, e]: one workgroup per expert, fixed reduction order
+__global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict__ d_z, float* __restrict__ out, int T, int E) {
+  __shared__ float part[256];
+  const int e = blockIdx.x;
+  float acc = 0.f;
+  for (int t = threadIdx.x; t < T; t += 256) acc += d_z[(size_t)t * E + e];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int m = 128; m >= 1; m >>= 1) {
+    if ((int)threadIdx.x < m) part[threadIdx.x] += part[threadIdx.x + m];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[e] = part[0];
+}
+
+constexpr int GB_TOK = 32;   // tokens per workgroup of the two kernels below
+constexpr int GB_MAXE = 64;  // experts they keep in registers
+
+// d_x[t, i] = (extra[t, i]) + sum over the kept choices j of d_xd[a2r[j*T+t], i] + sum_e d_z[t,e] * W_g[i,e],
+// rounded once.  A thread owns two columns i and keeps their router rows in registers across GB_TOK tokens.
+template <int EC>
+__global__ __launch_bounds__(256) void dx_kernel(const uint32_t* __restrict__ d_xd, const int32_t* __restrict__ a2r,
+                                                 const float* __restrict__ d_z, const float* __restrict__ w_router,
+                                                 const uint32_t* __restrict__ extra, uint32_t* __restrict__ d_x, int T, int d,
+                                                 int E, int k) {
+  const int i2 = blockIdx.x * 256 + threadIdx.x;  // column pair
+  if (i2 * 2 >= d) return;
+  float w0[EC], w1[EC];
+#pragma unroll
+  for (int e = 0; e < EC; ++e) {
+    w0[e] = e < E ? w_router[(size_t)(2 * i2) * E + e] : 0.f;
+    w1[e] = e < E ? w_router[(size_t)(2 * i2 + 1) * E + e] : 0.f;
+  }
+  const int t_end = min(T, (int)(blockIdx.y + 1) * GB_TOK);
+  for (int t = blockIdx.y * GB_TOK; t < t_end; ++t) {
+    float a0 = 0.f, a1 = 0.f;
+    if (extra) {
+      const uint32_t v = extra[(size_t)t * (d / 2) + i2];
+      a0 = bf16_lo(v); a1 = bf16_hi(v);
+    }
+    for (int j = 0; j < k; ++j) {
+      const int r = a2r[(size_t)j * T + t];
+      if (r >= 0) {
+        const uint32_t v = d_xd[(size_t)r * (d / 2) + i2];
+        a0 += bf16_lo(v); a1 += bf16_hi(v);
+      }
+    }
+    const float* dz = d_z + (size_t)t * E;
+#pragma unroll
+    for (int e = 0; e < EC; ++e) {
+      const float z = e < E ? dz[e] : 0.f;
+      a0 = fmaf(z, w0[e], a0);
+      a1 = fmaf(z, w1[e], a1);
+    }
+    d_x[(size_t)t * (d / 2) + i2] = to_bf16(a0) | (to_bf16(a1) << 16);
+  }
+}
+
+// partial[slice, i, e] = sum over the slice's tokens of x[t, i] * d_z[t, e]
+template <int EC>
+__global__ __launch_bounds__(256) void dwg_partial_kernel(const uint32_t* __restrict__ x, const float* __restrict__ d_z,
+                                                          float* __restrict__ partial, int T, int d, int E, int slice_tokens) {
+  const int i2 = blockIdx.x * 256 + threadIdx.x;
+  if (i2 * 2 >= d) return;
+  float a0[EC], a1[EC];
+#pragma unroll
+  for (int e = 0; e < EC; ++e) a0[e] = a1[e] = 0.f;
+  const int t_end = min(T, (int)(blockIdx.y + 1) * slice_tokens);
+  for (int t = blockIdx.y * slice_tokens; t < t_end; ++t) {
+    const uint32_t v = x[(size_t)t * (d / 2) + i2];
+    const float x0 = bf16_lo(v), x1 = bf16_hi(v);
+    const float* dz = d_z + (size_t)t * E;
+#pragma unroll
+    for (int e = 0; e < EC; ++e) {
+      const float z = e < E ? dz[e] : 0.f;
+      a0[e] = fmaf(x0, z, a0[e]);
+      a1[e] = fmaf(x1, z, a1[e]);
+    }
+  }
+  float* p0 = partial + ((size_t)blockIdx.y * d + 2 * i2) * E;
+#pragma unroll
+  for (int e = 0; e < EC; ++e)
+    if (e < E) { p0[e] = a0[e]; p0[E + e] = a1[e]; }
+}
+
+// out[n] = sum over the slices of partial[slice, n], in slice order
+__global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, size_t n, int slices) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int s = 0; s < slices; ++s) acc += partial[(size_t)s * n + i];
+  out[i] = acc;
+}
+
 __global__ void clear8_kernel(int32_t* p) {
   if (threadIdx.x < 8) p[threadIdx.x] = 0;
 }
@@ -84,24 +207,37 @@ extern "C" size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg)
   return 2 * rf + 256;  // u, d_h (becomes d_u), tile counters
 }
 
+static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
+                                 const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
+                                 const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1, float* d_w2,
+                                 float* d_b2, void* ws, size_t ws_bytes, void* stream);
+
 extern "C" int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                            const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
                                            const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1,
                                            float* d_w2, float* d_b2, void* ws, size_t ws_bytes, void* stream) {
+  return ffn_backward_impl("moe_expert_ffn_backward", cfg, w, w1_input_major, w2_input_major, xd, h, d_yd, expert_offsets,
+                           d_xd, d_w1, d_b1, d_w2, d_b2, ws, ws_bytes, stream);
+}
+
+static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
+                                 const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
+                                 const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1, float* d_w2,
+                                 float* d_b2, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = moe_config_check(cfg);
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
   if (cfg->dtype != MOE_BF16 || cfg->act != MOE_ACT_GELU)
-    return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_backward: bf16 GELU experts only");
-  if (w->expert_elem_offset) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_backward: contiguous expert arrays only");
+    return fail(MOE_ERR_UNSUPPORTED, "%s: bf16 GELU experts only", who);
+  if (w->expert_elem_offset) return fail(MOE_ERR_UNSUPPORTED, "%s: contiguous expert arrays only", who);
   if (!w1_input_major || !w2_input_major || !expert_offsets || !d_w1 || !d_w2)
-    return fail(MOE_ERR_INVALID_ARG, "moe_expert_ffn_backward: NULL argument");
-  if ((w->b1 && !d_b1) || (w->b2 && !d_b2)) return fail(MOE_ERR_INVALID_ARG, "moe_expert_ffn_backward: a bias without a gradient buffer");
+    return fail(MOE_ERR_INVALID_ARG, "%s: NULL argument", who);
+  if ((w->b1 && !d_b1) || (w->b2 && !d_b2)) return fail(MOE_ERR_INVALID_ARG, "%s: a bias without a gradient buffer", who);
   const size_t need = moe_expert_ffn_backward_workspace_bytes(cfg);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
-    return fail(MOE_ERR_WORKSPACE, "moe_expert_ffn_backward: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
+    return fail(MOE_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned (got %zu)", who, need, ws_bytes);
   const int64_t rmax = max_rows(cfg);
-  if (rmax > 0 && (!xd || !h || !d_yd || !d_xd)) return fail(MOE_ERR_INVALID_ARG, "moe_expert_ffn_backward: xd, h, d_yd, d_xd must be non-NULL");
+  if (rmax > 0 && (!xd || !h || !d_yd || !d_xd)) return fail(MOE_ERR_INVALID_ARG, "%s: xd, h, d_yd, d_xd must be non-NULL", who);
   hipStream_t s = (hipStream_t)stream;
   const int E = cfg->E, d = cfg->d_model, f = cfg->d_ff;
   const size_t rf = align_up((size_t)rmax * f * 2, 256);
@@ -138,4 +274,126 @@ extern "C" int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weig
   }
   if ((st = clear()) != MOE_OK) return st;
   return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr, s);
+}
+
+// ---- whole layer ------------------------------------------------------------------------------------
+namespace {
+
+struct BwLayout {
+  size_t probs, idx, w, d_w, d_z, xd, d_yd, d_xd, yd, partial, ffn, total;
+  int slices;
+};
+
+constexpr int DWG_SLICE = 256;  // tokens per partial sum of the router's weight gradient
+
+void bw_layout(const moe_config* cfg, BwLayout* L) {
+  const size_t T = (size_t)cfg->T, E = (size_t)cfg->E, k = (size_t)cfg->k, d = (size_t)cfg->d_model;
+  const size_t R = (size_t)max_rows(cfg);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; };
+  L->slices = (int)((T + DWG_SLICE - 1) / DWG_SLICE);
+  L->probs = take(T * E * 4);
+  L->idx = take(T * k * 4);
+  L->w = take(T * k * 4);
+  L->d_w = take(T * k * 4);
+  L->d_z = take(T * E * 4);
+  L->xd = take(R * d * 2);
+  L->d_yd = take(R * d * 2);
+  L->d_xd = take(R * d * 2);
+  L->yd = take(gemm2_can_combine(cfg) ? R * d * 2 + 256 : 0);  // (+ counters of the product that recomputes it)
+  L->partial = take((size_t)L->slices * d * E * 4);
+  L->ffn = take(moe_expert_ffn_backward_workspace_bytes(cfg));
+  L->total = off;
+}
+
+template <int EC>
+int32_t gate_products(const moe_config* cfg, const void* x, const float* w_router, const int32_t* a2r, const float* d_z,
+                      const void* d_xd, const void* extra, void* d_x, float* d_w_router, float* partial, int slices,
+                      hipStream_t s) {
+  const int T = cfg->T, d = cfg->d_model, E = cfg->E;
+  const dim3 block(256);
+  const unsigned col_blocks = (unsigned)((d / 2 + 255) / 256);
+  hipLaunchKernelGGL(dx_kernel<EC>, dim3(col_blocks, (unsigned)((T + GB_TOK - 1) / GB_TOK)), block, 0, s, (const uint32_t*)d_xd, a2r, d_z,
+                     w_router, (const uint32_t*)extra, (uint32_t*)d_x, T, d, E, cfg->k);
+  hipLaunchKernelGGL(dwg_partial_kernel<EC>, dim3(col_blocks, (unsigned)slices), block, 0, s, (const uint32_t*)x, d_z, partial, T, d, E,
+                     DWG_SLICE);
+  const size_t n = (size_t)d * E;
+  hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 255) / 256)), block, 0, s, partial, d_w_router, n, slices);
+  return check_hip(hipGetLastError(), "gate backward launch");
+}
+
+}  // namespace
+
+extern "C" size_t moe_layer_backward_workspace_bytes(const moe_config* cfg) {
+  if (moe_config_check(cfg) != MOE_OK) return 0;
+  BwLayout L;
+  bw_layout(cfg, &L);
+  return L.total;
+}
+
+extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
+                                      const void* w2_input_major, const void* x, const void* d_out, const void* add_to_d_x,
+                                      const void* fwd_ws, size_t fwd_ws_bytes, void* d_x, float* d_w_router,
+                                      float* d_b_router, float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if ((st = check_weights(cfg, w)) != MOE_OK) return st;
+  if (cfg->dtype != MOE_BF16 || cfg->act != MOE_ACT_GELU) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: bf16 GELU experts only");
+  if (cfg->E > GB_MAXE) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d experts", GB_MAXE);
+  if (!w->w_router || !d_w_router || (w->b_router && !d_b_router))
+    return fail(MOE_ERR_INVALID_ARG, "moe_layer_backward: router weights and their gradient buffers must be non-NULL");
+  if (cfg->T > 0 && (!x || !d_out || !d_x)) return fail(MOE_ERR_INVALID_ARG, "moe_layer_backward: x, d_out and d_x must be non-NULL");
+  moe_ws_layout F;
+  moe_workspace_layout(cfg, &F);
+  if (!fwd_ws || ((uintptr_t)fwd_ws & 255) || fwd_ws_bytes < F.total)
+    return fail(MOE_ERR_WORKSPACE, "moe_layer_backward: the forward workspace has %zu bytes (got %zu)", F.total, fwd_ws_bytes);
+  BwLayout L;
+  bw_layout(cfg, &L);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < L.total)
+    return fail(MOE_ERR_WORKSPACE, "moe_layer_backward: workspace needs %zu bytes, 256-byte aligned (got %zu)", L.total, ws_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  const char* fb = (const char*)fwd_ws;
+  char* b = (char*)ws;
+  const float* topk_w = (const float*)(fb + F.topk_w);
+  const int32_t* topk_idx = (const int32_t*)(fb + F.topk_idx);
+  const int32_t* offsets = (const int32_t*)(fb + F.expert_offsets);
+  const int32_t* a2r = (const int32_t*)(fb + F.assign_to_row);
+  const void* h = fb + F.h;
+  const void* yd = fb + F.yd;
+  float* probs = (float*)(b + L.probs);
+  float* d_w = (float*)(b + L.d_w);
+  float* d_z = (float*)(b + L.d_z);
+  if (cfg->T == 0) {  // nothing flows back; the gradients of the parameters are zero
+    if ((st = ffn_backward_impl("moe_layer_backward", cfg, w, w1_input_major, w2_input_major, nullptr, nullptr, nullptr, offsets,
+                                nullptr, d_w1, d_b1, d_w2, d_b2, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
+    const size_t n = (size_t)cfg->d_model * cfg->E;  // (sums over no slice and no token: zeros)
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)(b + L.partial), d_w_router, n, 0);
+    if (d_b_router) hipLaunchKernelGGL(gate_dbias_kernel, dim3(cfg->E), dim3(256), 0, s, d_z, d_b_router, 0, cfg->E);
+    return check_hip(hipGetLastError(), "moe_layer_backward");
+  }
+  // the probabilities are not kept by the forward pass: run the gate again (same routing, bit for bit)
+  if ((st = launch_gate(cfg, x, w->w_router, w->b_router, (int32_t*)(b + L.idx), (float*)(b + L.w), probs, s)) != MOE_OK) return st;
+  if (gemm2_can_combine(cfg)) {
+    // with one expert per token the forward pass wrote `out` directly: recompute the experts' outputs
+    int32_t* ctr = (int32_t*)(b + L.yd + align_up((size_t)max_rows(cfg) * cfg->d_model * 2, 256));
+    hipLaunchKernelGGL(clear8_kernel, dim3(1), dim3(64), 0, s, ctr);
+    if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
+    if ((st = launch_grouped_matmul_bf16(cfg, h, w->w2, w->b2, offsets, b + L.yd, cfg->d_model, cfg->d_ff, ctr, s)) != MOE_OK) return st;
+    yd = b + L.yd;
+  }
+  if ((st = moe_combine_backward(cfg, d_out, yd, a2r, topk_w, b + L.d_yd, d_w, stream)) != MOE_OK) return st;
+  if ((st = launch_gather_rows(cfg, x, a2r, b + L.xd, s)) != MOE_OK) return st;
+  if ((st = ffn_backward_impl("moe_layer_backward", cfg, w, w1_input_major, w2_input_major, b + L.xd, h, b + L.d_yd, offsets,
+                              b + L.d_xd, d_w1, d_b1, d_w2, d_b2, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
+  hipLaunchKernelGGL(gate_dlogits_kernel, dim3((cfg->T + 3) / 4), dim3(256), 0, s, probs, topk_idx, topk_w, d_w, d_z, cfg->T, cfg->E,
+                     cfg->k, cfg->renormalize);
+  if (d_b_router) hipLaunchKernelGGL(gate_dbias_kernel, dim3(cfg->E), dim3(256), 0, s, d_z, d_b_router, cfg->T, cfg->E);
+  if ((st = check_hip(hipGetLastError(), "gate backward launch")) != MOE_OK) return st;
+  float* partial = (float*)(b + L.partial);
+  if (cfg->E <= 16)
+    return gate_products<16>(cfg, x, w->w_router, a2r, d_z, b + L.d_xd, add_to_d_x, d_x, d_w_router, partial, L.slices, s);
+  if (cfg->E <= 32)
+    return gate_products<32>(cfg, x, w->w_router, a2r, d_z, b + L.d_xd, add_to_d_x, d_x, d_w_router, partial, L.slices, s);
+  return gate_products<64>(cfg, x, w->w_router, a2r, d_z, b + L.d_xd, add_to_d_x, d_x, d_w_router, partial, L.slices, s);
 }

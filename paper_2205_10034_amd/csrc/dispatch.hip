@@ -206,6 +206,16 @@ int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* top
   return check_hip(hipGetLastError(), "dispatch launch");
 }
 
+// xd[r] = x[token of row r] from existing tables (the backward pass gathers the rows the bf16 forward pass
+// never materialised).
+int32_t launch_gather_rows(const moe_config* cfg, const void* x, const int32_t* a2r, void* xd, hipStream_t s) {
+  if (cfg->T == 0) return MOE_OK;
+  const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
+  hipLaunchKernelGGL(dispatch_gather_kernel, dim3((cfg->T + 3) / 4), dim3(256), 0, s, (const uint4*)x, cfg->T, cfg->k, row_vec,
+                     a2r, (uint4*)xd);
+  return check_hip(hipGetLastError(), "gather launch");
+}
+
 }  // namespace moesys
 
 using namespace moesys;

@@ -96,3 +96,60 @@ def test_combine_and_expert_ffn_backward(kw):
         print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
         assert all(v < 1e-2 for v in errs.values()), errs
         assert errs["b2"] < 1e-5 and errs["w2"] < 6e-3      # exact products of the stored bf16 operands (h is the GPU's rounding of gelu)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("gpt", dict(T=700, E=4, d_model=256, d_ff=512)),
+    ("gpt", dict(T=1500, E=8, d_model=512, d_ff=256, capacity_factor=0.6)),
+    ("skew", dict(T=900, E=8, d_model=256, d_ff=512)),                     # top-1, router bias, not renormalised
+    ("gpt", dict(T=300, E=64, d_model=256, d_ff=256, k=4, capacity_factor=0.0)),
+], ids=lambda v: str(v).replace(" ", ""))
+def test_layer_backward(name, kw):
+    """moe_layer_forward with residual = x, then moe_layer_backward: every gradient against the fp64 oracle."""
+    wl = WORKLOADS[name].scaled(**kw)
+    print(f"layer backward case {wl}", flush=True)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    ws_f = alloc_ws(cfg)
+    out = torch.empty_like(x)
+    M.moe_layer_forward(cfg, W, x, x, out, ws_f)
+    rng = np.random.default_rng(4)
+    G_np = to_np(to_dev(rng.standard_normal(L["x"].shape).astype(np.float32), wl.dtype))
+    G = to_dev(G_np, wl.dtype)
+    ref = B.layer_backward(L["x"], L, G_np, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor, renormalize=wl.renormalize,
+                           act=wl.act)
+    lay = M.moe_workspace_layout(cfg)
+    from gpu_util import ws_view
+    torch.cuda.synchronize()
+    got_idx = ws_view(ws_f, lay["topk_idx"], wl.T * wl.k, torch.int32).cpu().numpy().reshape(wl.T, wl.k)
+    fw = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor, renormalize=wl.renormalize, act=wl.act)
+    assert np.array_equal(got_idx, fw["topk_idx"])
+    f32 = dict(dtype=torch.float32, device="cuda")
+    d_x = torch.full_like(x, float("nan"))
+    d_wr = torch.full((wl.d_model, wl.E), float("nan"), **f32)
+    d_br = torch.full((wl.E,), float("nan"), **f32) if "b_router" in W.tensors else None
+    d_w1 = torch.full((wl.E, wl.d_ff, wl.d_model), float("nan"), **f32)
+    d_w2 = torch.full((wl.E, wl.d_model, wl.d_ff), float("nan"), **f32)
+    d_b1 = torch.full((wl.E, wl.d_ff), float("nan"), **f32)
+    d_b2 = torch.full((wl.E, wl.d_model), float("nan"), **f32)
+    ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    w1_im, w2_im = to_dev(L["w1"], wl.dtype), to_dev(L["w2"], wl.dtype)
+    for rep in range(2):
+        M.moe_layer_backward(cfg, W, w1_im, w2_im, x, G, G, ws_f, d_x, d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b)
+        torch.cuda.synchronize()
+        errs = {
+            "x": rel_fro(to_np(d_x), ref["x"] + G_np),
+            "x (experts and gate only)": rel_fro(to_np(d_x).astype(np.float64) - G_np, ref["x"]),
+            "w_router": rel_fro(d_wr.cpu().numpy(), ref["w_router"]),
+            "w1": rel_fro(d_w1.cpu().numpy().transpose(0, 2, 1), ref["w1"]),
+            "w2": rel_fro(d_w2.cpu().numpy().transpose(0, 2, 1), ref["w2"]),
+            "b1": rel_fro(d_b1.cpu().numpy(), ref["b1"]),
+            "b2": rel_fro(d_b2.cpu().numpy(), ref["b2"]),
+        }
+        if d_br is not None:
+            errs["b_router"] = rel_fro(d_br.cpu().numpy(), ref["b_router"])
+        print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        assert errs["x"] < 1e-2
+        assert all(v < 2e-2 for v in errs.values()), errs
