@@ -13,6 +13,8 @@ namespace moesys {
 int32_t launch_gather_rows(const moe_config*, const void*, const int32_t*, void*, hipStream_t);
 int32_t launch_grouped_matmul_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, void*, int, int,
                                    int32_t*, hipStream_t);
+int32_t launch_gemm1_dgelu_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, const void*, void*,
+                                int32_t*, hipStream_t);
 int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, int, int, int, int64_t, hipStream_t);
 
 namespace {
@@ -22,26 +24,6 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ uint32_t to_bf16(float f) {  // round to nearest even (finite inputs)
   const uint32_t u = __float_as_uint(f);
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-// d/du [u Phi(u)] = Phi(u) + u phi(u)
-__device__ __forceinline__ float gelu_grad(float u) {
-  return 0.5f * (1.f + erff(u * 0.70710678118654752f)) + u * expf(-0.5f * u * u) * 0.3989422804014327f;
-}
-
-// d_u = d_h * gelu'(u), in place on d_h; n8 = number of 8-element vectors
-__global__ __launch_bounds__(256) void gelu_backward_kernel(uint4* __restrict__ dh, const uint4* __restrict__ u,
-                                                            const int32_t* __restrict__ offsets, int E, size_t row_vec) {
-  const size_t n8 = (size_t)offsets[E] * row_vec;  // only the kept rows
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
-    const uint4 a = dh[i], b = u[i];
-    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      o[q] = to_bf16(bf16_lo(aw[q]) * gelu_grad(bf16_lo(bw[q]))) | (to_bf16(bf16_hi(aw[q]) * gelu_grad(bf16_hi(bw[q]))) << 16);
-    dh[i] = uint4{o[0], o[1], o[2], o[3]};
-  }
 }
 
 // out[e, n] = sum over the rows r of expert e of d[r, n] (fp32).  One workgroup per (512-column block, expert):
@@ -113,8 +95,11 @@ __global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict
   if (threadIdx.x == 0) out[e] = part[0];
 }
 
-constexpr int GB_TOK = 32;   // tokens per workgroup of the two kernels below
+constexpr int DWG_SLICE = 64;  // tokens per partial sum of the router's weight gradient (many slices: the kernel's
+                               // parallelism is slices x column blocks)
+constexpr int GB_TOK = 16;   // tokens per workgroup of dx_kernel (their loads are issued together)
 constexpr int GB_MAXE = 64;  // experts they keep in registers
+constexpr int GB_MAXK = MOE_MAX_TOPK;  // choices per token
 
 // d_x[t, i] = (extra[t, i]) + sum over the kept choices j of d_xd[a2r[j*T+t], i] + sum_e d_z[t,e] * W_g[i,e],
 // rounded once.  A thread owns two columns i and keeps their router rows in registers across GB_TOK tokens.
@@ -123,36 +108,73 @@ __global__ __launch_bounds__(256) void dx_kernel(const uint32_t* __restrict__ d_
                                                  const float* __restrict__ d_z, const float* __restrict__ w_router,
                                                  const uint32_t* __restrict__ extra, uint32_t* __restrict__ d_x, int T, int d,
                                                  int E, int k) {
+  // The tokens' d_z rows and dispatch rows go through LDS.  Read straight from memory they are the same for
+  // every lane: E loads per token each, and row indices that the gathers would wait for one at a time.
+  __shared__ float s_dz[GB_TOK][EC];
+  __shared__ int32_t s_row[GB_MAXK][GB_TOK];
+  const int t0 = blockIdx.y * GB_TOK;
+  for (int i = threadIdx.x; i < GB_TOK * EC; i += 256) {
+    const int u = i / EC, e = i % EC;
+    s_dz[u][e] = (t0 + u < T && e < E) ? d_z[(size_t)(t0 + u) * E + e] : 0.f;
+  }
+  if ((int)threadIdx.x < k * GB_TOK) {
+    const int j = threadIdx.x / GB_TOK, u = threadIdx.x % GB_TOK;
+    s_row[j][u] = t0 + u < T ? a2r[(size_t)j * T + t0 + u] : -1;
+  }
+  __syncthreads();
   const int i2 = blockIdx.x * 256 + threadIdx.x;  // column pair
   if (i2 * 2 >= d) return;
   float w0[EC], w1[EC];
+  if (E == EC && (reinterpret_cast<uintptr_t>(w_router) & 15) == 0) {
+    // the thread's two router rows are 2*EC consecutive floats: 16-byte loads (a lane's rows share no cache line
+    // with another lane's, so the cost is per instruction)
+    const float4* wr = reinterpret_cast<const float4*>(w_router + (size_t)(2 * i2) * EC);
 #pragma unroll
-  for (int e = 0; e < EC; ++e) {
-    w0[e] = e < E ? w_router[(size_t)(2 * i2) * E + e] : 0.f;
-    w1[e] = e < E ? w_router[(size_t)(2 * i2 + 1) * E + e] : 0.f;
-  }
-  const int t_end = min(T, (int)(blockIdx.y + 1) * GB_TOK);
-  for (int t = blockIdx.y * GB_TOK; t < t_end; ++t) {
-    float a0 = 0.f, a1 = 0.f;
-    if (extra) {
-      const uint32_t v = extra[(size_t)t * (d / 2) + i2];
-      a0 = bf16_lo(v); a1 = bf16_hi(v);
+    for (int q = 0; q < EC / 4; ++q) {
+      const float4 p0 = wr[q], p1 = wr[EC / 4 + q];
+      w0[4 * q] = p0.x; w0[4 * q + 1] = p0.y; w0[4 * q + 2] = p0.z; w0[4 * q + 3] = p0.w;
+      w1[4 * q] = p1.x; w1[4 * q + 1] = p1.y; w1[4 * q + 2] = p1.z; w1[4 * q + 3] = p1.w;
     }
-    for (int j = 0; j < k; ++j) {
-      const int r = a2r[(size_t)j * T + t];
-      if (r >= 0) {
-        const uint32_t v = d_xd[(size_t)r * (d / 2) + i2];
-        a0 += bf16_lo(v); a1 += bf16_hi(v);
-      }
-    }
-    const float* dz = d_z + (size_t)t * E;
+  } else {
 #pragma unroll
     for (int e = 0; e < EC; ++e) {
-      const float z = e < E ? dz[e] : 0.f;
-      a0 = fmaf(z, w0[e], a0);
-      a1 = fmaf(z, w1[e], a1);
+      w0[e] = e < E ? w_router[(size_t)(2 * i2) * E + e] : 0.f;
+      w1[e] = e < E ? w_router[(size_t)(2 * i2 + 1) * E + e] : 0.f;
     }
-    d_x[(size_t)t * (d / 2) + i2] = to_bf16(a0) | (to_bf16(a1) << 16);
+  }
+  // every load of the workgroup's tokens is issued before the first is used (the addresses are clamped into
+  // the arrays; what a clamped load returns is discarded)
+  uint32_t v[GB_TOK];
+  const uint32_t* first = extra ? extra : d_xd;  // (without extra: row 0 of d_xd, a readable address; value unused)
+#pragma unroll
+  for (int u = 0; u < GB_TOK; ++u) v[u] = first[(extra ? (size_t)min(t0 + u, T - 1) * (d / 2) : (size_t)0) + i2];
+  float a0[GB_TOK], a1[GB_TOK];
+#pragma unroll
+  for (int u = 0; u < GB_TOK; ++u) {
+    a0[u] = extra ? bf16_lo(v[u]) : 0.f;
+    a1[u] = extra ? bf16_hi(v[u]) : 0.f;
+  }
+  for (int j = 0; j < k; ++j) {
+    int r[GB_TOK];
+#pragma unroll
+    for (int u = 0; u < GB_TOK; ++u) r[u] = s_row[j][u];
+#pragma unroll
+    for (int u = 0; u < GB_TOK; ++u) v[u] = d_xd[(size_t)max(r[u], 0) * (d / 2) + i2];
+#pragma unroll
+    for (int u = 0; u < GB_TOK; ++u) {
+      a0[u] += r[u] >= 0 ? bf16_lo(v[u]) : 0.f;
+      a1[u] += r[u] >= 0 ? bf16_hi(v[u]) : 0.f;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < GB_TOK; ++u) {
+    float s0 = a0[u], s1 = a1[u];
+#pragma unroll
+    for (int e = 0; e < EC; ++e) {
+      s0 = fmaf(s_dz[u][e], w0[e], s0);
+      s1 = fmaf(s_dz[u][e], w1[e], s1);
+    }
+    if (t0 + u < T) d_x[(size_t)(t0 + u) * (d / 2) + i2] = to_bf16(s0) | (to_bf16(s1) << 16);
   }
 }
 
@@ -160,21 +182,27 @@ __global__ __launch_bounds__(256) void dx_kernel(const uint32_t* __restrict__ d_
 template <int EC>
 __global__ __launch_bounds__(256) void dwg_partial_kernel(const uint32_t* __restrict__ x, const float* __restrict__ d_z,
                                                           float* __restrict__ partial, int T, int d, int E, int slice_tokens) {
+  __shared__ float s_dz[DWG_SLICE][EC];
+  const int ts = blockIdx.y * slice_tokens;
+  for (int i = threadIdx.x; i < slice_tokens * EC; i += 256) {
+    const int u = i / EC, e = i % EC;
+    s_dz[u][e] = (ts + u < T && e < E) ? d_z[(size_t)(ts + u) * E + e] : 0.f;  // (zero rows past the last token)
+  }
+  __syncthreads();
   const int i2 = blockIdx.x * 256 + threadIdx.x;
   if (i2 * 2 >= d) return;
   float a0[EC], a1[EC];
 #pragma unroll
   for (int e = 0; e < EC; ++e) a0[e] = a1[e] = 0.f;
-  const int t_end = min(T, (int)(blockIdx.y + 1) * slice_tokens);
-  for (int t = blockIdx.y * slice_tokens; t < t_end; ++t) {
-    const uint32_t v = x[(size_t)t * (d / 2) + i2];
+  const int n_tok = min(T - ts, slice_tokens);
+#pragma unroll 4
+  for (int u = 0; u < n_tok; ++u) {
+    const uint32_t v = x[(size_t)(ts + u) * (d / 2) + i2];
     const float x0 = bf16_lo(v), x1 = bf16_hi(v);
-    const float* dz = d_z + (size_t)t * E;
 #pragma unroll
     for (int e = 0; e < EC; ++e) {
-      const float z = e < E ? dz[e] : 0.f;
-      a0[e] = fmaf(x0, z, a0[e]);
-      a1[e] = fmaf(x1, z, a1[e]);
+      a0[e] = fmaf(x0, s_dz[u][e], a0[e]);
+      a1[e] = fmaf(x1, s_dz[u][e], a1[e]);
     }
   }
   float* p0 = partial + ((size_t)blockIdx.y * d + 2 * i2) * E;
@@ -188,12 +216,13 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   float acc = 0.f;
+#pragma unroll 8
   for (int s = 0; s < slices; ++s) acc += partial[(size_t)s * n + i];
   out[i] = acc;
 }
 
-__global__ void clear8_kernel(int32_t* p) {
-  if (threadIdx.x < 8) p[threadIdx.x] = 0;
+__global__ void clear_counters_kernel(int32_t* p, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 
 }  // namespace
@@ -204,7 +233,7 @@ using namespace moesys;
 extern "C" size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg) {
   if (moe_config_check(cfg) != MOE_OK) return 0;
   const size_t rf = align_up((size_t)max_rows(cfg) * cfg->d_ff * 2, 256);
-  return 2 * rf + 256;  // u, d_h (becomes d_u), tile counters
+  return rf + 256;  // d_h (becomes d_u), three blocks of tile counters
 }
 
 static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
@@ -242,38 +271,32 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   const int E = cfg->E, d = cfg->d_model, f = cfg->d_ff;
   const size_t rf = align_up((size_t)rmax * f * 2, 256);
   char* base = (char*)ws;
-  void* u = base;
-  void* dh = base + rf;
-  int32_t* ctr = (int32_t*)(base + 2 * rf);
+  void* dh = base;
+  int32_t* ctr = (int32_t*)(base + rf);
   int64_t per_expert = rmax;
   const int64_t C = moe_capacity(cfg);
   if (C != MOE_DROPLESS && C < per_expert) per_expert = C;
-  auto clear = [&]() -> int32_t {
-    hipLaunchKernelGGL(clear8_kernel, dim3(1), dim3(64), 0, s, ctr);
-    return check_hip(hipGetLastError(), "counter clear launch");
-  };
+  // every product draws its tiles from eight zeroed counters of its own
+  hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, ctr, 24);
+  if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
   // weight gradients that need nothing recomputed: dW2_e = d_yd_e^T h_e, db2_e = column sums of d_yd_e
   if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, E, d, f, per_expert, s)) != MOE_OK) return st;
   if (w->b2) {
     hipLaunchKernelGGL(bias_grad_kernel, dim3((d + 511) / 512, E), dim3(256), 0, s, (const uint4*)d_yd, expert_offsets, d_b2, d);
     if ((st = check_hip(hipGetLastError(), "bias gradient launch")) != MOE_OK) return st;
   }
-  // u = xd W1^T + b1 (recomputed), d_h = d_yd W2, d_u = d_h * gelu'(u)   (without any row: every product
-  // returns at once, the gradients come out as zeros)
-  if ((st = clear()) != MOE_OK) return st;
-  if ((st = launch_grouped_matmul_bf16(cfg, xd, w->w1, w->b1, expert_offsets, u, f, d, ctr, s)) != MOE_OK) return st;
-  if ((st = clear()) != MOE_OK) return st;
+  // d_h = d_yd W2, then d_u = d_h * gelu'(u) in place, u = xd W1^T + b1 being recomputed by the product whose
+  // epilogue applies the derivative: the pre-activations never reach memory.  (Without any row every product
+  // returns at once and the gradients come out as zeros.)
   if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
-  hipLaunchKernelGGL(gelu_backward_kernel, dim3(2048), dim3(256), 0, s, (uint4*)dh, (const uint4*)u, expert_offsets, E, (size_t)f / 8);
-  if ((st = check_hip(hipGetLastError(), "activation backward launch")) != MOE_OK) return st;
+  if ((st = launch_gemm1_dgelu_bf16(cfg, xd, w->w1, w->b1, expert_offsets, dh, dh, ctr + 8, s)) != MOE_OK) return st;
   // dW1_e = d_u_e^T xd_e, db1_e = column sums of d_u_e, d_xd = d_u W1
   if ((st = launch_wgrad_bf16((const uint16_t*)dh, (const uint16_t*)xd, expert_offsets, d_w1, E, f, d, per_expert, s)) != MOE_OK) return st;
   if (w->b1) {
     hipLaunchKernelGGL(bias_grad_kernel, dim3((f + 511) / 512, E), dim3(256), 0, s, (const uint4*)dh, expert_offsets, d_b1, f);
     if ((st = check_hip(hipGetLastError(), "bias gradient launch")) != MOE_OK) return st;
   }
-  if ((st = clear()) != MOE_OK) return st;
-  return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr, s);
+  return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr + 16, s);
 }
 
 // ---- whole layer ------------------------------------------------------------------------------------
@@ -284,7 +307,6 @@ struct BwLayout {
   int slices;
 };
 
-constexpr int DWG_SLICE = 256;  // tokens per partial sum of the router's weight gradient
 
 void bw_layout(const moe_config* cfg, BwLayout* L) {
   const size_t T = (size_t)cfg->T, E = (size_t)cfg->E, k = (size_t)cfg->k, d = (size_t)cfg->d_model;
@@ -341,6 +363,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
   if (cfg->dtype != MOE_BF16 || cfg->act != MOE_ACT_GELU) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: bf16 GELU experts only");
   if (cfg->E > GB_MAXE) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d experts", GB_MAXE);
+  if ((cfg->T + GB_TOK - 1) / GB_TOK > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d tokens", 65535 * GB_TOK);
   if (!w->w_router || !d_w_router || (w->b_router && !d_b_router))
     return fail(MOE_ERR_INVALID_ARG, "moe_layer_backward: router weights and their gradient buffers must be non-NULL");
   if (cfg->T > 0 && (!x || !d_out || !d_x)) return fail(MOE_ERR_INVALID_ARG, "moe_layer_backward: x, d_out and d_x must be non-NULL");
@@ -377,7 +400,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   if (gemm2_can_combine(cfg)) {
     // with one expert per token the forward pass wrote `out` directly: recompute the experts' outputs
     int32_t* ctr = (int32_t*)(b + L.yd + align_up((size_t)max_rows(cfg) * cfg->d_model * 2, 256));
-    hipLaunchKernelGGL(clear8_kernel, dim3(1), dim3(64), 0, s, ctr);
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, ctr, 8);
     if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
     if ((st = launch_grouped_matmul_bf16(cfg, h, w->w2, w->b2, offsets, b + L.yd, cfg->d_model, cfg->d_ff, ctr, s)) != MOE_OK) return st;
     yd = b + L.yd;

@@ -71,7 +71,10 @@ constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
 
 // EPI_COMBINE: the second GEMM with the top-1 combine folded in: row r goes to token row_map[r] as
 // residual + gate weight * (product + bias), rounded once.
-enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3 };
+// EPI_DGELU: the backward pass's recomputation of the first GEMM: out = aux * gelu'(product + bias), where aux
+// [R, N] (passed as the residual; it may be out itself) is the gradient of the activations; the
+// pre-activations never reach memory.
+enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3, EPI_DGELU = 4 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // two floats -> two bf16 in one dword (lo in the low half): one v_cvt_pk_bf16_f32, round to nearest even
@@ -110,6 +113,24 @@ __device__ __forceinline__ void gelu_table_n(float* u, const f32x2* tab) {
   for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
 #pragma unroll
   for (int r = 0; r < B; ++r) u[r] *= fmaf(__builtin_amdgcn_fractf(t[r]), e[r].y, e[r].x);  // t >= 0: fract(t) = t - floor(t)
+}
+// u[r] <- dh[r] * gelu'(u[r]), gelu'(u) = Phi(u) + u phi(u): Phi from the same table, phi(u) = exp(-u^2/2)/sqrt(2 pi)
+// with the hardware's exp2 (relative error ~1e-7, on a term that is at most 0.17 of the whole).
+template <int B>
+__device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, const f32x2* tab) {
+  float t[B];
+  f32x2 e[B];
+#pragma unroll
+  for (int r = 0; r < B; ++r)
+    t[r] = __builtin_amdgcn_fmed3f(fmaf(u[r], PHI_SCALE, PHI_RANGE * PHI_SCALE), 0.0f, (float)PHI_N - 0.001f);
+#pragma unroll
+  for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
+#pragma unroll
+  for (int r = 0; r < B; ++r) {
+    const float dens = 0.3989422804014327f * __builtin_amdgcn_exp2f(u[r] * u[r] * -0.7213475204444817f);
+    const float cdf = fmaf(__builtin_amdgcn_fractf(t[r]), e[r].y, e[r].x);
+    u[r] = dh[r] * fmaf(u[r], dens, cdf);
+  }
 }
 __device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
@@ -281,7 +302,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   __shared__ __attribute__((aligned(1024))) unsigned char s0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char s1[STAGE_BYTES];
-  __shared__ f32x2 s_phi[EPI == EPI_GELU ? PHI_N : 1];
+  __shared__ f32x2 s_phi[EPI == EPI_GELU || EPI == EPI_DGELU ? PHI_N : 1];
   __shared__ int s_pref[MOE_MAX_EXPERTS + 1];
   __shared__ int s_next;  // number of this workgroup's next tile
   __shared__ int s_tok[GATHER ? NW * 64 : 1];  // assignment id of every row of the next tile
@@ -299,7 +320,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   const int n_tiles = N / OUT_FEAT;
 
   if (clear_ctr && blockIdx.x == 0 && tid < NUM_XCD) clear_ctr[tid] = 0;
-  if (EPI == EPI_GELU) fill_phi_table(s_phi);
+  if (EPI == EPI_GELU || EPI == EPI_DGELU) fill_phi_table(s_phi);
   count_token_tiles(offsets, E, TOK, s_pref);  // ends with a barrier: s_pref and the table are visible
   TileWalker<TOK, 32 * WT> walk;
   walk.init(s_pref[E], n_tiles);
@@ -669,10 +690,22 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
         row_gw[tb] = gate_w[row_tok[tb]];
       }
     }
+    // EPI_DGELU: the activations' gradient for one (token block, feature block, group pair) step, loaded one
+    // step ahead of its use in the layout of the stores: 16 bytes per lane, the 8 features of group i0 in lane
+    // l and those of group i0 + 1 in lane l + 32 (rows past the tile's last re-read the last row)
+    auto aux_load = [&](int tb, int fb, int i0) {
+      const int trow = min((tb * WT + wt) * 32 + frow, done.rows - 1);
+      return *reinterpret_cast<const u32x4*>(residual + (size_t)(done.row0 + trow) * N + feat0 + wf * WFEAT + fb * 32 +
+                                             8 * (i0 + fhalf));
+    };
+    u32x4 aux_next = {0u, 0u, 0u, 0u};
+    if constexpr (EPI == EPI_DGELU) aux_next = aux_load(0, 0, 0);
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       const int trow = (tb * WT + wt) * 32 + frow;
-      if (trow >= done.rows) continue;  // (lanes l and l+32 share the row: they stay or leave together)
+      // (lanes l and l+32 share the row: they stay or leave together; the rows grow with tb, so nothing after
+      // a skipped block is processed either)
+      if (trow >= done.rows) continue;
       const size_t orow_idx = EPI == EPI_COMBINE ? (size_t)row_tok[tb] : (size_t)(done.row0 + trow);
       uint16_t* orow = out + orow_idx * N;
       if (EPI == EPI_SWIGLU) {
@@ -708,6 +741,30 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
               constexpr int GB = TOK > 256 ? 4 : 8;  // (8 at a time spills in the 320-row kernel)
 #pragma unroll
               for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, s_phi);
+            }
+            if constexpr (EPI == EPI_DGELU) {
+              // (every element is read by the lane that multiplies it, before the lanes trade halves and before
+              // that row segment is stored, so aux may be the output itself)
+              float dh[8];
+              // the store's trade of halves, backwards: lane l gets features 0..3 of both groups, lane l + 32
+              // features 4..7 (element g of sx, sy: this lane's features of group i0 + g)
+              const u32x2 sx = __builtin_amdgcn_permlane32_swap(aux_next.x, aux_next.z, false, false);
+              const u32x2 sy = __builtin_amdgcn_permlane32_swap(aux_next.y, aux_next.w, false, false);
+              {
+                int ni0 = i0 + 2, nfb = fb, ntb = tb;
+                if (ni0 == 4) { ni0 = 0; if (++nfb == FB) { nfb = 0; ++ntb; } }
+                if (ntb < TB) aux_next = aux_load(ntb, nfb, ni0);
+              }
+#pragma unroll
+              for (int g = 0; g < 2; ++g) {
+                const u32x2 rv = {g ? sx.y : sx.x, g ? sy.y : sy.x};
+                dh[4 * g + 0] = bf16_bits_to_f32(rv.x & 0xffffu);
+                dh[4 * g + 1] = __uint_as_float(rv.x & 0xffff0000u);
+                dh[4 * g + 2] = bf16_bits_to_f32(rv.y & 0xffffu);
+                dh[4 * g + 3] = __uint_as_float(rv.y & 0xffff0000u);
+              }
+#pragma unroll
+              for (int r = 0; r < 8; r += 4) dgelu_table_n<4>(p + r, dh + r, s_phi);
             }
             if constexpr (EPI == EPI_COMBINE) {
               // before the lanes trade halves: this lane's 4 + 4 features of the residual row
@@ -776,6 +833,8 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   } else if constexpr (EPI == EPI_SWIGLU) {
   } else if constexpr (EPI == EPI_BIAS) {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
+  } else if constexpr (EPI == EPI_DGELU) {
+    if (row_map || !residual) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: the activation-gradient epilogue reads contiguous rows and needs the activations' gradient");
   } else {
     if (!row_map || !gate_w || cfg->k != 1) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: combine epilogue needs k = 1, row map and gate weights");
   }
@@ -882,6 +941,15 @@ int32_t launch_grouped_matmul_bf16(const moe_config* cfg, const void* act, const
                                    const int32_t* offsets, void* out, int N, int K, int32_t* counters8, hipStream_t s) {
   return gemm_any<EPI_BIAS>(cfg, (const uint16_t*)act, (const uint16_t*)w, nullptr, (const uint16_t*)bias, offsets,
                             (uint16_t*)out, nullptr, counters8, nullptr, N, K, s, nullptr);
+}
+
+// d_u[r, n] = d_h[r, n] * gelu'(sum_k xd[r, k] * w1_e[n, k] + b1_e[n]): the first GEMM recomputed for the backward
+// pass with the activation's derivative in its epilogue.  d_u may be d_h.  counters8: eight zeroed ints.
+int32_t launch_gemm1_dgelu_bf16(const moe_config* cfg, const void* xd, const void* w1, const void* b1,
+                                const int32_t* offsets, const void* d_h, void* d_u, int32_t* counters8, hipStream_t s) {
+  return gemm_any<EPI_DGELU>(cfg, (const uint16_t*)xd, (const uint16_t*)w1, nullptr, (const uint16_t*)b1, offsets,
+                             (uint16_t*)d_u, nullptr, counters8, nullptr, cfg->d_ff, cfg->d_model, s, nullptr, nullptr,
+                             (const uint16_t*)d_h);
 }
 
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.
