@@ -103,6 +103,7 @@ def test_combine_and_expert_ffn_backward(kw):
     ("gpt", dict(T=1500, E=8, d_model=512, d_ff=256, capacity_factor=0.6)),
     ("skew", dict(T=900, E=8, d_model=256, d_ff=512)),                     # top-1, router bias, not renormalised
     ("gpt", dict(T=300, E=64, d_model=256, d_ff=256, k=4, capacity_factor=0.0)),
+    ("gpt", dict()),                          # the benchmark's configuration at full size, in its launch configuration
 ], ids=lambda v: str(v).replace(" ", ""))
 def test_layer_backward(name, kw):
     """moe_layer_forward with residual = x, then moe_layer_backward: every gradient against the fp64 oracle."""
