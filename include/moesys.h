@@ -297,7 +297,7 @@ int32_t moe_ring_release(moe_ring* r, int32_t layer, void* compute_stream);
 int32_t moe_ring_stats(moe_ring* r, uint64_t* bytes_copied, uint64_t* copies, double* copy_ms);
 int32_t moe_ring_destroy(moe_ring* r);
 
-/* ---- backward pass (first piece) ------------------------------------------ */
+/* ---- backward pass -------------------------------------------------------- */
 /* Backward of moe_combine for the gradient d_out [T,d_model] of its output: for every kept
  * choice (t,j) with row r = assign_to_row[j*T+t]
  *   d_yd[r] = topk_w[t,j] * d_out[t]   (cfg.dtype, one rounding)
@@ -320,13 +320,20 @@ int32_t moe_combine_backward(const moe_config* cfg, const void* d_out, const voi
 int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
                          int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert, void* stream);
 
-/* Backward of moe_expert_ffn for GELU experts in MOE_BF16, given d_yd [R_max,d_model]:
+/* Backward of moe_expert_ffn in MOE_BF16, given d_yd [R_max,d_model].  GELU experts:
  *   d_xd [R_max,d_model] (cfg.dtype), d_w1 [E,d_ff,d_model], d_b1 [E,d_ff], d_w2 [E,d_model,d_ff],
  *   d_b2 [E,d_model] (float32, OUTPUT_MAJOR like the weights; overwritten; the bias gradients are
  *   required exactly when w has the bias).
  * w holds the OUTPUT_MAJOR weights of the forward pass; w1_input_major [E,d_model,d_ff] and
  * w2_input_major [E,d_ff,d_model] are their transposed copies (moe_transpose_expert_weights),
- * on which the input gradients are plain grouped products.  xd [R_max,d_model] and
+ * on which the input gradients are plain grouped products.
+ * SwiGLU experts: the gate and up projections are treated as one stacked matrix:
+ *   d_w1 [E,2*d_ff,d_model]: rows [0,d_ff) of expert e are the gradient of w_gate_proj[e], rows
+ *   [d_ff,2*d_ff) that of w_up[e]; d_w2 [E,d_model,d_ff] is the gradient of w_down; d_b1, d_b2
+ *   are not used; w1_input_major [E,d_model,2*d_ff] holds, for every expert and input feature,
+ *   the d_ff gate weights followed by the d_ff up weights (the transposed stacked matrix);
+ *   w2_input_major [E,d_ff,d_model] is the transposed w_down.
+ * xd [R_max,d_model] and
  * h [R_max,d_ff] are the forward pass's dispatched rows and hidden activations (for
  * moe_layer_forward: gather xd with moe_dispatch; h is in the workspace); the
  * pre-activations are recomputed.  ws: moe_expert_ffn_backward_workspace_bytes(cfg), 256-byte
@@ -338,7 +345,7 @@ int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, con
                                 float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
                                 size_t ws_bytes, void* stream);
 
-/* Backward of moe_layer_forward (GELU experts, MOE_BF16, E <= 64) for the gradient d_out
+/* Backward of moe_layer_forward (MOE_BF16, E <= 64) for the gradient d_out
  * [T,d_model] of its output, with the routing of the forward pass held fixed:
  *   d_x [T,d_model] (cfg.dtype) = add_to_d_x (nullable; e.g. d_out when the layer ran with
  *       residual == x) + the experts' path (through dispatch) + the gate's path, one rounding;

@@ -1,6 +1,6 @@
-"""Forward + backward of one MoE layer (GELU experts, bf16): time per step and per phase of the backward pass.
+"""Forward + backward of one MoE layer (bf16, GELU or SwiGLU experts): time per step of each pass.
 
-    python -m paper_2205_10034_amd.backward_bench [--workload gpt] [--steps 30]
+    python -m paper_2205_10034_amd.backward_bench [--workload gpt|large|...] [--steps 30]
 
 Prints one JSON line.  The backward pass needs the transposed (input-major) copies of the expert matrices; they
 are made once, outside the timed region, like the forward pass's output-major ones.
@@ -25,26 +25,34 @@ def main():
     from workloads import WORKLOADS
 
     wl = WORKLOADS[args.workload]
-    if wl.act != "gelu" or wl.dtype != "bf16":
-        sys.exit("backward_bench: GELU experts in bf16 only")
+    if wl.dtype != "bf16":
+        sys.exit("backward_bench: bf16 only")
+    sw = wl.act == "swiglu"
     torch.manual_seed(0)
     dt = torch.bfloat16
     T, d, f, E = wl.T, wl.d_model, wl.d_ff, wl.E
     x = torch.randn(T, d, device="cuda").to(dt)
     g = torch.randn(T, d, device="cuda").to(dt)
     def mat(n, k): return (torch.randn(E, n, k, device="cuda") * k ** -0.5).to(dt)
-    w1, w2 = mat(f, d), mat(d, f)                      # output-major
-    w1_im = torch.empty(E, d, f, dtype=dt, device="cuda")
+    router = (torch.randn(d, E, device="cuda") * d ** -0.5).contiguous()
     w2_im = torch.empty(E, f, d, dtype=dt, device="cuda")
-    M.moe_transpose_expert_weights(w1, w1_im)
-    M.moe_transpose_expert_weights(w2, w2_im)
-    W = M.Weights({"w1": w1, "w2": w2, "w_router": (torch.randn(d, E, device="cuda") * d ** -0.5).contiguous()})
+    if sw:
+        wg, wu, wd = mat(f, d), mat(f, d), mat(d, f)   # output-major
+        w1_im = torch.cat([wg.transpose(1, 2), wu.transpose(1, 2)], dim=2).contiguous()     # [E, d, 2f]: gate | up
+        M.moe_transpose_expert_weights(wd, w2_im)
+        W = M.Weights({"w_gate_proj": wg, "w_up": wu, "w_down": wd, "w_router": router})
+    else:
+        w1, w2 = mat(f, d), mat(d, f)                  # output-major
+        w1_im = torch.empty(E, d, f, dtype=dt, device="cuda")
+        M.moe_transpose_expert_weights(w1, w1_im)
+        M.moe_transpose_expert_weights(w2, w2_im)
+        W = M.Weights({"w1": w1, "w2": w2, "w_router": router})
     cfg = M.MoEConfig.from_workload(wl)
     ws_f = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     out, d_x = torch.empty_like(x), torch.empty_like(x)
     f32 = dict(dtype=torch.float32, device="cuda")
-    d_wr, d_w1, d_w2 = torch.empty(d, E, **f32), torch.empty(E, f, d, **f32), torch.empty(E, d, f, **f32)
+    d_wr, d_w1, d_w2 = torch.empty(d, E, **f32), torch.empty(E, (2 if sw else 1) * f, d, **f32), torch.empty(E, d, f, **f32)
 
     def fwd():
         M.moe_layer_forward(cfg, W, x, x, out, ws_f)
@@ -71,12 +79,14 @@ def main():
     R = int(ws_f[lay["expert_offsets"]:lay["expert_offsets"] + 4 * (E + 1)].view(torch.int32)[-1].item())
     gemm = 2.0 * R * d * f
     res = {
-        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} gelu, kept rows {R}",
+        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} {wl.act}, kept rows {R}",
         "forward_ms": t_f, "backward_ms": t_b, "forward_backward_ms": t_fb,
         "tokens_per_s_forward_backward": T / (t_fb * 1e-3),
-        # two products forward; backward: two input gradients, two weight gradients, one recomputation
-        "backward_tflops": 5 * gemm / (t_b * 1e-3) / 1e12,
-        "forward_backward_tflops": 7 * gemm / (t_fb * 1e-3) / 1e12,
+        # products of 2 R d_model d_ff flops.  GELU: two forward; backward two input gradients, two weight gradients,
+        # one recomputation.  SwiGLU: three forward; backward three input gradients (d_h, and d_xd over gate and
+        # up), three weight gradients, two recomputations
+        "backward_tflops": (8 if sw else 5) * gemm / (t_b * 1e-3) / 1e12,
+        "forward_backward_tflops": (11 if sw else 7) * gemm / (t_fb * 1e-3) / 1e12,
     }
     print(json.dumps(res))
 

@@ -1,11 +1,13 @@
-// Backward pass of the expert FFN (GELU experts, bf16): the chain rule on
-//   u = xd W1_e^T + b1_e,  h = gelu(u),  yd = h W2_e^T + b2_e        (weights OUTPUT_MAJOR [E, out, in])
-// for the rows of every expert.  The paper's system is a training system (Section 3.2) and leaves the kernels
-// open.  Products run on the grouped GEMM kernels: input gradients are plain grouped products on the
-// INPUT_MAJOR copies of the weights (the contraction index of the transposed product is contiguous there),
-// weight gradients contract over an expert's rows (grouped_wgrad_bf16.hip).  The pre-activations are
-// recomputed rather than stored by the forward pass.  What is still separate from the GEMMs: the
-// activation's derivative (one elementwise pass) and the bias gradients (column sums per expert).
+// Backward pass of the layer (bf16): the chain rule on the forward definition with the routing held fixed.
+// Expert FFN, for the rows of every expert (weights OUTPUT_MAJOR [E, out, in]):
+//   GELU    u = xd W1_e^T + b1_e,  h = gelu(u),  yd = h W2_e^T + b2_e
+//   SwiGLU  g = xd Wg_e^T, u = xd Wu_e^T,  h = silu(g) * u,  yd = h Wd_e^T
+// The paper's system is a training system (Section 3.2) and leaves the kernels open.  Products run on the
+// grouped GEMM kernels: input gradients are plain grouped products on the INPUT_MAJOR copies of the weights
+// (the contraction index of the transposed product is contiguous there), weight gradients contract over an
+// expert's rows (grouped_wgrad_bf16.hip).  The pre-activations are recomputed rather than stored by the
+// forward pass, by a product whose epilogue applies the activation's derivative to d_h; they never reach
+// memory.  What is still separate from the GEMMs: the bias gradients (column sums per expert).
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -15,6 +17,8 @@ int32_t launch_grouped_matmul_bf16(const moe_config*, const void*, const void*, 
                                    int32_t*, hipStream_t);
 int32_t launch_gemm1_dgelu_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, const void*, void*,
                                 int32_t*, hipStream_t);
+int32_t launch_gemm1_dswiglu_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, const void*, void*,
+                                  int32_t*, hipStream_t);
 int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, int, int, int, int64_t, hipStream_t);
 
 namespace {
@@ -233,7 +237,8 @@ using namespace moesys;
 extern "C" size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg) {
   if (moe_config_check(cfg) != MOE_OK) return 0;
   const size_t rf = align_up((size_t)max_rows(cfg) * cfg->d_ff * 2, 256);
-  return rf + 256;  // d_h (becomes d_u), three blocks of tile counters
+  // GELU: d_h (becomes d_u); SwiGLU: d_h and [d_g | d_u]; three blocks of tile counters
+  return (cfg->act == MOE_ACT_SWIGLU ? 3 : 1) * rf + 256;
 }
 
 static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
@@ -256,12 +261,12 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   int32_t st = moe_config_check(cfg);
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
-  if (cfg->dtype != MOE_BF16 || cfg->act != MOE_ACT_GELU)
-    return fail(MOE_ERR_UNSUPPORTED, "%s: bf16 GELU experts only", who);
+  if (cfg->dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "%s: bf16 only", who);
+  const bool sw = cfg->act == MOE_ACT_SWIGLU;
   if (w->expert_elem_offset) return fail(MOE_ERR_UNSUPPORTED, "%s: contiguous expert arrays only", who);
   if (!w1_input_major || !w2_input_major || !expert_offsets || !d_w1 || !d_w2)
     return fail(MOE_ERR_INVALID_ARG, "%s: NULL argument", who);
-  if ((w->b1 && !d_b1) || (w->b2 && !d_b2)) return fail(MOE_ERR_INVALID_ARG, "%s: a bias without a gradient buffer", who);
+  if (!sw && ((w->b1 && !d_b1) || (w->b2 && !d_b2))) return fail(MOE_ERR_INVALID_ARG, "%s: a bias without a gradient buffer", who);
   const size_t need = moe_expert_ffn_backward_workspace_bytes(cfg);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
     return fail(MOE_ERR_WORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned (got %zu)", who, need, ws_bytes);
@@ -272,7 +277,7 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   const size_t rf = align_up((size_t)rmax * f * 2, 256);
   char* base = (char*)ws;
   void* dh = base;
-  int32_t* ctr = (int32_t*)(base + rf);
+  int32_t* ctr = (int32_t*)(base + (sw ? 3 : 1) * rf);
   int64_t per_expert = rmax;
   const int64_t C = moe_capacity(cfg);
   if (C != MOE_DROPLESS && C < per_expert) per_expert = C;
@@ -281,6 +286,15 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
   // weight gradients that need nothing recomputed: dW2_e = d_yd_e^T h_e, db2_e = column sums of d_yd_e
   if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, E, d, f, per_expert, s)) != MOE_OK) return st;
+  if (sw) {
+    // d_h = d_yd W_down; [d_g | d_u] from d_h and the recomputed gate and up products; the gradient of the
+    // stacked [W_gate; W_up] in one product, d_xd in one product over the 2 d_ff columns of [d_g | d_u]
+    void* dgu = base + rf;
+    if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
+    if ((st = launch_gemm1_dswiglu_bf16(cfg, xd, w->w_gate_proj, w->w_up, expert_offsets, dh, dgu, ctr + 8, s)) != MOE_OK) return st;
+    if ((st = launch_wgrad_bf16((const uint16_t*)dgu, (const uint16_t*)xd, expert_offsets, d_w1, E, 2 * f, d, per_expert, s)) != MOE_OK) return st;
+    return launch_grouped_matmul_bf16(cfg, dgu, w1_input_major, nullptr, expert_offsets, d_xd, d, 2 * f, ctr + 16, s);
+  }
   if (w->b2) {
     hipLaunchKernelGGL(bias_grad_kernel, dim3((d + 511) / 512, E), dim3(256), 0, s, (const uint4*)d_yd, expert_offsets, d_b2, d);
     if ((st = check_hip(hipGetLastError(), "bias gradient launch")) != MOE_OK) return st;
@@ -361,7 +375,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   int32_t st = moe_config_check(cfg);
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
-  if (cfg->dtype != MOE_BF16 || cfg->act != MOE_ACT_GELU) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: bf16 GELU experts only");
+  if (cfg->dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: bf16 only");
   if (cfg->E > GB_MAXE) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d experts", GB_MAXE);
   if ((cfg->T + GB_TOK - 1) / GB_TOK > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d tokens", 65535 * GB_TOK);
   if (!w->w_router || !d_w_router || (w->b_router && !d_b_router))
@@ -402,7 +416,9 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
     int32_t* ctr = (int32_t*)(b + L.yd + align_up((size_t)max_rows(cfg) * cfg->d_model * 2, 256));
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, ctr, 8);
     if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
-    if ((st = launch_grouped_matmul_bf16(cfg, h, w->w2, w->b2, offsets, b + L.yd, cfg->d_model, cfg->d_ff, ctr, s)) != MOE_OK) return st;
+    const bool sw = cfg->act == MOE_ACT_SWIGLU;
+    if ((st = launch_grouped_matmul_bf16(cfg, h, sw ? w->w_down : w->w2, sw ? nullptr : w->b2, offsets, b + L.yd, cfg->d_model,
+                                         cfg->d_ff, ctr, s)) != MOE_OK) return st;
     yd = b + L.yd;
   }
   if ((st = moe_combine_backward(cfg, d_out, yd, a2r, topk_w, b + L.d_yd, d_w, stream)) != MOE_OK) return st;

@@ -74,7 +74,11 @@ constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
 // EPI_DGELU: the backward pass's recomputation of the first GEMM: out = aux * gelu'(product + bias), where aux
 // [R, N] (passed as the residual; it may be out itself) is the gradient of the activations; the
 // pre-activations never reach memory.
-enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3, EPI_DGELU = 4 };
+// EPI_DSWIGLU: the same for SwiGLU experts: the gate and up products g, u are recomputed on the SwiGLU tile and
+// out [R, 2N] receives d_g = aux * u * silu'(g) in columns [0, N) and d_u = aux * silu(g) in columns [N, 2N).
+enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3, EPI_DGELU = 4, EPI_DSWIGLU = 5 };
+// tiles of a gate block and an up block side by side
+constexpr bool swiglu_tile(int epi) { return epi == EPI_SWIGLU || epi == EPI_DSWIGLU; }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // two floats -> two bf16 in one dword (lo in the low half): one v_cvt_pk_bf16_f32, round to nearest even
@@ -283,11 +287,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   constexpr int NSUB = KS / 16;                   // MFMA sub-steps per K-step
   constexpr int A_BYTES = TOK * ROW_BYTES, B_BYTES = FEAT * ROW_BYTES;
   // SwiGLU: LDS feature rows [0,FEAT/2) come from Wg, [FEAT/2,FEAT) from Wu, for FEAT/2 output features
-  constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
+  constexpr int OUT_FEAT = swiglu_tile(EPI) ? FEAT / 2 : FEAT;
   constexpr int B_ROWS = OUT_FEAT;                                    // rows per weight matrix per tile
   constexpr int A_LOADS = TOK / RPI / NW, B_LOADS = B_ROWS / RPI / NW;  // wave-instructions per wavefront per stage
   static_assert(TOK % (RPI * NW) == 0 && B_ROWS % (RPI * NW) == 0, "tile/wavefront mismatch");
-  static_assert(EPI != EPI_SWIGLU || FB == 2, "SwiGLU wave tile is one gate block + one up block");
+  static_assert(!swiglu_tile(EPI) || FB == 2, "SwiGLU wave tile is one gate block + one up block");
   static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
   constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
   constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
@@ -370,11 +374,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // one base per operand, the block goes into the constant part of the address.
   static_assert(32 % (RPB * CHUNKS) == 0, "the swizzle key must repeat every 32 rows");
   const int a_row0 = wt * 32 + frow;
-  const int w_row0 = (EPI == EPI_SWIGLU ? wf * 32 : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
+  const int w_row0 = (swiglu_tile(EPI) ? wf * 32 : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
   const int a_base = a_row0 * ROW_BYTES + ((fhalf ^ ((a_row0 / RPB) % CHUNKS)) << 4);
   const int w_base = w_row0 * ROW_BYTES + ((fhalf ^ ((w_row0 / RPB) % CHUNKS)) << 4);
   constexpr int A_BLK = WT * 32 * ROW_BYTES;                                   // next token block of this wavefront
-  constexpr int W_BLK = (EPI == EPI_SWIGLU ? FEAT / 2 : 32) * ROW_BYTES;        // next feature block
+  constexpr int W_BLK = (swiglu_tile(EPI) ? FEAT / 2 : 32) * ROW_BYTES;        // next feature block
 
   // ---- the current tile's operand windows (wave-uniform) ----------------------------------------
   const uint16_t *a_ptr = act, *b_ptr = wa, *b2_ptr = wa;
@@ -384,7 +388,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const size_t woff = (eoff ? (size_t)eoff[t.expert] : (size_t)t.expert * N * K) + (size_t)t.ntile * OUT_FEAT * K;
     a_ptr = GATHER ? act : act + (size_t)t.row0 * K;
     b_ptr = wa + woff;
-    b2_ptr = (EPI == EPI_SWIGLU ? wb : wa) + woff;
+    b2_ptr = (swiglu_tile(EPI) ? wb : wa) + woff;
     a_bytes = (GATHER ? (uint32_t)T : (uint32_t)t.rows) * row_bytes;
   };
   // One instruction moves 64 lanes x 16 B = RPI rows of a tile; lane l lands at row l/CHUNKS, physical
@@ -410,7 +414,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     for (int i = 0; i < B_LOADS; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(B + (i * NW + wave) * 1024), 16,
                                                b_voff, woff + i * b_blk, 0, 0);
-    if (EPI == EPI_SWIGLU) {
+    if (swiglu_tile(EPI)) {
       const __amdgpu_buffer_rsrc_t b2_rsrc = make_rsrc(b2_ptr, live ? b_bytes : 0u);
 #pragma unroll
       for (int i = 0; i < B_LOADS; ++i)
@@ -508,7 +512,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
   // hold at least one valid row (a partial tile - an expert's last rows - multiplies only those blocks;
   // a wavefront with none still takes part in the loads and the barriers).
-  constexpr int W_LOADS = B_LOADS * (EPI == EPI_SWIGLU ? 2 : 1);
+  constexpr int W_LOADS = B_LOADS * (swiglu_tile(EPI) ? 2 : 1);
   auto run_tile = [&](auto tbv_tag) {
     constexpr int TBV = decltype(tbv_tag)::value;
     constexpr int NFB = TBV > 0 ? FB : 0;  // weight fragments are needed only if there is a token block
@@ -695,11 +699,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // l and those of group i0 + 1 in lane l + 32 (rows past the tile's last re-read the last row)
     auto aux_load = [&](int tb, int fb, int i0) {
       const int trow = min((tb * WT + wt) * 32 + frow, done.rows - 1);
-      return *reinterpret_cast<const u32x4*>(residual + (size_t)(done.row0 + trow) * N + feat0 + wf * WFEAT + fb * 32 +
-                                             8 * (i0 + fhalf));
+      return *reinterpret_cast<const u32x4*>(residual + (size_t)(done.row0 + trow) * N + feat0 +
+                                             (swiglu_tile(EPI) ? wf * 32 : wf * WFEAT + fb * 32) + 8 * (i0 + fhalf));
     };
     u32x4 aux_next = {0u, 0u, 0u, 0u};
-    if constexpr (EPI == EPI_DGELU) aux_next = aux_load(0, 0, 0);
+    if constexpr (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) aux_next = aux_load(0, 0, 0);
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
       const int trow = (tb * WT + wt) * 32 + frow;
@@ -708,7 +712,34 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       if (trow >= done.rows) continue;
       const size_t orow_idx = EPI == EPI_COMBINE ? (size_t)row_tok[tb] : (size_t)(done.row0 + trow);
       uint16_t* orow = out + orow_idx * N;
-      if (EPI == EPI_SWIGLU) {
+      if constexpr (EPI == EPI_DSWIGLU) {
+        uint16_t* orow2 = out + orow_idx * (size_t)(2 * N);  // [d_g | d_u] rows
+#pragma unroll
+        for (int i0 = 0; i0 < 4; i0 += 2) {
+          // aux in the layout of the stores, the halves traded back (as in EPI_DGELU)
+          const u32x2 sx = __builtin_amdgcn_permlane32_swap(aux_next.x, aux_next.z, false, false);
+          const u32x2 sy = __builtin_amdgcn_permlane32_swap(aux_next.y, aux_next.w, false, false);
+          if (i0 + 2 < 4) aux_next = aux_load(tb, 0, i0 + 2);
+          else if (tb + 1 < TB) aux_next = aux_load(tb + 1, 0, 0);
+          float pg[8], pu[8];
+#pragma unroll
+          for (int g = 0; g < 2; ++g) {
+            const uint32_t lo = g ? sx.y : sx.x, hi = g ? sy.y : sy.x;
+            const float dh[4] = {bf16_bits_to_f32(lo & 0xffffu), __uint_as_float(lo & 0xffff0000u),
+                                 bf16_bits_to_f32(hi & 0xffffu), __uint_as_float(hi & 0xffff0000u)};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float gv = acc[tb][0][4 * (i0 + g) + q], uv = acc[tb][1][4 * (i0 + g) + q];
+              const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-gv));   // sigmoid(g)
+              const float ds = dh[q] * sg;
+              pu[4 * g + q] = ds * gv;                                     // d_u = d_h * silu(g)
+              pg[4 * g + q] = ds * uv * fmaf(gv, 1.f - sg, 1.f);           // d_g = d_h * u * s (1 + g (1 - s))
+            }
+          }
+          store_pair(orow2, feat0 + wf * 32, i0, pg);
+          store_pair(orow2 + N, feat0 + wf * 32, i0, pu);
+        }
+      } else if (EPI == EPI_SWIGLU) {
 #pragma unroll
         for (int i0 = 0; i0 < 4; i0 += 2) {
           float p[8];
@@ -801,7 +832,7 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
                int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s, const int64_t* eoff,
                const float* gate_w = nullptr, const uint16_t* residual = nullptr) {
-  constexpr int OUT_FEAT = EPI == EPI_SWIGLU ? FEAT / 2 : FEAT;
+  constexpr int OUT_FEAT = swiglu_tile(EPI) ? FEAT / 2 : FEAT;
   if (N % OUT_FEAT) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: N=%d is not a multiple of %d", N, OUT_FEAT);
   if (K % KS) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d is not a multiple of %d", K, KS);
   if ((int64_t)TOK * K * 2 >= ((int64_t)1 << 31)) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: K=%d too large", K);
@@ -821,7 +852,9 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
   // the gathering variant exists for the first GEMM's epilogues only
   auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, false>;
-  if constexpr (EPI == EPI_SWIGLU) {
+  if constexpr (EPI == EPI_DSWIGLU) {
+    if (row_map || !residual || bias) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: the SwiGLU-gradient epilogue reads contiguous rows, needs the activations' gradient and has no bias");
+  } else if constexpr (EPI == EPI_SWIGLU) {
     if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
   } else {
     if (bias) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, true>;
@@ -830,7 +863,7 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
     if (row_map)
       kern = bias ? grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, true>
                   : grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
-  } else if constexpr (EPI == EPI_SWIGLU) {
+  } else if constexpr (swiglu_tile(EPI)) {
   } else if constexpr (EPI == EPI_BIAS) {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
   } else if constexpr (EPI == EPI_DGELU) {
@@ -885,13 +918,13 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
                  const int32_t* offsets, uint16_t* o, const int32_t* row_map, int32_t* tile_ctr, int32_t* clear_ctr, int N,
                  int K, hipStream_t s, const int64_t* eoff, const float* gate_w = nullptr,
                  const uint16_t* residual = nullptr) {
-  constexpr int BF = EPI == EPI_SWIGLU ? 128 : 256;  // output features of the big tile
+  constexpr int BF = swiglu_tile(EPI) ? 128 : 256;  // output features of the big tile
   if (N % BF == 0) {
     if (pick_tile_rows(cfg, N / BF) == 320)
       return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
     return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
   }
-  if constexpr (EPI == EPI_SWIGLU)
+  if constexpr (swiglu_tile(EPI))
     return launch<128, 128, 2, 2, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
   else
     return launch<128, 64, 4, 1, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
@@ -950,6 +983,15 @@ int32_t launch_gemm1_dgelu_bf16(const moe_config* cfg, const void* xd, const voi
   return gemm_any<EPI_DGELU>(cfg, (const uint16_t*)xd, (const uint16_t*)w1, nullptr, (const uint16_t*)b1, offsets,
                              (uint16_t*)d_u, nullptr, counters8, nullptr, cfg->d_ff, cfg->d_model, s, nullptr, nullptr,
                              (const uint16_t*)d_h);
+}
+
+// SwiGLU experts: dgu[r, 0:N] = d_h * u * silu'(g), dgu[r, N:2N] = d_h * silu(g) with g = xd Wg_e^T, u = xd Wu_e^T
+// recomputed (N = d_ff; dgu [R, 2N]).  counters8: eight zeroed ints.
+int32_t launch_gemm1_dswiglu_bf16(const moe_config* cfg, const void* xd, const void* w_gate, const void* w_up,
+                                  const int32_t* offsets, const void* d_h, void* dgu, int32_t* counters8, hipStream_t s) {
+  return gemm_any<EPI_DSWIGLU>(cfg, (const uint16_t*)xd, (const uint16_t*)w_gate, (const uint16_t*)w_up, nullptr, offsets,
+                               (uint16_t*)dgu, nullptr, counters8, nullptr, cfg->d_ff, cfg->d_model, s, nullptr, nullptr,
+                               (const uint16_t*)d_h);
 }
 
 // The first GEMM can gather its rows from x when every byte offset into x fits the 32-bit buffer offset.
