@@ -345,7 +345,7 @@ int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, con
                                 float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
                                 size_t ws_bytes, void* stream);
 
-/* Backward of moe_layer_forward (MOE_BF16, E <= 64) for the gradient d_out
+/* Backward of moe_layer_forward (MOE_BF16) for the gradient d_out
  * [T,d_model] of its output, with the routing of the forward pass held fixed:
  *   d_x [T,d_model] (cfg.dtype) = add_to_d_x (nullable; e.g. d_out when the layer ran with
  *       residual == x) + the experts' path (through dispatch) + the gate's path, one rounding;

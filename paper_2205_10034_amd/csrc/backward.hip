@@ -102,7 +102,6 @@ __global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict
 constexpr int DWG_SLICE = 64;  // tokens per partial sum of the router's weight gradient (many slices: the kernel's
                                // parallelism is slices x column blocks)
 constexpr int GB_TOK = 16;   // tokens per workgroup of dx_kernel (their loads are issued together)
-constexpr int GB_MAXE = 64;  // experts they keep in registers
 constexpr int GB_MAXK = MOE_MAX_TOPK;  // choices per token
 
 // d_x[t, i] = (extra[t, i]) + sum over the kept choices j of d_xd[a2r[j*T+t], i] + sum_e d_z[t,e] * W_g[i,e],
@@ -117,35 +116,13 @@ __global__ __launch_bounds__(256) void dx_kernel(const uint32_t* __restrict__ d_
   __shared__ float s_dz[GB_TOK][EC];
   __shared__ int32_t s_row[GB_MAXK][GB_TOK];
   const int t0 = blockIdx.y * GB_TOK;
-  for (int i = threadIdx.x; i < GB_TOK * EC; i += 256) {
-    const int u = i / EC, e = i % EC;
-    s_dz[u][e] = (t0 + u < T && e < E) ? d_z[(size_t)(t0 + u) * E + e] : 0.f;
-  }
   if ((int)threadIdx.x < k * GB_TOK) {
     const int j = threadIdx.x / GB_TOK, u = threadIdx.x % GB_TOK;
     s_row[j][u] = t0 + u < T ? a2r[(size_t)j * T + t0 + u] : -1;
   }
   __syncthreads();
-  const int i2 = blockIdx.x * 256 + threadIdx.x;  // column pair
-  if (i2 * 2 >= d) return;
-  float w0[EC], w1[EC];
-  if (E == EC && (reinterpret_cast<uintptr_t>(w_router) & 15) == 0) {
-    // the thread's two router rows are 2*EC consecutive floats: 16-byte loads (a lane's rows share no cache line
-    // with another lane's, so the cost is per instruction)
-    const float4* wr = reinterpret_cast<const float4*>(w_router + (size_t)(2 * i2) * EC);
-#pragma unroll
-    for (int q = 0; q < EC / 4; ++q) {
-      const float4 p0 = wr[q], p1 = wr[EC / 4 + q];
-      w0[4 * q] = p0.x; w0[4 * q + 1] = p0.y; w0[4 * q + 2] = p0.z; w0[4 * q + 3] = p0.w;
-      w1[4 * q] = p1.x; w1[4 * q + 1] = p1.y; w1[4 * q + 2] = p1.z; w1[4 * q + 3] = p1.w;
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < EC; ++e) {
-      w0[e] = e < E ? w_router[(size_t)(2 * i2) * E + e] : 0.f;
-      w1[e] = e < E ? w_router[(size_t)(2 * i2 + 1) * E + e] : 0.f;
-    }
-  }
+  const bool active = (blockIdx.x * 256 + threadIdx.x) * 2 < (unsigned)d;
+  const int i2 = active ? blockIdx.x * 256 + threadIdx.x : 0;  // column pair (idle threads redo pair 0, store nothing)
   // every load of the workgroup's tokens is issued before the first is used (the addresses are clamped into
   // the arrays; what a clamped load returns is discarded)
   uint32_t v[GB_TOK];
@@ -170,27 +147,55 @@ __global__ __launch_bounds__(256) void dx_kernel(const uint32_t* __restrict__ d_
       a1[u] += r[u] >= 0 ? bf16_hi(v[u]) : 0.f;
     }
   }
-#pragma unroll
-  for (int u = 0; u < GB_TOK; ++u) {
-    float s0 = a0[u], s1 = a1[u];
-#pragma unroll
-    for (int e = 0; e < EC; ++e) {
-      s0 = fmaf(s_dz[u][e], w0[e], s0);
-      s1 = fmaf(s_dz[u][e], w1[e], s1);
+  // the gate's path, EC experts at a time: the thread keeps its two router rows' EC entries in registers
+  for (int e0 = 0; e0 < E; e0 += EC) {
+    if (e0) __syncthreads();  // (the previous chunk of s_dz has been read)
+    for (int i = threadIdx.x; i < GB_TOK * EC; i += 256) {
+      const int u = i / EC, e = e0 + i % EC;
+      s_dz[u][i % EC] = (t0 + u < T && e < E) ? d_z[(size_t)(t0 + u) * E + e] : 0.f;
     }
-    if (t0 + u < T) d_x[(size_t)(t0 + u) * (d / 2) + i2] = to_bf16(s0) | (to_bf16(s1) << 16);
+    __syncthreads();
+    float w0[EC], w1[EC];
+    const float* wr = w_router + (size_t)(2 * i2) * E + e0;
+    if (e0 + EC <= E && (E & 3) == 0 && (reinterpret_cast<uintptr_t>(w_router) & 15) == 0) {
+      // 16-byte loads (a lane's rows share no cache line with another lane's, so the cost is per instruction)
+#pragma unroll
+      for (int q = 0; q < EC / 4; ++q) {
+        const float4 p0 = reinterpret_cast<const float4*>(wr)[q], p1 = reinterpret_cast<const float4*>(wr + E)[q];
+        w0[4 * q] = p0.x; w0[4 * q + 1] = p0.y; w0[4 * q + 2] = p0.z; w0[4 * q + 3] = p0.w;
+        w1[4 * q] = p1.x; w1[4 * q + 1] = p1.y; w1[4 * q + 2] = p1.z; w1[4 * q + 3] = p1.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EC; ++e) {
+        w0[e] = e0 + e < E ? wr[e] : 0.f;
+        w1[e] = e0 + e < E ? wr[E + e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < GB_TOK; ++u)
+#pragma unroll
+      for (int e = 0; e < EC; ++e) {
+        a0[u] = fmaf(s_dz[u][e], w0[e], a0[u]);
+        a1[u] = fmaf(s_dz[u][e], w1[e], a1[u]);
+      }
+  }
+  if (active) {
+#pragma unroll
+    for (int u = 0; u < GB_TOK; ++u)
+      if (t0 + u < T) d_x[(size_t)(t0 + u) * (d / 2) + i2] = to_bf16(a0[u]) | (to_bf16(a1[u]) << 16);
   }
 }
 
-// partial[slice, i, e] = sum over the slice's tokens of x[t, i] * d_z[t, e]
+// partial[slice, i, e] = sum over the slice's tokens of x[t, i] * d_z[t, e]; blockIdx.z: which EC experts
 template <int EC>
 __global__ __launch_bounds__(256) void dwg_partial_kernel(const uint32_t* __restrict__ x, const float* __restrict__ d_z,
                                                           float* __restrict__ partial, int T, int d, int E, int slice_tokens) {
   __shared__ float s_dz[DWG_SLICE][EC];
-  const int ts = blockIdx.y * slice_tokens;
+  const int ts = blockIdx.y * slice_tokens, e0 = blockIdx.z * EC;
   for (int i = threadIdx.x; i < slice_tokens * EC; i += 256) {
-    const int u = i / EC, e = i % EC;
-    s_dz[u][e] = (ts + u < T && e < E) ? d_z[(size_t)(ts + u) * E + e] : 0.f;  // (zero rows past the last token)
+    const int u = i / EC, e = e0 + i % EC;
+    s_dz[u][i % EC] = (ts + u < T && e < E) ? d_z[(size_t)(ts + u) * E + e] : 0.f;  // (zero rows past the last token)
   }
   __syncthreads();
   const int i2 = blockIdx.x * 256 + threadIdx.x;
@@ -209,10 +214,10 @@ __global__ __launch_bounds__(256) void dwg_partial_kernel(const uint32_t* __rest
       a1[e] = fmaf(x1, s_dz[u][e], a1[e]);
     }
   }
-  float* p0 = partial + ((size_t)blockIdx.y * d + 2 * i2) * E;
+  float* p0 = partial + ((size_t)blockIdx.y * d + 2 * i2) * E + e0;
 #pragma unroll
   for (int e = 0; e < EC; ++e)
-    if (e < E) { p0[e] = a0[e]; p0[E + e] = a1[e]; }
+    if (e0 + e < E) { p0[e] = a0[e]; p0[E + e] = a1[e]; }
 }
 
 // out[n] = sum over the slices of partial[slice, n], in slice order
@@ -351,7 +356,7 @@ int32_t gate_products(const moe_config* cfg, const void* x, const float* w_route
   const unsigned col_blocks = (unsigned)((d / 2 + 255) / 256);
   hipLaunchKernelGGL(dx_kernel<EC>, dim3(col_blocks, (unsigned)((T + GB_TOK - 1) / GB_TOK)), block, 0, s, (const uint32_t*)d_xd, a2r, d_z,
                      w_router, (const uint32_t*)extra, (uint32_t*)d_x, T, d, E, cfg->k);
-  hipLaunchKernelGGL(dwg_partial_kernel<EC>, dim3(col_blocks, (unsigned)slices), block, 0, s, (const uint32_t*)x, d_z, partial, T, d, E,
+  hipLaunchKernelGGL(dwg_partial_kernel<EC>, dim3(col_blocks, (unsigned)slices, (unsigned)((E + EC - 1) / EC)), block, 0, s, (const uint32_t*)x, d_z, partial, T, d, E,
                      DWG_SLICE);
   const size_t n = (size_t)d * E;
   hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 255) / 256)), block, 0, s, partial, d_w_router, n, slices);
@@ -376,7 +381,6 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
   if (cfg->dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: bf16 only");
-  if (cfg->E > GB_MAXE) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d experts", GB_MAXE);
   if ((cfg->T + GB_TOK - 1) / GB_TOK > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_layer_backward: at most %d tokens", 65535 * GB_TOK);
   if (!w->w_router || !d_w_router || (w->b_router && !d_b_router))
     return fail(MOE_ERR_INVALID_ARG, "moe_layer_backward: router weights and their gradient buffers must be non-NULL");
