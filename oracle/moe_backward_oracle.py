@@ -22,6 +22,13 @@ the inputs.  For an upstream gradient G = d loss / d out [T, d_model]:
                d_p_i = d_w_i / S - (sum_j d_w_j w_j) / S;   otherwise d_p_i = d_w_i
                softmax: d_z = p * (d_p - sum_e d_p_e p_e), d_p being zero off the selected experts
                d_x += d_z W_g^T;  dW_g = x^T d_z;  db_g = sum_t d_z
+  auxiliary    the paper names auxiliary losses as the known remedy for expert imbalance (Section 1, the
+  loss         computation challenge) and gives no formula; the reading taken is the load-balancing loss of the
+               work it cites there (GShard / Switch Transformer):
+                 L_aux = coef * E * sum_e f_e * Pbar_e,
+               f_e = fraction of the tokens whose FIRST choice is expert e (before capacity), Pbar_e = mean over
+               the tokens of p[t, e].  f is piecewise constant, so d L_aux / d p[t, e] = coef * E * f_e / T,
+               which joins d_p before the softmax Jacobian (on every expert, not only the selected ones).
 
 Everything is float64 and unblocked: one ``numpy.matmul`` per product, one loop over
 experts.  Expert matrices are input-major ([E, in, out]) as in the forward oracle.
@@ -31,7 +38,9 @@ along random directions in every input and parameter (the step is small enough t
 the routing does not change, which the test checks); torch's autograd in float64 on a
 dense re-expression of the layer with the routing fixed; the special case E = 1 (a
 dense FFN: gate gradients vanish); the weight-gradient product by brute force and
-against the layer's own dW2.  No function here is "parity unpinned".
+against the layer's own dW2; the auxiliary loss by its closed forms (uniform probabilities or uniform routing
+give coef, everything on one expert gives coef * E * its mean probability), a from-scratch loop, and the same
+central differences and autograd with the loss added to the objective.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -51,6 +60,14 @@ def gelu_grad(u: np.ndarray) -> np.ndarray:
 def silu_grad(v: np.ndarray) -> np.ndarray:
     s = 1.0 / (1.0 + np.exp(-v))
     return s * (1.0 + v * (1.0 - s))
+
+
+def aux_loss(probs: np.ndarray, topk_idx: np.ndarray, coef: float) -> float:
+    """coef * E * sum_e f_e * Pbar_e (see the header): 1 * coef when either the routing or the probabilities are uniform."""
+    probs = np.asarray(probs, dtype=np.float64)
+    T, E = probs.shape
+    f = np.bincount(np.asarray(topk_idx)[:, 0].astype(np.int64), minlength=E) / T
+    return float(coef * E * np.sum(f * probs.mean(axis=0)))
 
 
 def expert_ffn_backward(xd, offsets, weights: Dict[str, np.ndarray], d_y, act: str) -> Dict[str, np.ndarray]:
@@ -104,8 +121,10 @@ def expert_ffn_backward(xd, offsets, weights: Dict[str, np.ndarray], d_y, act: s
 
 
 def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, capacity_factor: float,
-                   renormalize: bool, act: str, residual: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
-    """Gradients of sum(out * d_out) with respect to x, the residual and every parameter."""
+                   renormalize: bool, act: str, residual: Optional[np.ndarray] = None,
+                   aux_coef: float = 0.0) -> Dict[str, np.ndarray]:
+    """Gradients of sum(out * d_out) + aux_loss(probs, topk_idx, aux_coef) with respect to x, the residual and
+    every parameter."""
     x = np.asarray(x, dtype=np.float64)
     G = np.asarray(d_out, dtype=np.float64)
     T, d = x.shape
@@ -148,6 +167,9 @@ def layer_backward(x, weights: Dict[str, np.ndarray], d_out, *, E: int, k: int, 
     else:
         for j in range(k):
             d_p[rows_t, idx[:, j]] = d_w[:, j]
+    if aux_coef != 0.0:
+        f = np.bincount(idx[:, 0].astype(np.int64), minlength=E) / T
+        d_p = d_p + (aux_coef * E / T) * f[None, :]
     d_z = p * (d_p - np.sum(d_p * p, axis=1, keepdims=True))
     w_router = np.asarray(weights["w_router"], dtype=np.float64)
     d_x += np.matmul(d_z, w_router.T)

@@ -44,9 +44,16 @@ def kw(c):
     return dict(E=c["E"], k=c["k"], capacity_factor=c["cf"], renormalize=c["renorm"], act=c["act"])
 
 
+AUX = 0.7          # coefficient of the auxiliary loss in the pins below (large, so that a mistake in it shows)
+
+
+def objective(o, G):
+    return float(np.sum(o["out"] * G)) + B.aux_loss(o["probs"], o["topk_idx"], AUX)
+
+
 def pin_central_differences(c):
     x, W, res, G = make(c, 1)
-    g = B.layer_backward(x, W, G, residual=res, **kw(c))
+    g = B.layer_backward(x, W, G, residual=res, aux_coef=AUX, **kw(c))
     base = F.layer_forward(x, W, residual=res, **kw(c))
     if c["cf"] > 0 and c["cf"] < 1:
         assert (base["assign_to_row"] < 0).any()            # drops are part of the case
@@ -69,7 +76,7 @@ def pin_central_differences(c):
                 o = F.layer_forward(xx, WW, residual=rr, **kw(c))
                 assert np.array_equal(o["topk_idx"], base["topk_idx"])          # same routing: differentiable here
                 assert np.array_equal(o["assign_to_row"], base["assign_to_row"])
-                return float(np.sum(o["out"] * G))
+                return objective(o, G)
 
             num = (f(+1) - f(-1)) / (2 * eps)
             ana = float(np.sum(g[n] * delta))
@@ -78,7 +85,7 @@ def pin_central_differences(c):
 
 def pin_torch_autograd(c):
     x, W, res, G = make(c, 3)
-    g = B.layer_backward(x, W, G, residual=res, **kw(c))
+    g = B.layer_backward(x, W, G, residual=res, aux_coef=AUX, **kw(c))
     fw = F.layer_forward(x, W, residual=res, **kw(c))
     idx, a2r = fw["topk_idx"].astype(np.int64), fw["assign_to_row"]
     T, k = idx.shape
@@ -112,7 +119,12 @@ def pin_torch_autograd(c):
         outs.append(acc)
     out = torch.stack(outs)
     assert np.allclose(out.detach().numpy(), fw["out"], rtol=1e-12, atol=1e-12)
-    (out * torch.tensor(G)).sum().backward()
+    # the auxiliary loss written out from its definition: first-choice fractions (constants) times mean probabilities
+    T_, E_ = p.shape
+    first = torch.tensor([[1.0 if idx[t, 0] == e else 0.0 for e in range(E_)] for t in range(T_)], dtype=torch.float64)
+    aux = AUX * E_ * (first.mean(dim=0) * p.mean(dim=0)).sum()
+    assert abs(aux.item() - B.aux_loss(fw["probs"], fw["topk_idx"], AUX)) < 1e-12
+    ((out * torch.tensor(G)).sum() + aux).backward()
     assert np.allclose(tx.grad.numpy(), g["x"], rtol=1e-9, atol=1e-11)
     for n in W:
         got = tW[n].grad.numpy() if tW[n].grad is not None else np.zeros_like(W[n])
@@ -164,6 +176,38 @@ def test_expert_wgrad_bruteforce_and_against_layer_backward():
     assert np.allclose(B.expert_wgrad(h, d_y, fw["expert_offsets"]), g["w2"], rtol=1e-12, atol=1e-12)
 
 
+def test_aux_loss_closed_forms():
+    r = np.random.default_rng(11)
+    T, E = 40, 5
+    idx = r.integers(0, E, size=(T, 2))
+    assert abs(B.aux_loss(np.full((T, E), 1.0 / E), idx, 0.3) - 0.3) < 1e-15                 # uniform probabilities
+    p = r.random((T, E)); p /= p.sum(axis=1, keepdims=True)
+    even = np.stack([np.arange(T) % E, (np.arange(T) + 1) % E], axis=1)
+    assert abs(B.aux_loss(p, even, 0.3) - 0.3) < 1e-15                                       # uniform routing
+    one = np.zeros((T, 2), dtype=np.int64); one[:, 1] = 1
+    assert abs(B.aux_loss(p, one, 0.3) - 0.3 * E * p[:, 0].mean()) < 1e-15                   # everything on expert 0
+    # second choices do not count
+    idx2 = idx.copy(); idx2[:, 1] = (idx2[:, 1] + 1) % E
+    assert B.aux_loss(p, idx, 1.0) == B.aux_loss(p, idx2, 1.0)
+    # from scratch
+    want = 0.0
+    for e in range(E):
+        want += sum(1 for t in range(T) if idx[t, 0] == e) / T * sum(p[t, e] for t in range(T)) / T
+    assert abs(B.aux_loss(p, idx, 2.0) - 2.0 * E * want) < 1e-14
+    assert B.aux_loss(p, idx, 0.0) == 0.0
+
+
+def test_aux_gradient_is_additive():
+    c = CASES[0]
+    x, W, res, G = make(c, 6)
+    g0 = B.layer_backward(x, W, G, residual=res, **kw(c))
+    g1 = B.layer_backward(x, W, np.zeros_like(G), residual=res, aux_coef=AUX, **kw(c))
+    g = B.layer_backward(x, W, G, residual=res, aux_coef=AUX, **kw(c))
+    for n in ("x", "w_router", "b_router", "logits"):
+        assert np.allclose(g[n], g0[n] + g1[n], rtol=1e-12, atol=1e-14)
+    assert np.abs(g1["w_router"]).max() > 1e-4 and not g1["w1"].any()      # reaches the router only
+
+
 PINS = [pin_central_differences, pin_torch_autograd]
 
 
@@ -196,17 +240,26 @@ def _wrap(transform):
     return mutant
 
 
+def _wrap_kw(change):
+    orig = B.layer_backward
+
+    def mutant(*a, **k):
+        return orig(*a, **change(k))
+    return mutant
+
+
 def _renorm_term_dropped(g, a, k):
     # recompute the gate part without the -(sum d_w w)/S term
     if not k["renormalize"]:
         return g
     x, W = np.asarray(a[0], dtype=np.float64), a[1]
-    fw = F.layer_forward(x, W, **{n: v for n, v in k.items()})
+    fw = F.layer_forward(x, W, **{n: v for n, v in k.items() if n != "aux_coef"})
     p, idx = fw["probs"], fw["topk_idx"].astype(np.int64)
     S = np.take_along_axis(p, idx, axis=1).sum(axis=1)
     d_p = np.zeros_like(p)
     for j in range(idx.shape[1]):
         d_p[np.arange(len(p)), idx[:, j]] = g["topk_w"][:, j] / S
+    d_p += k.get("aux_coef", 0.0) * p.shape[1] / len(p) * (np.bincount(idx[:, 0], minlength=p.shape[1]) / len(p))[None, :]
     d_z = p * (d_p - np.sum(d_p * p, axis=1, keepdims=True))
     g = dict(g)
     g["x"] = g["x"] - g["logits"] @ np.asarray(W["w_router"]).T + d_z @ np.asarray(W["w_router"]).T
@@ -225,6 +278,8 @@ MUTANTS = {
         lambda g, a, k: {**g, "w_router": np.asarray(a[0]).T @ (g["logits"] * 0 + g["logits"].sum(axis=1, keepdims=True))})),
     "renormalisation's common term dropped": lambda: planted("layer_backward", _wrap(_renorm_term_dropped)),
     "residual gradient scaled": lambda: planted("layer_backward", _wrap(lambda g, a, k: {**g, "residual": 2 * g["residual"]})),
+    "auxiliary loss ignored by the backward pass": lambda: planted("layer_backward", _wrap_kw(lambda k: {**k, "aux_coef": 0.0})),
+    "auxiliary gradient without the factor E": lambda: planted("layer_backward", _wrap_kw(lambda k: {**k, "aux_coef": k.get("aux_coef", 0.0) / k["E"]})),
 }
 
 
