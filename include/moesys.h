@@ -345,12 +345,26 @@ int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, con
                                 float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
                                 size_t ws_bytes, void* stream);
 
+/* Load-balancing auxiliary loss.  The paper names auxiliary losses as the known remedy for
+ * expert imbalance (Section 1, the computation challenge) without a formula; this is the one
+ * of the work it cites there (GShard / Switch Transformer):
+ *   loss = coef * E * sum_e expert_fraction[e] * mean_prob[e]
+ * expert_fraction[e] = share of the T tokens whose FIRST choice topk_idx[t,0] is e (before
+ * capacity), mean_prob[e] = mean over the tokens of probs[t,e]; loss == coef when the routing or
+ * the probabilities are uniform.  probs [T,E] and topk_idx [T,k] as written by moe_gate; the
+ * three outputs are device float arrays of E, E and 1 elements.  T == 0: MOE_ERR_INVALID_ARG.
+ * Its gradient enters through moe_layer_backward's aux_loss_coef. */
+int32_t moe_gate_aux_loss(const moe_config* cfg, const float* probs, const int32_t* topk_idx, float coef,
+                          float* expert_fraction, float* mean_prob, float* loss, void* stream);
+
 /* Backward of moe_layer_forward (MOE_BF16) for the gradient d_out
  * [T,d_model] of its output, with the routing of the forward pass held fixed:
  *   d_x [T,d_model] (cfg.dtype) = add_to_d_x (nullable; e.g. d_out when the layer ran with
  *       residual == x) + the experts' path (through dispatch) + the gate's path, one rounding;
  *   d_w_router [d_model,E], d_b_router [E] (float32; the latter required iff w->b_router);
  *   d_w1, d_b1, d_w2, d_b2 as in moe_expert_ffn_backward.
+ * aux_loss_coef != 0 adds the gradient of moe_gate_aux_loss(coef = aux_loss_coef) of this layer's
+ * routing (it reaches d_x, d_w_router and d_b_router through the logits).
  * The gradient of the residual input is d_out itself.  fwd_ws is the workspace that
  * moe_layer_forward (or route + experts) left for the same cfg, x and w: its routing
  * tables and hidden activations are read; the gate is run again for the probabilities and
@@ -359,7 +373,8 @@ int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, con
 size_t moe_layer_backward_workspace_bytes(const moe_config* cfg);
 int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                            const void* w2_input_major, const void* x, const void* d_out,
-                           const void* add_to_d_x, const void* fwd_ws, size_t fwd_ws_bytes, void* d_x,
+                           const void* add_to_d_x, float aux_loss_coef, const void* fwd_ws,
+                           size_t fwd_ws_bytes, void* d_x,
                            float* d_w_router, float* d_b_router, float* d_w1, float* d_b1,
                            float* d_w2, float* d_b2, void* ws, size_t ws_bytes, void* stream);
 

@@ -126,8 +126,9 @@ def lib() -> C.CDLL:
         L.moe_expert_ffn_backward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 12 + [C.c_size_t, vp]
         L.moe_layer_backward_workspace_bytes.restype = C.c_size_t
         L.moe_layer_backward_workspace_bytes.argtypes = [C.POINTER(_Config)]
-        L.moe_layer_backward.argtypes = ([C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 6 + [C.c_size_t] + [vp] * 8 +
-                                         [C.c_size_t, vp])
+        L.moe_layer_backward.argtypes = ([C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 5 + [C.c_float, vp, C.c_size_t] +
+                                         [vp] * 8 + [C.c_size_t, vp])
+        L.moe_gate_aux_loss.argtypes = [C.POINTER(_Config), vp, vp, C.c_float, vp, vp, vp, vp]
         L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
@@ -294,13 +295,20 @@ def moe_layer_backward_workspace_bytes(cfg) -> int:
 
 
 def moe_layer_backward(cfg, weights: Weights, w1_input_major, w2_input_major, x, d_out, add_to_d_x, fwd_ws, d_x,
-                       d_w_router, d_b_router, d_w1, d_b1, d_w2, d_b2, ws, stream=None):
+                       d_w_router, d_b_router, d_w1, d_b1, d_w2, d_b2, ws, stream=None, aux_loss_coef: float = 0.0):
     c = cfg.c()
     _check(lib().moe_layer_backward(C.byref(c), C.byref(weights.c), _ptr(w1_input_major), _ptr(w2_input_major), _ptr(x),
-                                    _ptr(d_out), _ptr(add_to_d_x), _ptr(fwd_ws), fwd_ws.numel() * fwd_ws.element_size(),
+                                    _ptr(d_out), _ptr(add_to_d_x), aux_loss_coef, _ptr(fwd_ws),
+                                    fwd_ws.numel() * fwd_ws.element_size(),
                                     _ptr(d_x), _ptr(d_w_router), _ptr(d_b_router), _ptr(d_w1), _ptr(d_b1), _ptr(d_w2),
                                     _ptr(d_b2), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
            "moe_layer_backward")
+
+
+def moe_gate_aux_loss(cfg, probs, topk_idx, coef: float, expert_fraction, mean_prob, loss, stream=None):
+    c = cfg.c()
+    _check(lib().moe_gate_aux_loss(C.byref(c), _ptr(probs), _ptr(topk_idx), coef, _ptr(expert_fraction), _ptr(mean_prob),
+                                   _ptr(loss), _stream(stream)), "moe_gate_aux_loss")
 
 
 def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None):

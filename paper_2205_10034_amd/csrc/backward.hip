@@ -57,12 +57,49 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const uint4* __restrict_
 }
 
 // ---- gate ----------------------------------------------------------------------------------------
-// d_z[t, e] = p[t,e] * (d_p[t,e] - sum_e' d_p[t,e'] p[t,e']), where d_p is zero off the k selected experts and
-// there d_p = (d_w_j - sum_i d_w_i w_i) / S with S = sum of the selected probabilities if the weights are
-// renormalised, d_p = d_w_j otherwise.  One wavefront per token, lanes over the experts.
+// Load-balancing auxiliary loss (the remedy for expert imbalance that the paper's Section 1 points to, in the
+// form of the work cited there): L = coef * E * sum_e f_e * Pbar_e, f_e = fraction of the tokens whose first
+// choice is expert e, Pbar_e = mean probability of e.  One workgroup per expert; fixed reduction order.
+__global__ __launch_bounds__(256) void first_choice_fraction_kernel(const int32_t* __restrict__ topk_idx,
+                                                                    const float* __restrict__ probs, float* __restrict__ f,
+                                                                    float* __restrict__ pbar, int T, int E, int k) {
+  __shared__ int cnt[256];
+  __shared__ float sum[256];
+  const int e = blockIdx.x;
+  int c = 0;
+  float a = 0.f;
+  for (int t = threadIdx.x; t < T; t += 256) {
+    c += topk_idx[(size_t)t * k] == e;
+    if (probs) a += probs[(size_t)t * E + e];
+  }
+  cnt[threadIdx.x] = c;
+  sum[threadIdx.x] = a;
+  __syncthreads();
+  for (int m = 128; m >= 1; m >>= 1) {
+    if ((int)threadIdx.x < m) { cnt[threadIdx.x] += cnt[threadIdx.x + m]; sum[threadIdx.x] += sum[threadIdx.x + m]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    f[e] = (float)cnt[0] / (float)T;
+    if (pbar) pbar[e] = sum[0] / (float)T;
+  }
+}
+
+__global__ void aux_loss_kernel(const float* __restrict__ f, const float* __restrict__ pbar, float* __restrict__ loss, int E, float coef) {
+  if (threadIdx.x || blockIdx.x) return;
+  float a = 0.f;
+  for (int e = 0; e < E; ++e) a = fmaf(f[e], pbar[e], a);
+  *loss = coef * (float)E * a;
+}
+
+// d_z[t, e] = p[t,e] * (d_p[t,e] - sum_e' d_p[t,e'] p[t,e']).  d_p is, on the k selected experts,
+// (d_w_j - sum_i d_w_i w_i) / S with S = sum of the selected probabilities if the weights are renormalised and
+// d_w_j otherwise, zero elsewhere; plus, on every expert, aux_scale * f[e] (the auxiliary loss's gradient,
+// aux_scale = coef * E / T; f NULL: none).  One wavefront per token, lanes over the experts.
 __global__ __launch_bounds__(256) void gate_dlogits_kernel(const float* __restrict__ probs, const int32_t* __restrict__ topk_idx,
                                                            const float* __restrict__ topk_w, const float* __restrict__ d_topk_w,
-                                                           float* __restrict__ d_z, int T, int E, int k, int renorm) {
+                                                           float* __restrict__ d_z, int T, int E, int k, int renorm,
+                                                           const float* __restrict__ f, float aux_scale) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -71,15 +108,23 @@ __global__ __launch_bounds__(256) void gate_dlogits_kernel(const float* __restri
     S += probs[(size_t)t * E + topk_idx[(size_t)t * k + j]];
     common += d_topk_w[(size_t)t * k + j] * topk_w[(size_t)t * k + j];
   }
-  float s = 0.f;  // sum over the selected experts of d_p * p
+  float s = 0.f;  // sum over the experts of d_p * p: the selected ones ...
   for (int j = 0; j < k; ++j) {
     const float dp = renorm ? (d_topk_w[(size_t)t * k + j] - common) / S : d_topk_w[(size_t)t * k + j];
     s += dp * probs[(size_t)t * E + topk_idx[(size_t)t * k + j]];
+  }
+  if (f) {  // ... and the auxiliary term on all of them (lanes in a fixed butterfly order)
+    float a = 0.f;
+    for (int e = lane; e < E; e += 64) a = fmaf(f[e], probs[(size_t)t * E + e], a);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) a += __shfl_xor(a, m, 64);
+    s = fmaf(aux_scale, a, s);
   }
   for (int e = lane; e < E; e += 64) {
     float dp = 0.f;
     for (int j = 0; j < k; ++j)
       if (topk_idx[(size_t)t * k + j] == e) dp = renorm ? (d_topk_w[(size_t)t * k + j] - common) / S : d_topk_w[(size_t)t * k + j];
+    if (f) dp = fmaf(aux_scale, f[e], dp);
     d_z[(size_t)t * E + e] = probs[(size_t)t * E + e] * (dp - s);
   }
 }
@@ -318,11 +363,25 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr + 16, s);
 }
 
+extern "C" int32_t moe_gate_aux_loss(const moe_config* cfg, const float* probs, const int32_t* topk_idx, float coef,
+                                     float* expert_fraction, float* mean_prob, float* loss, void* stream) {
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if (!expert_fraction || !mean_prob || !loss) return fail(MOE_ERR_INVALID_ARG, "moe_gate_aux_loss: NULL output");
+  if (cfg->T == 0) return fail(MOE_ERR_INVALID_ARG, "moe_gate_aux_loss: no tokens (the loss is a mean over tokens)");
+  if (!probs || !topk_idx) return fail(MOE_ERR_INVALID_ARG, "moe_gate_aux_loss: NULL input");
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(first_choice_fraction_kernel, dim3(cfg->E), dim3(256), 0, s, topk_idx, probs, expert_fraction, mean_prob, cfg->T,
+                     cfg->E, cfg->k);
+  hipLaunchKernelGGL(aux_loss_kernel, dim3(1), dim3(64), 0, s, (const float*)expert_fraction, (const float*)mean_prob, loss, cfg->E, coef);
+  return check_hip(hipGetLastError(), "moe_gate_aux_loss");
+}
+
 // ---- whole layer ------------------------------------------------------------------------------------
 namespace {
 
 struct BwLayout {
-  size_t probs, idx, w, d_w, d_z, xd, d_yd, d_xd, yd, partial, ffn, total;
+  size_t probs, idx, w, d_w, d_z, frac, xd, d_yd, d_xd, yd, partial, ffn, total;
   int slices;
 };
 
@@ -338,6 +397,7 @@ void bw_layout(const moe_config* cfg, BwLayout* L) {
   L->w = take(T * k * 4);
   L->d_w = take(T * k * 4);
   L->d_z = take(T * E * 4);
+  L->frac = take(E * 4);
   L->xd = take(R * d * 2);
   L->d_yd = take(R * d * 2);
   L->d_xd = take(R * d * 2);
@@ -374,7 +434,7 @@ extern "C" size_t moe_layer_backward_workspace_bytes(const moe_config* cfg) {
 
 extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                       const void* w2_input_major, const void* x, const void* d_out, const void* add_to_d_x,
-                                      const void* fwd_ws, size_t fwd_ws_bytes, void* d_x, float* d_w_router,
+                                      float aux_loss_coef, const void* fwd_ws, size_t fwd_ws_bytes, void* d_x, float* d_w_router,
                                       float* d_b_router, float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
                                       size_t ws_bytes, void* stream) {
   int32_t st = moe_config_check(cfg);
@@ -429,8 +489,14 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   if ((st = launch_gather_rows(cfg, x, a2r, b + L.xd, s)) != MOE_OK) return st;
   if ((st = ffn_backward_impl("moe_layer_backward", cfg, w, w1_input_major, w2_input_major, b + L.xd, h, b + L.d_yd, offsets,
                               b + L.d_xd, d_w1, d_b1, d_w2, d_b2, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
+  const float* frac = nullptr;
+  if (aux_loss_coef != 0.f) {
+    frac = (const float*)(b + L.frac);
+    hipLaunchKernelGGL(first_choice_fraction_kernel, dim3(cfg->E), dim3(256), 0, s, topk_idx, (const float*)nullptr, (float*)(b + L.frac),
+                       (float*)nullptr, cfg->T, cfg->E, cfg->k);
+  }
   hipLaunchKernelGGL(gate_dlogits_kernel, dim3((cfg->T + 3) / 4), dim3(256), 0, s, probs, topk_idx, topk_w, d_w, d_z, cfg->T, cfg->E,
-                     cfg->k, cfg->renormalize);
+                     cfg->k, cfg->renormalize, frac, aux_loss_coef * (float)cfg->E / (float)cfg->T);
   if (d_b_router) hipLaunchKernelGGL(gate_dbias_kernel, dim3(cfg->E), dim3(256), 0, s, d_z, d_b_router, cfg->T, cfg->E);
   if ((st = check_hip(hipGetLastError(), "gate backward launch")) != MOE_OK) return st;
   float* partial = (float*)(b + L.partial);

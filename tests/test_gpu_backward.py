@@ -171,3 +171,63 @@ def test_layer_backward(name, kw):
         print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
         assert errs["x"] < 1e-2
         assert all(v < 2e-2 for v in errs.values()), errs
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("gpt", dict(T=700, E=4, d_model=256, d_ff=512)),
+    ("skew", dict(T=900, E=8, d_model=256, d_ff=512)),                     # top-1 with a router bias: unbalanced routing
+    ("gpt", dict(T=333, E=96, d_model=256, d_ff=256, k=3, capacity_factor=0.0)),
+], ids=lambda v: str(v).replace(" ", ""))
+def test_aux_loss_value_and_gradient(name, kw):
+    """moe_gate_aux_loss against the oracle, and its gradient alone (d_out = 0) through moe_layer_backward."""
+    wl = WORKLOADS[name].scaled(**kw)
+    print(f"aux loss case {wl}", flush=True)
+    coef = 3.0
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    fw = O.layer_forward(L["x"], L, E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor, renormalize=wl.renormalize, act=wl.act)
+    # ---- the value
+    idx = torch.empty(wl.T, wl.k, dtype=torch.int32, device="cuda")
+    w = torch.empty(wl.T, wl.k, dtype=torch.float32, device="cuda")
+    probs = torch.empty(wl.T, wl.E, dtype=torch.float32, device="cuda")
+    M.moe_gate(cfg, x, W.tensors["w_router"], W.tensors.get("b_router"), idx, w, probs)
+    frac = torch.full((wl.E,), float("nan"), dtype=torch.float32, device="cuda")
+    pbar = torch.full((wl.E,), float("nan"), dtype=torch.float32, device="cuda")
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    M.moe_gate_aux_loss(cfg, probs, idx, coef, frac, pbar, loss)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), fw["topk_idx"])
+    counts = np.bincount(fw["topk_idx"][:, 0], minlength=wl.E)
+    assert np.array_equal(frac.cpu().numpy(), (counts.astype(np.float32) / np.float32(wl.T)))        # exact counts
+    assert np.allclose(pbar.cpu().numpy(), fw["probs"].mean(axis=0), rtol=1e-5, atol=1e-7)
+    want = B.aux_loss(fw["probs"], fw["topk_idx"], coef)
+    assert abs(loss.item() - want) <= 1e-5 * abs(want), (loss.item(), want)
+    # ---- the gradient: nothing flows back from the output, so every gradient is the auxiliary loss's
+    ws_f = alloc_ws(cfg)
+    out = torch.empty_like(x)
+    M.moe_layer_forward(cfg, W, x, None, out, ws_f)
+    G = torch.zeros_like(x)
+    ref = B.layer_backward(L["x"], L, np.zeros(L["x"].shape), E=wl.E, k=wl.k, capacity_factor=wl.capacity_factor,
+                           renormalize=wl.renormalize, act=wl.act, aux_coef=coef)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    d_x = torch.full_like(x, float("nan"))
+    d_wr = torch.full((wl.d_model, wl.E), float("nan"), **f32)
+    d_br = torch.full((wl.E,), float("nan"), **f32)
+    w1_im, w2_im, d_w1, d_b1, d_w2, d_b2 = expert_grad_buffers(wl, L)
+    ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        M.moe_layer_backward(cfg, W, w1_im, w2_im, x, G, None, ws_f, d_x, d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b,
+                             aux_loss_coef=coef)
+        torch.cuda.synchronize()
+        errs = {"x": rel_fro(to_np(d_x), ref["x"]), "w_router": rel_fro(d_wr.cpu().numpy(), ref["w_router"]),
+                "b_router": rel_fro(d_br.cpu().numpy(), ref["b_router"])}
+        print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        assert np.abs(ref["w_router"]).max() > 0
+        assert errs["x"] < 1e-2 and errs["w_router"] < 1e-4 and errs["b_router"] < 1e-4, errs    # bf16 d_x; fp32 sums
+        assert not d_w1.any() and not d_w2.any()
+    # without the coefficient the same call gives zeros: the term is the only source
+    M.moe_layer_backward(cfg, W, w1_im, w2_im, x, G, None, ws_f, d_x, d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b)
+    torch.cuda.synchronize()
+    assert not d_x.float().any() and not d_wr.any()
