@@ -316,9 +316,12 @@ int32_t moe_combine_backward(const moe_config* cfg, const void* d_out, const voi
  * [E,N1,N2] (overwritten; zero for an expert without rows); expert_offsets is read on
  * the device; max_rows_per_expert is the caller's bound of any expert's row count (only
  * used to check that an expert's operand block stays below 2 GiB).  N1 and N2 must be
- * multiples of 256 (MOE_ERR_UNSUPPORTED otherwise). */
+ * multiples of 256 (MOE_ERR_UNSUPPORTED otherwise).  a_column_sums (nullable; device float32
+ * [E,N1], overwritten): the sums over an expert's rows of a[r, n1], i.e. the bias gradient that
+ * goes with the weight gradient (db2_e with dW2_e, db1_e with dW1_e), from the same pass. */
 int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
-                         int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert, void* stream);
+                         float* a_column_sums, int32_t E, int32_t N1, int32_t N2,
+                         int64_t max_rows_per_expert, void* stream);
 
 /* Backward of moe_expert_ffn in MOE_BF16, given d_yd [R_max,d_model].  GELU experts:
  *   d_xd [R_max,d_model] (cfg.dtype), d_w1 [E,d_ff,d_model], d_b1 [E,d_ff], d_w2 [E,d_model,d_ff],

@@ -19,6 +19,7 @@ def main():
     ap.add_argument("--workload", default="gpt")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--bias", action="store_true", help="GELU experts with biases (and their gradients)")
     args = ap.parse_args()
     import torch
     import paper_2205_10034_amd as M
@@ -46,7 +47,11 @@ def main():
         w1_im = torch.empty(E, d, f, dtype=dt, device="cuda")
         M.moe_transpose_expert_weights(w1, w1_im)
         M.moe_transpose_expert_weights(w2, w2_im)
-        W = M.Weights({"w1": w1, "w2": w2, "w_router": router})
+        t = {"w1": w1, "w2": w2, "w_router": router}
+        if args.bias:
+            t["b1"] = (torch.randn(E, f, device="cuda") * 0.1).to(dt)
+            t["b2"] = (torch.randn(E, d, device="cuda") * 0.1).to(dt)
+        W = M.Weights(t)
     cfg = M.MoEConfig.from_workload(wl)
     ws_f = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
@@ -57,8 +62,12 @@ def main():
     def fwd():
         M.moe_layer_forward(cfg, W, x, x, out, ws_f)
 
+    with_b = args.bias and not sw
+    d_b1 = torch.empty(E, f, **f32) if with_b else None
+    d_b2 = torch.empty(E, d, **f32) if with_b else None
+
     def bwd():
-        M.moe_layer_backward(cfg, W, w1_im, w2_im, x, g, g, ws_f, d_x, d_wr, None, d_w1, None, d_w2, None, ws_b)
+        M.moe_layer_backward(cfg, W, w1_im, w2_im, x, g, g, ws_f, d_x, d_wr, None, d_w1, d_b1, d_w2, d_b2, ws_b)
 
     def timed(fn, n):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -79,7 +88,7 @@ def main():
     R = int(ws_f[lay["expert_offsets"]:lay["expert_offsets"] + 4 * (E + 1)].view(torch.int32)[-1].item())
     gemm = 2.0 * R * d * f
     res = {
-        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} {wl.act}, kept rows {R}",
+        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} {wl.act}{' with biases' if with_b else ''}, kept rows {R}",
         "forward_ms": t_f, "backward_ms": t_b, "forward_backward_ms": t_fb,
         "tokens_per_s_forward_backward": T / (t_fb * 1e-3),
         # products of 2 R d_model d_ff flops.  GELU: two forward; backward two input gradients, two weight gradients,

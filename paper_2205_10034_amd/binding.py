@@ -129,7 +129,7 @@ def lib() -> C.CDLL:
         L.moe_layer_backward.argtypes = ([C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 5 + [C.c_float, vp, C.c_size_t] +
                                          [vp] * 8 + [C.c_size_t, vp])
         L.moe_gate_aux_loss.argtypes = [C.POINTER(_Config), vp, vp, C.c_float, vp, vp, vp, vp]
-        L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
+        L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
         L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
@@ -311,11 +311,12 @@ def moe_gate_aux_loss(cfg, probs, topk_idx, coef: float, expert_fraction, mean_p
                                    _ptr(loss), _stream(stream)), "moe_gate_aux_loss")
 
 
-def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None):
-    """c[e] = a[rows of e]^T @ b[rows of e]; a [R,N1], b [R,N2] bf16, c [E,N1,N2] float32."""
+def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None, a_column_sums=None):
+    """c[e] = a[rows of e]^T @ b[rows of e]; a [R,N1], b [R,N2] bf16, c [E,N1,N2] float32; a_column_sums [E,N1]
+    float32 (optional): sum over the rows of e of a."""
     E, N1, N2 = c.shape
-    _check(lib().moe_expert_wgrad(_ptr(a), _ptr(b), _ptr(expert_offsets), _ptr(c), E, N1, N2, max_rows_per_expert,
-                                  _stream(stream)), "moe_expert_wgrad")
+    _check(lib().moe_expert_wgrad(_ptr(a), _ptr(b), _ptr(expert_offsets), _ptr(c), _ptr(a_column_sums), E, N1, N2,
+                                  max_rows_per_expert, _stream(stream)), "moe_expert_wgrad")
 
 
 class StageTimer:

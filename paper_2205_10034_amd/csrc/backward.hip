@@ -7,7 +7,8 @@
 // (the contraction index of the transposed product is contiguous there), weight gradients contract over an
 // expert's rows (grouped_wgrad_bf16.hip).  The pre-activations are recomputed rather than stored by the
 // forward pass, by a product whose epilogue applies the activation's derivative to d_h; they never reach
-// memory.  What is still separate from the GEMMs: the bias gradients (column sums per expert).
+// memory; the bias gradients (column sums per expert of d_yd and d_u) are by-products of the weight-gradient
+// products that read those operands anyway.
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -19,7 +20,7 @@ int32_t launch_gemm1_dgelu_bf16(const moe_config*, const void*, const void*, con
                                 int32_t*, hipStream_t);
 int32_t launch_gemm1_dswiglu_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, const void*, void*,
                                   int32_t*, hipStream_t);
-int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, int, int, int, int64_t, hipStream_t);
+int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, float*, int, int, int, int64_t, hipStream_t);
 
 namespace {
 
@@ -30,33 +31,6 @@ __device__ __forceinline__ uint32_t to_bf16(float f) {  // round to nearest even
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-// out[e, n] = sum over the rows r of expert e of d[r, n] (fp32).  One workgroup per (512-column block, expert):
-// a lane owns 8 columns, the four wavefronts take every fourth row and meet in LDS (fixed order: results do
-// not depend on scheduling).
-__global__ __launch_bounds__(256) void bias_grad_kernel(const uint4* __restrict__ d, const int32_t* __restrict__ offsets,
-                                                        float* __restrict__ out, int N) {
-  __shared__ float part[4][512];
-  const int e = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = blockIdx.x * 512 + lane * 8;
-  const int row_vec = N / 8;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (col < N) {
-    for (int r = offsets[e] + wave; r < offsets[e + 1]; r += 4) {
-      const uint4 v = d[(size_t)r * row_vec + col / 8];
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { acc[2 * q] += bf16_lo(w[q]); acc[2 * q + 1] += bf16_hi(w[q]); }
-    }
-  }
-#pragma unroll
-  for (int q = 0; q < 8; ++q) part[wave][lane * 8 + q] = acc[q];
-  __syncthreads();
-  for (int c = threadIdx.x; c < 512; c += 256)
-    if (blockIdx.x * 512 + c < N)
-      out[(size_t)e * N + blockIdx.x * 512 + c] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
-}
-
-// ---- gate ----------------------------------------------------------------------------------------
 // Load-balancing auxiliary loss (the remedy for expert imbalance that the paper's Section 1 points to, in the
 // form of the work cited there): L = coef * E * sum_e f_e * Pbar_e, f_e = fraction of the tokens whose first
 // choice is expert e, Pbar_e = mean probability of e.  One workgroup per expert; fixed reduction order.
@@ -334,32 +308,26 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   // every product draws its tiles from eight zeroed counters of its own
   hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, ctr, 24);
   if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
-  // weight gradients that need nothing recomputed: dW2_e = d_yd_e^T h_e, db2_e = column sums of d_yd_e
-  if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, E, d, f, per_expert, s)) != MOE_OK) return st;
+  // weight gradients that need nothing recomputed: dW2_e = d_yd_e^T h_e, with db2_e = column sums of d_yd_e on the side
+  if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, (!sw && w->b2) ? d_b2 : nullptr, E, d, f,
+                              per_expert, s)) != MOE_OK) return st;
   if (sw) {
     // d_h = d_yd W_down; [d_g | d_u] from d_h and the recomputed gate and up products; the gradient of the
     // stacked [W_gate; W_up] in one product, d_xd in one product over the 2 d_ff columns of [d_g | d_u]
     void* dgu = base + rf;
     if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
     if ((st = launch_gemm1_dswiglu_bf16(cfg, xd, w->w_gate_proj, w->w_up, expert_offsets, dh, dgu, ctr + 8, s)) != MOE_OK) return st;
-    if ((st = launch_wgrad_bf16((const uint16_t*)dgu, (const uint16_t*)xd, expert_offsets, d_w1, E, 2 * f, d, per_expert, s)) != MOE_OK) return st;
+    if ((st = launch_wgrad_bf16((const uint16_t*)dgu, (const uint16_t*)xd, expert_offsets, d_w1, nullptr, E, 2 * f, d, per_expert, s)) != MOE_OK) return st;
     return launch_grouped_matmul_bf16(cfg, dgu, w1_input_major, nullptr, expert_offsets, d_xd, d, 2 * f, ctr + 16, s);
-  }
-  if (w->b2) {
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((d + 511) / 512, E), dim3(256), 0, s, (const uint4*)d_yd, expert_offsets, d_b2, d);
-    if ((st = check_hip(hipGetLastError(), "bias gradient launch")) != MOE_OK) return st;
   }
   // d_h = d_yd W2, then d_u = d_h * gelu'(u) in place, u = xd W1^T + b1 being recomputed by the product whose
   // epilogue applies the derivative: the pre-activations never reach memory.  (Without any row every product
   // returns at once and the gradients come out as zeros.)
   if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
   if ((st = launch_gemm1_dgelu_bf16(cfg, xd, w->w1, w->b1, expert_offsets, dh, dh, ctr + 8, s)) != MOE_OK) return st;
-  // dW1_e = d_u_e^T xd_e, db1_e = column sums of d_u_e, d_xd = d_u W1
-  if ((st = launch_wgrad_bf16((const uint16_t*)dh, (const uint16_t*)xd, expert_offsets, d_w1, E, f, d, per_expert, s)) != MOE_OK) return st;
-  if (w->b1) {
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((f + 511) / 512, E), dim3(256), 0, s, (const uint4*)dh, expert_offsets, d_b1, f);
-    if ((st = check_hip(hipGetLastError(), "bias gradient launch")) != MOE_OK) return st;
-  }
+  // dW1_e = d_u_e^T xd_e (db1_e = column sums of d_u_e on the side), d_xd = d_u W1
+  if ((st = launch_wgrad_bf16((const uint16_t*)dh, (const uint16_t*)xd, expert_offsets, d_w1, w->b1 ? d_b1 : nullptr, E, f, d, per_expert,
+                              s)) != MOE_OK) return st;
   return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr + 16, s);
 }
 

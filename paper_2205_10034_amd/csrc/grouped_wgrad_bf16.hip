@@ -19,6 +19,10 @@
 // the two 16-lane groups of a 32-lane pass hit all 64 banks once.
 // The first MFMA operand is the n2 side, so that a lane ends up with runs of four consecutive n2 of one
 // n1: 16-byte fp32 stores.
+// Column sums of A per expert (the bias gradients: db2_e = sum_r d_y[r, :], db1_e = sum_r d_u[r, :]) come from
+// the same fragments: the workgroups of the first n2 tile multiply one n1 fragment per wavefront and K-step
+// by a fragment of ones (one more MFMA on top of eight), which leaves the column's sum in every element of
+// that accumulator.  No extra pass over A.
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -44,11 +48,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t wg_rsrc(const void* base, uint
 }
 #endif
 
+template <bool COLSUM>
 __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
     const uint16_t* __restrict__ a,       // [R, N1]
     const uint16_t* __restrict__ b,       // [R, N2]
     const int32_t* __restrict__ offsets,  // [E+1]
     float* __restrict__ c,                // [E, N1, N2]
+    float* __restrict__ a_colsum,         // COLSUM: [E, N1]
     int N1, int N2) {
 #if defined(__HIP_DEVICE_COMPILE__)
   // one array per stage: the compiler can then tell the stage being filled from the one being read
@@ -122,6 +128,15 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // column sums: wavefront (w1, w2) of the first n2 tile's workgroups sums the n1 block i = w2 of its 128 columns
+  const bool do_colsum = COLSUM && blockIdx.x == 0;
+  f32x16 acc_sum;
+  bf16x8 ones;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc_sum[v] = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) ones[v] = (__bf16)1.0f;
+
   auto compute = [&](const unsigned char* stage) {
 #pragma unroll
     for (int ks = 0; ks < WG_KS / 16; ++ks) {
@@ -134,6 +149,12 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[j], f1[i], acc[i][j], 0, 0, 0);
+      if constexpr (COLSUM) {
+        if (do_colsum) {
+          const bf16x8 mine = w2 == 0 ? f1[0] : w2 == 1 ? f1[1] : w2 == 2 ? f1[2] : f1[3];
+          acc_sum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, mine, acc_sum, 0, 0, 0);
+        }
+      }
     }
   };
 
@@ -180,19 +201,25 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
         *reinterpret_cast<f32x4*>(crow + 32 * j + 8 * q) = v;
       }
   }
+  if constexpr (COLSUM) {
+    // every element of acc_sum in lane l (and l + 32) is the sum of column 128*w1 + 32*w2 + (l & 31)
+    if (do_colsum && lane < 32) a_colsum[(size_t)e * N1 + t1 + 128 * w1 + 32 * w2 + lane] = acc_sum[0];
+  }
 #endif
 }
 
 }  // namespace
 
-int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* offsets, float* c, int E, int N1, int N2,
-                          int64_t max_rows_per_expert, hipStream_t s) {
+int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* offsets, float* c, float* a_colsum, int E, int N1,
+                          int N2, int64_t max_rows_per_expert, hipStream_t s) {
   if (N1 % WG_N || N2 % WG_N) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: N1=%d and N2=%d must be multiples of %d", N1, N2, WG_N);
   const int64_t widest = N1 > N2 ? N1 : N2;
   if ((max_rows_per_expert + WG_KS) * widest * 2 >= ((int64_t)1 << 31))
     return fail(MOE_ERR_UNSUPPORTED, "weight gradient: an expert's operand block exceeds 2 GiB");
   if (N2 / WG_N > 65535 || N1 / WG_N > 65535 || E > 65535) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: too many tiles");
-  hipLaunchKernelGGL(grouped_wgrad_kernel, dim3(N2 / WG_N, N1 / WG_N, E), dim3(WG_WAVES * 64), 0, s, a, b, offsets, c, N1, N2);
+  const dim3 grid(N2 / WG_N, N1 / WG_N, E), block(WG_WAVES * 64);
+  if (a_colsum) hipLaunchKernelGGL(grouped_wgrad_kernel<true>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2);
+  else hipLaunchKernelGGL(grouped_wgrad_kernel<false>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2);
   return check_hip(hipGetLastError(), "weight gradient launch");
 }
 
@@ -200,11 +227,12 @@ int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* o
 
 using namespace moesys;
 
-extern "C" int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c, int32_t E,
-                                    int32_t N1, int32_t N2, int64_t max_rows_per_expert, void* stream) {
+extern "C" int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
+                                    float* a_column_sums, int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert,
+                                    void* stream) {
   if (!a || !b || !expert_offsets || !c) return fail(MOE_ERR_INVALID_ARG, "moe_expert_wgrad: NULL argument");
   if (E < 1 || E > MOE_MAX_EXPERTS || N1 < 1 || N2 < 1 || max_rows_per_expert < 0)
     return fail(MOE_ERR_INVALID_ARG, "moe_expert_wgrad: bad shape");
-  return launch_wgrad_bf16((const uint16_t*)a, (const uint16_t*)b, expert_offsets, c, E, N1, N2, max_rows_per_expert,
-                           (hipStream_t)stream);
+  return launch_wgrad_bf16((const uint16_t*)a, (const uint16_t*)b, expert_offsets, c, a_column_sums, E, N1, N2,
+                           max_rows_per_expert, (hipStream_t)stream);
 }

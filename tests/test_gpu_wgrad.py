@@ -30,12 +30,23 @@ def test_wgrad_matches_oracle(rows, N1, N2):
     ref = B.expert_wgrad(a.float().cpu().numpy()[:R], b.float().cpu().numpy()[:R], offsets_np)
     c = torch.full((E, N1, N2), float("nan"), dtype=torch.float32, device="cuda")
     offsets = torch.from_numpy(offsets_np).cuda()
+    sums = torch.full((E, N1), float("nan"), dtype=torch.float32, device="cuda")
+    a_np = a.float().cpu().numpy().astype(np.float64)
     for rep in range(2):
         c.fill_(float("nan"))
-        M.moe_expert_wgrad(a, b, offsets, c, max(rows + [1]))
+        sums.fill_(float("nan"))
+        # the second call also asks for the column sums of a (the bias gradient that goes with the product)
+        M.moe_expert_wgrad(a, b, offsets, c, max(rows + [1]), a_column_sums=sums if rep else None)
         torch.cuda.synchronize()
         got = c.cpu().numpy()
         assert np.isfinite(got).all()
+        if rep:
+            got_sums = sums.cpu().numpy()
+            for e in range(E):
+                want = a_np[offsets_np[e]:offsets_np[e + 1]].sum(axis=0)         # the definition: a plain column sum
+                assert np.allclose(got_sums[e], want, rtol=1e-5, atol=1e-5 * np.sqrt(max(rows[e], 1))), f"column sums, expert {e}"
+        else:
+            assert torch.isnan(sums).all()                                      # not asked for: not touched
         for e in range(E):
             if rows[e] == 0:
                 assert not got[e].any()
