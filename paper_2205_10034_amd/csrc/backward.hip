@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict
   if (threadIdx.x == 0) out[e] = part[0];
 }
 
-constexpr int DWG_SLICE = 64;  // tokens per partial sum of the router's weight gradient (many slices: the kernel's
+constexpr int DWG_SLICE = 64;  // (a multiple of 16) tokens per partial sum of the router's weight gradient (many slices: the kernel's
                                // parallelism is slices x column blocks)
 constexpr int GB_TOK = 16;   // tokens per workgroup of dx_kernel (their loads are issued together)
 constexpr int GB_MAXK = MOE_MAX_TOPK;  // choices per token
@@ -222,15 +222,20 @@ __global__ __launch_bounds__(256) void dwg_partial_kernel(const uint32_t* __rest
   float a0[EC], a1[EC];
 #pragma unroll
   for (int e = 0; e < EC; ++e) a0[e] = a1[e] = 0.f;
-  const int n_tok = min(T - ts, slice_tokens);
-#pragma unroll 4
-  for (int u = 0; u < n_tok; ++u) {
-    const uint32_t v = x[(size_t)(ts + u) * (d / 2) + i2];
-    const float x0 = bf16_lo(v), x1 = bf16_hi(v);
+  // the slice's tokens 16 at a time, their loads issued together (a workgroup per CU is all there is to hide
+  // the latency of one load after another); tokens past the end re-read the last one against zero rows of s_dz
+  for (int u0 = 0; u0 < slice_tokens; u0 += 16) {
+    uint32_t v[16];
 #pragma unroll
-    for (int e = 0; e < EC; ++e) {
-      a0[e] = fmaf(x0, s_dz[u][e], a0[e]);
-      a1[e] = fmaf(x1, s_dz[u][e], a1[e]);
+    for (int q = 0; q < 16; ++q) v[q] = x[(size_t)min(ts + u0 + q, T - 1) * (d / 2) + i2];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const float x0 = bf16_lo(v[q]), x1 = bf16_hi(v[q]);
+#pragma unroll
+      for (int e = 0; e < EC; ++e) {
+        a0[e] = fmaf(x0, s_dz[u0 + q][e], a0[e]);
+        a1[e] = fmaf(x1, s_dz[u0 + q][e], a1[e]);
+      }
     }
   }
   float* p0 = partial + ((size_t)blockIdx.y * d + 2 * i2) * E + e0;
