@@ -231,3 +231,51 @@ def test_aux_loss_value_and_gradient(name, kw):
     M.moe_layer_backward(cfg, W, w1_im, w2_im, x, G, None, ws_f, d_x, d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b)
     torch.cuda.synchronize()
     assert not d_x.float().any() and not d_wr.any()
+
+
+def test_layer_backward_of_an_empty_batch_gives_zero_parameter_gradients():
+    wl = WORKLOADS["gpt"].scaled(T=0, E=4, d_model=256, d_ff=256)
+    L = make_layer(WORKLOADS["gpt"].scaled(T=8, E=4, d_model=256, d_ff=256), with_bias=True)     # parameters only
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = torch.empty(0, wl.d_model, dtype=torch.bfloat16, device="cuda")
+    ws_f = alloc_ws(cfg)
+    M.moe_layer_forward(cfg, W, x, None, torch.empty_like(x), ws_f)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    d_wr = torch.full((wl.d_model, wl.E), float("nan"), **f32)
+    d_br = torch.full((wl.E,), float("nan"), **f32)
+    w1_im, w2_im, d_w1, d_b1, d_w2, d_b2 = expert_grad_buffers(wl, L)
+    ws_b = torch.empty(max(M.moe_layer_backward_workspace_bytes(cfg), 256), dtype=torch.uint8, device="cuda")
+    M.moe_layer_backward(cfg, W, w1_im, w2_im, x, x, None, ws_f, torch.empty_like(x), d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b,
+                         aux_loss_coef=0.5)
+    torch.cuda.synchronize()
+    for name, g in (("w_router", d_wr), ("b_router", d_br), ("w1", d_w1), ("b1", d_b1), ("w2", d_w2), ("b2", d_b2)):
+        assert not g.any(), name                              # (zeros, not the NaNs the buffers held)
+
+
+def test_backward_refuses_what_it_cannot_do():
+    wl = WORKLOADS["tiny"].scaled(T=64)                       # float32 layer: the backward pass is bf16 only
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    ws_f = alloc_ws(cfg)
+    buf = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    with pytest.raises(M.MoEError) as e:
+        M.moe_layer_backward(cfg, W, buf, buf, x, x, None, ws_f, x, buf, buf, buf, buf, buf, buf, buf)
+    assert "bf16" in str(e.value)
+    # a workspace that is too small is refused before anything is launched
+    wl = WORKLOADS["gpt"].scaled(T=64, E=4, d_model=256, d_ff=256)
+    L = make_layer(wl, with_bias=True)
+    cfg = M.MoEConfig.from_workload(wl)
+    W = upload_weights(L, wl.dtype)
+    x = to_dev(L["x"], wl.dtype)
+    ws_f = alloc_ws(cfg)
+    M.moe_layer_forward(cfg, W, x, None, torch.empty_like(x), ws_f)
+    w1_im, w2_im, d_w1, d_b1, d_w2, d_b2 = expert_grad_buffers(wl, L)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(M.MoEError) as e:
+        M.moe_layer_backward(cfg, W, w1_im, w2_im, x, x, None, ws_f, torch.empty_like(x), buf, buf, d_w1, d_b1, d_w2, d_b2, small)
+    assert "workspace" in str(e.value)
+    torch.cuda.synchronize()
+    assert torch.isnan(d_w1).all()                            # untouched
