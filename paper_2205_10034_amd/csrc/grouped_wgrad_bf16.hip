@@ -19,6 +19,11 @@
 // the two 16-lane groups of a 32-lane pass hit all 64 banks once.
 // The first MFMA operand is the n2 side, so that a lane ends up with runs of four consecutive n2 of one
 // n1: 16-byte fp32 stores.
+// Tile order.  The 8 XCDs have an L2 each, and the hardware deals workgroups out to them round robin.  A tile
+// streams a 256-column slab of A and one of B; tiles of one expert with the same n1 (n2) tile share the A (B)
+// slab.  Workgroups are therefore numbered so that the 32 that start together on one XCD are a block of
+// BY x BX tiles of ONE expert (BX = min(8, n2 tiles), BY = 32 / BX): BY + BX slabs for 32 tiles through that L2
+// instead of the 6 for 8 that the plain (n2, n1, expert) grid order gives at 16 x 4 tiles per expert.
 // Column sums of A per expert (the bias gradients: db2_e = sum_r d_y[r, :], db1_e = sum_r d_u[r, :]) come from
 // the same fragments: the workgroups of the first n2 tile multiply one n1 fragment per wavefront and K-step
 // by a fragment of ones (one more MFMA on top of eight), which leaves the column's sum in every element of
@@ -55,7 +60,7 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
     const int32_t* __restrict__ offsets,  // [E+1]
     float* __restrict__ c,                // [E, N1, N2]
     float* __restrict__ a_colsum,         // COLSUM: [E, N1]
-    int N1, int N2) {
+    int N1, int N2, int E, int BY, int BX) {
 #if defined(__HIP_DEVICE_COMPILE__)
   // one array per stage: the compiler can then tell the stage being filled from the one being read
   __shared__ __attribute__((aligned(1024))) unsigned char s0[2 * WG_CHUNK];
@@ -63,9 +68,17 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
   __shared__ __attribute__((aligned(1024))) unsigned char s2[2 * WG_CHUNK];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int w1 = wave >> 2, w2 = wave & 3;  // this wavefront: n1 columns [128*w1, +128), n2 columns [64*w2, +64)
-  const int e = blockIdx.z;
+  // workgroup -> (expert, n1 tile, n2 tile): see "Tile order" above
+  const int n1t = N1 / WG_N, n2t = N2 / WG_N;
+  const int nby = (n1t + BY - 1) / BY, nbx = (n2t + BX - 1) / BX;
+  const int slot = blockIdx.x / 8;                            // position in this XCD's sequence of workgroups
+  const int blk = (slot / (BY * BX)) * 8 + (int)(blockIdx.x % 8);  // blocks are dealt out to the XCDs in turn
+  const int in_blk = slot % (BY * BX);
+  const int e = blk / (nby * nbx);
+  const int ty = ((blk / nbx) % nby) * BY + in_blk / BX, tx = (blk % nbx) * BX + in_blk % BX;
+  if (e >= E || ty >= n1t || tx >= n2t) return;                // (wave-uniform: padding of the grid and of partial blocks)
   const int row0 = offsets[e], rows = offsets[e + 1] - row0;
-  const int t1 = blockIdx.y * WG_N, t2 = blockIdx.x * WG_N;
+  const int t1 = ty * WG_N, t2 = tx * WG_N;
   float* cout = c + ((size_t)e * N1 + t1) * N2 + t2;
   const int KT = (rows + WG_KS - 1) / WG_KS;
 
@@ -129,7 +142,7 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // column sums: wavefront (w1, w2) of the first n2 tile's workgroups sums the n1 block i = w2 of its 128 columns
-  const bool do_colsum = COLSUM && blockIdx.x == 0;
+  const bool do_colsum = COLSUM && tx == 0;
   f32x16 acc_sum;
   bf16x8 ones;
 #pragma unroll
@@ -216,10 +229,14 @@ int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* o
   const int64_t widest = N1 > N2 ? N1 : N2;
   if ((max_rows_per_expert + WG_KS) * widest * 2 >= ((int64_t)1 << 31))
     return fail(MOE_ERR_UNSUPPORTED, "weight gradient: an expert's operand block exceeds 2 GiB");
-  if (N2 / WG_N > 65535 || N1 / WG_N > 65535 || E > 65535) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: too many tiles");
-  const dim3 grid(N2 / WG_N, N1 / WG_N, E), block(WG_WAVES * 64);
-  if (a_colsum) hipLaunchKernelGGL(grouped_wgrad_kernel<true>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2);
-  else hipLaunchKernelGGL(grouped_wgrad_kernel<false>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2);
+  const int n1t = N1 / WG_N, n2t = N2 / WG_N;
+  const int BX = n2t < 8 ? n2t : 8, BY = 32 / BX;  // (BX in 1..8, so BY * BX is 32, or 28, 30 for BX = 7, 5, 6, 3)
+  const int64_t blocks = (int64_t)E * ((n1t + BY - 1) / BY) * ((n2t + BX - 1) / BX);
+  const int64_t wgs = ((blocks + 7) / 8) * 8 * BY * BX;
+  if (wgs > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: too many tiles");
+  const dim3 grid((unsigned)wgs), block(WG_WAVES * 64);
+  if (a_colsum) hipLaunchKernelGGL(grouped_wgrad_kernel<true>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2, E, BY, BX);
+  else hipLaunchKernelGGL(grouped_wgrad_kernel<false>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2, E, BY, BX);
   return check_hip(hipGetLastError(), "weight gradient launch");
 }
 
