@@ -1,11 +1,13 @@
 /*
- * moesys.h - C ABI of the MI355X (gfx950) MoE-layer forward library.
+ * moesys.h - C ABI of the MI355X (gfx950) MoE-layer library.
  *
  * The library implements the data-parallel hot path that the MoESys paper's
  * training and inference system exists to keep fed: the forward pass of a
  * sparsely-gated Mixture-of-Experts layer on one GPU (top-k softmax gate,
- * capacity-bounded dispatch, per-expert FFN, gate-weighted combine), and the
- * paper's ring memory offloading of expert parameters (Section 3.3.2).
+ * capacity-bounded dispatch, per-expert FFN, gate-weighted combine), the
+ * paper's ring memory offloading of expert parameters (Section 3.3.2), an
+ * expert-granular pool under its frequency-based scheduling (Algorithm 2),
+ * and the layer's backward pass (the paper is a training system, Section 3.2).
  *
  * General rules of the boundary
  *  - Every pointer marked "device" is caller-owned HBM; "host" is caller-owned
@@ -43,7 +45,7 @@ typedef enum {
   MOE_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for         */
   MOE_ERR_WORKSPACE = 3,   /* workspace pointer null/misaligned or too small     */
   MOE_ERR_HIP = 4,         /* a HIP runtime call failed (see moe_last_error)     */
-  MOE_ERR_STATE = 5        /* ring used out of order                             */
+  MOE_ERR_STATE = 5        /* ring used out of order; expert cache without a free slot */
 } moe_status;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
