@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "libmoesys_hip.so")
 PROF_LIB = os.path.join(HERE, "libmoesys_hip_prof.so")
 
 SOURCES = ["api.cpp", "gate.hip", "dispatch.hip", "combine.hip", "ffn.hip", "grouped_gemm_bf16.hip",
-           "grouped_wgrad_bf16.hip", "backward.hip", "layer.hip", "ring.cpp", "expert_cache.cpp"]
+           "grouped_wgrad_bf16.hip", "expert_gemv_bf16.hip", "backward.hip", "layer.hip", "ring.cpp", "expert_cache.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

@@ -941,10 +941,23 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
 
 }  // namespace
 
+// steps of very few tokens (no expert has more than a handful of rows) take the matrix-vector kernels
+bool expert_gemv_applies(const moe_config* cfg, int N, int K);
+int32_t launch_expert_gemv_bf16(int epi, const moe_config* cfg, const void* act, const void* wa, const void* wb, const void* bias,
+                                const int32_t* offsets, void* out, const int32_t* row_map, const float* gate_w,
+                                const void* residual, const int64_t* eoff, int N, int K, hipStream_t s);
+
 // row_map (nullable): row_to_assign; the token rows are then gathered from x[T, d_model] instead of read
 // from a dispatched copy.
 int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const void* xd, const int32_t* offsets,
                           void* h, const int32_t* row_map, int32_t* tile_counters, hipStream_t s) {
+  if (expert_gemv_applies(cfg, cfg->d_ff, cfg->d_model)) {
+    if (cfg->act == MOE_ACT_SWIGLU)
+      return launch_expert_gemv_bf16(EPI_SWIGLU, cfg, xd, w->w_gate_proj, w->w_up, nullptr, offsets, h, row_map, nullptr, nullptr,
+                                     w->expert_elem_offset, cfg->d_ff, cfg->d_model, s);
+    return launch_expert_gemv_bf16(EPI_GELU, cfg, xd, w->w1, nullptr, w->b1, offsets, h, row_map, nullptr, nullptr,
+                                   w->expert_elem_offset, cfg->d_ff, cfg->d_model, s);
+  }
   // the first GEMM draws from counters [0,8) and clears [8,16) for the second
   if (cfg->act == MOE_ACT_SWIGLU)
     return gemm_any<EPI_SWIGLU>(
@@ -958,6 +971,9 @@ int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const voi
 int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const void* h, const int32_t* offsets,
                           void* yd, int32_t* tile_counters, hipStream_t s) {
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
+  if (expert_gemv_applies(cfg, cfg->d_model, cfg->d_ff))
+    return launch_expert_gemv_bf16(EPI_BIAS, cfg, h, sw ? w->w_down : w->w2, nullptr, sw ? nullptr : w->b2, offsets, yd, nullptr,
+                                   nullptr, nullptr, w->expert_elem_offset, cfg->d_model, cfg->d_ff, s);
   return gemm_any<EPI_BIAS>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
       (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, nullptr,
@@ -970,6 +986,9 @@ int32_t launch_gemm2_combine_bf16(const moe_config* cfg, const moe_weights* w, c
                                   const int32_t* row_to_assign, const float* topk_w, const void* residual, void* out,
                                   int32_t* tile_counters, hipStream_t s) {
   const bool sw = cfg->act == MOE_ACT_SWIGLU;
+  if (expert_gemv_applies(cfg, cfg->d_model, cfg->d_ff))
+    return launch_expert_gemv_bf16(EPI_COMBINE, cfg, h, sw ? w->w_down : w->w2, nullptr, sw ? nullptr : w->b2, offsets, out,
+                                   row_to_assign, topk_w, residual, w->expert_elem_offset, cfg->d_model, cfg->d_ff, s);
   return gemm_any<EPI_COMBINE>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
       (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)out, row_to_assign, tile_counters + NUM_XCD, nullptr,

@@ -233,6 +233,20 @@ LAYER_CASES = [
     ("gpt", dict(T=1300, E=8, k=1, capacity_factor=0.6)),          # about half the tokens dropped
     ("large", dict(T=1111, d_model=512, d_ff=1024, E=4, k=1)),     # SwiGLU
     ("ring", dict(T=1500, d_model=320, d_ff=512, E=32, k=1, capacity_factor=1.0)),   # narrow output tiles
+    # steps of very few tokens (at most 8 assignments): the matrix-vector kernels
+    ("ring", dict(T=1, d_model=256, d_ff=512, E=64)),
+    ("ring", dict(T=4, d_model=512, d_ff=1024, E=64)),
+    ("gpt", dict(T=3, E=8, d_model=320, d_ff=512, capacity_factor=0.0)),       # K no multiple of 512: ragged last K block
+    ("gpt", dict(T=4, E=2, d_model=256, d_ff=512, capacity_factor=0.0)),       # several rows per expert
+    ("gpt", dict(T=4, E=2, d_model=256, d_ff=512, capacity_factor=0.5)),       # ... with drops
+    ("skew", dict(T=7, d_model=256, d_ff=512)),                                # top-1: combine in the second product
+    ("gpt", dict(T=8, E=4, d_model=256, d_ff=256, k=1, capacity_factor=0.5)),  # top-1 with dropped tokens
+    ("large", dict(T=2, d_model=512, d_ff=1024, E=4)),                         # SwiGLU
+    ("large", dict(T=5, d_model=512, d_ff=1024, E=4, k=1)),
+    ("ring", dict(T=8, d_model=256, d_ff=512, E=64)),                          # 9 to 16 assignments: the 4 x 16 shape
+    ("gpt", dict(T=6, E=2, d_model=256, d_ff=512, capacity_factor=0.0)),       # up to 12 rows in one expert
+    ("skew", dict(T=13, d_model=256, d_ff=512)),
+    ("large", dict(T=7, d_model=512, d_ff=1024, E=4)),
 ]
 
 
