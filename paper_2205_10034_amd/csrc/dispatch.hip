@@ -67,13 +67,16 @@ __global__ __launch_bounds__(MOE_MAX_EXPERTS) void dispatch_scan_kernel(int32_t*
   }
 }
 
-// prefixed = true: block_hist holds exclusive prefixes and a totals row (scan kernel ran);
-// prefixed = false: block_hist holds raw histograms and every block sums what it needs itself.
+// prefixed = 1: block_hist holds exclusive prefixes and a totals row (scan kernel ran);
+// prefixed = 0: block_hist holds raw histograms and every block sums what it needs itself;
+// prefixed = 2: a single block holds every assignment (few tokens): no histogram was made, the block counts its
+// own assignments while ranking them, and clears clear8 (nullable) as the count kernel would have.
 __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __restrict__ topk_idx, int T, int k,
                                                              int E, int C, const int32_t* __restrict__ block_hist,
                                                              int nblocks, int prefixed,
                                                              int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                             int32_t* __restrict__ a2r, int32_t* __restrict__ r2a) {
+                                                             int32_t* __restrict__ a2r, int32_t* __restrict__ r2a,
+                                                             int32_t* __restrict__ clear8) {
   constexpr int NW = BT / 64;
   __shared__ int base_s[MOE_MAX_EXPERTS];        // slots of this expert handed out by earlier blocks
   __shared__ int total_s[MOE_MAX_EXPERTS];       // assignments per expert before capacity
@@ -81,13 +84,13 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
   __shared__ int off_s[MOE_MAX_EXPERTS + 1];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int e = threadIdx.x; e < E; e += BT) {
-    base_s[e] = prefixed ? block_hist[(size_t)blockIdx.x * E + e] : 0;
-    total_s[e] = prefixed ? block_hist[(size_t)nblocks * E + e] : 0;
+    base_s[e] = prefixed == 1 ? block_hist[(size_t)blockIdx.x * E + e] : 0;
+    total_s[e] = prefixed == 1 ? block_hist[(size_t)nblocks * E + e] : 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) wave_cnt[w][e] = 0;
   }
   __syncthreads();
-  if (!prefixed) {
+  if (prefixed == 0) {
     // integer adds: the sums do not depend on the order the LDS atomics land in
     const int n = nblocks * E;
     for (int i = threadIdx.x; i < n; i += BT) {
@@ -100,14 +103,17 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    int off = 0;
-    for (int e = 0; e < E; ++e) {
-      off_s[e] = off;
-      off += min(total_s[e], C);
+  auto prefix_offsets = [&]() {
+    if (threadIdx.x == 0) {
+      int off = 0;
+      for (int e = 0; e < E; ++e) {
+        off_s[e] = off;
+        off += min(total_s[e], C);
+      }
+      off_s[E] = off;
     }
-    off_s[E] = off;
-  }
+  };
+  if (prefixed != 2) prefix_offsets();
   const int a = blockIdx.x * DISPATCH_BLOCK + threadIdx.x;
   const int e_in = a < T * k ? expert_of(topk_idx, a, T, k) : -1;
   const bool valid = (unsigned)e_in < (unsigned)E;
@@ -126,6 +132,18 @@ __global__ __launch_bounds__(BT) void dispatch_assign_kernel(const int32_t* __re
     todo &= ~same;
   }
   __syncthreads();
+  if (prefixed == 2) {  // the totals are this block's own counts
+    for (int e2 = threadIdx.x; e2 < E; e2 += BT) {
+      int n = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) n += wave_cnt[w][e2];
+      total_s[e2] = n;
+    }
+    __syncthreads();
+    prefix_offsets();
+    __syncthreads();
+    if (clear8 && threadIdx.x < 8) clear8[threadIdx.x] = 0;
+  }
   if (blockIdx.x == 0)
     for (int i = threadIdx.x; i <= E; i += BT) {
       offsets[i] = off_s[i];
@@ -192,12 +210,17 @@ int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* top
     hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, counts, offsets, clear8);
     return check_hip(hipGetLastError(), "dispatch launch");
   }
-  hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist, clear8);
-  const int prefixed = nblocks > FUSED_SCAN_MAX_BLOCKS;
-  if (prefixed)
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E);
-  hipLaunchKernelGGL(dispatch_assign_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist, nblocks,
-                     prefixed, counts, offsets, a2r, r2a);
+  if (nblocks == 1) {  // few tokens: one kernel counts, ranks and assigns
+    hipLaunchKernelGGL(dispatch_assign_kernel, dim3(1), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist, 1, 2, counts, offsets, a2r,
+                       r2a, clear8);
+  } else {
+    hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, block_hist, clear8);
+    const int prefixed = nblocks > FUSED_SCAN_MAX_BLOCKS;
+    if (prefixed)
+      hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s, block_hist, nblocks, E);
+    hipLaunchKernelGGL(dispatch_assign_kernel, dim3(nblocks), dim3(BT), 0, s, topk_idx, T, k, E, C, block_hist, nblocks,
+                       prefixed, counts, offsets, a2r, r2a, (int32_t*)nullptr);
+  }
   if (xd) {
     const int row_vec = (int)((size_t)cfg->d_model * elem_size(cfg->dtype) / 16);
     hipLaunchKernelGGL(dispatch_gather_kernel, dim3((T + 3) / 4), dim3(256), 0, s, (const uint4*)x, T, k, row_vec, a2r,

@@ -80,6 +80,70 @@ __device__ __forceinline__ double reduce_scatter16(double (&acc)[NE], int lane) 
   return v;
 }
 
+// One wavefront ranks one token from its float64 logits z[0..E): softmax in float32 (row maximum subtracted),
+// k rounds of arg-max on the float64 logits (ties -> lower expert index), weights p or p / sum of the selected.
+__device__ __forceinline__ void rank_token(const double* z, int lane, int E, int k, int renorm, int t,
+                                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                           float* __restrict__ probs) {
+  // each lane owns experts lane, lane+64, ...
+  double zd[4];
+  float zf[4];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int e = lane + 64 * s;
+    zd[s] = e < E ? z[e] : -INFINITY;
+    zf[s] = (float)zd[s];
+    mx = fmaxf(mx, zf[s]);
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  float ex[4], sum = 0.f;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    ex[s] = (lane + 64 * s) < E ? expf(zf[s] - mx) : 0.f;
+    sum += ex[s];
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+  float p[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    p[s] = ex[s] / sum;
+    if (probs && (lane + 64 * s) < E) probs[(size_t)t * E + lane + 64 * s] = p[s];
+  }
+  // k rounds of arg-max on the float64 logits; ties -> lower expert index
+  float wsel = 0.f, wsum = 0.f;  // lane j keeps the j-th selection
+  int isel = 0;
+  for (int j = 0; j < k; ++j) {
+    double bz = -INFINITY;
+    int be = 0x7fffffff;
+    float bp = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int e = lane + 64 * s;
+      if (e < E && (zd[s] > bz || (zd[s] == bz && e < be))) { bz = zd[s]; be = e; bp = p[s]; }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      double oz = shfl_xor_f64(bz, m);
+      int oe = __shfl_xor(be, m, 64);
+      float op = __shfl_xor(bp, m, 64);
+      if (oz > bz || (oz == bz && oe < be)) { bz = oz; be = oe; bp = op; }
+    }
+    // retire the winner (all lanes agree on be)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (lane + 64 * s == be) zd[s] = -INFINITY;
+    if (lane == j) { isel = be; wsel = bp; }
+    wsum += bp;
+  }
+  if (lane < k) {
+    topk_idx[(size_t)t * k + lane] = isel;
+    topk_w[(size_t)t * k + lane] = renorm ? wsel / wsum : wsel;
+  }
+}
+
 template <typename XT>
 __global__ __launch_bounds__(WAVES * 64) void gate_exact_kernel(
     const XT* __restrict__ x, const float* __restrict__ wr, const float* __restrict__ br, int T, int d,
@@ -130,66 +194,79 @@ __global__ __launch_bounds__(WAVES * 64) void gate_exact_kernel(
   for (int q = 0; q < TPW; ++q) {
     const int t = t0 + q;
     if (t >= T) break;  // uniform per wave
-    // each lane owns experts lane, lane+64, ...
-    double zd[4];
-    float zf[4];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int e = lane + 64 * s;
-      zd[s] = e < E ? zs[q * Epad + e] : -INFINITY;
-      zf[s] = (float)zd[s];
-      mx = fmaxf(mx, zf[s]);
-    }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-    float ex[4], sum = 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      ex[s] = (lane + 64 * s) < E ? expf(zf[s] - mx) : 0.f;
-      sum += ex[s];
-    }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
-    float p[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      p[s] = ex[s] / sum;
-      if (probs && (lane + 64 * s) < E) probs[(size_t)t * E + lane + 64 * s] = p[s];
-    }
-    // k rounds of arg-max on the float64 logits; ties -> lower expert index
-    float wsel = 0.f, wsum = 0.f;  // lane j keeps the j-th selection
-    int isel = 0;
-    for (int j = 0; j < k; ++j) {
-      double bz = -INFINITY;
-      int be = 0x7fffffff;
-      float bp = 0.f;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int e = lane + 64 * s;
-        if (e < E && (zd[s] > bz || (zd[s] == bz && e < be))) { bz = zd[s]; be = e; bp = p[s]; }
-      }
-#pragma unroll
-      for (int m = 32; m >= 1; m >>= 1) {
-        double oz = shfl_xor_f64(bz, m);
-        int oe = __shfl_xor(be, m, 64);
-        float op = __shfl_xor(bp, m, 64);
-        if (oz > bz || (oz == bz && oe < be)) { bz = oz; be = oe; bp = op; }
-      }
-      // retire the winner (all lanes agree on be)
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        if (lane + 64 * s == be) zd[s] = -INFINITY;
-      if (lane == j) { isel = be; wsel = bp; }
-      wsum += bp;
-    }
-    if (lane < k) {
-      topk_idx[(size_t)t * k + lane] = isel;
-      topk_w[(size_t)t * k + lane] = renorm ? wsel / wsum : wsel;
-    }
+    rank_token(zs + q * Epad, lane, E, k, renorm, t, topk_idx, topk_w, probs);
   }
 }
 
+// Few tokens (T <= FEW_MAX_T; E = 4, 8, 16, 32 or 64): one workgroup per token, so that the whole router matrix
+// is not read through one compute unit's handful of wavefronts, with loads that are contiguous across the
+// wavefront: a router row is E/4 chunks of four floats; lane (r, c) of a wavefront reads chunk c of the r-th of
+// the 64 / (E/4) rows that one wave-wide load covers, and accumulates those four logits in float64 (exact
+// products, see above) over its share of the rows.  The sums meet across the row groups of a wavefront by a
+// butterfly, across the wavefronts in wavefront order, and wavefront 0 ranks the token.
+constexpr int FEW_MAX_T = 16;
+constexpr int FEW_WAVES = 16;  // (all the loads of a token are in flight in two batches at d_model = 2048)
+constexpr int FEW_THREADS = FEW_WAVES * 64;
+
+template <typename XT>
+__global__ __launch_bounds__(FEW_THREADS) void gate_few_kernel(
+    const XT* __restrict__ x, const float* __restrict__ wr, const float* __restrict__ br, int T, int d, int E, int k,
+    int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ probs) {
+  __shared__ double part[FEW_WAVES][64];
+  __shared__ double zrow[64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x;
+  const int cpr = E >> 2, rpi = 64 / cpr;  // chunks per row, rows per wave-wide load
+  const int r = lane / cpr, c = lane % cpr;
+  const XT* xt = x + (size_t)t * d;
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll 16
+  for (int row = wave * rpi + r; row < d; row += FEW_WAVES * rpi) {
+    const float4 w4 = *reinterpret_cast<const float4*>(wr + (size_t)row * E + 4 * c);
+    float xv;
+    if constexpr (sizeof(XT) == 2) xv = bf16_to_f32(xt[row]);
+    else xv = xt[row];
+    const double xd = (double)xv;
+    a0 = fma(xd, (double)w4.x, a0);
+    a1 = fma(xd, (double)w4.y, a1);
+    a2 = fma(xd, (double)w4.z, a2);
+    a3 = fma(xd, (double)w4.w, a3);
+  }
+  for (int m = cpr; m < 64; m <<= 1) {  // lanes with the same chunk sit cpr apart
+    a0 += shfl_xor_f64(a0, m);
+    a1 += shfl_xor_f64(a1, m);
+    a2 += shfl_xor_f64(a2, m);
+    a3 += shfl_xor_f64(a3, m);
+  }
+  if (lane < cpr) {
+    part[wave][4 * c] = a0; part[wave][4 * c + 1] = a1; part[wave][4 * c + 2] = a2; part[wave][4 * c + 3] = a3;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < E) {
+    double zsum = 0.0;
+#pragma unroll
+    for (int w = 0; w < FEW_WAVES; ++w) zsum += part[w][threadIdx.x];
+    zrow[threadIdx.x] = zsum + (br ? (double)br[threadIdx.x] : 0.0);
+  }
+  __syncthreads();
+  if (wave == 0) rank_token(zrow, lane, E, k, renorm, t, topk_idx, topk_w, probs);
+}
+
+// the shapes the kernel above is written for
+bool gate_few_applies(const moe_config* cfg, const float* w_router) {
+  static const bool off = [] { const char* e = getenv("MOESYS_NO_GATE_FEW"); return e && atoi(e) != 0; }();
+  const int E = cfg->E;
+  return !off && cfg->T <= FEW_MAX_T && (E == 4 || E == 8 || E == 16 || E == 32 || E == 64) &&
+         (reinterpret_cast<uintptr_t>(w_router) & 15) == 0;
+}
+
+template <typename XT>
+int32_t launch_few(const moe_config* cfg, const void* x, const float* w_router, const float* b_router, int32_t* topk_idx,
+                   float* topk_w, float* probs, hipStream_t s) {
+  hipLaunchKernelGGL(gate_few_kernel<XT>, dim3(cfg->T), dim3(FEW_THREADS), 0, s, (const XT*)x, w_router, b_router, cfg->T,
+                     cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+  return check_hip(hipGetLastError(), "gate launch");
+}
 
 // ------------------------------------------------------------------------------------------------
 // Fast path.
@@ -527,6 +604,10 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   if (cfg->T == 0) return MOE_OK;
+  if (gate_few_applies(cfg, w_router)) {
+    if (cfg->dtype == MOE_BF16) return launch_few<uint16_t>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
+    return launch_few<float>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
+  }
   if (cfg->dtype == MOE_BF16 && cfg->E <= 64) {
     if (cfg->E <= 16) return launch_fast<1>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);
     if (cfg->E <= 32) return launch_fast<2>(cfg, x, w_router, b_router, topk_idx, topk_w, probs, s);

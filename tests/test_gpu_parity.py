@@ -35,6 +35,14 @@ GATE_CASES = [
     small("gpt", T=64, E=256, k=8, d_model=128),
     small("skew", T=2048),
     small("gpt", T=3, E=2, k=2, renormalize=False),
+    # at most 16 tokens and 4, 8, 16, 32 or 64 experts: one workgroup per token
+    small("ring", T=1, d_model=2048),
+    small("ring", T=16, d_model=512, k=8),
+    small("gpt", T=5, E=32, k=3, d_model=320),
+    small("skew", T=9, d_model=768),                      # 8 experts, router bias, top-1
+    small("tiny", T=16, E=4, k=4),                        # float32 activations, k = E
+    small("gpt", T=5, E=33, k=3, d_model=320),            # other expert counts: the general kernels
+    small("gpt", T=16, E=65, k=2, d_model=256),
 ]
 
 
