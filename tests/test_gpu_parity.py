@@ -161,6 +161,8 @@ FFN_CASES = [
     small("gpt", T=900, E=5, d_model=192, d_ff=320, act="gelu"),           # narrow-tile fallback
     small("gpt", T=1500, E=4, d_model=256, d_ff=384, act="swiglu"),
     small("gpt", T=700, E=3, d_model=192, d_ff=192, act="swiglu"),
+    small("gpt", T=5, E=4, d_model=256, d_ff=512, act="gelu"),             # few rows: matrix-vector kernels on dispatched rows
+    small("gpt", T=8, E=3, d_model=320, d_ff=256, act="swiglu"),
 ]
 
 
