@@ -41,7 +41,7 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ wa, const uint16_t* __restrict__ wb,
     const uint16_t* __restrict__ bias, const int32_t* __restrict__ offsets, uint16_t* out,
     const int32_t* __restrict__ row_map, const float* __restrict__ gate_w, const uint16_t* residual,
-    const int64_t* __restrict__ eoff, int T, int E, int N, int K) {
+    const int64_t* __restrict__ eoff, int T, int E, int N, int K, int reps) {
   constexpr int OUTF = EPI == GV_SWIGLU ? GV_FPW / 2 : GV_FPW;  // output features per wavefront
   __shared__ int s_e;
   const int r0 = blockIdx.y;
@@ -54,15 +54,7 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
   if (e < 0) return;
   const int rows = min(offsets[e + 1] - r0, GV_ROWS);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int n0 = (blockIdx.x * GV_WAVES + wave) * OUTF;  // first output feature of this wavefront
-
   const int64_t wbase = eoff ? eoff[e] : (int64_t)e * N * K;
-  const uint16_t* wrow[GV_FPW];
-#pragma unroll
-  for (int j = 0; j < GV_FPW; ++j) {
-    if (EPI == GV_SWIGLU) wrow[j] = (j < OUTF ? wa : wb) + wbase + (int64_t)(n0 + j % OUTF) * K;
-    else wrow[j] = wa + wbase + (int64_t)(n0 + j) * K;
-  }
   const uint16_t* xrow[GV_ROWS];
   int token[GV_ROWS];
 #pragma unroll
@@ -79,77 +71,88 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
     xrow[r] = act + (int64_t)src * K;
   }
 
-  float acc[GV_FPW][GV_ROWS];
+  // a workgroup works through `reps` consecutive blocks of output features (with a short contraction index one
+  // block is too little work per workgroup)
+  for (int rep = 0; rep < reps; ++rep) {
+    const int n0 = ((blockIdx.x * reps + rep) * GV_WAVES + wave) * OUTF;  // first output feature of this wavefront
+    const uint16_t* wrow[GV_FPW];
 #pragma unroll
-  for (int j = 0; j < GV_FPW; ++j)
-#pragma unroll
-    for (int r = 0; r < GV_ROWS; ++r) acc[j][r] = 0.f;
+    for (int j = 0; j < GV_FPW; ++j) {
+      if (EPI == GV_SWIGLU) wrow[j] = (j < OUTF ? wa : wb) + wbase + (int64_t)(n0 + j % OUTF) * K;
+      else wrow[j] = wa + wbase + (int64_t)(n0 + j) * K;
+    }
+    float acc[GV_FPW][GV_ROWS];
+  #pragma unroll
+    for (int j = 0; j < GV_FPW; ++j)
+  #pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r) acc[j][r] = 0.f;
 
-  for (int kb = lane * 8; kb < K; kb += 64 * 8) {
-    uint4 wv[GV_FPW], xv[GV_ROWS];
-#pragma unroll
-    for (int j = 0; j < GV_FPW; ++j) wv[j] = *reinterpret_cast<const uint4*>(wrow[j] + kb);
-#pragma unroll
-    for (int r = 0; r < GV_ROWS; ++r)
-      if (r < rows) xv[r] = *reinterpret_cast<const uint4*>(xrow[r] + kb);
-#pragma unroll
-    for (int r = 0; r < GV_ROWS; ++r) {
-      if (r < rows) {  // (wave-uniform)
-        const float x0 = lo16(xv[r].x), x1 = hi16(xv[r].x), x2 = lo16(xv[r].y), x3 = hi16(xv[r].y);
-        const float x4 = lo16(xv[r].z), x5 = hi16(xv[r].z), x6 = lo16(xv[r].w), x7 = hi16(xv[r].w);
-#pragma unroll
-        for (int j = 0; j < GV_FPW; ++j) {
-          float a = acc[j][r];
-          a = fmaf(lo16(wv[j].x), x0, a); a = fmaf(hi16(wv[j].x), x1, a);
-          a = fmaf(lo16(wv[j].y), x2, a); a = fmaf(hi16(wv[j].y), x3, a);
-          a = fmaf(lo16(wv[j].z), x4, a); a = fmaf(hi16(wv[j].z), x5, a);
-          a = fmaf(lo16(wv[j].w), x6, a); a = fmaf(hi16(wv[j].w), x7, a);
-          acc[j][r] = a;
+    for (int kb = lane * 8; kb < K; kb += 64 * 8) {
+      uint4 wv[GV_FPW], xv[GV_ROWS];
+  #pragma unroll
+      for (int j = 0; j < GV_FPW; ++j) wv[j] = *reinterpret_cast<const uint4*>(wrow[j] + kb);
+  #pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r)
+        if (r < rows) xv[r] = *reinterpret_cast<const uint4*>(xrow[r] + kb);
+  #pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r) {
+        if (r < rows) {  // (wave-uniform)
+          const float x0 = lo16(xv[r].x), x1 = hi16(xv[r].x), x2 = lo16(xv[r].y), x3 = hi16(xv[r].y);
+          const float x4 = lo16(xv[r].z), x5 = hi16(xv[r].z), x6 = lo16(xv[r].w), x7 = hi16(xv[r].w);
+  #pragma unroll
+          for (int j = 0; j < GV_FPW; ++j) {
+            float a = acc[j][r];
+            a = fmaf(lo16(wv[j].x), x0, a); a = fmaf(hi16(wv[j].x), x1, a);
+            a = fmaf(lo16(wv[j].y), x2, a); a = fmaf(hi16(wv[j].y), x3, a);
+            a = fmaf(lo16(wv[j].z), x4, a); a = fmaf(hi16(wv[j].z), x5, a);
+            a = fmaf(lo16(wv[j].w), x6, a); a = fmaf(hi16(wv[j].w), x7, a);
+            acc[j][r] = a;
+          }
         }
       }
     }
-  }
 
-  // sums over the lanes; afterwards every lane holds every total
-#pragma unroll
-  for (int r = 0; r < GV_ROWS; ++r) {
-    if (r < rows) {
-#pragma unroll
-      for (int j = 0; j < GV_FPW; ++j) {
-        float v = acc[j][r];
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-        acc[j][r] = v;
-      }
-    }
-  }
-
-  // lane j < OUTF finishes output feature n0 + j of every row
-  if (lane < OUTF) {
-    const int n = n0 + lane;
-    float b = 0.f;
-    if (EPI != GV_SWIGLU && bias) b = lo16((uint32_t)bias[(eoff ? eoff[e] : (int64_t)e * N) + n]);  // (eoff: as for the weights)
-#pragma unroll
+    // sums over the lanes; afterwards every lane holds every total
+  #pragma unroll
     for (int r = 0; r < GV_ROWS; ++r) {
       if (r < rows) {
-        float v = acc[0][r], u = 0.f;
-#pragma unroll
-        for (int j = 1; j < OUTF; ++j) v = lane == j ? acc[j][r] : v;
-        if (EPI == GV_SWIGLU) {
-          u = acc[OUTF][r];
-#pragma unroll
-          for (int j = 1; j < OUTF; ++j) u = lane == j ? acc[OUTF + j][r] : u;
-          v = v * __builtin_amdgcn_rcpf(1.f + __expf(-v)) * u;
-        } else {
-          v += b;
-          if (EPI == GV_GELU) v = gelu_exact(v);
+  #pragma unroll
+        for (int j = 0; j < GV_FPW; ++j) {
+          float v = acc[j][r];
+  #pragma unroll
+          for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+          acc[j][r] = v;
         }
-        if (EPI == GV_COMBINE) {
-          const size_t o = (size_t)token[r] * N + n;
-          const float res = residual ? lo16((uint32_t)residual[o]) : 0.f;
-          out[o] = bf16_of(fmaf(gate_w[token[r]], v, res));
-        } else {
-          out[(size_t)(r0 + r) * N + n] = bf16_of(v);
+      }
+    }
+
+    // lane j < OUTF finishes output feature n0 + j of every row
+    if (lane < OUTF) {
+      const int n = n0 + lane;
+      float b = 0.f;
+      if (EPI != GV_SWIGLU && bias) b = lo16((uint32_t)bias[(eoff ? eoff[e] : (int64_t)e * N) + n]);  // (eoff: as for the weights)
+  #pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r) {
+        if (r < rows) {
+          float v = acc[0][r], u = 0.f;
+  #pragma unroll
+          for (int j = 1; j < OUTF; ++j) v = lane == j ? acc[j][r] : v;
+          if (EPI == GV_SWIGLU) {
+            u = acc[OUTF][r];
+  #pragma unroll
+            for (int j = 1; j < OUTF; ++j) u = lane == j ? acc[OUTF + j][r] : u;
+            v = v * __builtin_amdgcn_rcpf(1.f + __expf(-v)) * u;
+          } else {
+            v += b;
+            if (EPI == GV_GELU) v = gelu_exact(v);
+          }
+          if (EPI == GV_COMBINE) {
+            const size_t o = (size_t)token[r] * N + n;
+            const float res = residual ? lo16((uint32_t)residual[o]) : 0.f;
+            out[o] = bf16_of(fmaf(gate_w[token[r]], v, res));
+          } else {
+            out[(size_t)(r0 + r) * N + n] = bf16_of(v);
+          }
         }
       }
     }
@@ -161,13 +164,18 @@ int32_t launch_shape(const moe_config* cfg, const uint16_t* act, const uint16_t*
                      const int32_t* offsets, uint16_t* out, const int32_t* row_map, const float* gate_w, const uint16_t* residual,
                      const int64_t* eoff, int N, int K, bool gather, hipStream_t s) {
   constexpr int OUTF = EPI == GV_SWIGLU ? FPW / 2 : FPW;
-  const dim3 grid(N / (GV_WAVES * OUTF), cfg->k * cfg->T), block(GV_WAVES * 64);
+  // about 256 KB of weights per workgroup, in whole blocks of output features
+  const int blocks = N / (GV_WAVES * OUTF);
+  int reps = (int)((256 * 1024) / ((int64_t)GV_WAVES * FPW * K * 2));
+  reps = reps < 1 ? 1 : reps > 8 ? 8 : reps;
+  while (blocks % reps) --reps;
+  const dim3 grid(blocks / reps, cfg->k * cfg->T), block(GV_WAVES * 64);
   if (gather)
     hipLaunchKernelGGL((expert_gemv_kernel<EPI, true, ROWS, FPW>), grid, block, 0, s, act, wa, wb, bias, offsets, out, row_map, gate_w,
-                       residual, eoff, cfg->T, cfg->E, N, K);
+                       residual, eoff, cfg->T, cfg->E, N, K, reps);
   else
     hipLaunchKernelGGL((expert_gemv_kernel<EPI, false, ROWS, FPW>), grid, block, 0, s, act, wa, wb, bias, offsets, out, row_map, gate_w,
-                       residual, eoff, cfg->T, cfg->E, N, K);
+                       residual, eoff, cfg->T, cfg->E, N, K, reps);
   return check_hip(hipGetLastError(), "expert GEMV launch");
 }
 
