@@ -82,9 +82,10 @@ __device__ __forceinline__ double reduce_scatter16(double (&acc)[NE], int lane) 
 
 // One wavefront ranks one token from its float64 logits z[0..E): softmax in float32 (row maximum subtracted),
 // k rounds of arg-max on the float64 logits (ties -> lower expert index), weights p or p / sum of the selected.
-__device__ __forceinline__ void rank_token(const double* z, int lane, int E, int k, int renorm, int t,
-                                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                           float* __restrict__ probs) {
+// Returns the j-th selected expert in lane j < k (0 in the other lanes).
+__device__ __forceinline__ int rank_token(const double* z, int lane, int E, int k, int renorm, int t,
+                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                          float* __restrict__ probs) {
   // each lane owns experts lane, lane+64, ...
   double zd[4];
   float zf[4];
@@ -142,6 +143,7 @@ __device__ __forceinline__ void rank_token(const double* z, int lane, int E, int
     topk_idx[(size_t)t * k + lane] = isel;
     topk_w[(size_t)t * k + lane] = renorm ? wsel / wsum : wsel;
   }
+  return isel;
 }
 
 template <typename XT>
@@ -211,7 +213,9 @@ constexpr int FEW_THREADS = FEW_WAVES * 64;
 template <typename XT>
 __global__ __launch_bounds__(FEW_THREADS) void gate_few_kernel(
     const XT* __restrict__ x, const float* __restrict__ wr, const float* __restrict__ br, int T, int d, int E, int k,
-    int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ probs) {
+    int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ probs,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ a2r, int32_t* __restrict__ r2a,
+    int32_t* __restrict__ clear8) {
   __shared__ double part[FEW_WAVES][64];
   __shared__ double zrow[64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -249,7 +253,26 @@ __global__ __launch_bounds__(FEW_THREADS) void gate_few_kernel(
     zrow[threadIdx.x] = zsum + (br ? (double)br[threadIdx.x] : 0.0);
   }
   __syncthreads();
-  if (wave == 0) rank_token(zrow, lane, E, k, renorm, t, topk_idx, topk_w, probs);
+  if (wave != 0) return;
+  const int sel = rank_token(zrow, lane, E, k, renorm, t, topk_idx, topk_w, probs);
+  // A step of ONE token (counts != NULL; T == 1): its dispatch tables follow from the selection at once.  The k
+  // experts are distinct and get one row each (the capacity is at least one, so nothing is dropped); rows are
+  // ordered by expert; assignment j (= j*T + t with T = 1) is the j-th choice.
+  if (counts) {
+    unsigned long long chosen = 0;  // bit e: expert e selected (E <= 64)
+    for (int j = 0; j < k; ++j) chosen |= 1ull << __shfl(sel, j, 64);
+    if (lane < E) {
+      counts[lane] = (int)((chosen >> lane) & 1ull);
+      offsets[lane] = __popcll(chosen & ((1ull << lane) - 1ull));
+    }
+    if (lane == 0) offsets[E] = k;
+    if (lane < k) {
+      const int row = __popcll(chosen & ((1ull << sel) - 1ull));
+      a2r[lane] = row;
+      r2a[row] = lane;
+    }
+    if (clear8 && lane < 8) clear8[lane] = 0;
+  }
 }
 
 // the shapes the kernel above is written for
@@ -262,9 +285,10 @@ bool gate_few_applies(const moe_config* cfg, const float* w_router) {
 
 template <typename XT>
 int32_t launch_few(const moe_config* cfg, const void* x, const float* w_router, const float* b_router, int32_t* topk_idx,
-                   float* topk_w, float* probs, hipStream_t s) {
+                   float* topk_w, float* probs, hipStream_t s, int32_t* counts = nullptr, int32_t* offsets = nullptr,
+                   int32_t* a2r = nullptr, int32_t* r2a = nullptr, int32_t* clear8 = nullptr) {
   hipLaunchKernelGGL(gate_few_kernel<XT>, dim3(cfg->T), dim3(FEW_THREADS), 0, s, (const XT*)x, w_router, b_router, cfg->T,
-                     cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+                     cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs, counts, offsets, a2r, r2a, clear8);
   return check_hip(hipGetLastError(), "gate launch");
 }
 
@@ -600,6 +624,17 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
 }
 
 }  // namespace
+
+// A step of one token: gate and dispatch tables from one kernel (bf16 activations: the layer then needs no
+// dispatched copy of the token).
+bool gate_dispatch_one_token_applies(const moe_config* cfg, const float* w_router) {
+  return cfg->T == 1 && cfg->dtype == MOE_BF16 && gate_few_applies(cfg, w_router);
+}
+int32_t launch_gate_dispatch_one_token(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                                       int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, int32_t* a2r,
+                                       int32_t* r2a, int32_t* clear8, hipStream_t s) {
+  return launch_few<uint16_t>(cfg, x, w_router, b_router, topk_idx, topk_w, nullptr, s, counts, offsets, a2r, r2a, clear8);
+}
 
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {

@@ -56,10 +56,18 @@ int32_t route_impl(const char* who, const moe_config* cfg, const moe_weights* w,
   if (st != MOE_OK) return st;
   if (!w->w_router) return fail(MOE_ERR_INVALID_ARG, "%s: w_router is NULL", who);
   if ((st = mark(timer, 0, s)) != MOE_OK) return st;
+  const bool gather = gemm1_can_gather(cfg);
+  if (gather && gate_dispatch_one_token_applies(cfg, w->w_router)) {
+    // a step of one token: the gate's kernel writes the dispatch tables as well
+    if ((st = launch_gate_dispatch_one_token(cfg, x, w->w_router, w->b_router, sg.topk_idx, sg.topk_w, sg.counts, sg.offsets,
+                                             sg.a2r, sg.r2a, sg.tile_ctr, s)) != MOE_OK)
+      return st;
+    if ((st = mark(timer, 1, s)) != MOE_OK) return st;
+    return mark(timer, 2, s);
+  }
   if ((st = launch_gate(cfg, x, w->w_router, w->b_router, sg.topk_idx, sg.topk_w, nullptr, s)) != MOE_OK) return st;
   if ((st = mark(timer, 1, s)) != MOE_OK) return st;
   // bf16: the first GEMM gathers its rows from x through row_to_assign, so no dispatched copy is made
-  const bool gather = gemm1_can_gather(cfg);
   if ((st = launch_dispatch(cfg, x, sg.topk_idx, sg.counts, sg.offsets, sg.a2r, sg.r2a, gather ? nullptr : sg.xd,
                             sg.scratch, sg.tile_ctr, s)) != MOE_OK)
     return st;

@@ -32,6 +32,10 @@ constexpr int TILE_COUNTER_INTS = 16;
 size_t ffn_counter_offset(const moe_config* cfg);
 
 // Stage launchers (arguments already validated).
+bool gate_dispatch_one_token_applies(const moe_config* cfg, const float* w_router);
+int32_t launch_gate_dispatch_one_token(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                                       int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, int32_t* a2r,
+                                       int32_t* r2a, int32_t* clear8, hipStream_t s);
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s);
 // clear8 (nullable): eight ints set to zero on the way (the first GEMM's tile counters).

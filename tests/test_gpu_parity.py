@@ -253,6 +253,10 @@ LAYER_CASES = [
     ("gpt", dict(T=8, E=4, d_model=256, d_ff=256, k=1, capacity_factor=0.5)),  # top-1 with dropped tokens
     ("large", dict(T=2, d_model=512, d_ff=1024, E=4)),                         # SwiGLU
     ("large", dict(T=5, d_model=512, d_ff=1024, E=4, k=1)),
+    # one token: the gate's kernel writes the dispatch tables too
+    ("skew", dict(T=1, d_model=256, d_ff=512)),
+    ("large", dict(T=1, d_model=512, d_ff=1024, E=4)),
+    ("gpt", dict(T=1, E=16, k=8, d_model=256, d_ff=256, capacity_factor=0.05)),   # capacity 1: still nothing dropped
     ("ring", dict(T=8, d_model=256, d_ff=512, E=64)),                          # 9 to 16 assignments: the 4 x 16 shape
     ("gpt", dict(T=6, E=2, d_model=256, d_ff=512, capacity_factor=0.0)),       # up to 12 rows in one expert
     ("skew", dict(T=13, d_model=256, d_ff=512)),

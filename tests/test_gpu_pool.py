@@ -34,7 +34,7 @@ def expert_blobs(W, e_count):
     return blobs, sizes
 
 
-@pytest.mark.parametrize("T,slots,steps", [(24, 10, 6), (3, 16, 12), (64, 13, 4)])
+@pytest.mark.parametrize("T,slots,steps", [(24, 10, 6), (3, 16, 12), (64, 13, 4), (1, 5, 16)])
 def test_pool_stack_matches_resident_and_policy_oracle(T, slots, steps):
     N, thr, beta, K = 3, 2.0, 0.5, 7
     wl = WORKLOADS["ring"].scaled(T=T, d_model=256, d_ff=512, E=8, capacity_factor=0.0)
