@@ -36,7 +36,9 @@ __device__ __forceinline__ float gelu_exact(float u) { return 0.5f * u * erfcf(-
 // FPW/2 of Wg and the same FPW/2 of Wu); GV_BIAS out = . + bias; GV_COMBINE (k = 1) out[token] =
 // residual[token] + gate_w[token] * (. + bias) with token = row_map[r].
 // GATHER: act is x[T, K] and row r reads token row_map[r] mod T.
-template <int EPI, bool GATHER, int GV_ROWS, int GV_FPW>
+// KSPLIT: the four wavefronts of a workgroup share one set of GV_FPW weight rows and split the contraction index
+// (their sums meet in LDS, in wavefront order): four times the workgroups, for long rows and few experts.
+template <int EPI, bool GATHER, int GV_ROWS, int GV_FPW, bool KSPLIT>
 __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
     const uint16_t* __restrict__ act, const uint16_t* __restrict__ wa, const uint16_t* __restrict__ wb,
     const uint16_t* __restrict__ bias, const int32_t* __restrict__ offsets, uint16_t* out,
@@ -44,6 +46,7 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
     const int64_t* __restrict__ eoff, int T, int E, int N, int K, int reps) {
   constexpr int OUTF = EPI == GV_SWIGLU ? GV_FPW / 2 : GV_FPW;  // output features per wavefront
   __shared__ int s_e;
+  __shared__ float red[KSPLIT ? GV_WAVES : 1][GV_ROWS][GV_FPW];
   const int r0 = blockIdx.y;
   if (threadIdx.x == 0) s_e = -1;
   __syncthreads();
@@ -74,7 +77,8 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
   // a workgroup works through `reps` consecutive blocks of output features (with a short contraction index one
   // block is too little work per workgroup)
   for (int rep = 0; rep < reps; ++rep) {
-    const int n0 = ((blockIdx.x * reps + rep) * GV_WAVES + wave) * OUTF;  // first output feature of this wavefront
+    // first output feature of this wavefront
+    const int n0 = KSPLIT ? (blockIdx.x * reps + rep) * OUTF : ((blockIdx.x * reps + rep) * GV_WAVES + wave) * OUTF;
     const uint16_t* wrow[GV_FPW];
 #pragma unroll
     for (int j = 0; j < GV_FPW; ++j) {
@@ -87,7 +91,7 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
   #pragma unroll
       for (int r = 0; r < GV_ROWS; ++r) acc[j][r] = 0.f;
 
-    for (int kb = lane * 8; kb < K; kb += 64 * 8) {
+    for (int kb = (KSPLIT ? (int)threadIdx.x : lane) * 8; kb < K; kb += (KSPLIT ? GV_WAVES : 1) * 64 * 8) {
       uint4 wv[GV_FPW], xv[GV_ROWS];
   #pragma unroll
       for (int j = 0; j < GV_FPW; ++j) wv[j] = *reinterpret_cast<const uint4*>(wrow[j] + kb);
@@ -126,8 +130,38 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
       }
     }
 
+    if constexpr (KSPLIT) {  // the wavefronts' sums meet: lane j < GV_FPW carries weight row j
+      if (rep) __syncthreads();  // (the previous block's sums have been read)
+#pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r) {
+        if (r < rows && lane < GV_FPW) {
+          float v = acc[0][r];
+#pragma unroll
+          for (int j = 1; j < GV_FPW; ++j) v = lane == j ? acc[j][r] : v;
+          red[wave][r][lane] = v;
+        }
+      }
+      __syncthreads();
+      if (wave == 0 && lane < GV_FPW) {
+#pragma unroll
+        for (int r = 0; r < GV_ROWS; ++r) {
+          if (r < rows) {
+            float v = red[0][r][lane];
+#pragma unroll
+            for (int w = 1; w < GV_WAVES; ++w) v += red[w][r][lane];
+            red[0][r][lane] = v;  // (only this lane reads and writes the element)
+          }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < GV_ROWS; ++r)
+        if (r < rows)
+#pragma unroll
+          for (int j = 0; j < GV_FPW; ++j) acc[j][r] = red[0][r][j];  // every lane holds every total again
+    }
     // lane j < OUTF finishes output feature n0 + j of every row
-    if (lane < OUTF) {
+    if ((!KSPLIT || wave == 0) && lane < OUTF) {
       const int n = n0 + lane;
       float b = 0.f;
       if (EPI != GV_SWIGLU && bias) b = lo16((uint32_t)bias[(eoff ? eoff[e] : (int64_t)e * N) + n]);  // (eoff: as for the weights)
@@ -164,18 +198,23 @@ int32_t launch_shape(const moe_config* cfg, const uint16_t* act, const uint16_t*
                      const int32_t* offsets, uint16_t* out, const int32_t* row_map, const float* gate_w, const uint16_t* residual,
                      const int64_t* eoff, int N, int K, bool gather, hipStream_t s) {
   constexpr int OUTF = EPI == GV_SWIGLU ? FPW / 2 : FPW;
-  // about 256 KB of weights per workgroup, in whole blocks of output features
-  const int blocks = N / (GV_WAVES * OUTF);
-  int reps = (int)((256 * 1024) / ((int64_t)GV_WAVES * FPW * K * 2));
+  // About 256 KB of weights per workgroup, in whole blocks of output features, as long as that leaves about two
+  // workgroups per CU (the experts with rows are at most k*T).  Long rows and too few workgroups even so: the
+  // wavefronts of a workgroup split the contraction index instead of the output features.
+  const int A = cfg->k * cfg->T;
+  int blocks = N / (GV_WAVES * OUTF);
+  const bool ksplit = K >= 4096 && (int64_t)blocks * A < 512;
+  if (ksplit) blocks *= GV_WAVES;
+  int reps = ksplit ? 1 : (int)((256 * 1024) / ((int64_t)GV_WAVES * FPW * K * 2));
   reps = reps < 1 ? 1 : reps > 8 ? 8 : reps;
-  while (blocks % reps) --reps;
-  const dim3 grid(blocks / reps, cfg->k * cfg->T), block(GV_WAVES * 64);
-  if (gather)
-    hipLaunchKernelGGL((expert_gemv_kernel<EPI, true, ROWS, FPW>), grid, block, 0, s, act, wa, wb, bias, offsets, out, row_map, gate_w,
-                       residual, eoff, cfg->T, cfg->E, N, K, reps);
-  else
-    hipLaunchKernelGGL((expert_gemv_kernel<EPI, false, ROWS, FPW>), grid, block, 0, s, act, wa, wb, bias, offsets, out, row_map, gate_w,
-                       residual, eoff, cfg->T, cfg->E, N, K, reps);
+  while (reps > 1 && (blocks % reps || (int64_t)(blocks / reps) * A < 512)) --reps;
+  const dim3 grid(blocks / reps, A), block(GV_WAVES * 64);
+#define MOESYS_GEMV(G, S)                                                                                                  \
+  hipLaunchKernelGGL((expert_gemv_kernel<EPI, G, ROWS, FPW, S>), grid, block, 0, s, act, wa, wb, bias, offsets, out, row_map, \
+                     gate_w, residual, eoff, cfg->T, cfg->E, N, K, reps)
+  if (gather) { if (ksplit) MOESYS_GEMV(true, true); else MOESYS_GEMV(true, false); }
+  else { if (ksplit) MOESYS_GEMV(false, true); else MOESYS_GEMV(false, false); }
+#undef MOESYS_GEMV
   return check_hip(hipGetLastError(), "expert GEMV launch");
 }
 
