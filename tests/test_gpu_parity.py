@@ -488,10 +488,11 @@ def test_layer_forward_does_not_need_a_cleared_workspace():
     assert torch.equal(out, want)
 
 
-def test_layer_forward_in_a_hip_graph():
+@pytest.mark.parametrize("kw", [dict(T=2048, E=8), dict(T=1, E=8), dict(T=6, E=16)], ids=lambda v: str(v).replace(" ", ""))
+def test_layer_forward_in_a_hip_graph(kw):
     """The call allocates nothing and never synchronises, so it can be captured; every replay (with eager
-    work and synchronisations in between) gives the eager result bit for bit."""
-    wl = small("gpt", T=2048, E=8)
+    work and synchronisations in between) gives the eager result bit for bit.  (T = 1 and 6: the few-token kernels.)"""
+    wl = small("gpt", **kw)
     L = make_layer(wl)
     cfg = M.MoEConfig.from_workload(wl)
     W = upload_weights(L, wl.dtype)
