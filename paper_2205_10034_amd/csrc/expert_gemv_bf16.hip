@@ -193,6 +193,78 @@ __global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_kernel(
   }
 }
 
+// A step of ONE token with k >= 2 experts: the second product and the combine in one kernel.  A workgroup owns
+// C1_FPW output features; for the k choices in turn (row = assign_to_row[j], its expert from the offsets table)
+// its four wavefronts split the contraction index, the sums meet in LDS in wavefront order, the result (+ bias)
+// is rounded to bf16 and stored in yd as the separate product would store it, and out accumulates
+// residual + sum_j w_j * yd[row_j] from those rounded values, in float32 and in the order of the combine kernel.
+constexpr int C1_FPW = 8;
+
+__global__ __launch_bounds__(GV_WAVES * 64) void expert_gemv_combine1_kernel(
+    const uint16_t* __restrict__ h, const uint16_t* __restrict__ w2, const uint16_t* __restrict__ bias,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ a2r, const float* __restrict__ topk_w,
+    const uint16_t* residual, uint16_t* __restrict__ yd, uint16_t* out, const int64_t* __restrict__ eoff, int E, int N,
+    int K, int k) {
+  __shared__ int s_e[MOE_MAX_TOPK];  // expert of dispatched row r (T = 1: there are exactly k rows)
+  __shared__ float red[GV_WAVES][C1_FPW];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  for (int e = threadIdx.x; e < E; e += GV_WAVES * 64)
+    for (int r = offsets[e]; r < offsets[e + 1] && r < MOE_MAX_TOPK; ++r) s_e[r] = e;
+  __syncthreads();
+  const int n0 = blockIdx.x * C1_FPW;
+  float o = 0.f;  // (used by lanes < C1_FPW of wavefront 0: output feature n0 + lane)
+  if (wave == 0 && lane < C1_FPW && residual) o = lo16((uint32_t)residual[n0 + lane]);
+  for (int j = 0; j < k; ++j) {
+    const int row = a2r[j];
+    if (row < 0) continue;  // (cannot happen with one token: the capacity is at least one; uniform anyway)
+    const int e = s_e[row];
+    const uint16_t* wbase = w2 + (eoff ? eoff[e] : (int64_t)e * N * K) + (int64_t)n0 * K;
+    const uint16_t* xrow = h + (int64_t)row * K;
+    float acc[C1_FPW];
+#pragma unroll
+    for (int f = 0; f < C1_FPW; ++f) acc[f] = 0.f;
+#pragma unroll 2
+    for (int kb = (int)threadIdx.x * 8; kb < K; kb += GV_WAVES * 64 * 8) {
+      uint4 wv[C1_FPW];
+#pragma unroll
+      for (int f = 0; f < C1_FPW; ++f) wv[f] = *reinterpret_cast<const uint4*>(wbase + (int64_t)f * K + kb);
+      const uint4 xv = *reinterpret_cast<const uint4*>(xrow + kb);
+      const float x0 = lo16(xv.x), x1 = hi16(xv.x), x2 = lo16(xv.y), x3 = hi16(xv.y);
+      const float x4 = lo16(xv.z), x5 = hi16(xv.z), x6 = lo16(xv.w), x7 = hi16(xv.w);
+#pragma unroll
+      for (int f = 0; f < C1_FPW; ++f) {
+        float a = acc[f];
+        a = fmaf(lo16(wv[f].x), x0, a); a = fmaf(hi16(wv[f].x), x1, a);
+        a = fmaf(lo16(wv[f].y), x2, a); a = fmaf(hi16(wv[f].y), x3, a);
+        a = fmaf(lo16(wv[f].z), x4, a); a = fmaf(hi16(wv[f].z), x5, a);
+        a = fmaf(lo16(wv[f].w), x6, a); a = fmaf(hi16(wv[f].w), x7, a);
+        acc[f] = a;
+      }
+    }
+    float mine = 0.f;  // lane f < C1_FPW: the wavefront's sum for output feature n0 + f
+#pragma unroll
+    for (int f = 0; f < C1_FPW; ++f) {
+      float v = acc[f];
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+      mine = lane == f ? v : mine;
+    }
+    if (lane < C1_FPW) red[wave][lane] = mine;
+    __syncthreads();
+    if (wave == 0 && lane < C1_FPW) {
+      float v = red[0][lane];
+#pragma unroll
+      for (int w = 1; w < GV_WAVES; ++w) v += red[w][lane];
+      if (bias) v += lo16((uint32_t)bias[(eoff ? eoff[e] : (int64_t)e * N) + n0 + lane]);
+      const uint16_t yb = bf16_of(v);
+      yd[(size_t)row * N + n0 + lane] = yb;
+      o = fmaf(topk_w[j], lo16((uint32_t)yb), o);
+    }
+    __syncthreads();  // (red is free for the next choice)
+  }
+  if (wave == 0 && lane < C1_FPW) out[n0 + lane] = bf16_of(o);
+}
+
 template <int EPI, int ROWS, int FPW>
 int32_t launch_shape(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb, const uint16_t* bias,
                      const int32_t* offsets, uint16_t* out, const int32_t* row_map, const float* gate_w, const uint16_t* residual,
@@ -235,6 +307,20 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
 bool expert_gemv_applies(const moe_config* cfg, int N, int K) {
   static const bool off = [] { const char* e = getenv("MOESYS_NO_GEMV"); return e && atoi(e) != 0; }();
   return !off && cfg->dtype == MOE_BF16 && (int64_t)cfg->k * cfg->T <= GV_MAX_ROWS && N % (GV_WAVES * 8) == 0 && K % 8 == 0;
+}
+
+// Second product + combine of a one-token step (k >= 2); see the kernel.  residual nullable; out may be residual.
+bool expert_gemv_combine_one_token_applies(const moe_config* cfg) {
+  return cfg->T == 1 && cfg->k >= 2 && expert_gemv_applies(cfg, cfg->d_model, cfg->d_ff);
+}
+int32_t launch_expert_gemv_combine_one_token(const moe_config* cfg, const void* h, const void* w2, const void* bias,
+                                             const int32_t* offsets, const int32_t* a2r, const float* topk_w,
+                                             const void* residual, void* yd, void* out, const int64_t* eoff, hipStream_t s) {
+  if (!expert_gemv_combine_one_token_applies(cfg)) return fail(MOE_ERR_UNSUPPORTED, "expert GEMV: not a one-token step");
+  hipLaunchKernelGGL(expert_gemv_combine1_kernel, dim3(cfg->d_model / C1_FPW), dim3(GV_WAVES * 64), 0, s, (const uint16_t*)h,
+                     (const uint16_t*)w2, (const uint16_t*)bias, offsets, a2r, topk_w, (const uint16_t*)residual, (uint16_t*)yd,
+                     (uint16_t*)out, eoff, cfg->E, cfg->d_model, cfg->d_ff, cfg->k);
+  return check_hip(hipGetLastError(), "expert GEMV launch");
 }
 
 // epi: 0 GELU (+bias), 1 SwiGLU (wa = gate, wb = up), 2 plain (+bias), 3 combine for k = 1 (row_map = row_to_assign,

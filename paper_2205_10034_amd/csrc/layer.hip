@@ -96,6 +96,13 @@ int32_t experts_impl(const char* who, const moe_config* cfg, const moe_weights* 
     const int64_t C = moe_capacity(cfg);  // an expert gets at most T rows: no drops unless C is smaller
     if (C != MOE_DROPLESS && C < cfg->T)
       if ((st = launch_fill_dropped(cfg, sg.a2r, residual, out, s)) != MOE_OK) return st;
+  } else if (expert_gemv_combine_one_token_applies(cfg)) {
+    // a step of one token with several experts: the second product and the combine in one kernel (same yd, same out)
+    const bool sw = cfg->act == MOE_ACT_SWIGLU;
+    if ((st = launch_expert_gemv_combine_one_token(cfg, sg.h, sw ? w->w_down : w->w2, sw ? nullptr : w->b2, sg.offsets, sg.a2r,
+                                                   sg.topk_w, residual, sg.yd, out, w->expert_elem_offset, s)) != MOE_OK)
+      return st;
+    if ((st = mark(timer, 4, s)) != MOE_OK) return st;
   } else {
     if ((st = launch_gemm2(cfg, w, sg.h, sg.offsets, sg.yd, sg.tile_ctr, s)) != MOE_OK) return st;
     if ((st = mark(timer, 4, s)) != MOE_OK) return st;

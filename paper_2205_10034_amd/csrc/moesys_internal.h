@@ -32,6 +32,10 @@ constexpr int TILE_COUNTER_INTS = 16;
 size_t ffn_counter_offset(const moe_config* cfg);
 
 // Stage launchers (arguments already validated).
+bool expert_gemv_combine_one_token_applies(const moe_config* cfg);
+int32_t launch_expert_gemv_combine_one_token(const moe_config* cfg, const void* h, const void* w2, const void* bias,
+                                             const int32_t* offsets, const int32_t* a2r, const float* topk_w,
+                                             const void* residual, void* yd, void* out, const int64_t* eoff, hipStream_t s);
 bool gate_dispatch_one_token_applies(const moe_config* cfg, const float* w_router);
 int32_t launch_gate_dispatch_one_token(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                                        int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, int32_t* a2r,
