@@ -125,6 +125,9 @@ def test_combine_and_expert_ffn_backward(name, kw):
     ("gpt", dict(T=300, E=96, d_model=256, d_ff=256, k=3, capacity_factor=0.0)),   # experts in two register chunks, the second partial
     ("gpt", dict(T=200, E=128, d_model=256, d_ff=256, k=2, capacity_factor=2.0)),
     ("gpt", dict()),                          # the benchmark's configuration at full size, in its launch configuration
+    ("gpt", dict(T=4, E=8, d_model=256, d_ff=256, capacity_factor=0.0)),      # forward pass on the few-token kernels
+    ("gpt", dict(T=1, E=8, d_model=256, d_ff=256, capacity_factor=0.0)),
+    ("skew", dict(T=1, d_model=256, d_ff=512)),
     ("large", dict(T=700, E=4, d_model=256, d_ff=512)),                                         # SwiGLU experts
     ("large", dict(T=1500, E=8, d_model=512, d_ff=256, capacity_factor=0.6)),
     ("large", dict(T=900, E=8, d_model=256, d_ff=512, k=1, capacity_factor=0.0, renormalize=False)),
