@@ -87,10 +87,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-// gelu(u) = u * Phi(u).  Phi comes from a table in LDS: PHI_N entries (Phi(x_i), Phi(x_i+1) - Phi(x_i)) on
-// x_i = -PHI_RANGE + i / PHI_SCALE, filled once per workgroup with the exact erf, and read with linear
-// interpolation.  Interpolation error <= h^2/8 * max|Phi''| = (1/64)^2 / 8 * 0.242 = 7.4e-6, far below the
-// bf16 rounding of h; outside the range Phi is 0 or 1 to 6e-16.  A table read plus ~9 ALU operations
+// gelu(u) = u * Phi(u).  Phi comes from a table in LDS: PHI_N entries on x_i = -PHI_RANGE + i / PHI_SCALE, filled
+// once per workgroup with the exact erf, and read with linear interpolation.  An entry is the line through
+// (x_i, Phi(x_i)) and (x_i+1, Phi(x_i+1)) as (intercept, slope) in u itself, so that the interpolation is one
+// fused multiply-add of u (no fractional part to extract; the intercept is of order one, its rounding 1e-7).
+// Interpolation error <= h^2/8 * max|Phi''| = (1/64)^2 / 8 * 0.242 = 7.4e-6, far below the
+// bf16 rounding of h; outside the range Phi is 0 or 1 to 6e-16.  A table read plus ~8 ALU operations
 // replaces ~50 for the library erff: the activation runs on every element of h while the matrix pipes
 // wait, so its instruction count is what the GEMM1 epilogue costs.
 constexpr int PHI_N = 1024;
@@ -100,7 +102,9 @@ __device__ __forceinline__ void fill_phi_table(f32x2* tab) {
   for (int i = threadIdx.x; i < PHI_N; i += blockDim.x) {
     const float x0 = -PHI_RANGE + (float)i / PHI_SCALE, x1 = -PHI_RANGE + (float)(i + 1) / PHI_SCALE;
     const float p0 = 0.5f * erfcf(-x0 * 0.70710678118654752f), p1 = 0.5f * erfcf(-x1 * 0.70710678118654752f);
-    tab[i] = f32x2{p0, p1 - p0};
+    // the two end cells also serve everything outside the range: constants there (Phi is 0 or 1 to 6e-16)
+    const float slope = (i == 0 || i == PHI_N - 1) ? 0.f : (p1 - p0) * PHI_SCALE;
+    tab[i] = f32x2{p0 - slope * x0, slope};
   }
 }
 // B values at a time, in three passes: table positions, the B table reads back to back, the
@@ -116,7 +120,7 @@ __device__ __forceinline__ void gelu_table_n(float* u, const f32x2* tab) {
 #pragma unroll
   for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
 #pragma unroll
-  for (int r = 0; r < B; ++r) u[r] *= fmaf(__builtin_amdgcn_fractf(t[r]), e[r].y, e[r].x);  // t >= 0: fract(t) = t - floor(t)
+  for (int r = 0; r < B; ++r) u[r] *= fmaf(u[r], e[r].y, e[r].x);
 }
 // The backward pass's table: gelu'(u) = Phi(u) + u phi(u) on the same grid, filled with the exact erf and exp.
 // Interpolation error <= h^2/8 * max|third derivative of gelu| = (1/64)^2 / 8 * 0.8 = 2.5e-5 on a factor of
@@ -126,9 +130,10 @@ __device__ __forceinline__ float gelu_prime_exact(float x) {
 }
 __device__ __forceinline__ void fill_gelu_prime_table(f32x2* tab) {
   for (int i = threadIdx.x; i < PHI_N; i += blockDim.x) {
-    const float g0 = gelu_prime_exact(-PHI_RANGE + (float)i / PHI_SCALE);
-    const float g1 = gelu_prime_exact(-PHI_RANGE + (float)(i + 1) / PHI_SCALE);
-    tab[i] = f32x2{g0, g1 - g0};
+    const float x0 = -PHI_RANGE + (float)i / PHI_SCALE;
+    const float g0 = gelu_prime_exact(x0), g1 = gelu_prime_exact(-PHI_RANGE + (float)(i + 1) / PHI_SCALE);
+    const float slope = (i == 0 || i == PHI_N - 1) ? 0.f : (g1 - g0) * PHI_SCALE;  // (end cells: constants)
+    tab[i] = f32x2{g0 - slope * x0, slope};  // (intercept, slope), as in the forward table
   }
 }
 // u[r] <- dh[r] * gelu'(u[r]), gelu' read from its table like Phi in the forward pass
@@ -142,7 +147,7 @@ __device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, const f
 #pragma unroll
   for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
 #pragma unroll
-  for (int r = 0; r < B; ++r) u[r] = dh[r] * fmaf(__builtin_amdgcn_fractf(t[r]), e[r].y, e[r].x);
+  for (int r = 0; r < B; ++r) u[r] = dh[r] * fmaf(u[r], e[r].y, e[r].x);
 }
 __device__ __forceinline__ float silu(float u) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)); }
 
