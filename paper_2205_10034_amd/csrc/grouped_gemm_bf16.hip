@@ -107,18 +107,32 @@ __device__ __forceinline__ void fill_phi_table(f32x2* tab) {
     tab[i] = f32x2{p0 - slope * x0, slope};
   }
 }
+// LDS address of the table cell of u (entries of 8 bytes).  u is clamped into the range, scaled to bytes and added
+// to 2^23 + the table's own LDS address: at that magnitude a float's unit in the last place is 1, so the sum's
+// low mantissa bits ARE the rounded address, and masking the low three bits (the table is 8-byte aligned) and the
+// bits above the LDS leaves the cell's address.  (Rounding to nearest instead of down moves the upper sixteenth
+// of a cell to the next cell's line, read h/16 outside its cell: error f'' h^2 / 32, below the h^2 / 8 inside a
+// cell.)  Three instructions (clamp, multiply-add, mask) where convert-to-integer, shift and base add took four.
+constexpr float PHI_CLAMP_HI = PHI_RANGE - 1.0f / 256.0f;
+typedef __attribute__((address_space(3))) const f32x2* phi_lds_ptr;
+// the addend of phi_cell(): 2^23 + (offset of u = 0 in bytes) + the table's LDS address
+__device__ __forceinline__ float phi_addend(const f32x2* tab) {
+  const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)tab;
+  return 8388608.0f + PHI_RANGE * PHI_SCALE * 8.0f + (float)base;  // (all integers below 2^24: exact)
+}
+__device__ __forceinline__ f32x2 phi_cell(float u, float addend) {
+  const float c = __builtin_amdgcn_fmed3f(u, -PHI_RANGE, PHI_CLAMP_HI);
+  const float tm = fmaf(c, PHI_SCALE * 8.0f, addend);
+  return *(phi_lds_ptr)(uintptr_t)(__float_as_uint(tm) & 0x3fff8u);  // (LDS addresses are below 2^18)
+}
 // B values at a time, in three passes: table positions, the B table reads back to back, the
 // interpolations.  (One value at a time the compiler waits for every read before it starts the next
 // value, and the epilogue then runs at the latency of the LDS instead of at the rate of the vector ALU.)
 template <int B>
-__device__ __forceinline__ void gelu_table_n(float* u, const f32x2* tab) {
-  float t[B];
+__device__ __forceinline__ void gelu_table_n(float* u, float addend) {
   f32x2 e[B];
 #pragma unroll
-  for (int r = 0; r < B; ++r)
-    t[r] = __builtin_amdgcn_fmed3f(fmaf(u[r], PHI_SCALE, PHI_RANGE * PHI_SCALE), 0.0f, (float)PHI_N - 0.001f);
-#pragma unroll
-  for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
+  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend);
 #pragma unroll
   for (int r = 0; r < B; ++r) u[r] *= fmaf(u[r], e[r].y, e[r].x);
 }
@@ -138,14 +152,10 @@ __device__ __forceinline__ void fill_gelu_prime_table(f32x2* tab) {
 }
 // u[r] <- dh[r] * gelu'(u[r]), gelu' read from its table like Phi in the forward pass
 template <int B>
-__device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, const f32x2* tab) {
-  float t[B];
+__device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, float addend) {
   f32x2 e[B];
 #pragma unroll
-  for (int r = 0; r < B; ++r)
-    t[r] = __builtin_amdgcn_fmed3f(fmaf(u[r], PHI_SCALE, PHI_RANGE * PHI_SCALE), 0.0f, (float)PHI_N - 0.001f);
-#pragma unroll
-  for (int r = 0; r < B; ++r) e[r] = tab[(int)t[r]];
+  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend);
 #pragma unroll
   for (int r = 0; r < B; ++r) u[r] = dh[r] * fmaf(u[r], e[r].y, e[r].x);
 }
@@ -339,6 +349,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   if (clear_ctr && blockIdx.x == 0 && tid < NUM_XCD) clear_ctr[tid] = 0;
   if (EPI == EPI_GELU) fill_phi_table(s_phi);
   if (EPI == EPI_DGELU) fill_gelu_prime_table(s_phi);
+  const float phi_add = phi_addend(s_phi);
   count_token_tiles(offsets, E, TOK, s_pref);  // ends with a barrier: s_pref and the table are visible
   TileWalker<TOK, 32 * WT> walk;
   walk.init(s_pref[E], n_tiles);
@@ -785,7 +796,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             if (EPI == EPI_GELU) {
               constexpr int GB = TOK > 256 ? 4 : 8;  // (8 at a time spills in the 320-row kernel)
 #pragma unroll
-              for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, s_phi);
+              for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, phi_add);
             }
             if constexpr (EPI == EPI_DGELU) {
               // (every element is read by the lane that multiplies it, before the lanes trade halves and before
@@ -809,7 +820,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
                 dh[4 * g + 3] = __uint_as_float(rv.y & 0xffff0000u);
               }
 #pragma unroll
-              for (int r = 0; r < 8; r += 4) dgelu_table_n<4>(p + r, dh + r, s_phi);
+              for (int r = 0; r < 8; r += 4) dgelu_table_n<4>(p + r, dh + r, phi_add);
             }
             if constexpr (EPI == EPI_COMBINE) {
               // before the lanes trade halves: this lane's 4 + 4 features of the residual row
