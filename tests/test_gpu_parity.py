@@ -404,7 +404,10 @@ def test_layer_forward_top1_writes_every_token(with_bias):
 
 @pytest.mark.parametrize("name,kw", [("gpt", dict(T=1500, E=8)), ("gpt", dict(T=40, E=16, k=2, capacity_factor=0.0)),
                                      ("skew", dict(T=2000)), ("large", dict(T=900, d_model=512, d_ff=1024, E=4)),
-                                     ("ring", dict(T=64, d_model=512, d_ff=1024, E=64, capacity_factor=0.0))],
+                                     ("ring", dict(T=64, d_model=512, d_ff=1024, E=64, capacity_factor=0.0)),
+                                     # few tokens: the matrix-vector kernels read the scattered experts too
+                                     ("skew", dict(T=3, d_model=256, d_ff=512)), ("gpt", dict(T=1, E=16, d_model=256, d_ff=512)),
+                                     ("large", dict(T=6, d_model=512, d_ff=1024, E=4))],
                          ids=lambda v: str(v).replace(" ", ""))
 def test_layer_with_experts_scattered_over_a_pool(name, kw):
     """Route, then experts, with every expert's parameters in its own slot of a pool (shuffled slots, one
