@@ -110,11 +110,12 @@ typedef struct {
   size_t expert_offsets; /* int32 [E+1]  first dispatched row of each expert    */
   size_t assign_to_row;  /* int32 [k*T]  row of assignment a=j*T+t, -1 dropped  */
   size_t row_to_assign;  /* int32 [k*T]  first R entries valid                  */
-  size_t xd;             /* dtype [R_max,d_model] dispatched rows (MOE_F32 only: the
-                            bf16 FFN gathers its rows from x through row_to_assign) */
+  size_t xd;             /* dtype [R_max,d_model] dispatched rows.  MOE_BF16: an empty
+                            segment (the FFN gathers its rows from x through
+                            row_to_assign), unless T*d_model*2 >= 2^31             */
   size_t h;              /* dtype [R_max,d_ff]    hidden activations            */
-  size_t yd;             /* dtype [R_max,d_model] expert outputs (not written when k == 1
-                            in MOE_BF16: the second GEMM then writes `out` itself)    */
+  size_t yd;             /* dtype [R_max,d_model] expert outputs.  MOE_BF16 with k == 1: an
+                            empty segment (the second GEMM writes `out` itself)       */
   size_t scratch;        /* dispatch bookkeeping scratch                        */
   size_t tile_counters;  /* int32 [16] work counters of the two grouped GEMMs   */
   size_t total;          /* == moe_workspace_bytes(cfg, MOE_WS_LAYER)           */
@@ -145,6 +146,19 @@ int32_t moe_capacity(const moe_config* cfg);
  * must be 256-byte aligned.  Returns 0 on an invalid cfg. */
 size_t moe_workspace_bytes(const moe_config* cfg, int32_t kind);
 int32_t moe_workspace_layout(const moe_config* cfg, moe_ws_layout* out);
+
+/* Process-wide tuning switches, for experiments and tests; every value gives the same
+ * results, only the kernels that compute them differ.  Set them while no call of the
+ * library is running on another thread.
+ *   MOE_TUNE_GEMM_TILE_ROWS    token rows per tile of the bf16 grouped GEMM: 256 or 320;
+ *                              0 (default) = chosen per call from the expected rows per expert
+ *   MOE_TUNE_FEW_TOKEN_KERNELS 1 (default): steps of at most 16 tokens / assignments use the
+ *                              matrix-vector expert kernels and the one-workgroup-per-token
+ *                              gate; 0: the general kernels at every size
+ * moe_set_tuning returns MOE_ERR_INVALID_ARG for an unknown key or value. */
+typedef enum { MOE_TUNE_GEMM_TILE_ROWS = 0, MOE_TUNE_FEW_TOKEN_KERNELS = 1, MOE_TUNE_COUNT = 2 } moe_tuning_key;
+int32_t moe_set_tuning(int32_t key, int32_t value);
+int32_t moe_get_tuning(int32_t key, int32_t* value);
 
 /* ---- the hot path -------------------------------------------------------- */
 
@@ -221,7 +235,9 @@ int32_t moe_layer_forward(const moe_config* cfg, const moe_weights* w, const voi
  * are the only weights read); moe_layer_experts runs expert FFN and combine
  * from what moe_layer_route left in the same workspace.  Same arguments,
  * workspace and rules as moe_layer_forward; calling one after the other is
- * moe_layer_forward. */
+ * moe_layer_forward.  moe_layer_experts leaves the routing tables as it found
+ * them, so it may run again on the same workspace (e.g. with other expert
+ * weights, or after a failed load) without a new moe_layer_route. */
 int32_t moe_layer_route(const moe_config* cfg, const moe_weights* w, const void* x, void* ws,
                         size_t ws_bytes, void* stream);
 int32_t moe_layer_experts(const moe_config* cfg, const moe_weights* w, const void* x,

@@ -135,6 +135,8 @@ def lib() -> C.CDLL:
         L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
         L.moe_expert_pool_stats.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 5
         L.moe_expert_pool_destroy.argtypes = [vp]
+        L.moe_set_tuning.argtypes = [C.c_int32, C.c_int32]
+        L.moe_get_tuning.argtypes = [C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -196,6 +198,19 @@ class Weights:
                           g("w_router"), g("b_router"),
                           MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR,
                           g("expert_elem_offset"))
+
+
+MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS = 0, 1
+
+
+def moe_set_tuning(key: int, value: int) -> None:
+    _check(lib().moe_set_tuning(key, value), "moe_set_tuning")
+
+
+def moe_get_tuning(key: int) -> int:
+    v = C.c_int32()
+    _check(lib().moe_get_tuning(key, C.byref(v)), "moe_get_tuning")
+    return v.value
 
 
 def moe_capacity(cfg: MoEConfig) -> int:

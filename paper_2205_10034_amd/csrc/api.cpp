@@ -1,4 +1,5 @@
 // Host-side part of the C ABI: validation, capacity, workspace layout, error text.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cmath>
@@ -21,6 +22,10 @@ int32_t check_hip(hipError_t e, const char* what) {
   if (e == hipSuccess) return MOE_OK;
   return fail(MOE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
+
+static std::atomic<int32_t> g_tuning[MOE_TUNE_COUNT] = {{0}, {1}};
+
+int32_t tuning(int32_t key) { return g_tuning[key].load(std::memory_order_relaxed); }
 
 static int32_t check_cfg(const moe_config* c) {
   if (!c) return fail(MOE_ERR_INVALID_ARG, "cfg is NULL");
@@ -82,9 +87,11 @@ static void layout_of(const moe_config* c, moe_ws_layout* L) {
   L->expert_offsets = take((size_t)(c->E + 1) * 4);
   L->assign_to_row = take(A * 4);
   L->row_to_assign = take(A * 4);
-  L->xd = take(R * c->d_model * s);
+  // segments that the bf16 path never writes are empty (the first GEMM gathers from x; with k = 1 the
+  // second GEMM writes `out`)
+  L->xd = take(gemm1_can_gather(c) ? 0 : R * c->d_model * s);
   L->h = take(R * c->d_ff * s);
-  L->yd = take(R * c->d_model * s);
+  L->yd = take(gemm2_can_combine(c) ? 0 : R * c->d_model * s);
   L->scratch = take(((size_t)dispatch_blocks(c) + 1) * c->E * 4 + 256);
   L->tile_counters = take(TILE_COUNTER_INTS * 4);
   L->total = off;
@@ -127,7 +134,28 @@ const char* moe_status_string(int32_t st) {
 }
 
 const char* moe_last_error(void) { return g_err; }
-int32_t moe_version(void) { return 100; }
+int32_t moe_version(void) { return 200; }
+
+int32_t moe_set_tuning(int32_t key, int32_t value) {
+  switch (key) {
+    case MOE_TUNE_GEMM_TILE_ROWS:
+      if (value != 0 && value != 256 && value != 320)
+        return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: tile rows must be 0, 256 or 320 (got %d)", value);
+      break;
+    case MOE_TUNE_FEW_TOKEN_KERNELS:
+      if (value != 0 && value != 1) return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: switch must be 0 or 1 (got %d)", value);
+      break;
+    default: return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: key %d unknown", key);
+  }
+  g_tuning[key].store(value, std::memory_order_relaxed);
+  return MOE_OK;
+}
+
+int32_t moe_get_tuning(int32_t key, int32_t* value) {
+  if (key < 0 || key >= MOE_TUNE_COUNT || !value) return fail(MOE_ERR_INVALID_ARG, "moe_get_tuning: key %d unknown or value NULL", key);
+  *value = tuning(key);
+  return MOE_OK;
+}
 int32_t moe_config_check(const moe_config* cfg) { return check_cfg(cfg); }
 
 int32_t moe_capacity(const moe_config* cfg) {

@@ -305,8 +305,7 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
 // Whether the few-row path serves this product: so few assignments that no expert exceeds GV_MAX_ROWS rows,
 // whole workgroups of output features, 16-byte chunks of the contraction index.
 bool expert_gemv_applies(const moe_config* cfg, int N, int K) {
-  static const bool off = [] { const char* e = getenv("MOESYS_NO_GEMV"); return e && atoi(e) != 0; }();
-  return !off && cfg->dtype == MOE_BF16 && (int64_t)cfg->k * cfg->T <= GV_MAX_ROWS && N % (GV_WAVES * 8) == 0 && K % 8 == 0;
+  return tuning(MOE_TUNE_FEW_TOKEN_KERNELS) != 0 && cfg->dtype == MOE_BF16 && (int64_t)cfg->k * cfg->T <= GV_MAX_ROWS && N % (GV_WAVES * 8) == 0 && K % 8 == 0;
 }
 
 // Second product + combine of a one-token step (k >= 2); see the kernel.  residual nullable; out may be residual.

@@ -277,9 +277,8 @@ __global__ __launch_bounds__(FEW_THREADS) void gate_few_kernel(
 
 // the shapes the kernel above is written for
 bool gate_few_applies(const moe_config* cfg, const float* w_router) {
-  static const bool off = [] { const char* e = getenv("MOESYS_NO_GATE_FEW"); return e && atoi(e) != 0; }();
   const int E = cfg->E;
-  return !off && cfg->T <= FEW_MAX_T && (E == 4 || E == 8 || E == 16 || E == 32 || E == 64) &&
+  return tuning(MOE_TUNE_FEW_TOKEN_KERNELS) != 0 && cfg->T <= FEW_MAX_T && (E == 4 || E == 8 || E == 16 || E == 32 || E == 64) &&
          (reinterpret_cast<uintptr_t>(w_router) & 15) == 0;
 }
 

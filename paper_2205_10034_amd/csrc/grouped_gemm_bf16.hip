@@ -910,7 +910,7 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
 // tiles (one round) or 320 (two).  The choice is made for the row count an evenly loaded expert would get,
 // with head-room for uneven routing and capped by the capacity; either kernel handles any routing.
 int pick_tile_rows(const moe_config* cfg, int n_tiles) {
-  static const int forced = [] { const char* e = getenv("MOESYS_GEMM_TOK"); return e ? atoi(e) : 0; }();
+  const int forced = tuning(MOE_TUNE_GEMM_TILE_ROWS);
   if (forced == 256 || forced == 320) return forced;
   const int64_t A = (int64_t)cfg->k * cfg->T;
   int64_t rows = (A + cfg->E - 1) / cfg->E;
@@ -974,7 +974,9 @@ int32_t launch_gemm1_bf16(const moe_config* cfg, const moe_weights* w, const voi
     return launch_expert_gemv_bf16(EPI_GELU, cfg, xd, w->w1, nullptr, w->b1, offsets, h, row_map, nullptr, nullptr,
                                    w->expert_elem_offset, cfg->d_ff, cfg->d_model, s);
   }
-  // the first GEMM draws from counters [0,8) and clears [8,16) for the second
+  // the first GEMM draws from counters [0,8) and clears [8,16) for the second, which in turn clears [0,8): after
+  // the pair has run the first GEMM's counters are back at zero, so the expert half of a layer can run again
+  // on the same routing tables
   if (cfg->act == MOE_ACT_SWIGLU)
     return gemm_any<EPI_SWIGLU>(
         cfg, (const uint16_t*)xd, (const uint16_t*)w->w_gate_proj, (const uint16_t*)w->w_up, nullptr, offsets,
@@ -992,7 +994,7 @@ int32_t launch_gemm2_bf16(const moe_config* cfg, const moe_weights* w, const voi
                                    nullptr, nullptr, w->expert_elem_offset, cfg->d_model, cfg->d_ff, s);
   return gemm_any<EPI_BIAS>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
-      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, nullptr,
+      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)yd, nullptr, tile_counters + NUM_XCD, tile_counters,
       cfg->d_model, cfg->d_ff, s, w->expert_elem_offset);
 }
 
@@ -1007,7 +1009,7 @@ int32_t launch_gemm2_combine_bf16(const moe_config* cfg, const moe_weights* w, c
                                    row_to_assign, topk_w, residual, w->expert_elem_offset, cfg->d_model, cfg->d_ff, s);
   return gemm_any<EPI_COMBINE>(
       cfg, (const uint16_t*)h, (const uint16_t*)(sw ? w->w_down : w->w2), nullptr,
-      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)out, row_to_assign, tile_counters + NUM_XCD, nullptr,
+      (const uint16_t*)(sw ? nullptr : w->b2), offsets, (uint16_t*)out, row_to_assign, tile_counters + NUM_XCD, tile_counters,
       cfg->d_model, cfg->d_ff, s, w->expert_elem_offset, topk_w, (const uint16_t*)residual);
 }
 

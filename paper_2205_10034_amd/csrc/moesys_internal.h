@@ -14,6 +14,9 @@ int32_t check_hip(hipError_t e, const char* what);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t elem_size(int32_t dtype) { return dtype == MOE_BF16 ? 2 : 4; }
 
+// Current value of a moe_tuning_key (moe_set_tuning).
+int32_t tuning(int32_t key);
+
 // Upper bound of dispatched rows: min(k*T, E*C).
 int64_t max_rows(const moe_config* cfg);
 

@@ -2,9 +2,9 @@
 (d_model 2048, d_ff 8192, 64 experts, top-2, bf16: 64 MiB per expert) run with 1 ... 256 tokens per step.
 With so few tokens the layer's time is the time to stream the activated experts' weights once; up to 16
 assignments per step the expert products run on the matrix-vector kernels instead of MFMA tiles
-(MOESYS_NO_GEMV=1 switches them off, for comparison).
+(``--general-kernels`` switches them off through moe_set_tuning, for comparison).
 
-    python -m paper_2205_10034_amd.decode_bench [--tokens 1,2,4,8,16,32,64,128,256] [--steps 50]
+    python -m paper_2205_10034_amd.decode_bench [--tokens 1,2,4,8,16,32,64,128,256] [--steps 50] [--general-kernels]
 
 One JSON line per batch size.
 """
@@ -22,9 +22,12 @@ def main():
     ap.add_argument("--tokens", default="1,2,4,8,16,32,64,128,256")
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--general-kernels", action="store_true")
     args = ap.parse_args()
     import torch
     import paper_2205_10034_amd as M
+    if args.general_kernels:
+        M.moe_set_tuning(M.MOE_TUNE_FEW_TOKEN_KERNELS, 0)
     from workloads import WORKLOADS
 
     base = WORKLOADS["ring"]
@@ -58,7 +61,7 @@ def main():
             "workload": f"ring layer, resident: T={T} d_model={d} d_ff={f} E={E} top-{wl.k}",
             "layer_us": ms * 1e3, "tokens_per_s": T / (ms * 1e-3), "experts_activated": active,
             "weights_streamed_mib": wbytes / 2 ** 20, "weights_tb_per_s": wbytes / (ms * 1e-3) / 1e12,
-            "matrix_vector_kernels": wl.k * T <= 16 and os.environ.get("MOESYS_NO_GEMV", "0") in ("", "0"),
+            "matrix_vector_kernels": wl.k * T <= 16 and not args.general_kernels,
         }), flush=True)
 
 

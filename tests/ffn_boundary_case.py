@@ -1,8 +1,7 @@
 """Grouped-GEMM tile boundaries: moe_expert_ffn on hand-made expert_offsets against the oracle.
 
-Run by tests/test_gpu_tiles.py in this process (default tile capacity) and in child processes with
-MOESYS_GEMM_TOK=256 / 320, which pins the kernel's tile capacity (the variable is read once per
-process).  Row counts sit on and around every boundary of the token tiling: empty experts, 1 row,
+Run by tests/test_gpu_tiles.py with the default tile capacity and with the capacity pinned to 256 and
+to 320 rows through moe_set_tuning.  Row counts sit on and around every boundary of the token tiling: empty experts, 1 row,
 one 64-row unit +-1, one tile +-1 for both capacities, several tiles with a short or an almost
 full remainder.  Exits non-zero (or raises) on a mismatch.
 """
@@ -59,7 +58,7 @@ def run_case(rows, act, d_model, d_ff, seed, bias=True):
 
 
 def main():
-    print("tile capacity override:", os.environ.get("MOESYS_GEMM_TOK", "(default)"), flush=True)
+    print("tile capacity override:", M.moe_get_tuning(M.MOE_TUNE_GEMM_TILE_ROWS) or "(default)", flush=True)
     for i, rows in enumerate(ROW_SETS):
         run_case(rows, "gelu", 256, 512, 100 + i)
     run_case(ROW_SETS[0], "swiglu", 256, 256, 200)

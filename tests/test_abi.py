@@ -89,6 +89,19 @@ def test_null_and_workspace_errors_launch_nothing():
     assert L.moe_timer_read(None, None) == 1
 
 
+def test_tuning_switches_validate_and_round_trip():
+    assert M.moe_get_tuning(M.MOE_TUNE_GEMM_TILE_ROWS) == 0
+    assert M.moe_get_tuning(M.MOE_TUNE_FEW_TOKEN_KERNELS) == 1
+    for v in (256, 320, 0):
+        M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, v)
+        assert M.moe_get_tuning(M.MOE_TUNE_GEMM_TILE_ROWS) == v
+    assert M.lib().moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 128) == 1
+    assert M.moe_get_tuning(M.MOE_TUNE_GEMM_TILE_ROWS) == 0
+    assert M.lib().moe_set_tuning(M.MOE_TUNE_FEW_TOKEN_KERNELS, 2) == 1
+    assert M.lib().moe_set_tuning(7, 0) == 1
+    assert M.lib().moe_get_tuning(7, None) == 1
+
+
 def test_workspace_layout_is_consistent():
     for kw in [dict(T=8192, d_model=1024, d_ff=4096, E=16, k=2, capacity_factor=1.25),
                dict(T=16384, d_model=768, d_ff=3072, E=8, k=1, capacity_factor=0.0),
@@ -104,8 +117,16 @@ def test_workspace_layout_is_consistent():
         offs = [L[n] for n in order]
         assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
         s = 2 if cfg.dtype == "bf16" else 4
-        assert L["h"] - L["xd"] >= L["r_max"] * cfg.d_model * s
+        # segments the bf16 path never writes are empty: xd (rows are gathered from x), yd when k = 1
+        if cfg.dtype == "bf16":
+            assert L["h"] == L["xd"]
+        else:
+            assert L["h"] - L["xd"] >= L["r_max"] * cfg.d_model * s
         assert L["yd"] - L["h"] >= L["r_max"] * cfg.d_ff * s
+        if cfg.dtype == "bf16" and cfg.k == 1:
+            assert L["scratch"] == L["yd"]
+        else:
+            assert L["scratch"] - L["yd"] >= L["r_max"] * cfg.d_model * s
         assert L["total"] - L["tile_counters"] >= 16 * 4
         assert M.moe_workspace_bytes(cfg, 2) >= L["r_max"] * cfg.d_ff * s + 16 * 4
 

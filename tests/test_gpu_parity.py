@@ -13,6 +13,7 @@ from oracle import moe_oracle as O
 from workloads import WORKLOADS, make_layer
 
 from gpu_util import alloc_ws, rel_fro, run_layer, tdtype, to_dev, to_np, upload_weights, ws_view
+from oracle_sampling import oracle_out_for_tokens
 
 pytestmark = pytest.mark.gpu
 
@@ -264,6 +265,21 @@ LAYER_CASES = [
 ]
 
 
+def max_block_err(got, ref, rows):
+    """Largest relative Frobenius error over blocks of `rows` consecutive rows (blocks whose reference is all
+    zero - tokens with every choice dropped - must be zero in `got` too)."""
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    n = (len(ref) // rows) * rows
+    worst = 0.0
+    for a, b in ((got[:n].reshape(-1, rows * ref.shape[1]), ref[:n].reshape(-1, rows * ref.shape[1])), (got[n:].reshape(1, -1), ref[n:].reshape(1, -1))):
+        if b.size == 0:
+            continue
+        num, den = np.linalg.norm(a - b, axis=1), np.linalg.norm(b, axis=1)
+        assert np.all(num[den == 0] == 0)
+        worst = max(worst, float(np.max(num[den > 0] / den[den > 0], initial=0.0)))
+    return worst
+
+
 def top1_fused(wl):
     """One expert per token in bf16: no dispatched-order output exists, the second GEMM writes `out`."""
     return wl.k == 1 and wl.dtype == "bf16"
@@ -310,6 +326,18 @@ def test_layer_forward_full_size(name):
     e_out = rel_fro(r["out"], ref["out"])
     print(f"{name}: loads {ref['expert_counts'].tolist()} rel fro yd {e_yd:.3e} out {e_out:.3e}", flush=True)
     assert e_yd < BF16_TOL and e_out < BF16_TOL
+    # the same bar on every block of 64 consecutive tokens and, for the dispatched-order output, on every
+    # block of 64 rows and every expert (a wrong tile cannot hide in the whole-matrix norm); three times the bar
+    # on every single token (one row's rounding errors do not average out as a block's do)
+    worst_blk, worst_tok = max_block_err(r["out"], ref["out"], 64), max_block_err(r["out"], ref["out"], 1)
+    print(f"{name}: worst 64-token block {worst_blk:.3e}, worst token {worst_tok:.3e}", flush=True)
+    assert worst_blk < BF16_TOL and worst_tok < 3 * BF16_TOL
+    if not top1_fused(wl):
+        assert max_block_err(r["yd"], ref["yd"], 64) < BF16_TOL
+        off = ref["expert_offsets"]
+        for e in range(wl.E):
+            if off[e + 1] > off[e]:
+                assert rel_fro(r["yd"][off[e]:off[e + 1]], ref["yd"][off[e]:off[e + 1]]) < BF16_TOL
 
 
 def test_layer_forward_large_sampled():
@@ -328,17 +356,44 @@ def test_layer_forward_large_sampled():
     assert np.array_equal(r["expert_counts"], counts) and np.array_equal(r["expert_offsets"], offsets)
     assert np.array_equal(r["assign_to_row"], a2r) and np.array_equal(r["row_to_assign"], r2a)
     assert (a2r < 0).any()                                   # capacity factor 1.0 drops some
-    R = int(offsets[-1])
+    # Sampled tokens, chosen by construction so that no tile position can be wrong unseen: the first and last
+    # row of every expert; both sides of every 256-row boundary of the fullest and the emptiest expert and of
+    # every 320-row boundary of the fullest (the tile capacities of the grouped GEMM); the last rows of every
+    # expert's last 64-row unit; tokens of every pattern of dropped choices; and random ones.
     rng = np.random.default_rng(0)
-    dropped_tok = np.nonzero((a2r[:wl.T] < 0) | (a2r[wl.T:] < 0))[0][:8]
-    toks = np.unique(np.concatenate([rng.integers(0, wl.T, 40), dropped_tok, [0, wl.T - 1]]))
+    rows = []
+    for e in range(wl.E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            rows += [lo, hi - 1, lo + (hi - lo - 1) // 64 * 64]
+    fullest, emptiest = int(np.argmax(counts)), int(np.argmin(counts))
+    for e, step in ((fullest, 256), (emptiest, 256), (fullest, 320)):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        for b in range(lo + step, hi, step):
+            rows += [b - 1, b]
+    toks = [int(r2a[r_]) % wl.T for r_ in rows]
+    kept = (a2r.reshape(wl.k, wl.T) >= 0)
+    for pattern in ((True, True), (True, False), (False, True), (False, False)):
+        hit = np.nonzero((kept[0] == pattern[0]) & (kept[1] == pattern[1]))[0]
+        print(f"large: {len(hit)} tokens with (first, second) choice kept = {pattern}", flush=True)
+        toks += hit[:6].tolist() + hit[-2:].tolist()
+    toks = np.unique(np.concatenate([np.array(toks, dtype=np.int64), rng.integers(0, wl.T, 40), [0, wl.T - 1]]))
     plan = dict(topk_idx=idx, topk_w=w, assign_to_row=a2r)
-    ref = O.sampled_tokens_forward(L["x"], L, plan, toks, act=wl.act)
-    err = rel_fro(r["out"][toks], ref)
-    print(f"large: loads {counts.tolist()} dropped {(a2r < 0).sum()} sampled rel fro {err:.3e}", flush=True)
+    ref = oracle_out_for_tokens(O, L["x"], L, plan, toks, act=wl.act)
+    got = r["out"][toks]
+    err = rel_fro(got, ref)
+    print(f"large: loads {counts.tolist()} dropped {(a2r < 0).sum()} sampled tokens {len(toks)} rel fro {err:.3e}", flush=True)
     assert err < BF16_TOL
     for i, t in enumerate(toks):
-        assert rel_fro(r["out"][t], ref[i]) < 3 * BF16_TOL
+        if np.any(ref[i]):
+            assert rel_fro(got[i], ref[i]) < 3 * BF16_TOL, f"token {t}"
+        else:
+            assert not np.any(got[i]), f"token {t}: every choice dropped, output must be zero"
+    # properties that hold at any size, over ALL tokens: a token whose choices were all dropped is exactly zero;
+    # every other row is finite and non-zero
+    all_dropped = ~kept.any(axis=0)
+    assert not np.any(r["out"][all_dropped])
+    assert np.isfinite(r["out"]).all() and np.all(np.any(r["out"][~all_dropped] != 0, axis=1))
 
 
 def test_layer_forward_ring_layer_full_size_sampled():
@@ -455,6 +510,26 @@ def test_layer_with_experts_scattered_over_a_pool(name, kw):
     M.moe_layer_experts(cfg, Wp, x, None, out, ws)
     torch.cuda.synchronize()
     assert torch.equal(out, want["out_tensor"])
+
+
+def test_layer_experts_runs_again_on_the_same_routing():
+    """moe_layer_route once, moe_layer_experts twice (and a third time after another layer's whole forward
+    on a second workspace): the expert half leaves the routing tables and its own work counters as it found
+    them, so every run gives the same bits as moe_layer_forward."""
+    for name, kw in (("gpt", dict(T=2048, E=8)), ("skew", dict(T=3001)), ("large", dict(T=1536, d_model=512, d_ff=1024, E=4))):
+        wl = small(name, **kw)
+        L = make_layer(wl, with_bias=True)
+        cfg = M.MoEConfig.from_workload(wl)
+        W = upload_weights(L, wl.dtype)
+        x = to_dev(L["x"], wl.dtype)
+        want = run_layer(cfg, W, x)["out_tensor"]
+        ws = alloc_ws(cfg)
+        M.moe_layer_route(cfg, W, x, ws)
+        for rep in range(3):
+            out = torch.full_like(x, float("nan"))
+            M.moe_layer_experts(cfg, W, x, None, out, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(out, want), f"{name}: run {rep} of the expert half differs"
 
 
 def test_determinism():

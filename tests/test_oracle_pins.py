@@ -357,6 +357,16 @@ def test_layer_bruteforce_token_by_token():
         assert np.allclose(r["out"][t], ref, rtol=1e-11, atol=1e-13)
     samp = O.sampled_tokens_forward(L["x"], L, r, np.array([0, 5, 39]), act="gelu")
     assert np.allclose(samp, r["out"][[0, 5, 39]], rtol=1e-12, atol=1e-13)
+    # the tests' grouped sampling (one FFN call per expert over the sampled rows) gives the same rows,
+    # with drops, with and without a residual, in any token order
+    from oracle_sampling import oracle_out_for_tokens
+    toks = np.array([39, 0, 5, 17, 18, 2])
+    assert ((r["assign_to_row"].reshape(2, 40)[:, toks] < 0).any())          # some sampled choice is dropped
+    grp = oracle_out_for_tokens(O, L["x"], L, r, toks, act="gelu")
+    assert np.allclose(grp, r["out"][toks], rtol=1e-12, atol=1e-13)
+    res = np.random.default_rng(3).standard_normal(L["x"].shape)
+    grp = oracle_out_for_tokens(O, L["x"], L, r, toks, act="gelu", residual=res)
+    assert np.allclose(grp, r["out"][toks] + res[toks], rtol=1e-12, atol=1e-13)
 
 
 def test_token_permutation_equivariance_when_dropless():
