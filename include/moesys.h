@@ -191,6 +191,20 @@ int32_t moe_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_i
                      int32_t* expert_counts, int32_t* expert_offsets, int32_t* assign_to_row,
                      int32_t* row_to_assign, void* xd, void* ws, size_t ws_bytes, void* stream);
 
+/* moe_dispatch for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, tables and results as moe_dispatch, without ws: the bookkeeping scratch is a
+ * static device array of MOE_DISPATCH_STATIC_SCRATCH_BYTES inside the library (one per GPU,
+ * held until the process ends).  The call allocates nothing, frees nothing and does not
+ * synchronise.  MOE_ERR_UNSUPPORTED if moe_workspace_bytes(cfg, MOE_WS_DISPATCH) exceeds
+ * that size (roughly k*T*E > 64 M).  All calls on one GPU share that GPU's array: calls that
+ * overlap on one GPU (different streams, or graphs replayed concurrently) race; calls on one
+ * stream, and calls on different GPUs, do not. */
+#define MOE_DISPATCH_STATIC_SCRATCH_BYTES ((size_t)1 << 20)
+int32_t moe_dispatch_static(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                            int32_t* expert_counts, int32_t* expert_offsets, int32_t* assign_to_row,
+                            int32_t* row_to_assign, void* xd, void* stream);
+
 /* Per-expert FFN (the sparsely activated "switching FFN" of Section 3.2) on
  * the dispatched rows: for r in [expert_offsets[e], expert_offsets[e+1])
  *   GELU  : yd[r] = gelu(xd[r] W1_e + b1_e) W2_e + b2_e,  gelu(u) = u*Phi(u)

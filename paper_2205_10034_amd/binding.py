@@ -97,6 +97,7 @@ def lib() -> C.CDLL:
         vp = C.c_void_p
         L.moe_gate.argtypes = [C.POINTER(_Config)] + [vp] * 7
         L.moe_dispatch.argtypes = [C.POINTER(_Config)] + [vp] * 8 + [C.c_size_t, vp]
+        L.moe_dispatch_static.argtypes = [C.POINTER(_Config)] + [vp] * 8
         L.moe_expert_ffn.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
         L.moe_combine.argtypes = [C.POINTER(_Config)] + [vp] * 6
         L.moe_layer_forward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
@@ -248,6 +249,13 @@ def moe_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row,
                               _ptr(assign_to_row), _ptr(row_to_assign), _ptr(xd), _ptr(ws),
                               ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_dispatch")
+
+
+def moe_dispatch_static(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, stream=None):
+    c = cfg.c()
+    _check(lib().moe_dispatch_static(C.byref(c), _ptr(x), _ptr(topk_idx), _ptr(expert_counts), _ptr(expert_offsets),
+                                     _ptr(assign_to_row), _ptr(row_to_assign), _ptr(xd), _stream(stream)),
+           "moe_dispatch_static")
 
 
 def moe_expert_ffn(cfg, weights: Weights, xd, expert_offsets, yd, ws, stream=None):

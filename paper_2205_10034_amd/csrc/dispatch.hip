@@ -21,7 +21,14 @@
 // Everything is integer arithmetic or byte copies: results are bit-exact and
 // independent of scheduling (no atomics whose order could matter: the LDS
 // histogram atomics only add).
+#include <atomic>
 #include "moesys_internal.h"
+
+// Bookkeeping scratch of moe_dispatch_static, the variant of moe_dispatch for callers that cannot allocate:
+// one array per GPU, held from the moment the library's code is loaded on that GPU until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t STATIC_SCRATCH_BYTES = MOE_DISPATCH_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace moesys {
 namespace {
@@ -255,6 +262,49 @@ extern "C" int32_t moe_dispatch(const moe_config* cfg, const void* x, const int3
   const size_t need = moe_workspace_bytes(cfg, MOE_WS_DISPATCH);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
     return fail(MOE_ERR_WORKSPACE, "moe_dispatch: workspace needs %zu bytes, 256-byte aligned (got %zu)", need, ws_bytes);
+  return launch_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
+                         nullptr, (hipStream_t)stream);
+}
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_addr[MAX_DEVICES];  // address of `scratch` on each device, resolved on first use
+
+// Device address of this GPU's copy of `scratch` (every GPU holds its own, at its own address).
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  int32_t st = check_hip(hipGetDevice(&dev), "hipGetDevice");
+  if (st != MOE_OK) return st;
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(MOE_ERR_UNSUPPORTED, "moe_dispatch_static: device ordinal %d outside 0..%d", dev, MAX_DEVICES - 1);
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    st = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (st != MOE_OK) return st;
+    if (!p || ((uintptr_t)p & 255)) return fail(MOE_ERR_HIP, "moe_dispatch_static: scratch symbol resolved to %p", p);
+    g_scratch_addr[dev].store(p, std::memory_order_release);  // (two threads racing here store the same address)
+  }
+  *out = p;
+  return MOE_OK;
+}
+}  // namespace
+
+extern "C" int32_t moe_dispatch_static(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                                       int32_t* expert_counts, int32_t* expert_offsets, int32_t* assign_to_row,
+                                       int32_t* row_to_assign, void* xd, void* stream) {
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if (!expert_counts || !expert_offsets) return fail(MOE_ERR_INVALID_ARG, "moe_dispatch_static: expert_counts/expert_offsets are NULL");
+  if (cfg->T > 0 && (!topk_idx || !assign_to_row || !row_to_assign))
+    return fail(MOE_ERR_INVALID_ARG, "moe_dispatch_static: topk_idx, assign_to_row and row_to_assign must be non-NULL");
+  if (cfg->T > 0 && xd && !x) return fail(MOE_ERR_INVALID_ARG, "moe_dispatch_static: xd given but x is NULL");
+  const size_t need = moe_workspace_bytes(cfg, MOE_WS_DISPATCH);
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(MOE_ERR_UNSUPPORTED, "moe_dispatch_static: k*T=%lld assignments over E=%d experts need %zu bytes of scratch, the static "
+                "buffer holds %zu (use moe_dispatch with a workspace)", (long long)cfg->k * cfg->T, cfg->E, need, STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if ((st = static_scratch(&ws)) != MOE_OK) return st;
+  // every word of the scratch that the kernels read is written first by the same call (per-block histograms,
+  // then their prefixes), so nothing has to be cleared; what the previous call left is never looked at
   return launch_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
                          nullptr, (hipStream_t)stream);
 }
