@@ -34,7 +34,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector rate (256 CUs, 2.4 GHz
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # the oracle's cost grows with T * d_model * d_ff; the CPU leg takes as many leading tokens as keep it near this
-CPU_SAMPLE_FLOPS = 1.5e12
+CPU_SAMPLE_FLOPS = 8e12
 
 
 def measured_traffic(workload, stage):
@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--prewarm-s", type=float, default=2.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
@@ -94,6 +96,11 @@ def main():
     from paper_2205_10034_amd.torch_util import alloc_ws, to_dev, upload_weights, ws_view
     from workloads import WORKLOADS, make_layer
 
+    tuned = {}
+    for kv in args.tune:
+        key, val = kv.split("=")
+        M.moe_set_tuning(getattr(M, "MOE_TUNE_" + key.upper()), int(val))
+        tuned[key] = int(val)
     wl = WORKLOADS[args.workload]
     big = wl.T * wl.d_model * wl.d_ff > 1e12
     steps = args.steps if args.steps is not None else (40 if big else 200)
@@ -184,7 +191,7 @@ def main():
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={wl.T} d_model={wl.d_model} d_ff={wl.d_ff} E={wl.E} top-{wl.k} "
                                f"CF={wl.capacity_factor} {wl.act} (seed {wl.seed})",
-                   "kept_rows": R, "prewarm_steps": n_pre},
+                   "kept_rows": R, "prewarm_steps": n_pre, **({"tuning": tuned} if tuned else {})},
         "roofline": roofline,
         "stage_ms": stage_ms,
         "stage_ms_cold_caches": dict(zip(M.STAGE_NAMES, [float(v) for v in cold])),

@@ -314,7 +314,10 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   constexpr int B_ROWS = OUT_FEAT;                                    // rows per weight matrix per tile
   constexpr int A_LOADS = TOK / RPI / NW, B_LOADS = B_ROWS / RPI / NW;  // wave-instructions per wavefront per stage
   static_assert(TOK % (RPI * NW) == 0 && B_ROWS % (RPI * NW) == 0, "tile/wavefront mismatch");
-  static_assert(!swiglu_tile(EPI) || FB == 2, "SwiGLU wave tile is one gate block + one up block");
+  // SwiGLU: a wavefront's FB blocks are FB/2 gate blocks followed by the FB/2 up blocks of the same features
+  constexpr int FBH = swiglu_tile(EPI) ? FB / 2 : FB;
+  static_assert(!swiglu_tile(EPI) || FB % 2 == 0, "SwiGLU wave tile is gate blocks + as many up blocks");
+  static_assert(EPI != EPI_DSWIGLU || FB == 2, "the SwiGLU-gradient epilogue is written for one gate and one up block");
   static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
   constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
   constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
@@ -399,11 +402,12 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // one base per operand, the block goes into the constant part of the address.
   static_assert(32 % (RPB * CHUNKS) == 0, "the swizzle key must repeat every 32 rows");
   const int a_row0 = wt * 32 + frow;
-  const int w_row0 = (swiglu_tile(EPI) ? wf * 32 : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
+  const int w_row0 = (swiglu_tile(EPI) ? wf * (WFEAT / 2) : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
   const int a_base = a_row0 * ROW_BYTES + ((fhalf ^ ((a_row0 / RPB) % CHUNKS)) << 4);
   const int w_base = w_row0 * ROW_BYTES + ((fhalf ^ ((w_row0 / RPB) % CHUNKS)) << 4);
   constexpr int A_BLK = WT * 32 * ROW_BYTES;                                   // next token block of this wavefront
-  constexpr int W_BLK = (swiglu_tile(EPI) ? FEAT / 2 : 32) * ROW_BYTES;        // next feature block
+  // byte distance of feature block j from block 0 (SwiGLU: blocks FBH.. are the up rows of blocks 0..FBH-1)
+  auto w_blk = [](int j) constexpr { return (swiglu_tile(EPI) ? (j / FBH) * (FEAT / 2) + (j % FBH) * 32 : j * 32) * ROW_BYTES; };
 
   // ---- the current tile's operand windows (wave-uniform) ----------------------------------------
   const uint16_t *a_ptr = act, *b_ptr = wa, *b2_ptr = wa;
@@ -554,7 +558,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // loads ahead of the MFMAs leaves the matrix pipes idle while the burst drains.
     auto read_w = [&](const unsigned char* B, int ks, bf16x8 (&w)[FB]) {
 #pragma unroll
-      for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base ^ (ks << 5)) + j * W_BLK);
+      for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base ^ (ks << 5)) + w_blk(j));
     };
     auto read_a = [&](const unsigned char* A, int ks, bf16x8& a, int i) {
       a = *reinterpret_cast<const bf16x8*>(A + (a_base ^ (ks << 5)) + i * A_BLK);
@@ -766,12 +770,14 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
         }
       } else if (EPI == EPI_SWIGLU) {
 #pragma unroll
-        for (int i0 = 0; i0 < 4; i0 += 2) {
-          float p[8];
+        for (int fb = 0; fb < FBH; ++fb)
 #pragma unroll
-          for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][0][4 * i0 + r]) * acc[tb][1][4 * i0 + r];
-          store_pair(orow, feat0 + wf * 32, i0, p);
-        }
+          for (int i0 = 0; i0 < 4; i0 += 2) {
+            float p[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][fb][4 * i0 + r]) * acc[tb][FBH + fb][4 * i0 + r];
+            store_pair(orow, feat0 + wf * (WFEAT / 2) + fb * 32, i0, p);
+          }
       } else {
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)

@@ -11,5 +11,6 @@ from .moe_inputs import (  # noqa: F401
     bf16_bits,
     make_layer,
     make_ring_stack,
+    RingStackPool,
     zipf_masses,
 )

@@ -129,35 +129,50 @@ def make_layer(wl: MoEWorkload, seed: Optional[int] = None, with_bias: bool = Fa
     return out
 
 
-def make_ring_stack(wl: MoEWorkload, n_layers: int, pool_seed: Optional[int] = None):
-    """Parameters for a stack of ``n_layers`` GELU MoE layers sharing one normal pool.
+class RingStackPool:
+    """The ring workload's stack of GELU MoE layers, drawn lazily.
 
-    Drawing 24 independent 4 GiB layers costs minutes of host time, so the
-    stack draws ONE pool of standard normals of a layer's size plus
-    ``n_layers`` extra elements and gives layer ``l`` the window starting at
-    element ``l`` (every layer sees N(0,1) marginals; consecutive layers are
-    shifted copies).  Router weights are drawn independently per layer.
-
-    Returns ``(x, layers)`` with ``layers[l]`` a dict like :func:`make_layer`'s
-    (without ``x``).  Expert tensors are views into the pool where possible.
+    Drawing 24 independent 4 GiB layers costs minutes of host time, so the stack draws ONE pool of
+    standard normals of a layer's size plus ``n_layers`` extra elements and gives layer ``l`` the
+    window starting at element ``l`` (every layer sees N(0,1) marginals; consecutive layers are
+    shifted copies): ``w1`` of layer l is ``pool[l : l + n1]`` as ``[E, d, f]`` times ``d^-1/2``,
+    ``w2`` is ``pool[n1 + l : n1 + l + n1]`` as ``[E, f, d]`` times ``f^-1/2 * w2_std_scale``, each
+    rounded once to the storage type.  Router weights are drawn independently per layer.
+    ``expert(l, e)`` materialises one expert's two matrices; ``layer(l)`` a whole layer.
     """
-    assert wl.act == "gelu"
-    rng = np.random.default_rng(wl.seed if pool_seed is None else pool_seed)
-    T, d, f, E = wl.T, wl.d_model, wl.d_ff, wl.E
-    x = _normal(rng, (T, d), 1.0, wl.dtype)
-    n1 = E * d * f
-    pool = rng.standard_normal(2 * n1 + n_layers, dtype=np.float32)
-    layers = []
-    for l in range(n_layers):
-        lr = np.random.default_rng([wl.seed, l])
-        w1 = _store(pool[l:l + n1] * np.float32(d ** -0.5), wl.dtype).reshape(E, d, f)
-        w2 = _store(pool[n1 + l:n1 + l + n1] * np.float32(f ** -0.5 * wl.w2_std_scale),
-                    wl.dtype).reshape(E, f, d)
-        layers.append({
-            "w_router": _normal(lr, (d, E), d ** -0.5, "f32"),
-            "b_router": np.zeros(E, dtype=np.float32),
-            "w1": w1, "w2": w2,
-            "b1": np.zeros((E, f), dtype=np.float32),
-            "b2": np.zeros((E, d), dtype=np.float32),
-        })
-    return x, layers
+
+    def __init__(self, wl: MoEWorkload, n_layers: int, pool_seed: Optional[int] = None):
+        assert wl.act == "gelu"
+        self.wl, self.n_layers = wl, n_layers
+        rng = np.random.default_rng(wl.seed if pool_seed is None else pool_seed)
+        T, d, f, E = wl.T, wl.d_model, wl.d_ff, wl.E
+        self.x = _normal(rng, (T, d), 1.0, wl.dtype)
+        self.n1 = E * d * f
+        self.pool = rng.standard_normal(2 * self.n1 + n_layers, dtype=np.float32)
+        self.w1_scale = np.float32(d ** -0.5)
+        self.w2_scale = np.float32(f ** -0.5 * wl.w2_std_scale)
+        self.routers = [_normal(np.random.default_rng([wl.seed, l]), (d, E), d ** -0.5, "f32") for l in range(n_layers)]
+
+    def expert(self, l: int, e: int):
+        """(w1[e] as [d, f], w2[e] as [f, d]) of layer l, float32 arrays of storage-representable values."""
+        d, f = self.wl.d_model, self.wl.d_ff
+        n = d * f
+        w1 = _store(self.pool[l + e * n:l + (e + 1) * n] * self.w1_scale, self.wl.dtype).reshape(d, f)
+        w2 = _store(self.pool[self.n1 + l + e * n:self.n1 + l + (e + 1) * n] * self.w2_scale, self.wl.dtype).reshape(f, d)
+        return w1, w2
+
+    def layer(self, l: int) -> Dict[str, np.ndarray]:
+        wl = self.wl
+        d, f, E = wl.d_model, wl.d_ff, wl.E
+        w1 = _store(self.pool[l:l + self.n1] * self.w1_scale, wl.dtype).reshape(E, d, f)
+        w2 = _store(self.pool[self.n1 + l:self.n1 + l + self.n1] * self.w2_scale, wl.dtype).reshape(E, f, d)
+        return {"w_router": self.routers[l], "b_router": np.zeros(E, dtype=np.float32), "w1": w1, "w2": w2,
+                "b1": np.zeros((E, f), dtype=np.float32), "b2": np.zeros((E, d), dtype=np.float32)}
+
+
+def make_ring_stack(wl: MoEWorkload, n_layers: int, pool_seed: Optional[int] = None):
+    """Parameters for a stack of ``n_layers`` GELU MoE layers sharing one normal pool (see
+    :class:`RingStackPool`).  Returns ``(x, layers)`` with ``layers[l]`` a dict like
+    :func:`make_layer`'s (without ``x``)."""
+    pool = RingStackPool(wl, n_layers, pool_seed)
+    return pool.x, [pool.layer(l) for l in range(n_layers)]
