@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--prewarm-s", type=float, default=2.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1")
+                    help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1, gate_tokens=32|64|128")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "

@@ -99,6 +99,8 @@ typedef struct {
   const float* b_router;
   int32_t layout; /* moe_layout of the expert matrices */
   const int64_t* expert_elem_offset;
+  const void* w_router_packed; /* nullable: w_router pre-split by moe_pack_router (MOE_BF16, E <= 64);
+                                  the layer's gate then runs at the rate the tokens stream from HBM */
 } moe_weights;
 
 /* Byte offsets of every intermediate inside the workspace of moe_layer_forward
@@ -155,8 +157,11 @@ int32_t moe_workspace_layout(const moe_config* cfg, moe_ws_layout* out);
  *   MOE_TUNE_FEW_TOKEN_KERNELS 1 (default): steps of at most 16 tokens / assignments use the
  *                              matrix-vector expert kernels and the one-workgroup-per-token
  *                              gate; 0: the general kernels at every size
+ *   MOE_TUNE_GATE_TOKENS       tokens per workgroup of the gate on a packed router: 32, 64 or 128 (where
+ *                              the expert count allows; otherwise the next smaller); 0 (default) = by T
  * moe_set_tuning returns MOE_ERR_INVALID_ARG for an unknown key or value. */
-typedef enum { MOE_TUNE_GEMM_TILE_ROWS = 0, MOE_TUNE_FEW_TOKEN_KERNELS = 1, MOE_TUNE_COUNT = 2 } moe_tuning_key;
+typedef enum { MOE_TUNE_GEMM_TILE_ROWS = 0, MOE_TUNE_FEW_TOKEN_KERNELS = 1, MOE_TUNE_GATE_TOKENS = 2,
+               MOE_TUNE_COUNT = 3 } moe_tuning_key;
 int32_t moe_set_tuning(int32_t key, int32_t value);
 int32_t moe_get_tuning(int32_t key, int32_t* value);
 
@@ -176,6 +181,20 @@ int32_t moe_get_tuning(int32_t key, int32_t* value);
  * [T,k]; probs device f32 [T,E] or NULL. */
 int32_t moe_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                  int32_t* topk_idx, float* topk_w, float* probs, void* stream);
+
+/* One-time router preparation, outside the hot path (like moe_transpose_expert_weights): every float32
+ * router weight is split into three bfloat16 pieces whose sum is the weight exactly, stored in the order
+ * the gate's matrix instructions read them, so that the gate's kernel only streams tokens and multiplies.
+ * Nothing about the result changes: products stay exact, ranking equals that of the exactly computed
+ * logits (near-ties are recomputed in float64 from w_router itself, which the gate still takes).
+ * packed: device, moe_router_pack_bytes(d_model, E) bytes (0 = this shape has no packed form: E > 64),
+ * 16-byte aligned.  moe_gate_packed is moe_gate on the packed router (MOE_BF16 only); moe_layer_forward
+ * and moe_layer_route use moe_weights.w_router_packed when it is given. */
+size_t moe_router_pack_bytes(int32_t d_model, int32_t E);
+int32_t moe_pack_router(const float* w_router, void* packed, int32_t d_model, int32_t E, void* stream);
+int32_t moe_gate_packed(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                        const void* w_router_packed, int32_t* topk_idx, float* topk_w, float* probs,
+                        void* stream);
 
 /* Capacity-bounded, order-preserving dispatch.  Assignment a = j*T + t
  * (choice-major: every first choice outranks every second choice; inside a

@@ -41,7 +41,7 @@ class _Weights(C.Structure):
     _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p),
                 ("w_gate_proj", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
                 ("w_router", C.c_void_p), ("b_router", C.c_void_p), ("layout", C.c_int32),
-                ("expert_elem_offset", C.c_void_p)]
+                ("expert_elem_offset", C.c_void_p), ("w_router_packed", C.c_void_p)]
 
 
 class _WsLayout(C.Structure):
@@ -96,6 +96,10 @@ def lib() -> C.CDLL:
         L.moe_workspace_layout.argtypes = [C.POINTER(_Config), C.POINTER(_WsLayout)]
         vp = C.c_void_p
         L.moe_gate.argtypes = [C.POINTER(_Config)] + [vp] * 7
+        L.moe_router_pack_bytes.restype = C.c_size_t
+        L.moe_router_pack_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.moe_pack_router.argtypes = [vp, vp, C.c_int32, C.c_int32, vp]
+        L.moe_gate_packed.argtypes = [C.POINTER(_Config)] + [vp] * 8
         L.moe_dispatch.argtypes = [C.POINTER(_Config)] + [vp] * 8 + [C.c_size_t, vp]
         L.moe_dispatch_static.argtypes = [C.POINTER(_Config)] + [vp] * 8
         L.moe_expert_ffn.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), vp, vp, vp, vp, C.c_size_t, vp]
@@ -198,10 +202,10 @@ class Weights:
         self.c = _Weights(g("w1"), g("b1"), g("w2"), g("b2"), g("w_gate_proj"), g("w_up"), g("w_down"),
                           g("w_router"), g("b_router"),
                           MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR,
-                          g("expert_elem_offset"))
+                          g("expert_elem_offset"), g("w_router_packed"))
 
 
-MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS = 0, 1
+MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS, MOE_TUNE_GATE_TOKENS = 0, 1, 2
 
 
 def moe_set_tuning(key: int, value: int) -> None:
@@ -240,6 +244,22 @@ def moe_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs=None, stream=No
     c = cfg.c()
     _check(lib().moe_gate(C.byref(c), _ptr(x), _ptr(w_router), _ptr(b_router), _ptr(topk_idx), _ptr(topk_w),
                           _ptr(probs), _stream(stream)), "moe_gate")
+
+
+def moe_router_pack_bytes(d_model: int, E: int) -> int:
+    return lib().moe_router_pack_bytes(d_model, E)
+
+
+def moe_pack_router(w_router, packed, stream=None):
+    """packed <- w_router [d_model, E] (float32) split into bfloat16 pieces in the gate's operand order."""
+    d, E = w_router.shape
+    _check(lib().moe_pack_router(_ptr(w_router), _ptr(packed), d, E, _stream(stream)), "moe_pack_router")
+
+
+def moe_gate_packed(cfg, x, w_router, b_router, w_router_packed, topk_idx, topk_w, probs=None, stream=None):
+    c = cfg.c()
+    _check(lib().moe_gate_packed(C.byref(c), _ptr(x), _ptr(w_router), _ptr(b_router), _ptr(w_router_packed), _ptr(topk_idx),
+                                 _ptr(topk_w), _ptr(probs), _stream(stream)), "moe_gate_packed")
 
 
 def moe_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,

@@ -23,7 +23,7 @@ int32_t check_hip(hipError_t e, const char* what) {
   return fail(MOE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-static std::atomic<int32_t> g_tuning[MOE_TUNE_COUNT] = {{0}, {1}};
+static std::atomic<int32_t> g_tuning[MOE_TUNE_COUNT] = {{0}, {1}, {0}};
 
 int32_t tuning(int32_t key) { return g_tuning[key].load(std::memory_order_relaxed); }
 
@@ -92,7 +92,7 @@ static void layout_of(const moe_config* c, moe_ws_layout* L) {
   L->xd = take(gemm1_can_gather(c) ? 0 : R * c->d_model * s);
   L->h = take(R * c->d_ff * s);
   L->yd = take(gemm2_can_combine(c) ? 0 : R * c->d_model * s);
-  L->scratch = take(((size_t)dispatch_blocks(c) + 1) * c->E * 4 + 256);
+  L->scratch = take(gate_flags_offset(c) + (size_t)c->T);   // dispatch bookkeeping, then one flag byte per token (gate)
   L->tile_counters = take(TILE_COUNTER_INTS * 4);
   L->total = off;
   L->r_max = (int64_t)R;
@@ -144,6 +144,10 @@ int32_t moe_set_tuning(int32_t key, int32_t value) {
       break;
     case MOE_TUNE_FEW_TOKEN_KERNELS:
       if (value != 0 && value != 1) return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: switch must be 0 or 1 (got %d)", value);
+      break;
+    case MOE_TUNE_GATE_TOKENS:
+      if (value != 0 && value != 32 && value != 64 && value != 128)
+        return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: gate tokens must be 0, 32, 64 or 128 (got %d)", value);
       break;
     default: return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: key %d unknown", key);
   }

@@ -8,7 +8,7 @@
 // accumulation: float32 inside a 64-wide K chunk (24 roundings at most), float64 across chunks and
 // across the four wavefronts that share the K range.  The logits therefore carry an error of about
 // 1e-7.  Ranking needs more: it must equal the ranking of the exactly computed logits.  Any token whose
-// k+1 leading logits have two neighbours closer than GATE_MARGIN is recomputed by the whole workgroup
+// k+1 leading logits have two neighbours closer than GATE_MARGIN_REL times its largest |logit| is recomputed by the whole workgroup
 // with float64 accumulation of the (exact) products and ranked on those values.
 //
 // Exact path (float32 activations, or E > 64): one wavefront works on TPW tokens at a time.  Each lane owns a
@@ -18,6 +18,7 @@
 // 64 lanes leaves one expert's logit per lane group, the logits go through
 // LDS, and the wave then does the fp32 softmax and k rounds of arg-max
 // (ties -> lower expert index) with cross-lane shuffles.
+#include <type_traits>
 #include "moesys_internal.h"
 
 namespace moesys {
@@ -301,7 +302,9 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int FT_TOK = 16;           // tokens per workgroup (one 16-token MFMA tile)
 constexpr int FT_KC = 64;            // K chunk: two 16x16x32 MFMA steps
 constexpr int FT_ROW = (FT_KC + 8) * 2;  // LDS row of one expert's chunk, padded to 144 B (conflict-free reads)
-constexpr float GATE_MARGIN = 1e-4f; // neighbours among the k+1 leading logits closer than this -> exact recompute
+// neighbours among the k+1 leading logits closer than this times the token's largest |logit| -> exact recompute
+// (the accumulation error scales with the data; for inputs of unit variance this is about 1e-4)
+constexpr float GATE_MARGIN_REL = 1.0f / 32768.0f;
 
 __device__ __forceinline__ uint32_t bf16_bits_rne(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
 
@@ -528,9 +531,15 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
       z[i] = v;
     }
     const int tc = min(t, T - 1);  // tail tokens run the same code on the last row, without storing
+    float zmax = 0.f;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i)
+      if (sub + 8 * i < E) zmax = fmaxf(zmax, fabsf((float)z[i]));
+#pragma unroll
+    for (int m = 1; m <= 4; m <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m, 64));
     bool flag = false;
     if (t < T)
-      flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_MARGIN, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
+      flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_MARGIN_REL * zmax, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
                                  probs ? probs + (size_t)tc * E : nullptr);
     if (sub == 0) s_flag[tok] = flag ? 1 : 0;
   }
@@ -622,6 +631,371 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
   return check_hip(hipGetLastError(), "gate launch");
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Fast path on a pre-split router (moe_pack_router): the HBM-rate gate.
+//
+// The split of the float32 router into three bfloat16 pieces does not depend on the tokens, so it is done once,
+// outside the hot path, into the order the MFMA reads its operand in: rows of the packed matrix are
+// (piece, expert) pairs, row = piece * E + expert, padded with zero rows to FR blocks of 32; the contraction
+// index runs in stages of KC = 16 G values, and inside a stage the lower 32 lanes of a wavefront hold its
+// first KC/2 values and the upper 32 lanes the others (a dot product does not care about the order, as long as
+// both operands use the same one): that way a lane's share of a token row is one contiguous run of KC bytes and
+// a wavefront's loads of one stage cover whole cache lines of every token row.  A fragment (stage, sub-step,
+// row block) is 1 KB, contiguous, in that order.
+//
+// One workgroup = NT = 32 NB tokens, eight wavefronts that split the contraction index in runs of a few stages.  A wavefront multiplies v_mfma_f32_32x32x16_bf16 tiles, router rows x tokens, and
+// every product is exact in float32 (a bfloat16 piece times a bfloat16 activation), so the only rounding is the
+// float32 accumulation over the wavefront's share of the contraction index; the eight partial sums and the three
+// pieces of an expert meet in float64 through LDS.  No staging through LDS on the way in, no conversion in the
+// loop: the loop is loads and MFMAs, and the kernel runs at the rate the token rows arrive from HBM.
+//
+// Ranking must equal the ranking of the exactly computed logits.  The partial sums carry errors of about
+// 2^-24 times their own magnitude, so a token is flagged when two neighbours among its k+1 leading logits are
+// closer than 2^-15 times the largest sum over the wavefronts of |partial logit| of that token (a margin that
+// scales with the data; about 1e-4 for inputs of unit variance) and recomputed by the whole workgroup with
+// float64 accumulation of the exact products, from the float32 router itself.
+#ifndef GATE_REL_MARGIN_VALUE
+#define GATE_REL_MARGIN_VALUE (1.0f / 32768.0f)
+#endif
+constexpr float GATE_REL_MARGIN = GATE_REL_MARGIN_VALUE;
+constexpr int GP_WAVES = 8;
+
+__host__ __device__ constexpr int gate_frags(int E) { return (3 * E + 31) / 32; }        // row blocks of the packed router
+__host__ __device__ constexpr int gate_substeps(int FR) { return FR <= 3 ? 4 : 2; }      // MFMA sub-steps per stage
+
+// one thread per 16-byte piece of the packed router
+__global__ __launch_bounds__(256) void pack_router_kernel(const float* __restrict__ wr, uint16_t* __restrict__ dst, int d, int E,
+                                                          int FR, int G) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)(d / (16 * G)) * G * FR * 64;
+  if (i >= total) return;
+  const int lane = (int)(i % 64);
+  const size_t frag = i / 64;
+  const int fr = (int)(frag % FR), s = (int)((frag / FR) % G);
+  const size_t c = frag / ((size_t)FR * G);
+  const int row = 32 * fr + (lane & 31), h = lane >> 5;
+  const int piece = row / E, e = row - piece * E;
+  const size_t k0 = c * (16 * G) + (size_t)(8 * G) * h + 8 * s;
+  uint32_t out[4] = {0u, 0u, 0u, 0u};
+  if (piece < 3) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = wr[(k0 + j) * E + e];
+      const uint32_t hi = bf16_bits_rne(w);
+      const float r1 = w - __uint_as_float(hi << 16);      // exact: the leading 8 bits of the significand are gone
+      const uint32_t mid = bf16_bits_rne(r1);
+      const float r2 = r1 - __uint_as_float(mid << 16);    // exact; at most 8 significant bits are left
+      const uint32_t lo = bf16_bits_rne(r2);
+      const uint32_t v = piece == 0 ? hi : piece == 1 ? mid : lo;
+      out[j >> 1] |= v << (16 * (j & 1));
+    }
+  }
+  *reinterpret_cast<u32x4*>(dst + i * 8) = u32x4{out[0], out[1], out[2], out[3]};
+}
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}), unrolled
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+// One token's logits with float64 accumulation of the exact products of the float32 router and the activations,
+// then softmax and ranking on those values: the whole workgroup of GP_WAVES wavefronts works on the token.  Every
+// wavefront takes a contiguous range of router rows; a load instruction covers whole rows (lane = expert quad + row
+// slot) and sixteen of them are in flight.  lds: (GP_WAVES + 1) * 64 doubles; the caller synchronises before.
+__device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, const float* __restrict__ wr, const float* __restrict__ br,
+                                            int t, int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
+                                            float* __restrict__ topk_w, float* __restrict__ probs, double* lds) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int EP = E <= 16 ? 16 : E <= 32 ? 32 : 64;
+  const int QN = EP / 4, RPI = 64 / QN;
+  double* zpart = lds;                  // [GP_WAVES][64]
+  double* zex = lds + GP_WAVES * 64;    // [64]
+  const int q = lane % QN, rs = lane / QN;
+  const int rows_per_wave = d / GP_WAVES;   // d is a multiple of 64
+  const bool vec = (E & 3) == 0 && (reinterpret_cast<uintptr_t>(wr) & 15) == 0;
+  const uint16_t* xt = x + (size_t)t * d;
+  double a[4] = {0.0, 0.0, 0.0, 0.0};
+  const int r_end = (wave + 1) * rows_per_wave;
+#pragma unroll 16
+  for (int r = wave * rows_per_wave + rs; r < r_end; r += RPI) {
+    const double xv = (double)bf16_to_f32(xt[r]);
+    const float* wq = wr + (size_t)r * E + q * 4;
+    float w4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (vec) {
+      if (q * 4 < E) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(wq);
+        w4[0] = v[0]; w4[1] = v[1]; w4[2] = v[2]; w4[3] = v[3];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (q * 4 + j < E) w4[j] = wq[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = fma(xv, (double)w4[j], a[j]);
+  }
+  for (int m = QN; m < 64; m <<= 1)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
+  if (rs == 0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) zpart[wave * 64 + q * 4 + j] = a[j];
+  }
+  __syncthreads();
+  if (tid < E) {
+    double v = zpart[tid];
+#pragma unroll
+    for (int w = 1; w < GP_WAVES; ++w) v += zpart[w * 64 + tid];
+    zex[tid] = v + (br ? (double)br[tid] : 0.0);
+  }
+  __syncthreads();
+  if (tid < 8) {
+    double z[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (tid + 8 * i) < E ? zex[tid + 8 * i] : -INFINITY;
+    finalize_group<8>(z, tid, E, k, renorm, 0.f, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
+                      probs ? probs + (size_t)t * E : nullptr);
+  }
+}
+
+// Recomputes the tokens that gate_packed_kernel marked: one workgroup looks at FIX_TOKENS flags and works through
+// the marked ones (almost always none, rarely one).
+constexpr int FIX_TOKENS = 16;
+__global__ __launch_bounds__(GP_WAVES * 64) void gate_fix_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
+                                                                 const float* __restrict__ br, const uint8_t* __restrict__ flags, int T,
+                                                                 int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
+                                                                 float* __restrict__ topk_w, float* __restrict__ probs) {
+  __shared__ double lds[(GP_WAVES + 1) * 64];
+  const int lane = threadIdx.x & 63;
+  const int t0 = blockIdx.x * FIX_TOKENS;
+  unsigned long long todo = __ballot(lane < FIX_TOKENS && t0 + lane < T && flags[min(t0 + lane, T - 1)] != 0);
+  while (todo) {
+    const int st = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    __syncthreads();
+    exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, lds);
+  }
+}
+
+template <int FR, int NB>
+__global__ __launch_bounds__(GP_WAVES * 64) void gate_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wp,
+                                                                    const float* __restrict__ wr, const float* __restrict__ br, int T,
+                                                                    int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
+                                                                    float* __restrict__ topk_w, float* __restrict__ probs,
+                                                                    uint8_t* __restrict__ flags) {
+  constexpr int G = gate_substeps(FR), KC = 16 * G, NT = 32 * NB, RW = 32 * FR;
+  constexpr int STRIDE = NT + 8;  // floats between the rows of a partial-sum matrix (conflict-free reads and writes)
+  constexpr int NPL = (32 * FR / 3 + 7) / 8;  // logits per lane of an 8-lane group (covers every E of this FR)
+  // all eight partial-sum matrices in LDS at once, or four and two rounds
+  constexpr bool TWO_ROUNDS = (size_t)GP_WAVES * RW * STRIDE * 4 > 150 * 1024;
+  constexpr int SLOTS = TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int s_flag[NT];
+  float* part = reinterpret_cast<float*>(smem);  // [SLOTS][RW][STRIDE]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tok = lane & 31, h = lane >> 5;
+  const int t0 = blockIdx.x * NT;
+  const int n_stages = d / KC;
+#ifdef GATE_PHASES
+  // debug builds: `probs` is a buffer of 8 time stamps (100 MHz counter) per workgroup instead
+  unsigned long long* stamps = reinterpret_cast<unsigned long long*>(probs) + (size_t)blockIdx.x * 8;
+  probs = nullptr;
+  if (tid == 0) stamps[0] = __builtin_amdgcn_s_memrealtime();
+#define GATE_STAMP(i) if (tid == 0) stamps[i] = __builtin_amdgcn_s_memrealtime();
+#else
+#define GATE_STAMP(i)
+#endif
+
+  // this lane's run of every token row (tail tokens recompute the last row and are never stored)
+  const uint16_t* xrow[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) xrow[nb] = x + (size_t)min(t0 + 32 * nb + tok, T - 1) * d + (KC / 2) * h;
+  const uint16_t* wlane = wp + lane * 8;
+
+  f32x16 acc[NB][FR];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][fr][v] = 0.f;
+
+  // PF register stages in flight.  Every stage load is unconditional (a stage index past the end re-reads the
+  // last stage) and every stage is multiplied, with the token fragments of a stage past the end replaced by
+  // zeros (which add nothing): loads and uses then sit in straight-line code, the compiler can neither sink a
+  // load into a branch next to its use nor merge the stages' registers, and a scheduling barrier after each
+  // group of loads keeps them ahead of the multiplications of the older stages.
+  constexpr int STAGE_REGS = (NB + FR) * G * 4;
+  constexpr int PF = STAGE_REGS <= 32 ? 4 : STAGE_REGS <= 48 ? 3 : 2;
+  u32x4 xs[PF][NB][G], ws[PF][G][FR];
+  auto load_stage = [&](auto b_tag, int c) {
+    constexpr int b = decltype(b_tag)::value;
+    const int cc = min(c, n_stages - 1);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int s = 0; s < G; ++s) xs[b][nb][s] = *reinterpret_cast<const u32x4*>(xrow[nb] + (size_t)cc * KC + 8 * s);
+#pragma unroll
+    for (int s = 0; s < G; ++s)
+#pragma unroll
+      for (int fr = 0; fr < FR; ++fr)
+        ws[b][s][fr] = *reinterpret_cast<const u32x4*>(wlane + (((size_t)cc * G + s) * FR + fr) * 512);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto multiply = [&](auto b_tag, int c) {
+    constexpr int b = decltype(b_tag)::value;
+    const uint32_t keep = c < n_stages ? 0xffffffffu : 0u;   // (uniform)
+#pragma unroll
+    for (int s = 0; s < G; ++s)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const u32x4 xv = xs[b][nb][s] & keep;
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+          acc[nb][fr] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ws[b][s][fr]),
+                                                                __builtin_bit_cast(bf16x8, xv), acc[nb][fr], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // wavefront w takes stages w PF .. w PF + PF - 1, then those 8 PF further on, ...: the PF stages it has in flight
+  // are one contiguous run of every token row (PF KC values), which is what DRAM pages and cache lines like
+  static_for<PF>([&](auto j) { load_stage(j, wave * PF + decltype(j)::value); });
+  for (int c = wave * PF; c < n_stages; c += PF * GP_WAVES)
+    static_for<PF>([&](auto j) {
+      constexpr int jj = decltype(j)::value;
+      multiply(j, c + jj);
+      load_stage(j, c + jj + PF * GP_WAVES);
+    });
+
+  GATE_STAMP(1)
+  // ---- the partial sums meet in LDS: part[slot][row][token] -------------------------------------
+  auto put = [&](int slot) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
+          part[((size_t)slot * RW + row) * STRIDE + 32 * nb + tok] = acc[nb][fr][v];
+        }
+  };
+  if constexpr (TWO_ROUNDS) {
+    // the upper four wavefronts hand their sums to the lower four (one float32 addition: 2^-24 of a partial sum)
+    if (wave >= SLOTS) put(wave - SLOTS);
+    __syncthreads();
+    if (wave < SLOTS) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
+            acc[nb][fr][v] += part[((size_t)wave * RW + row) * STRIDE + 32 * nb + tok];
+          }
+    }
+    __syncthreads();
+    if (wave < SLOTS) put(wave);
+  } else {
+    put(wave);
+  }
+  __syncthreads();
+
+  GATE_STAMP(2)
+  // ---- per token: float64 sum over wavefronts and pieces, float32 softmax, ranking, margin test ----------
+  for (int base = 0; base < NT; base += GP_WAVES * 8) {
+    const int slot_tok = base + (tid >> 3), sub = tid & 7;
+    const int t = t0 + slot_tok;
+    if (slot_tok < NT) {   // (uniform per 8-lane group)
+      double z[NPL];
+      float zabs = 0.f;
+#pragma unroll
+      for (int i = 0; i < NPL; ++i) {
+        const int e = sub + 8 * i;
+        double v = -INFINITY;
+        if (e < E) {
+          v = 0.0;
+          float a = 0.f;
+          for (int w = 0; w < SLOTS; ++w) {
+            const float* pw = part + ((size_t)w * RW + e) * STRIDE + slot_tok;
+            const double pz = (double)pw[0] + (double)pw[(size_t)E * STRIDE] + (double)pw[(size_t)2 * E * STRIDE];
+            v += pz;
+            a += fabsf((float)pz);
+          }
+          zabs = fmaxf(zabs, a);
+          if (br) v += (double)br[e];
+        }
+        z[i] = v;
+      }
+#pragma unroll
+      for (int m = 1; m <= 4; m <<= 1) zabs = fmaxf(zabs, __shfl_xor(zabs, m, 64));
+      const int tc = min(t, T - 1);
+      bool flag = false;
+      if (t < T)
+        flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
+                                   probs ? probs + (size_t)tc * E : nullptr);
+      if (sub == 0) s_flag[slot_tok] = flag ? 1 : 0;
+    }
+  }
+  __syncthreads();
+
+  GATE_STAMP(3)
+  // ---- exact recompute of the rare tokens whose ranking is within the margin ----------------------
+  // With a flag array from the caller the tokens are only marked here and gate_fix_kernel, launched behind this
+  // kernel, recomputes them, every one in a workgroup of its own: inside this kernel a flagged token would hold
+  // up its whole workgroup (and with it the kernel) for the time of a dependent chain of loads.
+  if (flags) {
+    for (int i = tid; i < NT && t0 + i < T; i += GP_WAVES * 64) flags[t0 + i] = (uint8_t)s_flag[i];
+  } else {
+    unsigned long long flagged[(NT + 63) / 64];
+#pragma unroll
+    for (int g = 0; g < (NT + 63) / 64; ++g) {
+      const int i = 64 * g + lane;
+      flagged[g] = __ballot(i < NT && s_flag[i < NT ? i : 0] != 0);
+    }
+#pragma unroll
+    for (int g = 0; g < (NT + 63) / 64; ++g)
+      while (flagged[g]) {
+        const int st = 64 * g + __builtin_ctzll(flagged[g]);
+        flagged[g] &= flagged[g] - 1;
+        __syncthreads();   // the previous readers of this LDS are done
+        exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, reinterpret_cast<double*>(smem));
+      }
+  }
+  GATE_STAMP(4)
+#undef GATE_STAMP
+}
+
+template <int FR, int NB>
+int32_t launch_packed(const moe_config* cfg, const void* x, const void* packed, const float* w_router, const float* b_router,
+                      int32_t* topk_idx, float* topk_w, float* probs, uint8_t* flags, hipStream_t s) {
+  constexpr int NT = 32 * NB, RW = 32 * FR, STRIDE = NT + 8;
+  constexpr bool TWO_ROUNDS = (size_t)GP_WAVES * RW * STRIDE * 4 > 150 * 1024;
+  constexpr size_t part_bytes = (size_t)(TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES) * RW * STRIDE * 4;
+  constexpr size_t exact_bytes = (size_t)(GP_WAVES + 1) * 64 * sizeof(double);
+  constexpr size_t shmem = part_bytes > exact_bytes ? part_bytes : exact_bytes;
+  static_assert(shmem + NT * 4 <= 160 * 1024, "partial sums do not fit the LDS");
+  auto kern = gate_packed_kernel<FR, NB>;
+  if (shmem > 65536) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
+  }
+  hipLaunchKernelGGL(kern, dim3((cfg->T + NT - 1) / NT), dim3(GP_WAVES * 64), shmem, s, (const uint16_t*)x, (const uint16_t*)packed,
+                     w_router, b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs, flags);
+  if (flags)
+    hipLaunchKernelGGL(gate_fix_kernel, dim3((cfg->T + FIX_TOKENS - 1) / FIX_TOKENS), dim3(GP_WAVES * 64), 0, s, (const uint16_t*)x,
+                       w_router, b_router, flags, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+  return check_hip(hipGetLastError(), "gate launch");
+}
+
 }  // namespace
 
 // A step of one token: gate and dispatch tables from one kernel (bf16 activations: the layer then needs no
@@ -661,6 +1035,55 @@ int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router,
   return check_hip(hipGetLastError(), "gate launch");
 }
 
+// The pre-split router serves bfloat16 activations and up to 64 experts (3 E rows in at most six blocks of 32).
+size_t router_pack_bytes(int d_model, int E) {
+  if (E < 1 || E > 64 || d_model < 64 || d_model % 64) return 0;
+  return (size_t)d_model * gate_frags(E) * 64;   // d/KC stages x G sub-steps x FR blocks x 1 KB
+}
+
+bool gate_packed_applies(const moe_config* cfg, const float* w_router) {
+  return cfg->dtype == MOE_BF16 && cfg->E <= 64 && !gate_few_applies(cfg, w_router);
+}
+// Inside a layer the packed router is used where it measured faster than splitting on the fly: long token streams
+// (from about 64 M activation elements; below, the kernels are bound by their chain of dependent steps and by the
+// second launch that recomputes the near-ties, not by the split).
+bool gate_packed_pays(const moe_config* cfg) { return (int64_t)cfg->T * cfg->d_model >= ((int64_t)1 << 26); }
+
+// flags (nullable): device scratch of T bytes; with it the near-tie tokens are recomputed by a second, small kernel
+int32_t launch_gate_packed(const moe_config* cfg, const void* x, const void* packed, const float* w_router, const float* b_router,
+                           int32_t* topk_idx, float* topk_w, float* probs, uint8_t* flags, hipStream_t s) {
+  if (cfg->T == 0) return MOE_OK;
+  const int FR = gate_frags(cfg->E);
+  // tokens per workgroup: as many 32-token blocks as still give every compute unit a workgroup (each workgroup
+  // reads the whole packed router once, from L2)
+  const int forced = tuning(MOE_TUNE_GATE_TOKENS);
+  auto wgs = [&](int nb) { return forced ? (forced == 32 * nb ? 1 << 20 : 0) : (cfg->T + 32 * nb - 1) / (32 * nb); };
+#define MOE_GATE_PACKED(fr, nb) return launch_packed<fr, nb>(cfg, x, packed, w_router, b_router, topk_idx, topk_w, probs, flags, s)
+  switch (FR) {
+    case 1:
+      if (wgs(4) >= 256) MOE_GATE_PACKED(1, 4);
+      if (wgs(2) >= 256) MOE_GATE_PACKED(1, 2);
+      MOE_GATE_PACKED(1, 1);
+    case 2:
+      if (wgs(2) >= 256) MOE_GATE_PACKED(2, 2);
+      MOE_GATE_PACKED(2, 1);
+    case 3: MOE_GATE_PACKED(3, 1);
+    case 4: MOE_GATE_PACKED(4, 1);
+    case 5: MOE_GATE_PACKED(5, 1);
+    case 6: MOE_GATE_PACKED(6, 1);
+  }
+#undef MOE_GATE_PACKED
+  return fail(MOE_ERR_UNSUPPORTED, "packed router: E=%d has no kernel", cfg->E);
+}
+
+// The gate of a layer: on the pre-split router when the weights carry one and it applies.
+int32_t launch_gate_of(const moe_config* cfg, const moe_weights* w, const void* x, int32_t* topk_idx, float* topk_w, float* probs,
+                       uint8_t* flags, hipStream_t s) {
+  if (w->w_router_packed && gate_packed_applies(cfg, w->w_router) && gate_packed_pays(cfg))
+    return launch_gate_packed(cfg, x, w->w_router_packed, w->w_router, w->b_router, topk_idx, topk_w, probs, flags, s);
+  return launch_gate(cfg, x, w->w_router, w->b_router, topk_idx, topk_w, probs, s);
+}
+
 }  // namespace moesys
 
 using namespace moesys;
@@ -673,4 +1096,30 @@ extern "C" int32_t moe_gate(const moe_config* cfg, const void* x, const float* w
   if (cfg->T > 0 && (!x || !w_router || !topk_idx || !topk_w))
     return fail(MOE_ERR_INVALID_ARG, "moe_gate: x, w_router, topk_idx and topk_w must be non-NULL");
   return launch_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs, (hipStream_t)stream);
+}
+
+extern "C" size_t moe_router_pack_bytes(int32_t d_model, int32_t E) { return router_pack_bytes(d_model, E); }
+
+extern "C" int32_t moe_pack_router(const float* w_router, void* packed, int32_t d_model, int32_t E, void* stream) {
+  const size_t bytes = router_pack_bytes(d_model, E);
+  if (!bytes) return fail(MOE_ERR_UNSUPPORTED, "moe_pack_router: d_model=%d (multiple of 64) and E=%d (1..64) only", d_model, E);
+  if (!w_router || !packed || ((uintptr_t)packed & 15)) return fail(MOE_ERR_INVALID_ARG, "moe_pack_router: NULL or misaligned pointer");
+  const int FR = gate_frags(E), G = gate_substeps(FR);
+  const size_t pieces = bytes / 16;
+  hipLaunchKernelGGL(pack_router_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)stream, w_router,
+                     (uint16_t*)packed, d_model, E, FR, G);
+  return check_hip(hipGetLastError(), "router pack launch");
+}
+
+extern "C" int32_t moe_gate_packed(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
+                                   const void* w_router_packed, int32_t* topk_idx, float* topk_w, float* probs, void* stream) {
+  int32_t st = moe_config_check(cfg);
+  if (st != MOE_OK) return st;
+  if (cfg->T > 0 && (!x || !w_router || !w_router_packed || !topk_idx || !topk_w))
+    return fail(MOE_ERR_INVALID_ARG, "moe_gate_packed: x, w_router, w_router_packed, topk_idx and topk_w must be non-NULL");
+  if (cfg->dtype != MOE_BF16 || cfg->E > 64)
+    return fail(MOE_ERR_UNSUPPORTED, "moe_gate_packed: bf16 activations and at most 64 experts (use moe_gate)");
+  if (!gate_packed_applies(cfg, w_router))   // steps of very few tokens: one workgroup per token on the float32 router
+    return launch_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs, (hipStream_t)stream);
+  return launch_gate_packed(cfg, x, w_router_packed, w_router, b_router, topk_idx, topk_w, probs, nullptr, (hipStream_t)stream);
 }

@@ -26,7 +26,8 @@ def to_np(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy() if t.dtype == torch.bfloat16 else t.detach().cpu().numpy()
 
 
-def upload_weights(L: dict, dtype: str, layout: str = "output_major", nullable_bias: bool = False) -> M.Weights:
+def upload_weights(L: dict, dtype: str, layout: str = "output_major", nullable_bias: bool = False,
+                   pack_router: bool = True) -> M.Weights:
     """Expert matrices arrive input-major ([E,in,out]); output-major copies are made on the device
     with the library's own transpose kernel."""
     t = {}
@@ -47,6 +48,10 @@ def upload_weights(L: dict, dtype: str, layout: str = "output_major", nullable_b
                 continue
             t[name] = to_dev(L[name], dtype)
     t["w_router"] = to_dev(L["w_router"], "f32")
+    n = M.moe_router_pack_bytes(*t["w_router"].shape) if (dtype == "bf16" and pack_router) else 0
+    if n:   # the gate's pre-split copy of the router (one-time preparation, like the transposes above)
+        t["w_router_packed"] = torch.empty(n, dtype=torch.uint8, device="cuda")
+        M.moe_pack_router(t["w_router"], t["w_router_packed"])
     if L.get("b_router") is not None:
         t["b_router"] = to_dev(L["b_router"], "f32")
     torch.cuda.synchronize()

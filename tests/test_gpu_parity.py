@@ -11,6 +11,7 @@ import torch
 import paper_2205_10034_amd as M
 from oracle import moe_oracle as O
 from workloads import WORKLOADS, make_layer
+from workloads import bf16_round as bf16_round_np
 
 from gpu_util import alloc_ws, rel_fro, run_layer, tdtype, to_dev, to_np, upload_weights, ws_view
 from oracle_sampling import oracle_out_for_tokens
@@ -65,7 +66,83 @@ def test_gate(wl):
     assert np.allclose(probs.cpu().numpy(), p_ref, rtol=GATE_RTOL, atol=1e-30)
 
 
-def test_gate_exact_ties_lower_index_first():
+def run_gate_packed(cfg, x_np, wr_np, br_np, with_probs=True):
+    x, wr = to_dev(x_np, "bf16"), to_dev(wr_np, "f32")
+    br = None if br_np is None else to_dev(br_np, "f32")
+    packed = torch.empty(M.moe_router_pack_bytes(cfg.d_model, cfg.E), dtype=torch.uint8, device="cuda")
+    M.moe_pack_router(wr, packed)
+    idx = torch.full((cfg.T, cfg.k), -7, dtype=torch.int32, device="cuda")
+    w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    probs = torch.zeros((cfg.T, cfg.E), dtype=torch.float32, device="cuda") if with_probs else None
+    M.moe_gate_packed(cfg, x, wr, br, packed, idx, w, probs)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), w.cpu().numpy(), None if probs is None else probs.cpu().numpy()
+
+
+PACKED_GATE_CASES = [wl for wl in GATE_CASES if wl.dtype == "bf16" and wl.E <= 64] + [
+    small("gpt", T=333, E=8, k=2, d_model=4096),           # one row block, the large workload's router
+    small("gpt", T=8200, E=8, k=2, d_model=512),           # 128 tokens per workgroup, ragged last workgroup
+    small("skew", T=16384 + 40, d_model=768),              # 64 tokens per workgroup; 12 stages over 8 wavefronts
+    small("gpt", T=8192 + 33, E=16, k=2, d_model=256),     # two row blocks, 64 tokens per workgroup
+    small("gpt", T=200, E=21, k=3, d_model=192),           # 63 rows in two blocks; 3 stages: five wavefronts idle
+    small("gpt", T=100, E=32, k=4, d_model=128),           # 96 rows = three full blocks
+    small("gpt", T=77, E=42, k=2, d_model=320),            # four blocks, stages of 32
+    small("gpt", T=90, E=53, k=5, d_model=128),            # five blocks
+    small("ring", T=4096, d_model=2048),                   # the ring workload's router: six blocks, two rounds through LDS
+]
+
+
+@pytest.mark.parametrize("wl", PACKED_GATE_CASES, ids=lambda w: f"{w.name}-T{w.T}-E{w.E}-k{w.k}-d{w.d_model}")
+def test_gate_packed_router(wl):
+    """The gate on the pre-split router: same bar as moe_gate (indices bit-exact, weights and probabilities 1e-5)."""
+    print(f"packed gate case {wl}", flush=True)
+    L = make_layer(wl.scaled(d_ff=64))
+    cfg = M.MoEConfig.from_workload(wl)
+    idx, w, probs = run_gate_packed(cfg, L["x"], L["w_router"], L["b_router"] if wl.router_bias != "none" else None)
+    p_ref, idx_ref, w_ref = O.gate(L["x"], L["w_router"], L["b_router"], wl.k, wl.renormalize)
+    assert np.array_equal(idx, idx_ref)
+    assert np.allclose(w, w_ref, rtol=GATE_RTOL, atol=0)
+    assert np.allclose(probs, p_ref, rtol=GATE_RTOL, atol=1e-30)
+
+
+@pytest.mark.parametrize("packed", [True, False])
+@pytest.mark.parametrize("scale", [1.0, 1e3, 1e-3])
+def test_gate_near_ties_at_any_scale(scale, packed):
+    """Planted near-ties: pairs of router columns that differ in the last bits of a few weights, so that two
+    experts' logits differ by far less than the fast path's accumulation error, at three input scales (the
+    recompute margin scales with the partial sums).  Ranking must still equal the float64 oracle's."""
+    rng = np.random.default_rng(11)
+    T, d, E, k = 700, 1024, 16, 2
+    x = bf16_round_np(rng.standard_normal((T, d)).astype(np.float32) * np.float32(scale))
+    wr = (rng.standard_normal((d, E)) / 32).astype(np.float32)
+    for a, b in ((0, 5), (3, 9), (7, 12)):                   # b is a, a few weights nudged by one unit in the last place
+        wr[:, b] = wr[:, a]
+        rows = rng.integers(0, d, 6)
+        wr[rows, b] = np.nextafter(wr[rows, b], np.float32(np.inf))
+    wr[:, :3] += np.float32(0.02)                            # make the tied experts likely winners
+    wr[:, 5] += np.float32(0.02)
+    cfg = M.MoEConfig(T=T, d_model=d, d_ff=64, E=E, k=k, renormalize=True, dtype="bf16")
+    if packed:
+        idx, w, _ = run_gate_packed(cfg, x, wr, None, with_probs=False)
+    else:
+        idx_t = torch.empty((T, k), dtype=torch.int32, device="cuda")
+        w_t = torch.empty((T, k), dtype=torch.float32, device="cuda")
+        M.moe_gate(cfg, to_dev(x, "bf16"), to_dev(wr, "f32"), None, idx_t, w_t, None)
+        torch.cuda.synchronize()
+        idx, w = idx_t.cpu().numpy(), w_t.cpu().numpy()
+    _, idx_ref, w_ref = O.gate(x, wr, None, k, True)
+    z = O.gate_logits(x, wr, None)
+    top = np.sort(z, axis=1)[:, ::-1]
+    print(f"scale {scale}: smallest gap among the three leading logits {np.min(top[:, :2] - top[:, 1:3]):.3e} "
+          f"(logit magnitude {np.abs(z).max():.3e})", flush=True)
+    assert np.array_equal(idx, idx_ref)
+    # the softmax is float32 (Section 5.2): a logit of magnitude |z| is rounded to 2^-24 |z| before the
+    # exponential, which is a relative error of that size in its probability
+    assert np.allclose(w, w_ref, rtol=GATE_RTOL + 2.0 ** -22 * np.abs(z).max(), atol=1e-30)
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_gate_exact_ties_lower_index_first(packed):
     # integer-valued x and router: logits are exact on both sides; columns repeat, so ties are real
     rng = np.random.default_rng(0)
     T, d, E = 200, 64, 6
@@ -73,11 +150,15 @@ def test_gate_exact_ties_lower_index_first():
     base = rng.integers(-2, 3, size=(d, 3)).astype(np.float32)
     wr = np.concatenate([base, base], axis=1)                  # expert e and e+3 always tie
     cfg = M.MoEConfig(T=T, d_model=d, d_ff=64, E=E, k=4, renormalize=True, dtype="bf16")
+    _, idx_ref, w_ref = O.gate(x, wr, None, 4, True)
+    if packed:
+        idx, w, _ = run_gate_packed(cfg, x, wr, None, with_probs=False)
+        assert np.array_equal(idx, idx_ref) and np.allclose(w, w_ref, rtol=GATE_RTOL)
+        return
     idx = torch.empty((T, 4), dtype=torch.int32, device="cuda")
     w = torch.empty((T, 4), dtype=torch.float32, device="cuda")
     M.moe_gate(cfg, to_dev(x, "bf16"), to_dev(wr, "f32"), None, idx, w, None)
     torch.cuda.synchronize()
-    _, idx_ref, w_ref = O.gate(x, wr, None, 4, True)
     assert np.array_equal(idx.cpu().numpy(), idx_ref)
     assert np.allclose(w.cpu().numpy(), w_ref, rtol=GATE_RTOL)
 
@@ -492,8 +573,9 @@ def test_layer_with_experts_scattered_over_a_pool(name, kw):
             o += n
     offs = torch.tensor([int(slot_of[e]) * stride if counts[e] else 0 for e in range(E)], dtype=torch.int64, device="cuda")
     t = {"w_router": W.tensors["w_router"], "expert_elem_offset": offs}
-    if "b_router" in W.tensors:
-        t["b_router"] = W.tensors["b_router"]
+    for n in ("b_router", "w_router_packed"):            # the same gate as the reference run
+        if n in W.tensors:
+            t[n] = W.tensors[n]
     base = pool.data_ptr()
     o = 0
     for n_, size in zip([n for n in names if n in W.tensors], sizes):

@@ -73,6 +73,8 @@ def test_pool_stack_matches_resident_and_policy_oracle(T, slots, steps):
             t = {"w_router": Ws[l].tensors["w_router"], "expert_elem_offset": offs, "w1": base,
                  "w2": base + 2 * sizes[0], "b1": base + 2 * (sizes[0] + sizes[1]),
                  "b2": base + 2 * (sizes[0] + sizes[1] + sizes[2])}
+            if "w_router_packed" in Ws[l].tensors:          # the same gate as the resident reference
+                t["w_router_packed"] = Ws[l].tensors["w_router_packed"]
             Wp = M.Weights(t)
             M.moe_layer_route(cfg, Wp, x, ws)
             pool.prepare(l, counts_dev, 2, offs)
