@@ -784,34 +784,134 @@ __global__ __launch_bounds__(GP_WAVES * 64) void gate_fix_kernel(const uint16_t*
   }
 }
 
+// What follows the contraction in the gate kernels on a packed router: acc[nb][fr] holds this wavefront's partial
+// sums (router rows x tokens, the MFMA's accumulator layout) for the NT = 32 NB tokens from t0 on.  The partial sums
+// of the eight wavefronts and the three pieces of every expert meet in float64 through LDS (smem: room for the
+// partial-sum matrices), then softmax, ranking and the margin test per token, and the exact recompute (or the
+// marks for gate_fix_kernel).
+template <int FR, int NB>
+__device__ __forceinline__ void gate_finish(f32x16 (&acc)[NB][FR], unsigned char* smem, int* s_flag, int t0,
+                                            const uint16_t* __restrict__ x, const float* __restrict__ wr,
+                                            const float* __restrict__ br, int T, int d, int E, int k, int renorm,
+                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ probs,
+                                            uint8_t* __restrict__ flags) {
+  constexpr int NT = 32 * NB, RW = 32 * FR;
+  constexpr int STRIDE = NT + 8;  // floats between the rows of a partial-sum matrix (conflict-free reads and writes)
+  constexpr int NPL = (32 * FR / 3 + 7) / 8;  // logits per lane of an 8-lane group (covers every E of this FR)
+  // all eight partial-sum matrices in LDS at once, or four and two rounds
+  constexpr bool TWO_ROUNDS = (size_t)GP_WAVES * RW * STRIDE * 4 > 150 * 1024;
+  constexpr int SLOTS = TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES;
+  float* part = reinterpret_cast<float*>(smem);  // [SLOTS][RW][STRIDE]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tok = lane & 31, h = lane >> 5;
+  // ---- the partial sums meet in LDS: part[slot][row][token] -------------------------------------
+  auto put = [&](int slot) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
+          part[((size_t)slot * RW + row) * STRIDE + 32 * nb + tok] = acc[nb][fr][v];
+        }
+  };
+  if constexpr (TWO_ROUNDS) {
+    // the upper four wavefronts hand their sums to the lower four (one float32 addition: 2^-24 of a partial sum)
+    if (wave >= SLOTS) put(wave - SLOTS);
+    __syncthreads();
+    if (wave < SLOTS) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
+            acc[nb][fr][v] += part[((size_t)wave * RW + row) * STRIDE + 32 * nb + tok];
+          }
+    }
+    __syncthreads();
+    if (wave < SLOTS) put(wave);
+  } else {
+    put(wave);
+  }
+  __syncthreads();
+
+  // ---- per token: float64 sum over wavefronts and pieces, float32 softmax, ranking, margin test ----------
+  for (int base = 0; base < NT; base += GP_WAVES * 8) {
+    const int slot_tok = base + (tid >> 3), sub = tid & 7;
+    const int t = t0 + slot_tok;
+    if (slot_tok < NT) {   // (uniform per 8-lane group)
+      double z[NPL];
+      float zabs = 0.f;
+#pragma unroll
+      for (int i = 0; i < NPL; ++i) {
+        const int e = sub + 8 * i;
+        double v = -INFINITY;
+        if (e < E) {
+          v = 0.0;
+          float a = 0.f;
+          for (int w = 0; w < SLOTS; ++w) {
+            const float* pw = part + ((size_t)w * RW + e) * STRIDE + slot_tok;
+            const double pz = (double)pw[0] + (double)pw[(size_t)E * STRIDE] + (double)pw[(size_t)2 * E * STRIDE];
+            v += pz;
+            a += fabsf((float)pz);
+          }
+          zabs = fmaxf(zabs, a);
+          if (br) v += (double)br[e];
+        }
+        z[i] = v;
+      }
+#pragma unroll
+      for (int m = 1; m <= 4; m <<= 1) zabs = fmaxf(zabs, __shfl_xor(zabs, m, 64));
+      const int tc = min(t, T - 1);
+      bool flag = false;
+      if (t < T)
+        flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
+                                   probs ? probs + (size_t)tc * E : nullptr);
+      if (sub == 0) s_flag[slot_tok] = flag ? 1 : 0;
+    }
+  }
+  __syncthreads();
+
+  // ---- exact recompute of the rare tokens whose ranking is within the margin ----------------------
+  // With a flag array from the caller the tokens are only marked here and gate_fix_kernel, launched behind this
+  // kernel, recomputes them, every one in a workgroup of its own: inside this kernel a flagged token would hold
+  // up its whole workgroup (and with it the kernel) for the time of a dependent chain of loads.
+  if (flags) {
+    for (int i = tid; i < NT && t0 + i < T; i += GP_WAVES * 64) flags[t0 + i] = (uint8_t)s_flag[i];
+  } else {
+    unsigned long long flagged[(NT + 63) / 64];
+#pragma unroll
+    for (int g = 0; g < (NT + 63) / 64; ++g) {
+      const int i = 64 * g + lane;
+      flagged[g] = __ballot(i < NT && s_flag[i < NT ? i : 0] != 0);
+    }
+#pragma unroll
+    for (int g = 0; g < (NT + 63) / 64; ++g)
+      while (flagged[g]) {
+        const int st = 64 * g + __builtin_ctzll(flagged[g]);
+        flagged[g] &= flagged[g] - 1;
+        __syncthreads();   // the previous readers of this LDS are done
+        exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, reinterpret_cast<double*>(smem));
+      }
+  }
+}
+
 template <int FR, int NB>
 __global__ __launch_bounds__(GP_WAVES * 64) void gate_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wp,
                                                                     const float* __restrict__ wr, const float* __restrict__ br, int T,
                                                                     int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
                                                                     float* __restrict__ topk_w, float* __restrict__ probs,
                                                                     uint8_t* __restrict__ flags) {
-  constexpr int G = gate_substeps(FR), KC = 16 * G, NT = 32 * NB, RW = 32 * FR;
-  constexpr int STRIDE = NT + 8;  // floats between the rows of a partial-sum matrix (conflict-free reads and writes)
-  constexpr int NPL = (32 * FR / 3 + 7) / 8;  // logits per lane of an 8-lane group (covers every E of this FR)
-  // all eight partial-sum matrices in LDS at once, or four and two rounds
-  constexpr bool TWO_ROUNDS = (size_t)GP_WAVES * RW * STRIDE * 4 > 150 * 1024;
-  constexpr int SLOTS = TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES;
+  constexpr int G = gate_substeps(FR), KC = 16 * G, NT = 32 * NB;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int s_flag[NT];
-  float* part = reinterpret_cast<float*>(smem);  // [SLOTS][RW][STRIDE]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tok = lane & 31, h = lane >> 5;
   const int t0 = blockIdx.x * NT;
   const int n_stages = d / KC;
-#ifdef GATE_PHASES
-  // debug builds: `probs` is a buffer of 8 time stamps (100 MHz counter) per workgroup instead
-  unsigned long long* stamps = reinterpret_cast<unsigned long long*>(probs) + (size_t)blockIdx.x * 8;
-  probs = nullptr;
-  if (tid == 0) stamps[0] = __builtin_amdgcn_s_memrealtime();
-#define GATE_STAMP(i) if (tid == 0) stamps[i] = __builtin_amdgcn_s_memrealtime();
-#else
-#define GATE_STAMP(i)
-#endif
 
   // this lane's run of every token row (tail tokens recompute the last row and are never stored)
   const uint16_t* xrow[NB];
@@ -874,104 +974,7 @@ __global__ __launch_bounds__(GP_WAVES * 64) void gate_packed_kernel(const uint16
       load_stage(j, c + jj + PF * GP_WAVES);
     });
 
-  GATE_STAMP(1)
-  // ---- the partial sums meet in LDS: part[slot][row][token] -------------------------------------
-  auto put = [&](int slot) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int fr = 0; fr < FR; ++fr)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
-          part[((size_t)slot * RW + row) * STRIDE + 32 * nb + tok] = acc[nb][fr][v];
-        }
-  };
-  if constexpr (TWO_ROUNDS) {
-    // the upper four wavefronts hand their sums to the lower four (one float32 addition: 2^-24 of a partial sum)
-    if (wave >= SLOTS) put(wave - SLOTS);
-    __syncthreads();
-    if (wave < SLOTS) {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int fr = 0; fr < FR; ++fr)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = 32 * fr + 8 * (v >> 2) + 4 * h + (v & 3);
-            acc[nb][fr][v] += part[((size_t)wave * RW + row) * STRIDE + 32 * nb + tok];
-          }
-    }
-    __syncthreads();
-    if (wave < SLOTS) put(wave);
-  } else {
-    put(wave);
-  }
-  __syncthreads();
-
-  GATE_STAMP(2)
-  // ---- per token: float64 sum over wavefronts and pieces, float32 softmax, ranking, margin test ----------
-  for (int base = 0; base < NT; base += GP_WAVES * 8) {
-    const int slot_tok = base + (tid >> 3), sub = tid & 7;
-    const int t = t0 + slot_tok;
-    if (slot_tok < NT) {   // (uniform per 8-lane group)
-      double z[NPL];
-      float zabs = 0.f;
-#pragma unroll
-      for (int i = 0; i < NPL; ++i) {
-        const int e = sub + 8 * i;
-        double v = -INFINITY;
-        if (e < E) {
-          v = 0.0;
-          float a = 0.f;
-          for (int w = 0; w < SLOTS; ++w) {
-            const float* pw = part + ((size_t)w * RW + e) * STRIDE + slot_tok;
-            const double pz = (double)pw[0] + (double)pw[(size_t)E * STRIDE] + (double)pw[(size_t)2 * E * STRIDE];
-            v += pz;
-            a += fabsf((float)pz);
-          }
-          zabs = fmaxf(zabs, a);
-          if (br) v += (double)br[e];
-        }
-        z[i] = v;
-      }
-#pragma unroll
-      for (int m = 1; m <= 4; m <<= 1) zabs = fmaxf(zabs, __shfl_xor(zabs, m, 64));
-      const int tc = min(t, T - 1);
-      bool flag = false;
-      if (t < T)
-        flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
-                                   probs ? probs + (size_t)tc * E : nullptr);
-      if (sub == 0) s_flag[slot_tok] = flag ? 1 : 0;
-    }
-  }
-  __syncthreads();
-
-  GATE_STAMP(3)
-  // ---- exact recompute of the rare tokens whose ranking is within the margin ----------------------
-  // With a flag array from the caller the tokens are only marked here and gate_fix_kernel, launched behind this
-  // kernel, recomputes them, every one in a workgroup of its own: inside this kernel a flagged token would hold
-  // up its whole workgroup (and with it the kernel) for the time of a dependent chain of loads.
-  if (flags) {
-    for (int i = tid; i < NT && t0 + i < T; i += GP_WAVES * 64) flags[t0 + i] = (uint8_t)s_flag[i];
-  } else {
-    unsigned long long flagged[(NT + 63) / 64];
-#pragma unroll
-    for (int g = 0; g < (NT + 63) / 64; ++g) {
-      const int i = 64 * g + lane;
-      flagged[g] = __ballot(i < NT && s_flag[i < NT ? i : 0] != 0);
-    }
-#pragma unroll
-    for (int g = 0; g < (NT + 63) / 64; ++g)
-      while (flagged[g]) {
-        const int st = 64 * g + __builtin_ctzll(flagged[g]);
-        flagged[g] &= flagged[g] - 1;
-        __syncthreads();   // the previous readers of this LDS are done
-        exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, reinterpret_cast<double*>(smem));
-      }
-  }
-  GATE_STAMP(4)
-#undef GATE_STAMP
+  gate_finish<FR, NB>(acc, smem, s_flag, t0, x, wr, br, T, d, E, k, renorm, topk_idx, topk_w, probs, flags);
 }
 
 template <int FR, int NB>

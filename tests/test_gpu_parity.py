@@ -89,6 +89,11 @@ PACKED_GATE_CASES = [wl for wl in GATE_CASES if wl.dtype == "bf16" and wl.E <= 6
     small("gpt", T=77, E=42, k=2, d_model=320),            # four blocks, stages of 32
     small("gpt", T=90, E=53, k=5, d_model=128),            # five blocks
     small("ring", T=4096, d_model=2048),                   # the ring workload's router: six blocks, two rounds through LDS
+    # longer token streams
+    small("gpt", T=5000 + 7, E=8, k=2, d_model=1024),      # one row block, two stages, ragged last workgroup
+    small("gpt", T=4100, E=16, k=2, d_model=1024),         # two row blocks
+    small("gpt", T=8300, E=32, k=4, d_model=512),          # three row blocks, a single stage
+    small("skew", T=3000, d_model=1536),                   # router bias, three stages (odd count)
 ]
 
 
