@@ -766,8 +766,9 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
 }
 
 // Recomputes the tokens that gate_packed_kernel marked: one workgroup looks at FIX_TOKENS flags and works through
-// the marked ones (almost always none, rarely one).
-constexpr int FIX_TOKENS = 16;
+// the marked ones (almost always none, rarely one or two; few, large workgroups: launching thousands of
+// workgroups that find nothing to do took longer than the recomputes themselves).
+constexpr int FIX_TOKENS = 256;
 __global__ __launch_bounds__(GP_WAVES * 64) void gate_fix_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
                                                                  const float* __restrict__ br, const uint8_t* __restrict__ flags, int T,
                                                                  int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
@@ -775,12 +776,16 @@ __global__ __launch_bounds__(GP_WAVES * 64) void gate_fix_kernel(const uint16_t*
   __shared__ double lds[(GP_WAVES + 1) * 64];
   const int lane = threadIdx.x & 63;
   const int t0 = blockIdx.x * FIX_TOKENS;
-  unsigned long long todo = __ballot(lane < FIX_TOKENS && t0 + lane < T && flags[min(t0 + lane, T - 1)] != 0);
-  while (todo) {
-    const int st = __builtin_ctzll(todo);
-    todo &= todo - 1;
-    __syncthreads();
-    exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, lds);
+#pragma unroll
+  for (int g = 0; g < FIX_TOKENS / 64; ++g) {
+    const int t = t0 + 64 * g + lane;
+    unsigned long long todo = __ballot(t < T && flags[min(t, T - 1)] != 0);
+    while (todo) {
+      const int st = 64 * g + __builtin_ctzll(todo);
+      todo &= todo - 1;
+      __syncthreads();
+      exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, lds);
+    }
   }
 }
 

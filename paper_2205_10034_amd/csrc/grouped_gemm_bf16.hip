@@ -175,7 +175,10 @@ struct TileInfo {
 // the eight XCDs work on eight token groups of the SAME feature group at the same time (one HBM read of
 // those weights serves all of them through the shared cache level).  A trailing partial set of token
 // groups is spread over the XCDs feature group by feature group instead, to keep them equally loaded.
-__host__ __device__ inline int group_n(int n_tiles) { return n_tiles < 8 ? n_tiles : 8; }
+#ifndef MOE_GROUP_N
+#define MOE_GROUP_N 8
+#endif
+__host__ __device__ inline int group_n(int n_tiles) { return n_tiles < MOE_GROUP_N ? n_tiles : MOE_GROUP_N; }
 
 // Token tiling of one expert with n rows, for a kernel whose tile holds up to `cap` rows: the fewest tiles
 // that can hold them, ceil(n / cap), with the rows spread over them as evenly as whole units allow (a unit =
