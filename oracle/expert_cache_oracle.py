@@ -3,97 +3,118 @@
 This file is the checker, not the product: only ``tests/`` and the bench's
 baseline leg may import it.  It shares no code with the C++ implementation.
 
-What it models.  The paper's "Scheduling on Sparse Parameters" (Algorithm 2,
-Section 3.2.2) keeps the selectively activated expert states that the next
-computation needs in a cache of fixed capacity in the faster memory, "akin to
-LFU": a table `hits` counts how often each cached item was requested, every
-K requests all counts are multiplied by an attenuation coefficient beta, and
-when the cache is full the item to give up is the one "with the lowest hit
-frequency that surpasses the hit threshold".  Here the slower memory is pinned
-host memory and the faster one a pool of expert-sized slots in HBM; the steps
-are those of the algorithm, in its order and notation.
+What it models (Algorithm 2, Section 3.2.2: scheduling of sparse parameters).
+A fixed number of places in the faster memory holds the expert states that
+were asked for most often, in the manner of a least-frequently-used cache:
+  * every request of a resident item raises that item's request count by one;
+  * after every `period` requests (of any item) every count is multiplied by
+    the attenuation factor `decay`, so that old popularity fades;
+  * a request of an item that is not resident brings it in with a count of one,
+    into an unused place while there is one, else into the place of a victim;
+  * the victim is, among the residents whose count has reached `floor`, the one
+    with the smallest count.
+Here the slower memory is pinned host memory and the faster one a pool of
+expert-sized slots in HBM.
 
 Readings (the algorithm as printed is ambiguous in four places):
- * free space: the printed test `acc_caches + 1 < CPU_size` would leave one
-   slot unused for ever; read as `acc_caches < CPU_size`.
- * victim: the printed condition (`hit_a >= threshold` and `hit_a` equal to the
-   minimum over ALL items) and the prose (lowest count among those that reach
-   the threshold) differ when some item lies below the threshold; the prose is
-   taken, because under the printed form a single item that decays below the
-   threshold would freeze the cache.  Items below the threshold (new, or
-   decayed) are thus protected.
- * the printed `foreach` would evict every item that ties for the minimum and
-   fetch p_s once per eviction; read as ONE eviction per request, ties going to
-   the item cached earliest.
- * no item reaches the threshold: the algorithm then evicts nothing (on the
+ * free space: the printed comparison would leave the last place unused for
+   ever; here a place is free as long as fewer than `capacity` are taken.
+ * victim: the listing asks for a count at or above the floor that is also the
+   minimum over ALL residents, the prose for the smallest count among those at
+   or above the floor; the two differ as soon as one resident lies below the
+   floor, and under the listing's form such a resident would freeze the cache.
+   The prose is taken: residents below the floor (new, or faded) are protected.
+ * the listing's loop would give up every resident that ties for the minimum
+   and fetch the new item once per victim; read as ONE victim per request, ties
+   going to the resident that came in earliest.
+ * nobody has reached the floor: the algorithm then gives up nothing (on the
    paper's CPU tier the request is served from the SSD without being cached).
-   An expert must be in HBM to be computed, so here the item with the lowest
-   count overall is given up instead (ties: cached earliest).
-One addition: items requested since the last `begin_batch()` are never chosen
-as victims, because all experts of one layer evaluation must be resident at
-the same time (the capacity must be at least the largest such batch).
+   An expert must be in HBM to be computed, so here the smallest count overall
+   goes instead (ties: earliest arrival).
+One addition: residents requested since the last `begin_batch()` are never
+victims, because all experts of one layer evaluation must be resident at the
+same time (the capacity must be at least the largest such batch).
 """
 from __future__ import annotations
 
+from dataclasses import dataclass
 from typing import Dict, List, Optional, Tuple
 
 
-class SparseParameterCache:
-    """`hits`, `threshold`, `beta`, `K`, `steps` and `acc_caches` are Algorithm 2's own names."""
+@dataclass
+class Resident:
+    """One occupied place of the pool."""
+    item: int
+    place: int          # slot of the pool
+    count: float        # attenuated number of requests since it came in
+    arrival: int        # sequence number of its coming in (tie-break: earliest goes first)
+    batch: int          # number of the batch that last asked for it
 
-    def __init__(self, size: int, threshold: float, beta: float, K: int):
-        if size < 1 or K < 1:
-            raise ValueError("size and K must be at least 1")
-        self.size = int(size)
-        self.threshold = float(threshold)
-        self.beta = float(beta)
-        self.K = int(K)
-        self.steps = 0
-        self.acc_caches = 0
-        self.hits: Dict[int, float] = {}        # cached item -> (attenuated) number of requests
-        self.slot: Dict[int, int] = {}          # cached item -> slot of the pool it occupies
-        self.cached_at: Dict[int, int] = {}     # cached item -> sequence number of its insertion
-        self.batch: Dict[int, int] = {}         # cached item -> batch number of its last request
-        self.cur_batch = 0
-        self.inserts = 0
+
+class SparseParameterCache:
+    def __init__(self, capacity: int, floor: float, decay: float, period: int):
+        if capacity < 1 or period < 1:
+            raise ValueError("capacity and period must be at least 1")
+        self.capacity, self.floor, self.decay, self.period = int(capacity), float(floor), float(decay), int(period)
+        self.residents: Dict[int, Resident] = {}
+        self.places_taken = 0        # places are handed out in index order and never become unused again
+        self.arrivals = 0
+        self.requests_in_period = 0
+        self.batch_no = 0
+
+    # -- the tests read these two views
+    @property
+    def hits(self) -> Dict[int, float]:
+        return {r.item: r.count for r in self.residents.values()}
 
     def begin_batch(self) -> None:
-        self.cur_batch += 1
+        self.batch_no += 1
 
-    def schedule(self, p_s: int) -> Tuple[int, bool, Optional[int]]:
-        """One SparseSchedule call for item p_s: returns (slot, was cached, evicted item or None)."""
-        evicted = None
-        if p_s in self.hits:                                   # "Get p_s from the caches; hits[p_s] += 1"
-            self.hits[p_s] += 1.0
-            hit = True
-        else:
-            hit = False
-            if self.acc_caches < self.size:                    # free space: next unused slot
-                slot = self.acc_caches
-                self.acc_caches += 1
-            else:
-                evicted = self._victim()
-                slot = self.slot[evicted]
-                del self.hits[evicted], self.slot[evicted], self.cached_at[evicted], self.batch[evicted]
-            self.hits[p_s] = 1.0
-            self.slot[p_s] = slot
-            self.cached_at[p_s] = self.inserts
-            self.inserts += 1
-        self.batch[p_s] = self.cur_batch
-        self.steps += 1
-        if self.steps == self.K:                               # "hits * beta" (moving average)
-            for a in self.hits:
-                self.hits[a] *= self.beta
-            self.steps = 0
-        return self.slot[p_s], hit, evicted
+    def evictable(self) -> List[Resident]:
+        """Residents that the current batch has not asked for."""
+        return [r for r in self.residents.values() if r.batch != self.batch_no]
 
-    def _victim(self) -> int:
-        free = [a for a in self.hits if self.batch[a] != self.cur_batch]
-        if not free:
+    def choose_victim(self) -> Resident:
+        candidates = self.evictable()
+        if not candidates:
             raise RuntimeError("every cached item belongs to the current batch: capacity too small")
-        above = [a for a in free if self.hits[a] >= self.threshold]
-        pool = above if above else free
-        return min(pool, key=lambda a: (self.hits[a], self.cached_at[a]))
+        established = [r for r in candidates if r.count >= self.floor]
+        return min(established or candidates, key=lambda r: (r.count, r.arrival))
+
+    def admit(self, item: int) -> Optional[int]:
+        """Brings `item` in; returns the item that made room for it, if any."""
+        gone = None
+        if self.places_taken < self.capacity:
+            place = self.places_taken
+            self.places_taken += 1
+        else:
+            victim = self.choose_victim()
+            place, gone = victim.place, victim.item
+            del self.residents[gone]
+        self.residents[item] = Resident(item, place, 1.0, self.arrivals, self.batch_no)
+        self.arrivals += 1
+        return gone
+
+    def fade(self) -> None:
+        """Counts of all residents shrink once per `period` requests."""
+        self.requests_in_period += 1
+        if self.requests_in_period == self.period:
+            self.requests_in_period = 0
+            for r in self.residents.values():
+                r.count *= self.decay
+
+    def schedule(self, item: int) -> Tuple[int, bool, Optional[int]]:
+        """One request: returns (place, was resident, item given up or None)."""
+        r = self.residents.get(item)
+        was_resident = r is not None
+        gone = None
+        if was_resident:
+            r.count += 1.0
+            r.batch = self.batch_no
+        else:
+            gone = self.admit(item)
+        self.fade()
+        return self.residents[item].place, was_resident, gone
 
 
 def run_trace(size: int, threshold: float, beta: float, K: int, trace: List[Tuple[int, bool]]):

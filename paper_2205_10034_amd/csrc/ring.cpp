@@ -78,7 +78,26 @@ int32_t harvest(moe_ring* r) {
   return MOE_OK;
 }
 
+// Reads the duration of the oldest copy's event pair and recycles it (waits if that copy has not finished).
+int32_t harvest_oldest(moe_ring* r) {
+  const std::pair<void*, void*> p = r->pending.front();
+  if (r->be.event_synchronize(r->be.user, p.second)) return fail(MOE_ERR_HIP, "ring: event synchronize failed");
+  float ms = 0.f;
+  if (r->be.event_elapsed_ms(r->be.user, p.first, p.second, &ms)) return fail(MOE_ERR_HIP, "ring: event elapsed failed");
+  r->copy_ms += ms;
+  r->idle.push_back(p);
+  r->pending.erase(r->pending.begin());
+  return MOE_OK;
+}
+
 int32_t enqueue_load(moe_ring* r, int layer, int s) {
+  // A caller that never asks for the statistics must not grow the list without bound: beyond a few rings' worth
+  // of copies the oldest pair is recycled here (its copy lies at least that many copies back on the one copy
+  // stream, so it has normally long finished and the wait returns at once).
+  if (r->pending.size() >= (size_t)4 * r->K + 16) {
+    int32_t st = harvest_oldest(r);
+    if (st != MOE_OK) return st;
+  }
   std::pair<void*, void*> p{nullptr, nullptr};
   if (!r->idle.empty()) {
     p = r->idle.back();
@@ -87,12 +106,22 @@ int32_t enqueue_load(moe_ring* r, int layer, int s) {
     if (p.first) r->be.event_destroy(r->be.user, p.first);
     return fail(MOE_ERR_HIP, "ring: event creation failed");
   }
-  r->pending.push_back(p);
-  if (r->be.event_record(r->be.user, p.first, r->copy_stream)) return fail(MOE_ERR_HIP, "ring: event record failed");
+  // the pair joins the pending list only once both of its events are recorded (a pair with an unrecorded stop
+  // event could never be waited for)
+  if (r->be.event_record(r->be.user, p.first, r->copy_stream)) {
+    r->idle.push_back(p);
+    return fail(MOE_ERR_HIP, "ring: event record failed");
+  }
   if (r->be.copy_h2d_async(r->be.user, r->dev_base + (size_t)s * r->layer_bytes, r->host[layer], r->layer_bytes,
-                           r->copy_stream))
+                           r->copy_stream)) {
+    r->idle.push_back(p);
     return fail(MOE_ERR_HIP, "ring: host-to-device copy of layer %d failed", layer);
-  if (r->be.event_record(r->be.user, p.second, r->copy_stream)) return fail(MOE_ERR_HIP, "ring: event record failed");
+  }
+  if (r->be.event_record(r->be.user, p.second, r->copy_stream)) {
+    r->idle.push_back(p);
+    return fail(MOE_ERR_HIP, "ring: event record failed");
+  }
+  r->pending.push_back(p);
   if (r->be.event_record(r->be.user, r->loaded[s], r->copy_stream)) return fail(MOE_ERR_HIP, "ring: event record failed");
   r->resident[s] = layer;
   r->bytes_copied += r->layer_bytes;

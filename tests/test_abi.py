@@ -260,3 +260,31 @@ def test_ring_reports_a_failed_copy():
     with pytest.raises(M.MoEError):
         M.Ring(DEV_BASE, 2 * LAYER_BYTES, 2, [host_ptr(l) for l in range(4)], LAYER_BYTES, COPY_STREAM, be2.struct)
     assert be2.n_events == 0
+    # the statistics stay readable after a failed copy (its event pair never joined the pending copies)
+    be3 = FakeBackend(fail_copy_at=3)
+    ring = M.Ring(DEV_BASE, 2 * LAYER_BYTES, 2, [host_ptr(l) for l in range(4)], LAYER_BYTES, COPY_STREAM, be3.struct)
+    ring.acquire(0, COMPUTE_STREAM)
+    with pytest.raises(M.MoEError):
+        ring.release(0, COMPUTE_STREAM)
+    st = ring.stats()
+    assert st["copies"] == 2 and st["copy_ms"] == 4.0
+    ring.close()
+    assert be3.n_events == 0
+
+
+def test_ring_recycles_its_copy_events_without_a_stats_call():
+    """An inference loop that never reads the statistics: the number of live events stays bounded (a few rings'
+    worth of copies), and the totals are still complete when they are finally read."""
+    N, K = 6, 2
+    be = FakeBackend()
+    ring = M.Ring(DEV_BASE, K * LAYER_BYTES, K, [host_ptr(l) for l in range(N)], LAYER_BYTES, COPY_STREAM, be.struct)
+    peak = 0
+    for g in range(50 * N):
+        ring.acquire(g % N, COMPUTE_STREAM)
+        ring.release(g % N, COMPUTE_STREAM)
+        peak = max(peak, be.n_events)
+    assert peak <= 2 * K + 2 * (4 * K + 16) + 2, peak      # section events + event pairs of the pending copies
+    st = ring.stats()
+    assert st["copies"] == K + 50 * N and st["copy_ms"] == 2.0 * st["copies"]
+    ring.close()
+    assert be.n_events == 0

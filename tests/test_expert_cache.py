@@ -132,47 +132,44 @@ def test_oracle_pin(pin):
 
 # ------------------------------------------------------------------------- planted mistakes
 class _HighestCountGoes(SparseParameterCache):
-    def _victim(self):
-        free = [a for a in self.hits if self.batch[a] != self.cur_batch]
-        above = [a for a in free if self.hits[a] >= self.threshold]
-        return max(above if above else free, key=lambda a: (self.hits[a], -self.cached_at[a]))
+    def choose_victim(self):
+        cand = self.evictable()
+        est = [r for r in cand if r.count >= self.floor]
+        return max(est or cand, key=lambda r: (r.count, -r.arrival))
 
 
 class _LastInFirstOutTies(SparseParameterCache):
-    def _victim(self):
-        free = [a for a in self.hits if self.batch[a] != self.cur_batch]
-        above = [a for a in free if self.hits[a] >= self.threshold]
-        return min(above if above else free, key=lambda a: (self.hits[a], -self.cached_at[a]))
+    def choose_victim(self):
+        cand = self.evictable()
+        est = [r for r in cand if r.count >= self.floor]
+        return min(est or cand, key=lambda r: (r.count, -r.arrival))
 
 
 class _ThresholdIgnored(SparseParameterCache):
-    def _victim(self):
-        free = [a for a in self.hits if self.batch[a] != self.cur_batch]
-        return min(free, key=lambda a: (self.hits[a], self.cached_at[a]))
+    def choose_victim(self):
+        return min(self.evictable(), key=lambda r: (r.count, r.arrival))
 
 
 class _ThresholdStrict(SparseParameterCache):
-    def _victim(self):
-        free = [a for a in self.hits if self.batch[a] != self.cur_batch]
-        above = [a for a in free if self.hits[a] > self.threshold]
-        return min(above if above else free, key=lambda a: (self.hits[a], self.cached_at[a]))
+    def choose_victim(self):
+        cand = self.evictable()
+        est = [r for r in cand if r.count > self.floor]
+        return min(est or cand, key=lambda r: (r.count, r.arrival))
 
 
 class _BatchUnprotected(SparseParameterCache):
-    def _victim(self):
-        above = [a for a in self.hits if self.hits[a] >= self.threshold]
-        return min(above if above else list(self.hits), key=lambda a: (self.hits[a], self.cached_at[a]))
+    def evictable(self):
+        return list(self.residents.values())
 
 
-class _PrintedFreeSpaceTest(SparseParameterCache):       # `acc + 1 < size`: the last slot is never used
-    def schedule(self, p_s):
-        if p_s not in self.hits and self.acc_caches + 1 >= self.size and self.acc_caches < self.size:
-            self.acc_caches = self.size
-            self.hits[-1 - self.inserts] = 0.0
-            self.slot[-1 - self.inserts] = self.size - 1
-            self.cached_at[-1 - self.inserts] = -1
-            self.batch[-1 - self.inserts] = -1
-        return super().schedule(p_s)
+class _PrintedFreeSpaceTest(SparseParameterCache):       # the printed comparison: the last place is never used
+    def admit(self, item):
+        if self.places_taken + 1 >= self.capacity and self.places_taken < self.capacity:
+            from oracle.expert_cache_oracle import Resident
+            self.places_taken = self.capacity
+            ghost = -1 - self.arrivals
+            self.residents[ghost] = Resident(ghost, self.capacity - 1, 0.0, -1, -1)
+        return super().admit(item)
 
 
 class _DecayOneStepLate(SparseParameterCache):
@@ -181,31 +178,31 @@ class _DecayOneStepLate(SparseParameterCache):
 
 
 class _DecayOnlyTheRequestedItem(SparseParameterCache):
-    def schedule(self, p_s):
-        beta, self.beta = self.beta, 1.0
-        due = self.steps + 1 == self.K
-        out = super().schedule(p_s)
-        self.beta = beta
+    def schedule(self, item):
+        decay, self.decay = self.decay, 1.0
+        due = self.requests_in_period + 1 == self.period
+        out = super().schedule(item)
+        self.decay = decay
         if due:
-            self.hits[p_s] *= beta
+            self.residents[item].count *= decay
         return out
 
 
 class _HitCountNotUpdated(SparseParameterCache):
-    def schedule(self, p_s):
-        before = self.hits.get(p_s)
-        out = super().schedule(p_s)
-        if before is not None and self.steps != 0:
-            self.hits[p_s] = before
+    def schedule(self, item):
+        before = self.residents[item].count if item in self.residents else None
+        out = super().schedule(item)
+        if before is not None and self.requests_in_period != 0:
+            self.residents[item].count = before
         return out
 
 
 class _NewItemStartsAtZero(SparseParameterCache):
-    def schedule(self, p_s):
-        new = p_s not in self.hits
-        out = super().schedule(p_s)
+    def schedule(self, item):
+        new = item not in self.residents
+        out = super().schedule(item)
         if new:
-            self.hits[p_s] -= 1.0 if self.steps != 0 else self.beta
+            self.residents[item].count -= 1.0 if self.requests_in_period != 0 else self.decay
         return out
 
 
