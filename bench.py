@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--prewarm-s", type=float, default=2.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pack-router", action="store_true", help="do not give the layer a pre-split router (moe_pack_router)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1, gate_tokens=32|64|128")
     args = ap.parse_args()
@@ -107,7 +108,7 @@ def main():
     warmup = args.warmup if args.warmup is not None else (5 if big else 20)
     L = make_layer(wl)
     cfg = M.MoEConfig.from_workload(wl)
-    W = upload_weights(L, wl.dtype, nullable_bias=True)
+    W = upload_weights(L, wl.dtype, nullable_bias=True, pack_router=not args.no_pack_router)
     x = to_dev(L["x"], wl.dtype)
     out = torch.empty_like(x)
     ws = alloc_ws(cfg)

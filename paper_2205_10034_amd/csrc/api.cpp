@@ -92,7 +92,7 @@ static void layout_of(const moe_config* c, moe_ws_layout* L) {
   L->xd = take(gemm1_can_gather(c) ? 0 : R * c->d_model * s);
   L->h = take(R * c->d_ff * s);
   L->yd = take(gemm2_can_combine(c) ? 0 : R * c->d_model * s);
-  L->scratch = take(gate_flags_offset(c) + (size_t)c->T);   // dispatch bookkeeping, then one flag byte per token (gate)
+  L->scratch = take(((size_t)dispatch_blocks(c) + 1) * c->E * 4 + 256);
   L->tile_counters = take(TILE_COUNTER_INTS * 4);
   L->total = off;
   L->r_max = (int64_t)R;

@@ -447,7 +447,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
     return check_hip(hipGetLastError(), "moe_layer_backward");
   }
   // the probabilities are not kept by the forward pass: run the gate again (same routing, bit for bit)
-  if ((st = launch_gate_of(cfg, w, x, (int32_t*)(b + L.idx), (float*)(b + L.w), probs, nullptr, s)) != MOE_OK) return st;
+  if ((st = launch_gate_of(cfg, w, x, (int32_t*)(b + L.idx), (float*)(b + L.w), probs, s)) != MOE_OK) return st;
   if (gemm2_can_combine(cfg)) {
     // with one expert per token the forward pass wrote `out` directly: recompute the experts' outputs
     int32_t* ctr = (int32_t*)(b + L.yd + align_up((size_t)max_rows(cfg) * cfg->d_model * 2, 256));

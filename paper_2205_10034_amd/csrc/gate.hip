@@ -316,7 +316,7 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f) { return (uint32_t)__
 template <int NPL>
 __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E, int k, int renorm, float margin,
                                                int32_t* __restrict__ idx_out, float* __restrict__ w_out,
-                                               float* __restrict__ probs_out) {
+                                               float* __restrict__ probs_out, bool mark_close = false) {
   float mx = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NPL; ++i) mx = fmaxf(mx, (float)z[i]);
@@ -367,7 +367,11 @@ __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E,
   }
   if (sub < k) {
     idx_out[sub] = my_idx;
-    w_out[sub] = renorm ? my_w / wsum : my_w;
+    float w = renorm ? my_w / wsum : my_w;
+    // mark_close: a token within the margin carries the sign bit on its first weight (a probability, never
+    // negative otherwise) until the kernel that recomputes such tokens has replaced its results
+    if (mark_close && close && sub == 0) w = __uint_as_float(__float_as_uint(w) | 0x80000000u);
+    w_out[sub] = w;
   }
   return close;
 }
@@ -713,8 +717,8 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
                                             int t, int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
                                             float* __restrict__ topk_w, float* __restrict__ probs, double* lds) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int EP = E <= 16 ? 16 : E <= 32 ? 32 : 64;
-  const int QN = EP / 4, RPI = 64 / QN;
+  // expert quads per router row (a power of two that covers E) and router rows per wave-wide load instruction
+  const int QN = E <= 4 ? 1 : E <= 8 ? 2 : E <= 16 ? 4 : E <= 32 ? 8 : 16, RPI = 64 / QN;
   double* zpart = lds;                  // [GP_WAVES][64]
   double* zex = lds + GP_WAVES * 64;    // [64]
   const int q = lane % QN, rs = lane / QN;
@@ -722,25 +726,44 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
   const bool vec = (E & 3) == 0 && (reinterpret_cast<uintptr_t>(wr) & 15) == 0;
   const uint16_t* xt = x + (size_t)t * d;
   double a[4] = {0.0, 0.0, 0.0, 0.0};
-  const int r_end = (wave + 1) * rows_per_wave;
-#pragma unroll 16
-  for (int r = wave * rows_per_wave + rs; r < r_end; r += RPI) {
-    const double xv = (double)bf16_to_f32(xt[r]);
-    const float* wq = wr + (size_t)r * E + q * 4;
-    float w4[4] = {0.f, 0.f, 0.f, 0.f};
-    if (vec) {
-      if (q * 4 < E) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(wq);
-        w4[0] = v[0]; w4[1] = v[1]; w4[2] = v[2]; w4[3] = v[3];
+  // All loads of a batch are issued before the first is used, and the trip count is the same for every lane (rows
+  // past the wavefront's range re-read its first row and are multiplied by zero): a loop that can leave early
+  // makes the compiler wait for every load where it stands, and the token then costs one memory latency per
+  // router row instead of one per batch.
+  const int r_begin = wave * rows_per_wave, r_end = r_begin + rows_per_wave;
+  const int n_it = (rows_per_wave + RPI - 1) / RPI;
+  constexpr int BATCH = 16;
+  const bool q_live = q * 4 < E;
+  const int last = q_live ? min(3, E - 1 - q * 4) : 0;   // scalar loads of a ragged last quad stay inside the row
+  auto rows = [&](auto is_vec) {
+    for (int it0 = 0; it0 < n_it; it0 += BATCH) {
+      float w4[BATCH][4];
+      uint16_t xb[BATCH];
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const int r = r_begin + rs + (it0 + j) * RPI;
+        const int rc = r < r_end ? r : r_begin;
+        const float* wq = q_live ? wr + (size_t)rc * E + q * 4 : wr;   // quads past the last expert read the first row
+        if constexpr (decltype(is_vec)::value) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(wq);
+          w4[j][0] = v[0]; w4[j][1] = v[1]; w4[j][2] = v[2]; w4[j][3] = v[3];
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) w4[j][c] = wq[min(c, last)];
+        }
+        xb[j] = xt[rc];
       }
-    } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (q * 4 + j < E) w4[j] = wq[j];
+      for (int j = 0; j < BATCH; ++j) {
+        const int r = r_begin + rs + (it0 + j) * RPI;
+        const double xd = r < r_end ? (double)bf16_to_f32(xb[j]) : 0.0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[c] = fma(xd, (q * 4 + c < E) ? (double)w4[j][c] : 0.0, a[c]);
+      }
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) a[j] = fma(xv, (double)w4[j], a[j]);
-  }
+  };
+  if (vec) rows(std::true_type{});
+  else rows(std::false_type{});
   for (int m = QN; m < 64; m <<= 1)
 #pragma unroll
     for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
@@ -765,41 +788,38 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
   }
 }
 
-// Recomputes the tokens that gate_packed_kernel marked: one workgroup looks at FIX_TOKENS flags and works through
-// the marked ones (almost always none, rarely one or two; few, large workgroups: launching thousands of
-// workgroups that find nothing to do took longer than the recomputes themselves).
-constexpr int FIX_TOKENS = 256;
+// Recomputes the tokens that gate_packed_kernel marked (sign bit of the first gate weight): one workgroup looks at
+// FIX_TOKENS tokens and works through the marked ones (almost always none, rarely one), replacing indices, weights
+// and probabilities.  Launched behind every gate_packed_kernel: inside that kernel a marked token would hold up its
+// whole workgroup, and with it the kernel, for the time of a chain of dependent loads.
+constexpr int FIX_TOKENS = 64;
 __global__ __launch_bounds__(GP_WAVES * 64) void gate_fix_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
-                                                                 const float* __restrict__ br, const uint8_t* __restrict__ flags, int T,
-                                                                 int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
-                                                                 float* __restrict__ topk_w, float* __restrict__ probs) {
+                                                                 const float* __restrict__ br, int T, int d, int E, int k, int renorm,
+                                                                 int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                                 float* __restrict__ probs) {
   __shared__ double lds[(GP_WAVES + 1) * 64];
   const int lane = threadIdx.x & 63;
   const int t0 = blockIdx.x * FIX_TOKENS;
-#pragma unroll
-  for (int g = 0; g < FIX_TOKENS / 64; ++g) {
-    const int t = t0 + 64 * g + lane;
-    unsigned long long todo = __ballot(t < T && flags[min(t, T - 1)] != 0);
-    while (todo) {
-      const int st = 64 * g + __builtin_ctzll(todo);
-      todo &= todo - 1;
-      __syncthreads();
-      exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, lds);
-    }
+  static_assert(FIX_TOKENS == 64, "one ballot");
+  const int t = t0 + lane;
+  unsigned long long todo = __ballot(t < T && (__float_as_uint(topk_w[(size_t)min(t, T - 1) * k]) >> 31) != 0);
+  while (todo) {
+    const int st = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    __syncthreads();
+    exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, lds);
   }
 }
 
 // What follows the contraction in the gate kernels on a packed router: acc[nb][fr] holds this wavefront's partial
 // sums (router rows x tokens, the MFMA's accumulator layout) for the NT = 32 NB tokens from t0 on.  The partial sums
 // of the eight wavefronts and the three pieces of every expert meet in float64 through LDS (smem: room for the
-// partial-sum matrices), then softmax, ranking and the margin test per token, and the exact recompute (or the
-// marks for gate_fix_kernel).
+// partial-sum matrices), then softmax, ranking and the margin test per token; tokens within the margin are
+// marked for gate_fix_kernel.
 template <int FR, int NB>
-__device__ __forceinline__ void gate_finish(f32x16 (&acc)[NB][FR], unsigned char* smem, int* s_flag, int t0,
-                                            const uint16_t* __restrict__ x, const float* __restrict__ wr,
-                                            const float* __restrict__ br, int T, int d, int E, int k, int renorm,
-                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ probs,
-                                            uint8_t* __restrict__ flags) {
+__device__ __forceinline__ void gate_finish(f32x16 (&acc)[NB][FR], unsigned char* smem, int t0, const float* __restrict__ br, int T,
+                                            int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                            float* __restrict__ probs) {
   constexpr int NT = 32 * NB, RW = 32 * FR;
   constexpr int STRIDE = NT + 8;  // floats between the rows of a partial-sum matrix (conflict-free reads and writes)
   constexpr int NPL = (32 * FR / 3 + 7) / 8;  // logits per lane of an 8-lane group (covers every E of this FR)
@@ -871,48 +891,21 @@ __device__ __forceinline__ void gate_finish(f32x16 (&acc)[NB][FR], unsigned char
 #pragma unroll
       for (int m = 1; m <= 4; m <<= 1) zabs = fmaxf(zabs, __shfl_xor(zabs, m, 64));
       const int tc = min(t, T - 1);
-      bool flag = false;
       if (t < T)
-        flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
-                                   probs ? probs + (size_t)tc * E : nullptr);
-      if (sub == 0) s_flag[slot_tok] = flag ? 1 : 0;
+        finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
+                            probs ? probs + (size_t)tc * E : nullptr, true);
     }
   }
-  __syncthreads();
 
-  // ---- exact recompute of the rare tokens whose ranking is within the margin ----------------------
-  // With a flag array from the caller the tokens are only marked here and gate_fix_kernel, launched behind this
-  // kernel, recomputes them, every one in a workgroup of its own: inside this kernel a flagged token would hold
-  // up its whole workgroup (and with it the kernel) for the time of a dependent chain of loads.
-  if (flags) {
-    for (int i = tid; i < NT && t0 + i < T; i += GP_WAVES * 64) flags[t0 + i] = (uint8_t)s_flag[i];
-  } else {
-    unsigned long long flagged[(NT + 63) / 64];
-#pragma unroll
-    for (int g = 0; g < (NT + 63) / 64; ++g) {
-      const int i = 64 * g + lane;
-      flagged[g] = __ballot(i < NT && s_flag[i < NT ? i : 0] != 0);
-    }
-#pragma unroll
-    for (int g = 0; g < (NT + 63) / 64; ++g)
-      while (flagged[g]) {
-        const int st = 64 * g + __builtin_ctzll(flagged[g]);
-        flagged[g] &= flagged[g] - 1;
-        __syncthreads();   // the previous readers of this LDS are done
-        exact_token(x, wr, br, t0 + st, d, E, k, renorm, topk_idx, topk_w, probs, reinterpret_cast<double*>(smem));
-      }
-  }
 }
 
 template <int FR, int NB>
 __global__ __launch_bounds__(GP_WAVES * 64) void gate_packed_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wp,
                                                                     const float* __restrict__ wr, const float* __restrict__ br, int T,
                                                                     int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx,
-                                                                    float* __restrict__ topk_w, float* __restrict__ probs,
-                                                                    uint8_t* __restrict__ flags) {
+                                                                    float* __restrict__ topk_w, float* __restrict__ probs) {
   constexpr int G = gate_substeps(FR), KC = 16 * G, NT = 32 * NB;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int s_flag[NT];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tok = lane & 31, h = lane >> 5;
   const int t0 = blockIdx.x * NT;
@@ -979,28 +972,25 @@ __global__ __launch_bounds__(GP_WAVES * 64) void gate_packed_kernel(const uint16
       load_stage(j, c + jj + PF * GP_WAVES);
     });
 
-  gate_finish<FR, NB>(acc, smem, s_flag, t0, x, wr, br, T, d, E, k, renorm, topk_idx, topk_w, probs, flags);
+  gate_finish<FR, NB>(acc, smem, t0, br, T, E, k, renorm, topk_idx, topk_w, probs);
 }
 
 template <int FR, int NB>
 int32_t launch_packed(const moe_config* cfg, const void* x, const void* packed, const float* w_router, const float* b_router,
-                      int32_t* topk_idx, float* topk_w, float* probs, uint8_t* flags, hipStream_t s) {
+                      int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   constexpr int NT = 32 * NB, RW = 32 * FR, STRIDE = NT + 8;
   constexpr bool TWO_ROUNDS = (size_t)GP_WAVES * RW * STRIDE * 4 > 150 * 1024;
-  constexpr size_t part_bytes = (size_t)(TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES) * RW * STRIDE * 4;
-  constexpr size_t exact_bytes = (size_t)(GP_WAVES + 1) * 64 * sizeof(double);
-  constexpr size_t shmem = part_bytes > exact_bytes ? part_bytes : exact_bytes;
-  static_assert(shmem + NT * 4 <= 160 * 1024, "partial sums do not fit the LDS");
+  constexpr size_t shmem = (size_t)(TWO_ROUNDS ? GP_WAVES / 2 : GP_WAVES) * RW * STRIDE * 4;
+  static_assert(shmem <= 160 * 1024, "partial sums do not fit the LDS");
   auto kern = gate_packed_kernel<FR, NB>;
   if (shmem > 65536) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
   }
   hipLaunchKernelGGL(kern, dim3((cfg->T + NT - 1) / NT), dim3(GP_WAVES * 64), shmem, s, (const uint16_t*)x, (const uint16_t*)packed,
-                     w_router, b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs, flags);
-  if (flags)
-    hipLaunchKernelGGL(gate_fix_kernel, dim3((cfg->T + FIX_TOKENS - 1) / FIX_TOKENS), dim3(GP_WAVES * 64), 0, s, (const uint16_t*)x,
-                       w_router, b_router, flags, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+                     w_router, b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
+  hipLaunchKernelGGL(gate_fix_kernel, dim3((cfg->T + FIX_TOKENS - 1) / FIX_TOKENS), dim3(GP_WAVES * 64), 0, s, (const uint16_t*)x,
+                     w_router, b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
   return check_hip(hipGetLastError(), "gate launch");
 }
 
@@ -1057,16 +1047,15 @@ bool gate_packed_applies(const moe_config* cfg, const float* w_router) {
 // second launch that recomputes the near-ties, not by the split).
 bool gate_packed_pays(const moe_config* cfg) { return (int64_t)cfg->T * cfg->d_model >= ((int64_t)1 << 26); }
 
-// flags (nullable): device scratch of T bytes; with it the near-tie tokens are recomputed by a second, small kernel
 int32_t launch_gate_packed(const moe_config* cfg, const void* x, const void* packed, const float* w_router, const float* b_router,
-                           int32_t* topk_idx, float* topk_w, float* probs, uint8_t* flags, hipStream_t s) {
+                           int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
   if (cfg->T == 0) return MOE_OK;
   const int FR = gate_frags(cfg->E);
   // tokens per workgroup: as many 32-token blocks as still give every compute unit a workgroup (each workgroup
   // reads the whole packed router once, from L2)
   const int forced = tuning(MOE_TUNE_GATE_TOKENS);
   auto wgs = [&](int nb) { return forced ? (forced == 32 * nb ? 1 << 20 : 0) : (cfg->T + 32 * nb - 1) / (32 * nb); };
-#define MOE_GATE_PACKED(fr, nb) return launch_packed<fr, nb>(cfg, x, packed, w_router, b_router, topk_idx, topk_w, probs, flags, s)
+#define MOE_GATE_PACKED(fr, nb) return launch_packed<fr, nb>(cfg, x, packed, w_router, b_router, topk_idx, topk_w, probs, s)
   switch (FR) {
     case 1:
       if (wgs(4) >= 256) MOE_GATE_PACKED(1, 4);
@@ -1086,9 +1075,9 @@ int32_t launch_gate_packed(const moe_config* cfg, const void* x, const void* pac
 
 // The gate of a layer: on the pre-split router when the weights carry one and it applies.
 int32_t launch_gate_of(const moe_config* cfg, const moe_weights* w, const void* x, int32_t* topk_idx, float* topk_w, float* probs,
-                       uint8_t* flags, hipStream_t s) {
+                       hipStream_t s) {
   if (w->w_router_packed && gate_packed_applies(cfg, w->w_router) && gate_packed_pays(cfg))
-    return launch_gate_packed(cfg, x, w->w_router_packed, w->w_router, w->b_router, topk_idx, topk_w, probs, flags, s);
+    return launch_gate_packed(cfg, x, w->w_router_packed, w->w_router, w->b_router, topk_idx, topk_w, probs, s);
   return launch_gate(cfg, x, w->w_router, w->b_router, topk_idx, topk_w, probs, s);
 }
 
@@ -1129,5 +1118,5 @@ extern "C" int32_t moe_gate_packed(const moe_config* cfg, const void* x, const f
     return fail(MOE_ERR_UNSUPPORTED, "moe_gate_packed: bf16 activations and at most 64 experts (use moe_gate)");
   if (!gate_packed_applies(cfg, w_router))   // steps of very few tokens: one workgroup per token on the float32 router
     return launch_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs, (hipStream_t)stream);
-  return launch_gate_packed(cfg, x, w_router_packed, w_router, b_router, topk_idx, topk_w, probs, nullptr, (hipStream_t)stream);
+  return launch_gate_packed(cfg, x, w_router_packed, w_router, b_router, topk_idx, topk_w, probs, (hipStream_t)stream);
 }

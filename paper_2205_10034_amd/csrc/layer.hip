@@ -65,7 +65,7 @@ int32_t route_impl(const char* who, const moe_config* cfg, const moe_weights* w,
     if ((st = mark(timer, 1, s)) != MOE_OK) return st;
     return mark(timer, 2, s);
   }
-  if ((st = launch_gate_of(cfg, w, x, sg.topk_idx, sg.topk_w, nullptr, (uint8_t*)sg.scratch + gate_flags_offset(cfg), s)) != MOE_OK) return st;
+  if ((st = launch_gate_of(cfg, w, x, sg.topk_idx, sg.topk_w, nullptr, s)) != MOE_OK) return st;
   if ((st = mark(timer, 1, s)) != MOE_OK) return st;
   // bf16: the first GEMM gathers its rows from x through row_to_assign, so no dispatched copy is made
   if ((st = launch_dispatch(cfg, x, sg.topk_idx, sg.counts, sg.offsets, sg.a2r, sg.r2a, gather ? nullptr : sg.xd,

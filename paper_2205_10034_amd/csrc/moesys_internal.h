@@ -46,13 +46,8 @@ int32_t launch_gate_dispatch_one_token(const moe_config* cfg, const void* x, con
 int32_t launch_gate(const moe_config* cfg, const void* x, const float* w_router, const float* b_router,
                     int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s);
 // the same on the pre-split router when w carries one (moe_weights.w_router_packed) and it applies
-// gate_flags (nullable): T bytes of device scratch for the packed gate's near-tie marks
 int32_t launch_gate_of(const moe_config* cfg, const moe_weights* w, const void* x, int32_t* topk_idx, float* topk_w, float* probs,
-                       uint8_t* gate_flags, hipStream_t s);
-// Byte offset of the gate's flag bytes inside the dispatch scratch segment of a layer workspace.
-inline size_t gate_flags_offset(const moe_config* cfg) {
-  return align_up(((size_t)dispatch_blocks(cfg) + 1) * cfg->E * 4 + 256, 256);
-}
+                       hipStream_t s);
 // clear8 (nullable): eight ints set to zero on the way (the first GEMM's tile counters).
 int32_t launch_dispatch(const moe_config* cfg, const void* x, const int32_t* topk_idx, int32_t* counts,
                         int32_t* offsets, int32_t* a2r, int32_t* r2a, void* xd, void* ws, int32_t* clear8,

@@ -24,6 +24,7 @@ def main():
     ap.add_argument("--sections", type=int, default=4)
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=4096)
+    ap.add_argument("--distinct", type=int, default=8, help="distinct layer blobs held in pinned host memory")
     args = ap.parse_args()
 
     import torch
@@ -39,23 +40,34 @@ def main():
     print(f"ring bench: {N} layers x {layer_bytes / 2**30:.2f} GiB in pinned host memory, "
           f"{K} sections = {K * layer_bytes / 2**30:.1f} GiB of HBM", flush=True)
 
-    torch.manual_seed(0)
+    # The seeded ring stack of workloads/ (one normal pool, layer l = the window at element l): the box caps pinned
+    # host memory near 64 GiB, below the stack's 96 GiB, so `--distinct` blobs are drawn (layers 0 .. distinct-1
+    # of the stack) and layer l streams blob l mod distinct; every layer has its own router.
+    from workloads import RingStackPool
     t0 = time.time()
-    blobs, routers = [], []
-    for l in range(N):
+    pool = RingStackPool(wl, N)
+    H = min(args.distinct, N)
+    pool_dev = torch.from_numpy(pool.pool).cuda()
+    distinct = []
+    for h in range(H):
+        dev = torch.empty(2 * n1, dtype=torch.bfloat16, device="cuda")
+        w1 = (pool_dev[h:h + n1] * float(pool.w1_scale)).to(torch.bfloat16).view(E, d, f)
+        M.moe_transpose_expert_weights(w1, dev[:n1].view(E, f, d))
+        w2 = (pool_dev[n1 + h:n1 + h + n1] * float(pool.w2_scale)).to(torch.bfloat16).view(E, f, d)
+        M.moe_transpose_expert_weights(w2, dev[n1:].view(E, d, f))
+        torch.cuda.synchronize()
+        del w1, w2
         blob = torch.empty(2 * n1, dtype=torch.bfloat16, pin_memory=True)
-        g = torch.randn(n1, device="cuda", dtype=torch.float32)
-        blob[:n1].copy_((g * d ** -0.5).to(torch.bfloat16))
-        g.normal_()
-        blob[n1:].copy_((g * (f ** -0.5 * wl.w2_std_scale)).to(torch.bfloat16))
-        blobs.append(blob)
-        routers.append((torch.randn(d, E, device="cuda") * d ** -0.5).contiguous())
-        if l % 4 == 3:
-            print(f"  filled {l + 1}/{N} layers ({time.time() - t0:.0f} s)", flush=True)
-    del g
+        blob.copy_(dev)
+        distinct.append(blob)
+        del dev
+        print(f"  drew {h + 1}/{H} distinct layer blobs ({time.time() - t0:.0f} s)", flush=True)
+    del pool_dev
+    blobs = [distinct[l % H] for l in range(N)]
+    routers = [torch.from_numpy(r).cuda() for r in pool.routers]
     torch.cuda.synchronize()
 
-    x0 = torch.randn(wl.T, d, device="cuda").to(torch.bfloat16)
+    x0 = torch.from_numpy(pool.x).cuda().to(torch.bfloat16)
     ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     region = torch.empty(min(K, N) * layer_bytes, dtype=torch.uint8, device="cuda")
     compute = torch.cuda.current_stream()
@@ -107,6 +119,7 @@ def main():
         "compute_only_ms_per_step": compute_ms,
         "overlap_efficiency": max(copy_ms, compute_ms) / step_ms,
         "hbm_weight_budget_gib": K * layer_bytes / 2 ** 30, "host_weight_gib": N * layer_bytes / 2 ** 30,
+        "distinct_layer_blobs_in_pinned_memory": H, "data": "seeded ring stack of workloads/ (synthetic)",
     }
     print(json.dumps(res))
 
