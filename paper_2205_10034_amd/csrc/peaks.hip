@@ -68,7 +68,7 @@ using namespace moesys;
 // out (host, 6 doubles): copy GB/s (read + written bytes), read GB/s, MFMA TFLOP/s, shader clock of the MFMA
 // loop in MHz, LDS read bytes per shader clock per CU, number of CUs.
 extern "C" int32_t moe_hw_peaks(double* out) {
-  if (!out) return fail(MOE_ERR_INVALID_ARG, "moe_hw_peaks: out is NULL");
+  if (!out) return fail(MOE_ERR_INVALID_ARG, "moe_hw_peaks: out (8 doubles) is NULL");
   hipDeviceProp_t prop;
   int32_t st;
   if ((st = check_hip(hipGetDeviceProperties(&prop, 0), "hipGetDeviceProperties")) != MOE_OK) return st;
@@ -99,6 +99,19 @@ extern "C" int32_t moe_hw_peaks(double* out) {
   (void)hipEventSynchronize(e1);
   (void)hipEventElapsedTime(&ms, e0, e1);
   out[1] = (double)bytes * reps / (ms * 1e-3) / 1e9;
+  // one launch that reads 256 MiB no cache holds (a 1 GiB copy ran since): what a kernel that reads its input once,
+  // in a layer whose GEMMs have replaced the caches' contents, can get
+  double cold_ms = 0.0;
+  for (int i = 0; i < reps; ++i) {
+    hipLaunchKernelGGL(copy_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, (u32x4*)dst, n);
+    (void)hipEventRecord(e0, 0);
+    hipLaunchKernelGGL(read_kernel, dim3(cus * 16), dim3(256), 0, 0, (const u32x4*)src, n / 4, (unsigned*)small);
+    (void)hipEventRecord(e1, 0);
+    (void)hipEventSynchronize(e1);
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    cold_ms += ms;
+  }
+  out[6] = (double)(bytes / 4) * reps / (cold_ms * 1e-3) / 1e9;
   unsigned long long* clocks = (unsigned long long*)((char*)small + 1024);
   const int iters = 20000;
   hipLaunchKernelGGL(mfma_kernel, dim3(cus), dim3(512), 0, 0, 100, (float*)small, clocks);

@@ -21,7 +21,7 @@ def main() -> int:
         return 2
     binding.use_library(PROF_LIB)
     L = binding.lib()
-    out = (ctypes.c_double * 6)()
+    out = (ctypes.c_double * 8)()
     L.moe_hw_peaks.argtypes = [ctypes.POINTER(ctypes.c_double)]
     st = L.moe_hw_peaks(out)
     if st != 0:
@@ -31,6 +31,7 @@ def main() -> int:
     print(f"compute units: {cus}")
     print(f"streaming copy, 1 GiB -> 1 GiB: {out[0]:8.0f} GB/s read+written   ({out[0] / 8000:.2f} of 8 TB/s)")
     print(f"streaming read, 1 GiB:          {out[1]:8.0f} GB/s                ({out[1] / 8000:.2f} of 8 TB/s)")
+    print(f"one cold read of 256 MiB:       {out[6]:8.0f} GB/s                ({out[6] / 8000:.2f} of 8 TB/s; one launch, events around it)")
     print(f"bf16 MFMA 32x32x16 loop:        {out[2]:8.1f} TFLOP/s at a shader clock of {out[3]:.0f} MHz "
           f"({out[2] / 2500:.2f} of 2.5 PFLOP/s; {out[2] * 1e12 / (cus * 4 * out[3] * 1e6):.0f} flop per clock per SIMD)")
     print(f"LDS 16-byte reads, conflict-free layout: {out[4]:6.1f} B per shader clock per CU")
