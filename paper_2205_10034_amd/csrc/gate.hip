@@ -732,10 +732,10 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
   // router row instead of one per batch.
   const int r_begin = wave * rows_per_wave, r_end = r_begin + rows_per_wave;
   const int n_it = (rows_per_wave + RPI - 1) / RPI;
-  constexpr int BATCH = 16;
   const bool q_live = q * 4 < E;
   const int last = q_live ? min(3, E - 1 - q * 4) : 0;   // scalar loads of a ragged last quad stay inside the row
-  auto rows = [&](auto is_vec) {
+  auto rows = [&](auto is_vec, auto batch) {
+    constexpr int BATCH = decltype(batch)::value;
     for (int it0 = 0; it0 < n_it; it0 += BATCH) {
       float w4[BATCH][4];
       uint16_t xb[BATCH];
@@ -762,8 +762,8 @@ __device__ __forceinline__ void exact_token(const uint16_t* __restrict__ x, cons
       }
     }
   };
-  if (vec) rows(std::true_type{});
-  else rows(std::false_type{});
+  if (vec) rows(std::true_type{}, std::integral_constant<int, 16>{});
+  else rows(std::false_type{}, std::integral_constant<int, 16>{});
   for (int m = QN; m < 64; m <<= 1)
 #pragma unroll
     for (int j = 0; j < 4; ++j) a[j] += shfl_xor_f64(a[j], m);
@@ -1044,8 +1044,11 @@ bool gate_packed_applies(const moe_config* cfg, const float* w_router) {
 }
 // Inside a layer the packed router is used where it measured faster than splitting on the fly: long token streams
 // (from about 64 M activation elements; below, the kernels are bound by their chain of dependent steps and by the
-// second launch that recomputes the near-ties, not by the split).
-bool gate_packed_pays(const moe_config* cfg) { return (int64_t)cfg->T * cfg->d_model >= ((int64_t)1 << 26); }
+// second launch that recomputes the near-ties, not by the split) and wide routers (more than 42 experts: there
+// the split, which every workgroup repeats for the whole router, is most of the other kernel's time).
+bool gate_packed_pays(const moe_config* cfg) {
+  return (int64_t)cfg->T * cfg->d_model >= ((int64_t)1 << 26) || (gate_frags(cfg->E) >= 4 && cfg->T >= 1024);
+}
 
 int32_t launch_gate_packed(const moe_config* cfg, const void* x, const void* packed, const float* w_router, const float* b_router,
                            int32_t* topk_idx, float* topk_w, float* probs, hipStream_t s) {
