@@ -61,6 +61,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -79,6 +80,18 @@ constexpr int NUM_CU = NUM_XCD * CU_PER_XCD;
 enum Epi { EPI_GELU = 0, EPI_SWIGLU = 1, EPI_BIAS = 2, EPI_COMBINE = 3, EPI_DGELU = 4, EPI_DSWIGLU = 5 };
 // tiles of a gate block and an up block side by side
 constexpr bool swiglu_tile(int epi) { return epi == EPI_SWIGLU || epi == EPI_DSWIGLU; }
+
+// Which MFMA multiplies.  Under these kernels the board sits at its power limit and the clock follows the energy
+// an instruction stream costs; measured on MI355X with random bf16 operands in registers and nothing else going on,
+// v_mfma_f32_16x16x32_bf16 delivers 2049 TFLOP/s and v_mfma_f32_32x32x16_bf16 1875 TFLOP/s at the same 1.3 kW (both
+// 2.47 PFLOP/s on all-zero operands, at 755 W and 881 W).  The LDS traffic is the same for both: a wavefront's
+// fragments per 32 values of the contraction index are (token rows + feature rows) x 64 bytes either way.  The
+// 16x16x32 form is used where a wavefront's token blocks come in pairs (the loop alternates between them);
+// bit e of the mask switches it on for epilogue e.
+#ifndef MOE_MI16_MASK
+#define MOE_MI16_MASK 0x3f
+#endif
+constexpr bool use_mi16(int tok, int wt, int epi) { return tok <= 256 && (tok / 32 / wt) % 2 == 0 && ((MOE_MI16_MASK >> epi) & 1); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // two floats -> two bf16 in one dword (lo in the low half): one v_cvt_pk_bf16_f32, round to nearest even
@@ -282,7 +295,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // WT-th 32-row block) x FEAT/WF LDS feature rows.  WPE = wavefronts per SIMD the register budget is sized for.
 // HASB = false: the caller passed no bias; its staging and the two vector instructions per element that add it
 // are compiled out (SwiGLU never has one).
-template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER, bool HASB>
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool GATHER, bool HASB, bool MI16_>
 __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     const uint16_t* __restrict__ act,     // [R, K]
     const uint16_t* __restrict__ wa,      // [E, N, K]   (W1 / Wg / W2)
@@ -323,6 +336,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   static_assert(EPI != EPI_DSWIGLU || FB == 2, "the SwiGLU-gradient epilogue is written for one gate and one up block");
   static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
   constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
+  constexpr bool MI16 = MI16_ && use_mi16(TOK, WT, EPI);  // 16x16x32 MFMAs, see `phase16`
   constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
   constexpr int PF_MIN_KT = 64;            // shortest K loop (in K-steps) that prefetches, see bind_prefetch
 
@@ -400,10 +414,13 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   const int b_blk = NW * RPI * (int)row_bytes;  // distance between the rows of consecutive loads
   // LDS byte address of this lane's fragment row with chunk key folded in: the chunk of K sub-step ks is
   // (2*ks + half) ^ key = (half ^ key) ^ 2*ks, i.e. base ^ (ks << 5).
-  const int frow = lane & 31, fhalf = lane >> 5;
+  // (16x16x32: a fragment is 16 rows x 32 values, lane = row + 16 * chunk; sub-step kk of 32 values is chunks
+  // 4*kk .. 4*kk+3, i.e. base ^ (kk << 6); a 32-row block is two such fragments 16 rows apart, same key)
+  const int frow = MI16 ? lane & 15 : lane & 31, fhalf = MI16 ? lane >> 4 : lane >> 5;
   // Block i of this wavefront lies a whole number of 32-row blocks further on, which leaves the key alone:
   // one base per operand, the block goes into the constant part of the address.
   static_assert(32 % (RPB * CHUNKS) == 0, "the swizzle key must repeat every 32 rows");
+  static_assert(!MI16 || (16 % (RPB * CHUNKS) == 0 && KS == 64), "16-row fragments: the key must repeat every 16 rows");
   const int a_row0 = wt * 32 + frow;
   const int w_row0 = (swiglu_tile(EPI) ? wf * (WFEAT / 2) : wf * WFEAT) + frow;  // SwiGLU: gate rows, the up rows FEAT/2 further
   const int a_base = a_row0 * ROW_BYTES + ((fhalf ^ ((a_row0 / RPB) % CHUNKS)) << 4);
@@ -539,8 +556,10 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 
   MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0; } pf = {};
            pf.c0 = __builtin_readcyclecounter(); pf.r0 = __builtin_amdgcn_s_memrealtime();)
+  // (16x16x32: acc[i][j] holds the four 16x16 sub-blocks of the 32x32 block, four registers each, number
+  // 2 * (token half) + (feature half); the fragment sets hold half of the token blocks, 16 rows at a time)
   f32x16 acc[TB][FB];
-  bf16x8 af[ABUF][TB], wfr[2][FB];
+  bf16x8 af[ABUF][MI16 ? (TB / 2) * 2 : TB], wfr[2][MI16 ? FB * 2 : FB];
   // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
   // hold at least one valid row (a partial tile - an expert's last rows - multiplies only those blocks;
   // a wavefront with none still takes part in the loads and the barriers).
@@ -559,7 +578,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // after each MFMA (group) while there are any.  Spreading the loads matters: the texture path accepts
     // one 1 KB load per 16 clocks and the issuing wavefront waits when its queue is full, so a burst of
     // loads ahead of the MFMAs leaves the matrix pipes idle while the burst drains.
-    auto read_w = [&](const unsigned char* B, int ks, bf16x8 (&w)[FB]) {
+    auto read_w = [&](const unsigned char* B, int ks, auto& w) {
 #pragma unroll
       for (int j = 0; j < NFB; ++j) w[j] = *reinterpret_cast<const bf16x8*>(B + (w_base ^ (ks << 5)) + w_blk(j));
     };
@@ -569,6 +588,9 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     auto substep = [&](const unsigned char* A, const unsigned char* B, int ks, int c, auto vm_tag) {
       constexpr int VM = decltype(vm_tag)::value;
       constexpr int MFMAS = TBV * FB;
+      if constexpr (MI16) {
+        return;  // (this wavefront's K loop is `step16`)
+      } else {
       read_w(B, ks, wfr[c ^ 1]);
       if constexpr (ABUF == 2) {
 #pragma unroll
@@ -603,6 +625,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             if (i * PER + p < VM) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // VMEM
         }
       }
+      }
     };
     // One K-step on the stage in `cur`.  On entry af/wfr[0] hold the fragments of sub-step 0 of that stage,
     // stage kt+1 has its token half in flight, and `nxt` (read by nobody since the last barrier) is free for
@@ -627,17 +650,104 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       issue_tokens(kt + 2, kt + 2 < KT, cur);
       substep(nxt, nxt + A_BYTES, 0, (NSUB - 1) & 1, std::integral_constant<int, A_LOADS>{});
     };
-    read_w(s0 + A_BYTES, 0, wfr[0]);
+    // ---- the same with 16x16x32 MFMAs ----
+    // A stage (64 values of the contraction index) is four phases: (kk, th) = (phase / 2, phase % 2) multiplies
+    // values 32*kk .. 32*kk+31 for the token blocks 2*th and 2*th+1 of this wavefront (those of them that hold
+    // rows).  A phase needs the 2*FB weight fragments of kk (kept twice: set kk & 1) and the up to four token
+    // fragments of (kk, th) (kept twice: set phase & 1), and reads the next phase's token fragments, plus the
+    // next kk's weight fragments when it is the last phase of its kk, while it multiplies: 16 MFMAs of half
+    // the length and 4 or 8 fragment reads, where the 32x32x16 loop has 8 MFMAs and 6 reads per sub-step.
+    constexpr int HTB = TB / 2;
+    auto read_w16 = [&](const unsigned char* B, int kk, bf16x8 (&w)[MI16 ? FB * 2 : FB]) {
+      if constexpr (MI16) {
 #pragma unroll
-    for (int i = 0; i < TBV; ++i) read_a(s0, 0, af[0][i], i);
+        for (int j = 0; j < NFB; ++j)
+#pragma unroll
+          for (int fh = 0; fh < 2; ++fh)
+            w[2 * j + fh] = *reinterpret_cast<const bf16x8*>(B + (w_base ^ (kk << 6)) + w_blk(j) + fh * 16 * ROW_BYTES);
+      }
+    };
+    // token blocks of half th that hold rows
+    auto blocks_of = [](int th) constexpr { return TBV - HTB * th < 0 ? 0 : (TBV - HTB * th > HTB ? HTB : TBV - HTB * th); };
+    auto read_a16 = [&](const unsigned char* A, int kk, int th, auto nb_tag, bf16x8 (&a)[MI16 ? HTB * 2 : TB]) {
+      if constexpr (MI16) {
+#pragma unroll
+        for (int i = 0; i < decltype(nb_tag)::value; ++i)
+#pragma unroll
+          for (int sh = 0; sh < 2; ++sh)
+            a[2 * i + sh] = *reinterpret_cast<const bf16x8*>(A + (a_base ^ (kk << 6)) + (th * HTB + i) * A_BLK + sh * 16 * ROW_BYTES);
+      }
+    };
+    // phase PH of the stage whose fragments are at hand; the fragments of phase (PH + 1) % 4 are read from (A, B),
+    // which is the same stage, or the next one for PH = 3
+    auto phase16 = [&](const unsigned char* A, const unsigned char* B, auto ph_tag, auto vm_tag) {
+      if constexpr (MI16) {
+        constexpr int PH = decltype(ph_tag)::value, VM = decltype(vm_tag)::value;
+        constexpr int KK = PH / 2, TH = PH % 2, NPH = (PH + 1) % 4, NKK = NPH / 2, NTH = NPH % 2;
+        constexpr int NB = blocks_of(TH), NNB = blocks_of(NTH);
+        constexpr int MFMAS = NB * 2 * FB * 2;
+        constexpr int READS = NNB * 2 + (NKK != KK ? NFB * 2 : 0);
+        if constexpr (NKK != KK) read_w16(B, NKK, wfr[NKK & 1]);
+        read_a16(A, NKK, NTH, std::integral_constant<int, NNB>{}, af[NPH & 1]);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+          for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int sh = 0; sh < 2; ++sh)
+#pragma unroll
+              for (int fh = 0; fh < 2; ++fh) {
+                f32x16& t = acc[TH * HTB + i][j];
+                const int q = (2 * sh + fh) * 4;
+                f32x4 c = {t[q], t[q + 1], t[q + 2], t[q + 3]};
+                c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[KK & 1][2 * j + fh], af[PH & 1][2 * i + sh], c, 0, 0, 0);
+                t[q] = c[0]; t[q + 1] = c[1]; t[q + 2] = c[2]; t[q + 3] = c[3];
+              }
+        // two MFMAs, then a fragment read and a global load while there are any
+        constexpr int SLOTS = MFMAS / 2;
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                 // MFMA
+          if (q < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+          if (q < VM) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);     // VMEM
+        }
+      }
+    };
+    auto step16 = [&](int kt, unsigned char* cur, unsigned char* nxt) {
+      issue_weights(kt + 1, kt + 1 < KT, nxt);
+      issue_prefetch(kt + 1 + PF_LEAD);
+      phase16(cur, cur + A_BYTES, std::integral_constant<int, 0>{}, std::integral_constant<int, W_LOADS + 1>{});
+      phase16(cur, cur + A_BYTES, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+      phase16(cur, cur + A_BYTES, std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
+      MOE_PROF(__builtin_amdgcn_s_waitcnt(0xc07f); const unsigned long long t_a = __builtin_readcyclecounter();)
+      __builtin_amdgcn_s_waitcnt(0x0071);  // vmcnt(1), expcnt untouched, lgkmcnt(0)
+      MOE_PROF(const unsigned long long t_b = __builtin_readcyclecounter();)
+      __builtin_amdgcn_s_barrier();
+      MOE_PROF(const unsigned long long t_c = __builtin_readcyclecounter(); pf.comp += t_a - pf.last; pf.vm += t_b - t_a;
+               pf.bar += t_c - t_b; pf.last = t_c; ++pf.steps;)
+      issue_tokens(kt + 2, kt + 2 < KT, cur);
+      phase16(nxt, nxt + A_BYTES, std::integral_constant<int, 3>{}, std::integral_constant<int, A_LOADS>{});
+    };
+    if constexpr (MI16) {
+      read_w16(s0 + A_BYTES, 0, wfr[0]);
+      read_a16(s0, 0, 0, std::integral_constant<int, blocks_of(0)>{}, af[0]);
+    } else {
+      read_w(s0 + A_BYTES, 0, wfr[0]);
+#pragma unroll
+      for (int i = 0; i < TBV; ++i) read_a(s0, 0, af[0][i], i);
+    }
+    auto any_step = [&](int kt, unsigned char* cur, unsigned char* nxt) {
+      if constexpr (MI16) step16(kt, cur, nxt);
+      else step(kt, cur, nxt);
+    };
     int kt = 0;
     for (; kt + 1 < KT; kt += 2) {
-      step(kt, s0, s1);
-      step(kt + 1, s1, s0);
+      any_step(kt, s0, s1);
+      any_step(kt + 1, s1, s0);
       if (kt == 0) publish_next();
       if (kt == 2) resolve_next();  // the two K-steps since publish_next() each passed a barrier
     }
-    if (kt < KT) step(kt, s0, s1);
+    if (kt < KT) any_step(kt, s0, s1);
   };
 
   // ---- persistent loop over this workgroup's slots ------------------------------------------------
@@ -711,46 +821,68 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     // (i, i+1) they trade halves (v_permlane32_swap: the upper lanes' first operand against the lower lanes'
     // second), after which lane l owns all 8 features of group i and lane l+32 those of group i+1: one
     // 16-byte store per lane and pair instead of two 8-byte ones.
+    // With 16x16x32 MFMAs a lane holds token (lane&15) of each 16-token half of the block and features
+    // 4*(lane>>4) + r of each 16-feature half: registers 4*(2*sh + fh) + r of acc[tb][fb].  The code below is the
+    // same for both with the pair index i0 = 0, 2 read as the token half sh = i0/2 and the member g of a pair
+    // as the feature half: lanes l and l+16 hold features 4m..4m+3 and 4m+4..4m+7 of both feature halves and
+    // trade (v_permlane16_swap), after which the even 16-lane row owns 8 features of the first half and the odd
+    // row 8 of the second.
     const int feat0 = done.ntile * OUT_FEAT;
-    auto store_pair = [&](uint16_t* orow, int n0, int i0, const float (&p)[8]) {
-      const u32x2 sx = __builtin_amdgcn_permlane32_swap(pack_bf16(p[0], p[1]), pack_bf16(p[4], p[5]), false, false);
-      const u32x2 sy = __builtin_amdgcn_permlane32_swap(pack_bf16(p[2], p[3]), pack_bf16(p[6], p[7]), false, false);
-      *reinterpret_cast<u32x4*>(orow + n0 + 8 * (i0 + fhalf)) = u32x4{sx.x, sy.x, sx.y, sy.y};
+    // where this lane's four features of member g of pair i0 start inside a 32-feature block (before the trade)
+    auto run_off = [&](int i0, int g) { return MI16 ? 16 * g + 4 * fhalf : 8 * (i0 + g) + 4 * fhalf; };
+    // where the eight features this lane stores for pair i0 start (after the trade)
+    auto store_off = [&](int i0) { return MI16 ? 16 * (fhalf & 1) + 8 * (fhalf >> 1) : 8 * (i0 + fhalf); };
+    // this lane's row of the tile for token block tb and pair i0
+    auto tile_row = [&](int tb, int i0) { return (tb * WT + wt) * 32 + (MI16 ? 16 * (i0 >> 1) : 0) + frow; };
+    auto trade = [&](uint32_t x, uint32_t y) {
+      if constexpr (MI16) return __builtin_amdgcn_permlane16_swap(x, y, false, false);
+      else return __builtin_amdgcn_permlane32_swap(x, y, false, false);
     };
-    int row_tok[TB];   // EPI_COMBINE: token and gate weight of this lane's row in every token block
-    float row_gw[TB];
+    auto store_pair = [&](uint16_t* orow, int n0, int i0, const float (&p)[8], bool live) {
+      const u32x2 sx = trade(pack_bf16(p[0], p[1]), pack_bf16(p[4], p[5]));
+      const u32x2 sy = trade(pack_bf16(p[2], p[3]), pack_bf16(p[6], p[7]));
+      if (live) *reinterpret_cast<u32x4*>(orow + n0 + store_off(i0)) = u32x4{sx.x, sy.x, sx.y, sy.y};
+    };
+    constexpr int RSETS = MI16 ? 2 : 1;  // rows of a lane per token block
+    int row_tok[TB * RSETS];   // EPI_COMBINE: token and gate weight of this lane's rows in every token block
+    float row_gw[TB * RSETS];
     if constexpr (EPI == EPI_COMBINE) {
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb) {
-        row_tok[tb] = s_rowtok[done_set * NW * 64 + min((tb * WT + wt) * 32 + frow, done.rows - 1)];
-        row_gw[tb] = gate_w[row_tok[tb]];
-      }
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int rs = 0; rs < RSETS; ++rs) {
+          row_tok[tb * RSETS + rs] = s_rowtok[done_set * NW * 64 + min(tile_row(tb, 2 * rs), done.rows - 1)];
+          row_gw[tb * RSETS + rs] = gate_w[row_tok[tb * RSETS + rs]];
+        }
     }
     // EPI_DGELU: the activations' gradient for one (token block, feature block, group pair) step, loaded one
-    // step ahead of its use in the layout of the stores: 16 bytes per lane, the 8 features of group i0 in lane
-    // l and those of group i0 + 1 in lane l + 32 (rows past the tile's last re-read the last row)
+    // step ahead of its use in the layout of the stores: 16 bytes per lane, the 8 features this lane stores
+    // (rows past the tile's last re-read the last row)
     auto aux_load = [&](int tb, int fb, int i0) {
-      const int trow = min((tb * WT + wt) * 32 + frow, done.rows - 1);
+      const int trow = min(tile_row(tb, i0), done.rows - 1);
       return *reinterpret_cast<const u32x4*>(residual + (size_t)(done.row0 + trow) * N + feat0 +
-                                             (swiglu_tile(EPI) ? wf * 32 : wf * WFEAT + fb * 32) + 8 * (i0 + fhalf));
+                                             (swiglu_tile(EPI) ? wf * 32 : wf * WFEAT + fb * 32) + store_off(i0));
     };
     u32x4 aux_next = {0u, 0u, 0u, 0u};
     if constexpr (EPI == EPI_DGELU || EPI == EPI_DSWIGLU) aux_next = aux_load(0, 0, 0);
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-      const int trow = (tb * WT + wt) * 32 + frow;
-      // (lanes l and l+32 share the row: they stay or leave together; the rows grow with tb, so nothing after
-      // a skipped block is processed either)
-      if (trow >= done.rows) continue;
-      const size_t orow_idx = EPI == EPI_COMBINE ? (size_t)row_tok[tb] : (size_t)(done.row0 + trow);
-      uint16_t* orow = out + orow_idx * N;
+      // 32x32x16: lanes l and l+32 share the row, they stay or leave together; the rows grow with tb, so nothing
+      // after a skipped block is processed either.  16x16x32: a block is left when it holds no row at all (the
+      // same for the whole wavefront); inside a block only the stores depend on the row, because the second
+      // half's rows may lie past the end when the first half's do not.
+      if (MI16 ? (tb * WT + wt) * 32 >= done.rows : tile_row(tb, 0) >= done.rows) continue;
+      auto live_row = [&](int i0) { return !MI16 || tile_row(tb, i0) < done.rows; };
+      auto out_row = [&](int i0) {
+        return EPI == EPI_COMBINE ? (size_t)row_tok[tb * RSETS + (MI16 ? i0 >> 1 : 0)] : (size_t)(done.row0 + tile_row(tb, i0));
+      };
       if constexpr (EPI == EPI_DSWIGLU) {
-        uint16_t* orow2 = out + orow_idx * (size_t)(2 * N);  // [d_g | d_u] rows
 #pragma unroll
         for (int i0 = 0; i0 < 4; i0 += 2) {
+          uint16_t* orow2 = out + out_row(i0) * (size_t)(2 * N);  // [d_g | d_u] rows
           // aux in the layout of the stores, the halves traded back (as in EPI_DGELU)
-          const u32x2 sx = __builtin_amdgcn_permlane32_swap(aux_next.x, aux_next.z, false, false);
-          const u32x2 sy = __builtin_amdgcn_permlane32_swap(aux_next.y, aux_next.w, false, false);
+          const u32x2 sx = trade(aux_next.x, aux_next.z);
+          const u32x2 sy = trade(aux_next.y, aux_next.w);
           if (i0 + 2 < 4) aux_next = aux_load(tb, 0, i0 + 2);
           else if (tb + 1 < TB) aux_next = aux_load(tb + 1, 0, 0);
           float pg[8], pu[8];
@@ -768,8 +900,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
               pg[4 * g + q] = ds * uv * fmaf(gv, 1.f - sg, 1.f);           // d_g = d_h * u * s (1 + g (1 - s))
             }
           }
-          store_pair(orow2, feat0 + wf * 32, i0, pg);
-          store_pair(orow2 + N, feat0 + wf * 32, i0, pu);
+          store_pair(orow2, feat0 + wf * 32, i0, pg, live_row(i0));
+          store_pair(orow2 + N, feat0 + wf * 32, i0, pu, live_row(i0));
         }
       } else if (EPI == EPI_SWIGLU) {
 #pragma unroll
@@ -779,20 +911,21 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             float p[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][fb][4 * i0 + r]) * acc[tb][FBH + fb][4 * i0 + r];
-            store_pair(orow, feat0 + wf * (WFEAT / 2) + fb * 32, i0, p);
+            store_pair(out + out_row(i0) * N, feat0 + wf * (WFEAT / 2) + fb * 32, i0, p, live_row(i0));
           }
       } else {
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
           for (int i0 = 0; i0 < 4; i0 += 2) {
+            const size_t orow_idx = out_row(i0);
             float p[8];
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
               if constexpr (HASB) {
                 // the bias sits in this wavefront's LDS slot since the tile's prologue
                 const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 +
-                                                                (fb * 32 + 8 * (i0 + g) + 4 * fhalf) * 2);
+                                                                (fb * 32 + run_off(i0, g)) * 2);
                 p[4 * g + 0] = acc[tb][fb][4 * (i0 + g) + 0] + bf16_bits_to_f32(b.x & 0xffffu);
                 p[4 * g + 1] = acc[tb][fb][4 * (i0 + g) + 1] + __uint_as_float(b.x & 0xffff0000u);
                 p[4 * g + 2] = acc[tb][fb][4 * (i0 + g) + 2] + bf16_bits_to_f32(b.y & 0xffffu);
@@ -811,10 +944,10 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
               // (every element is read by the lane that multiplies it, before the lanes trade halves and before
               // that row segment is stored, so aux may be the output itself)
               float dh[8];
-              // the store's trade of halves, backwards: lane l gets features 0..3 of both groups, lane l + 32
-              // features 4..7 (element g of sx, sy: this lane's features of group i0 + g)
-              const u32x2 sx = __builtin_amdgcn_permlane32_swap(aux_next.x, aux_next.z, false, false);
-              const u32x2 sy = __builtin_amdgcn_permlane32_swap(aux_next.y, aux_next.w, false, false);
+              // the store's trade of halves, backwards: every lane gets its own four features of both members
+              // of the pair (element g of sx, sy: this lane's features of member g)
+              const u32x2 sx = trade(aux_next.x, aux_next.z);
+              const u32x2 sy = trade(aux_next.y, aux_next.w);
               {
                 int ni0 = i0 + 2, nfb = fb, ntb = tb;
                 if (ni0 == 4) { ni0 = 0; if (++nfb == FB) { nfb = 0; ++ntb; } }
@@ -833,19 +966,19 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             }
             if constexpr (EPI == EPI_COMBINE) {
               // before the lanes trade halves: this lane's 4 + 4 features of the residual row
+              const float gw = row_gw[tb * RSETS + (MI16 ? i0 >> 1 : 0)];
 #pragma unroll
               for (int g = 0; g < 2; ++g) {
                 u32x2 rv = {0u, 0u};
                 if (residual)
-                  rv = *reinterpret_cast<const u32x2*>(residual + orow_idx * N + feat0 + wf * WFEAT + fb * 32 +
-                                                       8 * (i0 + g) + 4 * fhalf);
-                p[4 * g + 0] = __builtin_fmaf(row_gw[tb], p[4 * g + 0], bf16_bits_to_f32(rv.x & 0xffffu));
-                p[4 * g + 1] = __builtin_fmaf(row_gw[tb], p[4 * g + 1], __uint_as_float(rv.x & 0xffff0000u));
-                p[4 * g + 2] = __builtin_fmaf(row_gw[tb], p[4 * g + 2], bf16_bits_to_f32(rv.y & 0xffffu));
-                p[4 * g + 3] = __builtin_fmaf(row_gw[tb], p[4 * g + 3], __uint_as_float(rv.y & 0xffff0000u));
+                  rv = *reinterpret_cast<const u32x2*>(residual + orow_idx * N + feat0 + wf * WFEAT + fb * 32 + run_off(i0, g));
+                p[4 * g + 0] = __builtin_fmaf(gw, p[4 * g + 0], bf16_bits_to_f32(rv.x & 0xffffu));
+                p[4 * g + 1] = __builtin_fmaf(gw, p[4 * g + 1], __uint_as_float(rv.x & 0xffff0000u));
+                p[4 * g + 2] = __builtin_fmaf(gw, p[4 * g + 2], bf16_bits_to_f32(rv.y & 0xffffu));
+                p[4 * g + 3] = __builtin_fmaf(gw, p[4 * g + 3], __uint_as_float(rv.y & 0xffff0000u));
               }
             }
-            store_pair(orow, feat0 + wf * WFEAT + fb * 32, i0, p);
+            store_pair(out + orow_idx * N, feat0 + wf * WFEAT + fb * 32, i0, p, live_row(i0));
           }
       }
     }
@@ -861,7 +994,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #endif
 }
 
-template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI>
+template <int TOK, int FEAT, int WT, int WF, int KS, int WPE, int EPI, bool MI16_ = false>
 int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, const uint16_t* wb,
                const uint16_t* bias, const int32_t* offsets, uint16_t* out, const int32_t* row_map,
                int32_t* tile_ctr, int32_t* clear_ctr, int N, int K, hipStream_t s, const int64_t* eoff,
@@ -885,18 +1018,18 @@ int32_t launch(const moe_config* cfg, const uint16_t* act, const uint16_t* wa, c
   const int64_t per_xcd = ((blocks + NUM_XCD - 1) / NUM_XCD) * CU_PER_XCD;  // tiles one XCD may own
   const int64_t grid = (per_xcd < CU_PER_XCD ? per_xcd : CU_PER_XCD) * NUM_XCD;
   // the gathering variant exists for the first GEMM's epilogues only
-  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, false>;
+  auto kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, false, MI16_>;
   if constexpr (EPI == EPI_DSWIGLU) {
     if (row_map || !residual || bias) return fail(MOE_ERR_INVALID_ARG, "grouped GEMM: the SwiGLU-gradient epilogue reads contiguous rows, needs the activations' gradient and has no bias");
   } else if constexpr (EPI == EPI_SWIGLU) {
-    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
+    if (row_map) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false, MI16_>;
   } else {
-    if (bias) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, true>;
+    if (bias) kern = grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, false, true, MI16_>;
   }
   if constexpr (EPI == EPI_GELU) {
     if (row_map)
-      kern = bias ? grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, true>
-                  : grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false>;
+      kern = bias ? grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, true, MI16_>
+                  : grouped_gemm_kernel<TOK, FEAT, WT, WF, KS, WPE, EPI, true, false, MI16_>;
   } else if constexpr (swiglu_tile(EPI)) {
   } else if constexpr (EPI == EPI_BIAS) {
     if (row_map) return fail(MOE_ERR_UNSUPPORTED, "grouped GEMM: the second GEMM reads contiguous rows");
@@ -944,6 +1077,16 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
   return best;
 }
 
+// The 16x16x32 loop is used where an evenly loaded expert fills whole tiles; with few rows per expert (the kernel is
+// then bound by streaming the weights, and half of the loop's phases have nothing to multiply) the 32x32x16 loop
+// measured 3 % faster.
+bool prefer_mi16(const moe_config* cfg) {
+  int64_t rows = ((int64_t)cfg->k * cfg->T + cfg->E - 1) / cfg->E;
+  const int64_t C = moe_capacity(cfg);
+  if (C != MOE_DROPLESS && rows > C) rows = C;
+  return rows >= 192;
+}
+
 // One grouped GEMM.  256x256x64 tiles (8 wavefronts, the highest arithmetic intensity that fits the
 // 160 KB LDS) whenever the feature count allows; feature counts that are multiples of 64 but not of 256
 // use narrow tiles.
@@ -956,6 +1099,8 @@ int32_t gemm_any(const moe_config* cfg, const uint16_t* a, const uint16_t* wa, c
   if (N % BF == 0) {
     if (pick_tile_rows(cfg, N / BF) == 320)
       return launch<320, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
+    if (use_mi16(256, 2, EPI) && prefer_mi16(cfg))
+      return launch<256, 256, 2, 4, 64, 2, EPI, true>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
     return launch<256, 256, 2, 4, 64, 2, EPI>(cfg, a, wa, wb, bias, offsets, o, row_map, tile_ctr, clear_ctr, N, K, s, eoff, gate_w, residual);
   }
   if constexpr (swiglu_tile(EPI))
