@@ -67,6 +67,59 @@ using namespace moesys;
 
 // out (host, 6 doubles): copy GB/s (read + written bytes), read GB/s, MFMA TFLOP/s, shader clock of the MFMA
 // loop in MHz, LDS read bytes per shader clock per CU, number of CUs.
+// Loops of nothing but MFMAs on random (or all-zero) bf16 operands held in registers, for the power probe: the rate
+// the matrix pipes reach at the board's power limit depends on the instruction and on the operand values.
+// KIND 0: v_mfma_f32_32x32x16_bf16, 4 x 2 fragments of two sub-steps (one 128 x 64 wave tile, 32 values of the
+// contraction index); KIND 1: v_mfma_f32_16x16x32_bf16, 8 x 4 fragments (the same wave tile and values).
+__device__ inline unsigned mix32(unsigned x) { x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16; return x; }
+__device__ inline bf16x8 random_fragment(unsigned seed, bool zero) {
+  bf16x8 v;
+  for (int i = 0; i < 8; ++i) {
+    const unsigned h = mix32(seed * 8 + i);  // roughly normal: four uniforms, centred
+    const float u = ((h & 255) + ((h >> 8) & 255) + ((h >> 16) & 255) + (h >> 24)) / 256.f - 2.f;
+    v[i] = (__bf16)(zero ? 0.f : u);
+  }
+  return v;
+}
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int KIND>
+__global__ __launch_bounds__(512) void mfma_operand_loop(int iters, int zero, float* out) {
+  const unsigned tid = blockIdx.x * 512 + threadIdx.x;
+  float s = 0.f;
+  if constexpr (KIND == 0) {
+    f32x16 acc[4][2];
+    for (auto& r : acc) for (auto& a : r) for (int v = 0; v < 16; ++v) a[v] = 0.f;
+    bf16x8 A[2][4], B[2][2];
+    for (int c = 0; c < 2; ++c) {
+      for (int i = 0; i < 4; ++i) A[c][i] = random_fragment(tid * 64 + c * 8 + i, zero);
+      for (int j = 0; j < 2; ++j) B[c][j] = random_fragment(tid * 64 + 32 + c * 4 + j, zero);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[c][i], B[c][j], acc[i][j], 0, 0, 0);
+    }
+    for (auto& r : acc) for (auto& a : r) s += a[0] + a[7];
+  } else {
+    f32x4 acc[8][4];
+    for (auto& r : acc) for (auto& a : r) for (int v = 0; v < 4; ++v) a[v] = 0.f;
+    bf16x8 A[8], B[4];
+    for (int i = 0; i < 8; ++i) A[i] = random_fragment(tid * 64 + i, zero);
+    for (int j = 0; j < 4; ++j) B[j] = random_fragment(tid * 64 + 32 + j, zero);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[i], B[j], acc[i][j], 0, 0, 0);
+    }
+    for (auto& r : acc) for (auto& a : r) s += a[0] + a[3];
+  }
+  if (s == 12345.678f) out[0] = s;  // never true; keeps the loop
+}
+
 extern "C" int32_t moe_hw_peaks(double* out) {
   if (!out) return fail(MOE_ERR_INVALID_ARG, "moe_hw_peaks: out (8 doubles) is NULL");
   hipDeviceProp_t prop;
@@ -135,4 +188,31 @@ extern "C" int32_t moe_hw_peaks(double* out) {
   (void)hipFree(small);
   if (st != MOE_OK) return st;
   return check_hip(hipGetLastError(), "moe_hw_peaks");
+}
+
+// One launch of the MFMA-only loop (kind 0: 32x32x16, 1: 16x16x32; zero != 0: all-zero operands) on every compute unit,
+// synchronous; *tflops receives its rate.  Allocates 4 KB on its first call and keeps it.
+extern "C" int32_t moe_mfma_operand_loop(int32_t kind, int32_t zero, int32_t iters, double* tflops) {
+  if (!tflops || iters < 1 || kind < 0 || kind > 1) return fail(MOE_ERR_INVALID_ARG, "moe_mfma_operand_loop: bad argument");
+  static float* out = nullptr;
+  int32_t st;
+  if (!out && (st = check_hip(hipMalloc(&out, 4096), "hipMalloc")) != MOE_OK) return st;
+  hipDeviceProp_t prop;
+  if ((st = check_hip(hipGetDeviceProperties(&prop, 0), "hipGetDeviceProperties")) != MOE_OK) return st;
+  const int cus = prop.multiProcessorCount;
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0);
+  (void)hipEventCreate(&e1);
+  (void)hipEventRecord(e0, 0);
+  if (kind == 0) hipLaunchKernelGGL(mfma_operand_loop<0>, dim3(cus), dim3(512), 0, 0, iters, zero, out);
+  else hipLaunchKernelGGL(mfma_operand_loop<1>, dim3(cus), dim3(512), 0, 0, iters, zero, out);
+  (void)hipEventRecord(e1, 0);
+  st = check_hip(hipEventSynchronize(e1), "moe_mfma_operand_loop");
+  float ms = 0.f;
+  (void)hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  // flops per wavefront and iteration: 16 MFMAs x 32768 (kind 0) = 32 MFMAs x 16384 (kind 1)
+  *tflops = ms > 0.f ? (double)cus * 8 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12 : 0.0;
+  return st;
 }

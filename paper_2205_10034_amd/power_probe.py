@@ -2,13 +2,15 @@
 
 ``python -m paper_2205_10034_amd.power_probe [--workload large]`` samples the GPU's power sensor (hwmon, read-only)
 every 20 ms while it repeats (a) ``moe_layer_forward`` of the workload, (b) ``torch.matmul`` (the vendor's bf16
-product) of one expert's first-GEMM shapes on random operands and (c) the same on all-zero operands, and prints the
-mean power, the board's power cap and the rate of each.  It answers one question: whether the grouped GEMM's rate
+product) of one expert's first-GEMM shapes on random operands and (c) the same on all-zero operands and (d) loops of nothing but MFMAs of either shape on random and on zero operands held in
+registers (from the phase-timing build of the library, if it is built), and prints the mean power, the board's power
+cap and the rate of each.  It answers one question: whether the grouped GEMM's rate
 is set by the power cap rather than by the matrix pipes' issue rate.  Diagnostics only.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import glob
 import os
 import sys
@@ -18,6 +20,7 @@ import time
 import torch
 
 import paper_2205_10034_amd as M
+from paper_2205_10034_amd.build import PROF_LIB
 from workloads import WORKLOADS
 
 
@@ -104,6 +107,21 @@ def main() -> int:
     p.zero_()
     q.zero_()
     measure(f"vendor product {rows} x {d} x {n1}, zero operands  ", lambda: torch.matmul(p, q.t(), out=r), 2.0 * rows * d * n1)
+    if os.path.exists(PROF_LIB):
+        L = ctypes.CDLL(PROF_LIB)
+        L.moe_mfma_operand_loop.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double)]
+        for kind, name in ((0, "32x32x16"), (1, "16x16x32")):
+            for zero in (0, 1):
+                rate, t0, n, tf = 0.0, time.time(), 0, ctypes.c_double()
+                while time.time() - t0 < a.seconds:
+                    if L.moe_mfma_operand_loop(kind, zero, 20000, ctypes.byref(tf)) != 0:
+                        print("moe_mfma_operand_loop failed", file=sys.stderr)
+                        return 1
+                    rate += tf.value
+                    n += 1
+                pw = [p for t, p in samples if t > t0 + 1.5 and p == p]
+                print(f"MFMA-only loop, v_mfma_f32_{name}_bf16, {'zero  ' if zero else 'random'} operands: {rate / n:7.0f} TFLOP/s, "
+                      f"power mean {sum(pw) / max(len(pw), 1):5.0f} W", flush=True)
     stop.set()
     return 0
 
