@@ -15,7 +15,8 @@
 // global memory straight into LDS (buffer_load ... lds, 16 bytes per lane, no
 // register staging) as rows of KS bf16 whose 16-byte chunks are XOR-swizzled
 // with the row index, so that the per-lane 16-byte fragment reads of
-// v_mfma_f32_32x32x16_bf16 are free of bank conflicts.  Two LDS stages rotate,
+// v_mfma_f32_32x32x16_bf16 (32-row fragments) and v_mfma_f32_16x16x32_bf16
+// (16-row fragments) are free of bank conflicts.  Two LDS stages rotate,
 // with ONE barrier per K-step placed before the step's last sub-step, so that
 // the first fragments of the next step are read under the tail of the current
 // one.  A stage is requested in two halves, each spread between the MFMAs of
@@ -36,10 +37,13 @@
 // the eight XCDs walk the same weight columns at the same time so that HBM
 // serves each weight tile once.
 //
-// Clocks.  Under this kernel the MI355X runs at 1.6-2.0 GHz, not at the 2.4 GHz
-// its peak figure assumes (measured: shader clock counter against the 100 MHz
-// reference counter); in shader clocks the K loop keeps the matrix pipes ~85 %
-// busy.
+// Clocks and power.  Under this kernel the MI355X draws its full board power
+// and runs at 1.6-2.0 GHz, not at the 2.4 GHz its peak figure assumes (measured:
+// shader clock counter against the 100 MHz reference counter, and the board's
+// power sensor); in shader clocks the K loop keeps the matrix pipes ~80 % busy.
+// At the power limit the rate follows the energy per flop, which is why the
+// 16x16x32 instruction (half the accumulator registers moved per flop) is the
+// one used wherever experts fill their tiles, see use_mi16().
 #include <cstdlib>
 #include <type_traits>
 #include "moesys_internal.h"
