@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pack-router", action="store_true", help="do not give the layer a pre-split router (moe_pack_router)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1, gate_tokens=32|64|128")
+                    help="moe_set_tuning before the run: gemm_tile_rows=256|320, few_token_kernels=0|1, gate_tokens=32|64|128, gemm_mfma=16|32")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "

@@ -159,9 +159,12 @@ int32_t moe_workspace_layout(const moe_config* cfg, moe_ws_layout* out);
  *                              gate; 0: the general kernels at every size
  *   MOE_TUNE_GATE_TOKENS       tokens per workgroup of the gate on a packed router: 32, 64 or 128 (where
  *                              the expert count allows; otherwise the next smaller); 0 (default) = by T
+ *   MOE_TUNE_GEMM_MFMA         matrix instruction of the 256-row grouped GEMM kernels: 16 (16x16x32) or 32
+ *                              (32x32x16); 0 (default) = 16 where an evenly loaded expert fills tiles.  The
+ *                              results of the two are bit-identical.
  * moe_set_tuning returns MOE_ERR_INVALID_ARG for an unknown key or value. */
 typedef enum { MOE_TUNE_GEMM_TILE_ROWS = 0, MOE_TUNE_FEW_TOKEN_KERNELS = 1, MOE_TUNE_GATE_TOKENS = 2,
-               MOE_TUNE_COUNT = 3 } moe_tuning_key;
+               MOE_TUNE_GEMM_MFMA = 3, MOE_TUNE_COUNT = 4 } moe_tuning_key;
 int32_t moe_set_tuning(int32_t key, int32_t value);
 int32_t moe_get_tuning(int32_t key, int32_t* value);
 

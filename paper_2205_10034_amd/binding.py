@@ -205,7 +205,7 @@ class Weights:
                           g("expert_elem_offset"), g("w_router_packed"))
 
 
-MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS, MOE_TUNE_GATE_TOKENS = 0, 1, 2
+MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS, MOE_TUNE_GATE_TOKENS, MOE_TUNE_GEMM_MFMA = 0, 1, 2, 3
 
 
 def moe_set_tuning(key: int, value: int) -> None:

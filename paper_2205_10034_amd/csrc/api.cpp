@@ -23,7 +23,7 @@ int32_t check_hip(hipError_t e, const char* what) {
   return fail(MOE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-static std::atomic<int32_t> g_tuning[MOE_TUNE_COUNT] = {{0}, {1}, {0}};
+static std::atomic<int32_t> g_tuning[MOE_TUNE_COUNT] = {{0}, {1}, {0}, {0}};
 
 int32_t tuning(int32_t key) { return g_tuning[key].load(std::memory_order_relaxed); }
 
@@ -148,6 +148,10 @@ int32_t moe_set_tuning(int32_t key, int32_t value) {
     case MOE_TUNE_GATE_TOKENS:
       if (value != 0 && value != 32 && value != 64 && value != 128)
         return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: gate tokens must be 0, 32, 64 or 128 (got %d)", value);
+      break;
+    case MOE_TUNE_GEMM_MFMA:
+      if (value != 0 && value != 16 && value != 32)
+        return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: the MFMA shape must be 0, 16 or 32 (got %d)", value);
       break;
     default: return fail(MOE_ERR_INVALID_ARG, "moe_set_tuning: key %d unknown", key);
   }

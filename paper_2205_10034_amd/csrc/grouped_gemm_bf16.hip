@@ -1085,6 +1085,8 @@ int pick_tile_rows(const moe_config* cfg, int n_tiles) {
 // then bound by streaming the weights, and half of the loop's phases have nothing to multiply) the 32x32x16 loop
 // measured 3 % faster.
 bool prefer_mi16(const moe_config* cfg) {
+  const int forced = tuning(MOE_TUNE_GEMM_MFMA);
+  if (forced) return forced == 16;
   int64_t rows = ((int64_t)cfg->k * cfg->T + cfg->E - 1) / cfg->E;
   const int64_t C = moe_capacity(cfg);
   if (C != MOE_DROPLESS && rows > C) rows = C;

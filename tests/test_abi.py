@@ -98,6 +98,10 @@ def test_tuning_switches_validate_and_round_trip():
     assert M.lib().moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 128) == 1
     assert M.moe_get_tuning(M.MOE_TUNE_GEMM_TILE_ROWS) == 0
     assert M.lib().moe_set_tuning(M.MOE_TUNE_FEW_TOKEN_KERNELS, 2) == 1
+    for v in (16, 32, 0):
+        M.moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, v)
+        assert M.moe_get_tuning(M.MOE_TUNE_GEMM_MFMA) == v
+    assert M.lib().moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, 8) == 1
     assert M.lib().moe_set_tuning(7, 0) == 1
     assert M.lib().moe_get_tuning(7, None) == 1
 

@@ -619,6 +619,27 @@ def test_layer_experts_runs_again_on_the_same_routing():
             assert torch.equal(out, want), f"{name}: run {rep} of the expert half differs"
 
 
+def test_both_matrix_instructions_give_the_same_bits():
+    """The grouped GEMM multiplies with 16x16x32 or 32x32x16 MFMAs (chosen from the expected rows per expert);
+    the layer's output does not depend on which: GELU with biases, SwiGLU, the fused top-1 combine, ragged experts."""
+    for name, kw in (("gpt", dict(T=2048, E=8)), ("skew", dict(T=3001)), ("large", dict(T=1536, d_model=512, d_ff=1024, E=4))):
+        wl = small(name, **kw)
+        L = make_layer(wl, with_bias=True)
+        cfg = M.MoEConfig.from_workload(wl)
+        W = upload_weights(L, wl.dtype)
+        x = to_dev(L["x"], wl.dtype)
+        outs = {}
+        try:
+            M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 256)
+            for shape in (16, 32):
+                M.moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, shape)
+                outs[shape] = run_layer(cfg, W, x)["out_tensor"].clone()
+        finally:
+            M.moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, 0)
+            M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 0)
+        assert torch.equal(outs[16], outs[32]), name
+
+
 def test_determinism():
     wl = small("gpt", T=2048, E=8)
     L = make_layer(wl)

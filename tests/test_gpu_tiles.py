@@ -19,3 +19,15 @@ def test_tile_boundaries_forced_capacity(cap):
         assert ffn_boundary_case.main() == 0
     finally:
         M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 0)
+
+
+@pytest.mark.parametrize("mfma", [16, 32])
+def test_tile_boundaries_forced_mfma_shape(mfma):
+    """The 256-row kernels with either matrix instruction (few rows per expert pick 32x32x16 by themselves)."""
+    M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 256)
+    M.moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, mfma)
+    try:
+        assert ffn_boundary_case.main() == 0
+    finally:
+        M.moe_set_tuning(M.MOE_TUNE_GEMM_TILE_ROWS, 0)
+        M.moe_set_tuning(M.MOE_TUNE_GEMM_MFMA, 0)
