@@ -655,10 +655,11 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
 // loop: the loop is loads and MFMAs, and the kernel runs at the rate the token rows arrive from HBM.
 //
 // Ranking must equal the ranking of the exactly computed logits.  The partial sums carry errors of about
-// 2^-24 times their own magnitude, so a token is flagged when two neighbours among its k+1 leading logits are
+// 2^-24 times their own magnitude, so a token is marked when two neighbours among its k+1 leading logits are
 // closer than 2^-15 times the largest sum over the wavefronts of |partial logit| of that token (a margin that
-// scales with the data; about 1e-4 for inputs of unit variance) and recomputed by the whole workgroup with
-// float64 accumulation of the exact products, from the float32 router itself.
+// scales with the data; about 1e-4 for inputs of unit variance): the mark is the sign bit of its first gate
+// weight, and gate_fix_kernel, launched behind this kernel, recomputes the marked tokens with float64
+// accumulation of the exact products, from the float32 router itself.
 #ifndef GATE_REL_MARGIN_VALUE
 #define GATE_REL_MARGIN_VALUE (1.0f / 32768.0f)
 #endif
