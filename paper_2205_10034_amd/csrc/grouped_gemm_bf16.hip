@@ -95,6 +95,27 @@ constexpr bool swiglu_tile(int epi) { return epi == EPI_SWIGLU || epi == EPI_DSW
 #ifndef MOE_MI16_MASK
 #define MOE_MI16_MASK 0x3f
 #endif
+// The accumulators of one 32x32 block of the output: one 16-register MFMA result, or the four 4-register results of
+// its 16x16 sub-blocks (number 2 * (token half) + (feature half)); element r of either is the same output element
+// of the block's owner lane, see the epilogue.  (Separate types: a 16-register value cut into four operands makes
+// the compiler copy registers around every MFMA once the accumulators live in the second half of the register file.)
+template <bool MI16> struct AccBlock;
+template <> struct AccBlock<false> {
+  f32x16 v;
+  __device__ __forceinline__ float get(int r) const { return v[r]; }
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) v[r] = 0.f;
+  }
+};
+template <> struct AccBlock<true> {
+  f32x4 q[4];
+  __device__ __forceinline__ float get(int r) const { return q[r >> 2][r & 3]; }
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+};
 constexpr bool use_mi16(int tok, int wt, int epi) { return tok <= 256 && (tok / 32 / wt) % 2 == 0 && ((MOE_MI16_MASK >> epi) & 1); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -562,7 +583,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
            pf.c0 = __builtin_readcyclecounter(); pf.r0 = __builtin_amdgcn_s_memrealtime();)
   // (16x16x32: acc[i][j] holds the four 16x16 sub-blocks of the 32x32 block, four registers each, number
   // 2 * (token half) + (feature half); the fragment sets hold half of the token blocks, 16 rows at a time)
-  f32x16 acc[TB][FB];
+  AccBlock<MI16> acc[TB][FB];
   bf16x8 af[ABUF][MI16 ? (TB / 2) * 2 : TB], wfr[2][MI16 ? FB * 2 : FB];
   // The K loop of one tile, compiled once per number TBV of 32-row token blocks of this wavefront that
   // hold at least one valid row (a partial tile - an expert's last rows - multiplies only those blocks;
@@ -603,7 +624,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
         for (int i = 0; i < TBV; ++i)
 #pragma unroll
           for (int j = 0; j < FB; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[c][i], acc[i][j], 0, 0, 0);
+            acc[i][j].v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[c][i], acc[i][j].v, 0, 0, 0);
 #pragma unroll
         for (int q = 0; q < MFMAS; ++q) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // MFMA
@@ -615,7 +636,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
         for (int i = 0; i < TBV; ++i) {
 #pragma unroll
           for (int j = 0; j < FB; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[0][i], acc[i][j], 0, 0, 0);
+            acc[i][j].v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][j], af[0][i], acc[i][j].v, 0, 0, 0);
           read_a(A, ks, af[0][i], i);
         }
         if (NFB) __builtin_amdgcn_sched_group_barrier(0x100, NFB, 0);
@@ -701,11 +722,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             for (int sh = 0; sh < 2; ++sh)
 #pragma unroll
               for (int fh = 0; fh < 2; ++fh) {
-                f32x16& t = acc[TH * HTB + i][j];
-                const int q = (2 * sh + fh) * 4;
-                f32x4 c = {t[q], t[q + 1], t[q + 2], t[q + 3]};
+                f32x4& c = acc[TH * HTB + i][j].q[2 * sh + fh];
                 c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[KK & 1][2 * j + fh], af[PH & 1][2 * i + sh], c, 0, 0, 0);
-                t[q] = c[0]; t[q + 1] = c[1]; t[q + 2] = c[2]; t[q + 3] = c[3];
               }
         // two MFMAs, then a fragment read and a global load while there are any
         constexpr int SLOTS = MFMAS / 2;
@@ -771,9 +789,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
 #pragma unroll
     for (int i = 0; i < TB; ++i)
 #pragma unroll
-      for (int j = 0; j < FB; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int j = 0; j < FB; ++j) acc[i][j].clear();
 
     // Everything this wavefront has in flight (the tile's first stages and bias; the previous tile's stores,
     // which do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
@@ -897,7 +913,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
                                  bf16_bits_to_f32(hi & 0xffffu), __uint_as_float(hi & 0xffff0000u)};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              const float gv = acc[tb][0][4 * (i0 + g) + q], uv = acc[tb][1][4 * (i0 + g) + q];
+              const float gv = acc[tb][0].get(4 * (i0 + g) + q), uv = acc[tb][1].get(4 * (i0 + g) + q);
               const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-gv));   // sigmoid(g)
               const float ds = dh[q] * sg;
               pu[4 * g + q] = ds * gv;                                     // d_u = d_h * silu(g)
@@ -914,7 +930,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
           for (int i0 = 0; i0 < 4; i0 += 2) {
             float p[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][fb][4 * i0 + r]) * acc[tb][FBH + fb][4 * i0 + r];
+            for (int r = 0; r < 8; ++r) p[r] = silu(acc[tb][fb].get(4 * i0 + r)) * acc[tb][FBH + fb].get(4 * i0 + r);
             store_pair(out + out_row(i0) * N, feat0 + wf * (WFEAT / 2) + fb * 32, i0, p, live_row(i0));
           }
       } else {
@@ -930,13 +946,13 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
                 // the bias sits in this wavefront's LDS slot since the tile's prologue
                 const u32x2 b = *reinterpret_cast<const u32x2*>(s_bias + (done_set * NW + wave) * 256 +
                                                                 (fb * 32 + run_off(i0, g)) * 2);
-                p[4 * g + 0] = acc[tb][fb][4 * (i0 + g) + 0] + bf16_bits_to_f32(b.x & 0xffffu);
-                p[4 * g + 1] = acc[tb][fb][4 * (i0 + g) + 1] + __uint_as_float(b.x & 0xffff0000u);
-                p[4 * g + 2] = acc[tb][fb][4 * (i0 + g) + 2] + bf16_bits_to_f32(b.y & 0xffffu);
-                p[4 * g + 3] = acc[tb][fb][4 * (i0 + g) + 3] + __uint_as_float(b.y & 0xffff0000u);
+                p[4 * g + 0] = acc[tb][fb].get(4 * (i0 + g) + 0) + bf16_bits_to_f32(b.x & 0xffffu);
+                p[4 * g + 1] = acc[tb][fb].get(4 * (i0 + g) + 1) + __uint_as_float(b.x & 0xffff0000u);
+                p[4 * g + 2] = acc[tb][fb].get(4 * (i0 + g) + 2) + bf16_bits_to_f32(b.y & 0xffffu);
+                p[4 * g + 3] = acc[tb][fb].get(4 * (i0 + g) + 3) + __uint_as_float(b.y & 0xffff0000u);
               } else {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) p[4 * g + q] = acc[tb][fb][4 * (i0 + g) + q];
+                for (int q = 0; q < 4; ++q) p[4 * g + q] = acc[tb][fb].get(4 * (i0 + g) + q);
               }
             }
             if (EPI == EPI_GELU) {
