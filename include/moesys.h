@@ -366,21 +366,23 @@ int32_t moe_combine_backward(const moe_config* cfg, const void* d_out, const voi
  * training system, Section 3.2, and leaves the kernels open): for every expert e
  *   c[e, n1, n2] = sum over r in [expert_offsets[e], expert_offsets[e+1]) of a[r, n1] * b[r, n2]
  * e.g. dW2_e = d_y_e^T h_e (a = d_y [R,d_model], b = h [R,d_ff]) and dW1_e = d_u_e^T xd_e for
- * OUTPUT_MAJOR weights.  a device bf16 [R,N1], b device bf16 [R,N2], c device float32
- * [E,N1,N2] (overwritten; zero for an expert without rows); expert_offsets is read on
+ * OUTPUT_MAJOR weights.  a device bf16 [R,N1], b device bf16 [R,N2], c device [E,N1,N2] of
+ * c_dtype = MOE_F32, or MOE_BF16 (the float32 sums rounded once: half the bytes written, for
+ * callers that keep bf16 gradients) (overwritten; zero for an expert without rows); expert_offsets is read on
  * the device; max_rows_per_expert is the caller's bound of any expert's row count (only
  * used to check that an expert's operand block stays below 2 GiB).  N1 and N2 must be
  * multiples of 256 (MOE_ERR_UNSUPPORTED otherwise).  a_column_sums (nullable; device float32
  * [E,N1], overwritten): the sums over an expert's rows of a[r, n1], i.e. the bias gradient that
  * goes with the weight gradient (db2_e with dW2_e, db1_e with dW1_e), from the same pass. */
-int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
-                         float* a_column_sums, int32_t E, int32_t N1, int32_t N2,
+int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, void* c,
+                         int32_t c_dtype, float* a_column_sums, int32_t E, int32_t N1, int32_t N2,
                          int64_t max_rows_per_expert, void* stream);
 
 /* Backward of moe_expert_ffn in MOE_BF16, given d_yd [R_max,d_model].  GELU experts:
  *   d_xd [R_max,d_model] (cfg.dtype), d_w1 [E,d_ff,d_model], d_b1 [E,d_ff], d_w2 [E,d_model,d_ff],
- *   d_b2 [E,d_model] (float32, OUTPUT_MAJOR like the weights; overwritten; the bias gradients are
- *   required exactly when w has the bias).
+ *   d_b2 [E,d_model] (OUTPUT_MAJOR like the weights; overwritten; d_w1 and d_w2 of d_w_dtype =
+ *   MOE_F32 or MOE_BF16 as in moe_expert_wgrad, the bias gradients float32 and required exactly
+ *   when w has the bias).
  * w holds the OUTPUT_MAJOR weights of the forward pass; w1_input_major [E,d_model,d_ff] and
  * w2_input_major [E,d_ff,d_model] are their transposed copies (moe_transpose_expert_weights),
  * on which the input gradients are plain grouped products.
@@ -399,8 +401,8 @@ size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg);
 int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                 const void* w2_input_major, const void* xd, const void* h,
                                 const void* d_yd, const int32_t* expert_offsets, void* d_xd,
-                                float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
-                                size_t ws_bytes, void* stream);
+                                void* d_w1, float* d_b1, void* d_w2, float* d_b2, int32_t d_w_dtype,
+                                void* ws, size_t ws_bytes, void* stream);
 
 /* Load-balancing auxiliary loss.  The paper names auxiliary losses as the known remedy for
  * expert imbalance (Section 1, the computation challenge) without a formula; this is the one
@@ -419,7 +421,7 @@ int32_t moe_gate_aux_loss(const moe_config* cfg, const float* probs, const int32
  *   d_x [T,d_model] (cfg.dtype) = add_to_d_x (nullable; e.g. d_out when the layer ran with
  *       residual == x) + the experts' path (through dispatch) + the gate's path, one rounding;
  *   d_w_router [d_model,E], d_b_router [E] (float32; the latter required iff w->b_router);
- *   d_w1, d_b1, d_w2, d_b2 as in moe_expert_ffn_backward.
+ *   d_w1, d_b1, d_w2, d_b2, d_w_dtype as in moe_expert_ffn_backward.
  * aux_loss_coef != 0 adds the gradient of moe_gate_aux_loss(coef = aux_loss_coef) of this layer's
  * routing (it reaches d_x, d_w_router and d_b_router through the logits).
  * The gradient of the residual input is d_out itself.  fwd_ws is the workspace that
@@ -432,8 +434,9 @@ int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const vo
                            const void* w2_input_major, const void* x, const void* d_out,
                            const void* add_to_d_x, float aux_loss_coef, const void* fwd_ws,
                            size_t fwd_ws_bytes, void* d_x,
-                           float* d_w_router, float* d_b_router, float* d_w1, float* d_b1,
-                           float* d_w2, float* d_b2, void* ws, size_t ws_bytes, void* stream);
+                           float* d_w_router, float* d_b_router, void* d_w1, float* d_b1,
+                           void* d_w2, float* d_b2, int32_t d_w_dtype, void* ws, size_t ws_bytes,
+                           void* stream);
 
 /* ---- frequency-based expert cache (Algorithm 2, Section 3.2.2) ----------- */
 /*

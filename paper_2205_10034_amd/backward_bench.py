@@ -20,6 +20,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--bias", action="store_true", help="GELU experts with biases (and their gradients)")
+    ap.add_argument("--bf16-grads", action="store_true", help="weight gradients rounded once to bfloat16 (half the bytes written)")
     args = ap.parse_args()
     import torch
     import paper_2205_10034_amd as M
@@ -57,7 +58,8 @@ def main():
     ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     out, d_x = torch.empty_like(x), torch.empty_like(x)
     f32 = dict(dtype=torch.float32, device="cuda")
-    d_wr, d_w1, d_w2 = torch.empty(d, E, **f32), torch.empty(E, (2 if sw else 1) * f, d, **f32), torch.empty(E, d, f, **f32)
+    gw = dict(dtype=torch.bfloat16 if args.bf16_grads else torch.float32, device="cuda")
+    d_wr, d_w1, d_w2 = torch.empty(d, E, **f32), torch.empty(E, (2 if sw else 1) * f, d, **gw), torch.empty(E, d, f, **gw)
 
     def fwd():
         M.moe_layer_forward(cfg, W, x, x, out, ws_f)
@@ -88,7 +90,7 @@ def main():
     R = int(ws_f[lay["expert_offsets"]:lay["expert_offsets"] + 4 * (E + 1)].view(torch.int32)[-1].item())
     gemm = 2.0 * R * d * f
     res = {
-        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} {wl.act}{' with biases' if with_b else ''}, kept rows {R}",
+        "workload": f"{wl.name}: T={T} d_model={d} d_ff={f} E={E} top-{wl.k} CF={wl.capacity_factor} {wl.act}{' with biases' if with_b else ''}{', bf16 weight gradients' if args.bf16_grads else ''}, kept rows {R}",
         "forward_ms": t_f, "backward_ms": t_b, "forward_backward_ms": t_fb,
         "tokens_per_s_forward_backward": T / (t_fb * 1e-3),
         # products of 2 R d_model d_ff flops.  GELU: two forward; backward two input gradients, two weight gradients,

@@ -128,13 +128,13 @@ def lib() -> C.CDLL:
         L.moe_combine_backward.argtypes = [C.POINTER(_Config)] + [vp] * 7
         L.moe_expert_ffn_backward_workspace_bytes.restype = C.c_size_t
         L.moe_expert_ffn_backward_workspace_bytes.argtypes = [C.POINTER(_Config)]
-        L.moe_expert_ffn_backward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 12 + [C.c_size_t, vp]
+        L.moe_expert_ffn_backward.argtypes = [C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 11 + [C.c_int32, vp, C.c_size_t, vp]
         L.moe_layer_backward_workspace_bytes.restype = C.c_size_t
         L.moe_layer_backward_workspace_bytes.argtypes = [C.POINTER(_Config)]
         L.moe_layer_backward.argtypes = ([C.POINTER(_Config), C.POINTER(_Weights)] + [vp] * 5 + [C.c_float, vp, C.c_size_t] +
-                                         [vp] * 8 + [C.c_size_t, vp])
+                                         [vp] * 7 + [C.c_int32, vp, C.c_size_t, vp])
         L.moe_gate_aux_loss.argtypes = [C.POINTER(_Config), vp, vp, C.c_float, vp, vp, vp, vp]
-        L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
+        L.moe_expert_wgrad.argtypes = [vp, vp, vp, vp, C.c_int32, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp]
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
         L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
@@ -323,12 +323,20 @@ def moe_expert_ffn_backward_workspace_bytes(cfg) -> int:
     return lib().moe_expert_ffn_backward_workspace_bytes(C.byref(c))
 
 
+def _grad_dtype(*tensors) -> int:
+    """MOE_F32 or MOE_BF16 from the element size of the weight-gradient tensors (which must agree)."""
+    sizes = {t.element_size() for t in tensors if t is not None}
+    if len(sizes) > 1:
+        raise ValueError("the weight gradients must have one element type")
+    return MOE_BF16 if sizes == {2} else MOE_F32
+
+
 def moe_expert_ffn_backward(cfg, weights: Weights, w1_input_major, w2_input_major, xd, h, d_yd, expert_offsets, d_xd,
                             d_w1, d_b1, d_w2, d_b2, ws, stream=None):
     c = cfg.c()
     _check(lib().moe_expert_ffn_backward(C.byref(c), C.byref(weights.c), _ptr(w1_input_major), _ptr(w2_input_major),
                                          _ptr(xd), _ptr(h), _ptr(d_yd), _ptr(expert_offsets), _ptr(d_xd), _ptr(d_w1),
-                                         _ptr(d_b1), _ptr(d_w2), _ptr(d_b2), _ptr(ws),
+                                         _ptr(d_b1), _ptr(d_w2), _ptr(d_b2), _grad_dtype(d_w1, d_w2), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)), "moe_expert_ffn_backward")
 
 
@@ -344,7 +352,8 @@ def moe_layer_backward(cfg, weights: Weights, w1_input_major, w2_input_major, x,
                                     _ptr(d_out), _ptr(add_to_d_x), aux_loss_coef, _ptr(fwd_ws),
                                     fwd_ws.numel() * fwd_ws.element_size(),
                                     _ptr(d_x), _ptr(d_w_router), _ptr(d_b_router), _ptr(d_w1), _ptr(d_b1), _ptr(d_w2),
-                                    _ptr(d_b2), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+                                    _ptr(d_b2), _grad_dtype(d_w1, d_w2), _ptr(ws), ws.numel() * ws.element_size(),
+                                    _stream(stream)),
            "moe_layer_backward")
 
 
@@ -355,10 +364,10 @@ def moe_gate_aux_loss(cfg, probs, topk_idx, coef: float, expert_fraction, mean_p
 
 
 def moe_expert_wgrad(a, b, expert_offsets, c, max_rows_per_expert: int, stream=None, a_column_sums=None):
-    """c[e] = a[rows of e]^T @ b[rows of e]; a [R,N1], b [R,N2] bf16, c [E,N1,N2] float32; a_column_sums [E,N1]
-    float32 (optional): sum over the rows of e of a."""
+    """c[e] = a[rows of e]^T @ b[rows of e]; a [R,N1], b [R,N2] bf16, c [E,N1,N2] float32 or bfloat16; a_column_sums
+    [E,N1] float32 (optional): sum over the rows of e of a."""
     E, N1, N2 = c.shape
-    _check(lib().moe_expert_wgrad(_ptr(a), _ptr(b), _ptr(expert_offsets), _ptr(c), _ptr(a_column_sums), E, N1, N2,
+    _check(lib().moe_expert_wgrad(_ptr(a), _ptr(b), _ptr(expert_offsets), _ptr(c), _grad_dtype(c), _ptr(a_column_sums), E, N1, N2,
                                   max_rows_per_expert, _stream(stream)), "moe_expert_wgrad")
 
 

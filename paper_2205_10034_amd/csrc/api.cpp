@@ -134,7 +134,7 @@ const char* moe_status_string(int32_t st) {
 }
 
 const char* moe_last_error(void) { return g_err; }
-int32_t moe_version(void) { return 200; }
+int32_t moe_version(void) { return 210; }
 
 int32_t moe_set_tuning(int32_t key, int32_t value) {
   switch (key) {

@@ -20,7 +20,7 @@ int32_t launch_gemm1_dgelu_bf16(const moe_config*, const void*, const void*, con
                                 int32_t*, hipStream_t);
 int32_t launch_gemm1_dswiglu_bf16(const moe_config*, const void*, const void*, const void*, const int32_t*, const void*, void*,
                                   int32_t*, hipStream_t);
-int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, float*, float*, int, int, int, int64_t, hipStream_t);
+int32_t launch_wgrad_bf16(const uint16_t*, const uint16_t*, const int32_t*, void*, int, float*, int, int, int, int64_t, hipStream_t);
 
 namespace {
 
@@ -272,22 +272,25 @@ extern "C" size_t moe_expert_ffn_backward_workspace_bytes(const moe_config* cfg)
 
 static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                  const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
-                                 const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1, float* d_w2,
-                                 float* d_b2, void* ws, size_t ws_bytes, void* stream);
+                                 const int32_t* expert_offsets, void* d_xd, void* d_w1, float* d_b1, void* d_w2,
+                                 float* d_b2, int32_t d_w_dtype, void* ws, size_t ws_bytes, void* stream);
 
 extern "C" int32_t moe_expert_ffn_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                            const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
-                                           const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1,
-                                           float* d_w2, float* d_b2, void* ws, size_t ws_bytes, void* stream) {
+                                           const int32_t* expert_offsets, void* d_xd, void* d_w1, float* d_b1,
+                                           void* d_w2, float* d_b2, int32_t d_w_dtype, void* ws, size_t ws_bytes,
+                                           void* stream) {
   return ffn_backward_impl("moe_expert_ffn_backward", cfg, w, w1_input_major, w2_input_major, xd, h, d_yd, expert_offsets,
-                           d_xd, d_w1, d_b1, d_w2, d_b2, ws, ws_bytes, stream);
+                           d_xd, d_w1, d_b1, d_w2, d_b2, d_w_dtype, ws, ws_bytes, stream);
 }
 
 static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                  const void* w2_input_major, const void* xd, const void* h, const void* d_yd,
-                                 const int32_t* expert_offsets, void* d_xd, float* d_w1, float* d_b1, float* d_w2,
-                                 float* d_b2, void* ws, size_t ws_bytes, void* stream) {
+                                 const int32_t* expert_offsets, void* d_xd, void* d_w1, float* d_b1, void* d_w2,
+                                 float* d_b2, int32_t d_w_dtype, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = moe_config_check(cfg);
+  if (d_w_dtype != MOE_F32 && d_w_dtype != MOE_BF16)
+    return fail(MOE_ERR_INVALID_ARG, "%s: the weight gradients are MOE_F32 or MOE_BF16 (got %d)", who, d_w_dtype);
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
   if (cfg->dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "%s: bf16 only", who);
@@ -314,7 +317,7 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, s, ctr, 24);
   if ((st = check_hip(hipGetLastError(), "counter clear launch")) != MOE_OK) return st;
   // weight gradients that need nothing recomputed: dW2_e = d_yd_e^T h_e, with db2_e = column sums of d_yd_e on the side
-  if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, (!sw && w->b2) ? d_b2 : nullptr, E, d, f,
+  if ((st = launch_wgrad_bf16((const uint16_t*)d_yd, (const uint16_t*)h, expert_offsets, d_w2, d_w_dtype, (!sw && w->b2) ? d_b2 : nullptr, E, d, f,
                               per_expert, s)) != MOE_OK) return st;
   if (sw) {
     // d_h = d_yd W_down; [d_g | d_u] from d_h and the recomputed gate and up products; the gradient of the
@@ -322,7 +325,7 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
     void* dgu = base + rf;
     if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
     if ((st = launch_gemm1_dswiglu_bf16(cfg, xd, w->w_gate_proj, w->w_up, expert_offsets, dh, dgu, ctr + 8, s)) != MOE_OK) return st;
-    if ((st = launch_wgrad_bf16((const uint16_t*)dgu, (const uint16_t*)xd, expert_offsets, d_w1, nullptr, E, 2 * f, d, per_expert, s)) != MOE_OK) return st;
+    if ((st = launch_wgrad_bf16((const uint16_t*)dgu, (const uint16_t*)xd, expert_offsets, d_w1, d_w_dtype, nullptr, E, 2 * f, d, per_expert, s)) != MOE_OK) return st;
     return launch_grouped_matmul_bf16(cfg, dgu, w1_input_major, nullptr, expert_offsets, d_xd, d, 2 * f, ctr + 16, s);
   }
   // d_h = d_yd W2, then d_u = d_h * gelu'(u) in place, u = xd W1^T + b1 being recomputed by the product whose
@@ -331,7 +334,7 @@ static int32_t ffn_backward_impl(const char* who, const moe_config* cfg, const m
   if ((st = launch_grouped_matmul_bf16(cfg, d_yd, w2_input_major, nullptr, expert_offsets, dh, f, d, ctr, s)) != MOE_OK) return st;
   if ((st = launch_gemm1_dgelu_bf16(cfg, xd, w->w1, w->b1, expert_offsets, dh, dh, ctr + 8, s)) != MOE_OK) return st;
   // dW1_e = d_u_e^T xd_e (db1_e = column sums of d_u_e on the side), d_xd = d_u W1
-  if ((st = launch_wgrad_bf16((const uint16_t*)dh, (const uint16_t*)xd, expert_offsets, d_w1, w->b1 ? d_b1 : nullptr, E, f, d, per_expert,
+  if ((st = launch_wgrad_bf16((const uint16_t*)dh, (const uint16_t*)xd, expert_offsets, d_w1, d_w_dtype, w->b1 ? d_b1 : nullptr, E, f, d, per_expert,
                               s)) != MOE_OK) return st;
   return launch_grouped_matmul_bf16(cfg, dh, w1_input_major, nullptr, expert_offsets, d_xd, d, f, ctr + 16, s);
 }
@@ -408,8 +411,8 @@ extern "C" size_t moe_layer_backward_workspace_bytes(const moe_config* cfg) {
 extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* w, const void* w1_input_major,
                                       const void* w2_input_major, const void* x, const void* d_out, const void* add_to_d_x,
                                       float aux_loss_coef, const void* fwd_ws, size_t fwd_ws_bytes, void* d_x, float* d_w_router,
-                                      float* d_b_router, float* d_w1, float* d_b1, float* d_w2, float* d_b2, void* ws,
-                                      size_t ws_bytes, void* stream) {
+                                      float* d_b_router, void* d_w1, float* d_b1, void* d_w2, float* d_b2,
+                                      int32_t d_w_dtype, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = moe_config_check(cfg);
   if (st != MOE_OK) return st;
   if ((st = check_weights(cfg, w)) != MOE_OK) return st;
@@ -440,7 +443,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   float* d_z = (float*)(b + L.d_z);
   if (cfg->T == 0) {  // nothing flows back; the gradients of the parameters are zero
     if ((st = ffn_backward_impl("moe_layer_backward", cfg, w, w1_input_major, w2_input_major, nullptr, nullptr, nullptr, offsets,
-                                nullptr, d_w1, d_b1, d_w2, d_b2, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
+                                nullptr, d_w1, d_b1, d_w2, d_b2, d_w_dtype, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
     const size_t n = (size_t)cfg->d_model * cfg->E;  // (sums over no slice and no token: zeros)
     hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)(b + L.partial), d_w_router, n, 0);
     if (d_b_router) hipLaunchKernelGGL(gate_dbias_kernel, dim3(cfg->E), dim3(256), 0, s, d_z, d_b_router, 0, cfg->E);
@@ -461,7 +464,7 @@ extern "C" int32_t moe_layer_backward(const moe_config* cfg, const moe_weights* 
   if ((st = moe_combine_backward(cfg, d_out, yd, a2r, topk_w, b + L.d_yd, d_w, stream)) != MOE_OK) return st;
   if ((st = launch_gather_rows(cfg, x, a2r, b + L.xd, s)) != MOE_OK) return st;
   if ((st = ffn_backward_impl("moe_layer_backward", cfg, w, w1_input_major, w2_input_major, b + L.xd, h, b + L.d_yd, offsets,
-                              b + L.d_xd, d_w1, d_b1, d_w2, d_b2, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
+                              b + L.d_xd, d_w1, d_b1, d_w2, d_b2, d_w_dtype, b + L.ffn, ws_bytes - L.ffn, stream)) != MOE_OK) return st;
   const float* frac = nullptr;
   if (aux_loss_coef != 0.f) {
     frac = (const float*)(b + L.frac);

@@ -38,6 +38,10 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WG_N = 256;        // tile edge (both n1 and n2)
 constexpr int WG_KS = 32;        // rows per K-step
@@ -53,12 +57,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t wg_rsrc(const void* base, uint
 }
 #endif
 
-template <bool COLSUM>
+template <bool COLSUM, bool OUT_BF16>
 __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
     const uint16_t* __restrict__ a,       // [R, N1]
     const uint16_t* __restrict__ b,       // [R, N2]
     const int32_t* __restrict__ offsets,  // [E+1]
-    float* __restrict__ c,                // [E, N1, N2]
+    void* __restrict__ c_out,             // [E, N1, N2] float32, or bfloat16 (OUT_BF16: one rounding of the fp32 sums)
     float* __restrict__ a_colsum,         // COLSUM: [E, N1]
     int N1, int N2, int E, int BY, int BX) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
   if (e >= E || ty >= n1t || tx >= n2t) return;                // (wave-uniform: padding of the grid and of partial blocks)
   const int row0 = offsets[e], rows = offsets[e + 1] - row0;
   const int t1 = ty * WG_N, t2 = tx * WG_N;
-  float* cout = c + ((size_t)e * N1 + t1) * N2 + t2;
+  const size_t c_tile = ((size_t)e * N1 + t1) * N2 + t2;  // element offset of this tile in c
   const int KT = (rows + WG_KS - 1) / WG_KS;
 
   // ---- direct-to-LDS loads: one instruction = 2 rows of a chunk; lane -> (row = lane / 32, physical slot =
@@ -205,14 +209,31 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
   const int o1 = lane & 31, o2 = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    float* crow = cout + (size_t)(128 * w1 + 32 * i + o1) * N2 + 64 * w2 + o2;
+    const size_t crow = c_tile + (size_t)(128 * w1 + 32 * i + o1) * N2 + 64 * w2;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
+      if constexpr (OUT_BF16) {
+        // lanes l and l + 32 hold columns 8q + 0..3 and 8q + 4..7 of the same row: for a pair (q, q + 1) they trade
+        // halves, after which lane l stores the eight columns of q and lane l + 32 those of q + 1 (16 bytes each;
+        // 8-byte stores of half as many bytes took as long as the float32 ones)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const f32x4 v = {acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        *reinterpret_cast<f32x4*>(crow + 32 * j + 8 * q) = v;
+        for (int q = 0; q < 4; q += 2) {
+          auto pk = [&](int qq, int r) {
+            const bf16x2 h = __builtin_convertvector(f32x2{acc[i][j][4 * qq + r], acc[i][j][4 * qq + r + 1]}, bf16x2);
+            return __builtin_bit_cast(uint32_t, h);
+          };
+          const u32x2 sx = __builtin_amdgcn_permlane32_swap(pk(q, 0), pk(q + 1, 0), false, false);
+          const u32x2 sy = __builtin_amdgcn_permlane32_swap(pk(q, 2), pk(q + 1, 2), false, false);
+          *reinterpret_cast<u32x4*>((uint16_t*)c_out + crow + 32 * j + 8 * (q + (lane >> 5))) = u32x4{sx.x, sy.x, sx.y, sy.y};
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = {acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<f32x4*>((float*)c_out + crow + o2 + 32 * j + 8 * q) = v;
+        }
       }
+    }
   }
   if constexpr (COLSUM) {
     // every element of acc_sum in lane l (and l + 32) is the sum of column 128*w1 + 32*w2 + (l & 31)
@@ -223,8 +244,9 @@ __global__ __launch_bounds__(WG_WAVES * 64, 2) void grouped_wgrad_kernel(
 
 }  // namespace
 
-int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* offsets, float* c, float* a_colsum, int E, int N1,
-                          int N2, int64_t max_rows_per_expert, hipStream_t s) {
+int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* offsets, void* c, int c_dtype, float* a_colsum, int E,
+                          int N1, int N2, int64_t max_rows_per_expert, hipStream_t s) {
+  if (c_dtype != MOE_F32 && c_dtype != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "weight gradient: output type must be MOE_F32 or MOE_BF16");
   if (N1 % WG_N || N2 % WG_N) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: N1=%d and N2=%d must be multiples of %d", N1, N2, WG_N);
   const int64_t widest = N1 > N2 ? N1 : N2;
   if ((max_rows_per_expert + WG_KS) * widest * 2 >= ((int64_t)1 << 31))
@@ -235,8 +257,10 @@ int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* o
   const int64_t wgs = ((blocks + 7) / 8) * 8 * BY * BX;
   if (wgs > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "weight gradient: too many tiles");
   const dim3 grid((unsigned)wgs), block(WG_WAVES * 64);
-  if (a_colsum) hipLaunchKernelGGL(grouped_wgrad_kernel<true>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2, E, BY, BX);
-  else hipLaunchKernelGGL(grouped_wgrad_kernel<false>, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2, E, BY, BX);
+  const bool h = c_dtype == MOE_BF16;
+  auto kern = a_colsum ? (h ? grouped_wgrad_kernel<true, true> : grouped_wgrad_kernel<true, false>)
+                       : (h ? grouped_wgrad_kernel<false, true> : grouped_wgrad_kernel<false, false>);
+  hipLaunchKernelGGL(kern, grid, block, 0, s, a, b, offsets, c, a_colsum, N1, N2, E, BY, BX);
   return check_hip(hipGetLastError(), "weight gradient launch");
 }
 
@@ -244,12 +268,12 @@ int32_t launch_wgrad_bf16(const uint16_t* a, const uint16_t* b, const int32_t* o
 
 using namespace moesys;
 
-extern "C" int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, float* c,
+extern "C" int32_t moe_expert_wgrad(const void* a, const void* b, const int32_t* expert_offsets, void* c, int32_t c_dtype,
                                     float* a_column_sums, int32_t E, int32_t N1, int32_t N2, int64_t max_rows_per_expert,
                                     void* stream) {
   if (!a || !b || !expert_offsets || !c) return fail(MOE_ERR_INVALID_ARG, "moe_expert_wgrad: NULL argument");
   if (E < 1 || E > MOE_MAX_EXPERTS || N1 < 1 || N2 < 1 || max_rows_per_expert < 0)
     return fail(MOE_ERR_INVALID_ARG, "moe_expert_wgrad: bad shape");
-  return launch_wgrad_bf16((const uint16_t*)a, (const uint16_t*)b, expert_offsets, c, a_column_sums, E, N1, N2,
+  return launch_wgrad_bf16((const uint16_t*)a, (const uint16_t*)b, expert_offsets, c, c_dtype, a_column_sums, E, N1, N2,
                            max_rows_per_expert, (hipStream_t)stream);
 }

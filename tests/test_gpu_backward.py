@@ -36,20 +36,21 @@ def forward_pieces(wl, L, W, x):
     return cfg, dict(idx=idx, w=w, offsets=offsets, a2r=a2r, xd=xd, yd=yd, h=h, r_max=lay["r_max"])
 
 
-def expert_grad_buffers(wl, L):
+def expert_grad_buffers(wl, L, grad_dtype=torch.float32):
     """(w1_input_major, w2_input_major, d_w1, d_b1, d_w2, d_b2) in the layouts the C ABI documents; SwiGLU: the gate
-    and up projections stacked."""
+    and up projections stacked.  grad_dtype: the element type of the weight gradients (the bias gradients are float32)."""
     nan32 = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    nanw = lambda *shape: torch.full(shape, float("nan"), dtype=grad_dtype, device="cuda")
     if wl.act == "swiglu":
         w1_im = to_dev(np.concatenate([L["w_gate_proj"], L["w_up"]], axis=2), wl.dtype)      # [E, d_model, 2 d_ff]
-        return w1_im, to_dev(L["w_down"], wl.dtype), nan32(wl.E, 2 * wl.d_ff, wl.d_model), None, nan32(wl.E, wl.d_model, wl.d_ff), None
-    return (to_dev(L["w1"], wl.dtype), to_dev(L["w2"], wl.dtype), nan32(wl.E, wl.d_ff, wl.d_model), nan32(wl.E, wl.d_ff),
-            nan32(wl.E, wl.d_model, wl.d_ff), nan32(wl.E, wl.d_model))
+        return w1_im, to_dev(L["w_down"], wl.dtype), nanw(wl.E, 2 * wl.d_ff, wl.d_model), None, nanw(wl.E, wl.d_model, wl.d_ff), None
+    return (to_dev(L["w1"], wl.dtype), to_dev(L["w2"], wl.dtype), nanw(wl.E, wl.d_ff, wl.d_model), nan32(wl.E, wl.d_ff),
+            nanw(wl.E, wl.d_model, wl.d_ff), nan32(wl.E, wl.d_model))
 
 
 def expert_grad_errors(wl, ref, d_w1, d_b1, d_w2, d_b2):
     """Relative Frobenius error of every expert-parameter gradient against the oracle's (input-major) ones."""
-    g1, g2 = d_w1.cpu().numpy().transpose(0, 2, 1), d_w2.cpu().numpy().transpose(0, 2, 1)
+    g1, g2 = d_w1.float().cpu().numpy().transpose(0, 2, 1), d_w2.float().cpu().numpy().transpose(0, 2, 1)
     if wl.act == "swiglu":
         return {"w_gate_proj": rel_fro(g1[:, :, :wl.d_ff], ref["w_gate_proj"]), "w_up": rel_fro(g1[:, :, wl.d_ff:], ref["w_up"]),
                 "w_down": rel_fro(g2, ref["w_down"])}
@@ -132,8 +133,10 @@ def test_combine_and_expert_ffn_backward(name, kw):
     ("large", dict(T=1500, E=8, d_model=512, d_ff=256, capacity_factor=0.6)),
     ("large", dict(T=900, E=8, d_model=256, d_ff=512, k=1, capacity_factor=0.0, renormalize=False)),
 ], ids=lambda v: str(v).replace(" ", ""))
-def test_layer_backward(name, kw):
-    """moe_layer_forward with residual = x, then moe_layer_backward: every gradient against the fp64 oracle."""
+@pytest.mark.parametrize("grad_dtype", [torch.float32, torch.bfloat16], ids=["f32grads", "bf16grads"])
+def test_layer_backward(name, kw, grad_dtype):
+    """moe_layer_forward with residual = x, then moe_layer_backward: every gradient against the fp64 oracle, with the
+    weight gradients in float32 and rounded once to bfloat16."""
     wl = WORKLOADS[name].scaled(**kw)
     print(f"layer backward case {wl}", flush=True)
     L = make_layer(wl, with_bias=True)
@@ -158,7 +161,7 @@ def test_layer_backward(name, kw):
     d_x = torch.full_like(x, float("nan"))
     d_wr = torch.full((wl.d_model, wl.E), float("nan"), **f32)
     d_br = torch.full((wl.E,), float("nan"), **f32) if "b_router" in W.tensors else None
-    w1_im, w2_im, d_w1, d_b1, d_w2, d_b2 = expert_grad_buffers(wl, L)
+    w1_im, w2_im, d_w1, d_b1, d_w2, d_b2 = expert_grad_buffers(wl, L, grad_dtype)
     ws_b = torch.empty(M.moe_layer_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     for rep in range(2):
         M.moe_layer_backward(cfg, W, w1_im, w2_im, x, G, G, ws_f, d_x, d_wr, d_br, d_w1, d_b1, d_w2, d_b2, ws_b)

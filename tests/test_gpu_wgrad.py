@@ -57,6 +57,26 @@ def test_wgrad_matches_oracle(rows, N1, N2):
                 assert np.allclose(got[e], ref[e], rtol=1e-4, atol=1e-4 * np.sqrt(rows[e]))
 
 
+@pytest.mark.parametrize("rows,N1,N2", [([0, 1, 33, 0, 95, 256], 256, 512), ([1000, 1100], 256, 768)])
+def test_wgrad_bf16_output_is_the_float32_result_rounded_once(rows, N1, N2):
+    """c as bfloat16: bit for bit the float32 result of the same call rounded to nearest even (the sums are the same
+    fp32 accumulators); experts without rows come out as zeros; the column sums stay float32."""
+    E, R = len(rows), int(sum(rows))
+    rng = np.random.default_rng(7 + N1 + N2)
+    offsets = torch.from_numpy(np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)).cuda()
+    a = to_dev(rng.standard_normal((R, N1)).astype(np.float32), "bf16")
+    b = to_dev((rng.standard_normal((R, N2)) + 0.5).astype(np.float32), "bf16")
+    c32 = torch.full((E, N1, N2), float("nan"), dtype=torch.float32, device="cuda")
+    c16 = torch.full((E, N1, N2), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s32 = torch.full((E, N1), float("nan"), dtype=torch.float32, device="cuda")
+    s16 = torch.full((E, N1), float("nan"), dtype=torch.float32, device="cuda")
+    M.moe_expert_wgrad(a, b, offsets, c32, max(rows), a_column_sums=s32)
+    M.moe_expert_wgrad(a, b, offsets, c16, max(rows), a_column_sums=s16)
+    torch.cuda.synchronize()
+    assert torch.equal(c16, c32.to(torch.bfloat16))
+    assert torch.equal(s16, s32)
+
+
 def test_wgrad_rejects_what_it_cannot_do():
     a = torch.zeros(8, 128, dtype=torch.bfloat16, device="cuda")
     offsets = torch.tensor([0, 8], dtype=torch.int32, device="cuda")
