@@ -27,6 +27,19 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), f"{n} declared in moesys.h but not exported"
 
 
+def test_diagnostics_library_exports_what_the_measurement_tools_call():
+    """The phase-timing build carries the whole library plus the entry points of gemm_profile, hw_peaks and
+    power_probe (loaded here without calling anything: those need a GPU)."""
+    import ctypes
+    import os
+    from paper_2205_10034_amd.build import PROF_LIB
+    if not os.path.exists(PROF_LIB):
+        pytest.skip("diagnostics library not built")
+    P = ctypes.CDLL(PROF_LIB)
+    for n in declared_symbols() + ["moe_hw_peaks", "moe_mfma_operand_loop", "moe_gemm_profile_set"]:
+        assert hasattr(P, n), n
+
+
 def test_status_strings_and_version():
     L = M.lib()
     assert L.moe_version() >= 100
