@@ -22,7 +22,7 @@
 // one.  A stage is requested in two halves, each spread between the MFMAs of
 // one sub-step (a burst of loads would stall the issuing wavefronts, and with
 // them the matrix pipes, while the texture path drains it), and one more load
-// per K-step prefetches into L2 the lines that will be requested two K-steps
+// per K-step prefetches into L2 the lines that will be requested one K-step
 // later (the operands stream from HBM; the stage loads themselves have less
 // than one K-step to land).  The first stages of the NEXT tile, its bias and
 // its gathered row indices are requested before the epilogue of the current
@@ -362,7 +362,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   static_assert(NSUB == 2 || NSUB == 4, "K-step is 32 or 64");  // (an even count: the fragment sets alternate)
   constexpr int ABUF = TOK > 256 ? 1 : 2;  // sets of token fragments, see `substep`
   constexpr bool MI16 = MI16_ && use_mi16(TOK, WT, EPI);  // 16x16x32 MFMAs, see `phase16`
-  constexpr int PF_LEAD = 2;               // K-steps between a line's prefetch and the request of its stage
+  constexpr int PF_LEAD = 1;               // K-steps between a line's prefetch and the request of its stage (2 and 3
+                                           // measured 1 % and 2 % slower at the large SwiGLU workload, none 4-8 %)
   constexpr int PF_MIN_KT = 64;            // shortest K loop (in K-steps) that prefetches, see bind_prefetch
 
   // LDS tile layout: row r keeps its logical 16-byte chunk c at physical chunk c ^ key(r), key(r) =
