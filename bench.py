@@ -173,13 +173,29 @@ def main():
     other = "gemm2" if dom == "gemm1" else "gemm1"
     other_flops = flops2 if dom == "gemm1" else flops1
     if wl.dtype == "bf16":
-        roofline = {"bound": "mfma", "kernel": f"grouped_gemm_kernel ({dom})", "achieved": achieved,
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": measured_traffic(wl.name, dom),
-                    "flops_per_launch": dom_flops, "avg_launch_ms": stage_ms[dom],
-                    "other_gemm": {"kernel": f"grouped_gemm_kernel ({other})", "flops_per_launch": other_flops,
-                                   "avg_launch_ms": stage_ms[other],
-                                   "frac": other_flops / (stage_ms[other] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+        # unique bytes of the two GEMMs (every weight matrix, the kept rows in and out, once): with few rows per expert
+        # the dominant GEMM streams weights and the HBM roofline is the one that binds
+        wbytes = wl.E * wl.d_model * wl.d_ff * s
+        gemm_bytes = {"gemm1": R * wl.d_model * s + (mats - 1) * wbytes + R * wl.d_ff * s,
+                      "gemm2": R * wl.d_ff * s + wbytes + R * wl.d_model * s}
+        hbm_frac_dom = gemm_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        mfma_frac_dom = achieved / MFMA_BF16_PEAK_TFLOPS
+        if hbm_frac_dom > mfma_frac_dom:
+            roofline = {"bound": "hbm", "kernel": f"grouped_gemm_kernel ({dom})",
+                        "achieved": hbm_frac_dom * HBM_PEAK_GBS, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac_dom,
+                        "traffic": measured_traffic(wl.name, dom), "bytes_per_launch": gemm_bytes[dom],
+                        "avg_launch_ms": stage_ms[dom], "mfma_frac": mfma_frac_dom,
+                        "other_gemm": {"kernel": f"grouped_gemm_kernel ({other})", "bytes_per_launch": gemm_bytes[other],
+                                       "avg_launch_ms": stage_ms[other],
+                                       "frac": gemm_bytes[other] / (stage_ms[other] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+        else:
+            roofline = {"bound": "mfma", "kernel": f"grouped_gemm_kernel ({dom})", "achieved": achieved,
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac_dom,
+                        "traffic": measured_traffic(wl.name, dom),
+                        "flops_per_launch": dom_flops, "avg_launch_ms": stage_ms[dom],
+                        "other_gemm": {"kernel": f"grouped_gemm_kernel ({other})", "flops_per_launch": other_flops,
+                                       "avg_launch_ms": stage_ms[other],
+                                       "frac": other_flops / (stage_ms[other] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
     else:   # the all-fp32 correctness configuration: plain FMA kernels, a few hundred kB of data
         roofline = {"bound": "alu", "kernel": f"ffn_f32_kernel ({dom})", "achieved": achieved,
                     "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
