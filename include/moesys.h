@@ -494,6 +494,17 @@ int32_t moe_expert_pool_create(void* dev_pool, size_t pool_bytes, size_t slot_by
                                void* copy_stream, moe_expert_pool** out);
 int32_t moe_expert_pool_prepare(moe_expert_pool* p, int32_t layer, const int32_t* counts_dev,
                                 int32_t elem_bytes, int64_t* dev_offsets, void* compute_stream);
+/* Copies ahead of time (Section 3.2.2 uses the gate's results to prefetch; Section 3.3.2 overlaps loads with
+ * compute): while the experts of one layer run, the caller routes the NEXT layer on what it has (e.g. the
+ * running layer's input, on a second stream and workspace) and hands those counts over.  Every guessed expert
+ * that is not resident is requested from the policy inside the current batch (so the running layer's experts are
+ * never its victims) and its copy is enqueued on the copy stream; resident ones are left alone (a guess is not
+ * a use).  Waits for `stream` (the one counts_dev was produced on), not for the compute stream.  The next
+ * moe_expert_pool_prepare makes the compute stream wait for these copies as for its own.  A wrong guess costs
+ * one copy and one slot.  *n_copied (nullable): blobs enqueued.  Stops without error when every slot holds an
+ * item of the current batch. */
+int32_t moe_expert_pool_prefetch(moe_expert_pool* p, int32_t layer, const int32_t* counts_dev, void* stream,
+                                 int32_t* n_copied);
 /* Totals since creation (nullable outputs). */
 int32_t moe_expert_pool_stats(const moe_expert_pool* p, uint64_t* bytes_copied, uint64_t* copies,
                               uint64_t* hits, uint64_t* misses, uint64_t* evictions);

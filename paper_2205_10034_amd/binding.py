@@ -138,6 +138,7 @@ def lib() -> C.CDLL:
         L.moe_expert_pool_create.argtypes = [vp, C.c_size_t, C.c_size_t, C.POINTER(vp), C.c_int32, C.c_int32, C.c_size_t,
                                              C.c_float, C.c_float, C.c_int32, vp, C.POINTER(vp)]
         L.moe_expert_pool_prepare.argtypes = [vp, C.c_int32, vp, C.c_int32, vp, vp]
+        L.moe_expert_pool_prefetch.argtypes = [vp, C.c_int32, vp, vp, C.POINTER(C.c_int32)]
         L.moe_expert_pool_stats.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 5
         L.moe_expert_pool_destroy.argtypes = [vp]
         L.moe_set_tuning.argtypes = [C.c_int32, C.c_int32]
@@ -507,6 +508,13 @@ class ExpertPool:
     def prepare(self, layer: int, counts_dev, elem_bytes: int, dev_offsets, compute_stream=None) -> None:
         _check(lib().moe_expert_pool_prepare(self.h, layer, _ptr(counts_dev), elem_bytes, _ptr(dev_offsets),
                                              _stream(compute_stream)), "moe_expert_pool_prepare")
+
+    def prefetch(self, layer: int, counts_dev, stream=None) -> int:
+        """Enqueue the copies of the guessed experts of ``layer`` that are not resident; returns how many."""
+        n = C.c_int32()
+        _check(lib().moe_expert_pool_prefetch(self.h, layer, _ptr(counts_dev), _stream(stream), C.byref(n)),
+               "moe_expert_pool_prefetch")
+        return n.value
 
     def stats(self):
         v = [C.c_uint64() for _ in range(5)]

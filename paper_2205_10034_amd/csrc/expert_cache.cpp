@@ -162,9 +162,10 @@ struct moe_expert_pool {
   hipStream_t copy_stream;
   bool own_stream;
   hipEvent_t copied;
-  int32_t* counts_host;            // pinned [E]
+  int32_t* counts_host;            // pinned [2][E]: the layer's counts, a prefetch's counts
   int64_t* offsets_host;           // pinned [E]
-  uint64_t bytes_copied, copies;
+  uint64_t bytes_copied, copies, prefetched;
+  bool copies_pending;             // copies enqueued since the compute stream last waited for the copy stream
 };
 
 extern "C" {
@@ -197,7 +198,8 @@ int32_t moe_expert_pool_create(void* dev_pool, size_t pool_bytes, size_t slot_by
     p->n_layers = n_layers;
     p->E = E;
     p->host.assign(host_blobs, host_blobs + (size_t)n_layers * E);
-    p->bytes_copied = p->copies = 0;
+    p->bytes_copied = p->copies = p->prefetched = 0;
+    p->copies_pending = false;
     if (copy_stream) {
       p->copy_stream = (hipStream_t)copy_stream;
     } else {
@@ -206,7 +208,7 @@ int32_t moe_expert_pool_create(void* dev_pool, size_t pool_bytes, size_t slot_by
     }
   }
   if (st == MOE_OK) st = check_hip(hipEventCreateWithFlags(&p->copied, hipEventDisableTiming), "hipEventCreate");
-  if (st == MOE_OK) st = check_hip(hipHostMalloc((void**)&p->counts_host, sizeof(int32_t) * E, hipHostMallocDefault), "hipHostMalloc");
+  if (st == MOE_OK) st = check_hip(hipHostMalloc((void**)&p->counts_host, sizeof(int32_t) * 2 * E, hipHostMallocDefault), "hipHostMalloc");
   if (st == MOE_OK) st = check_hip(hipHostMalloc((void**)&p->offsets_host, sizeof(int64_t) * E, hipHostMallocDefault), "hipHostMalloc");
   if (st != MOE_OK) {
     moe_expert_pool_destroy(p);
@@ -256,11 +258,46 @@ int32_t moe_expert_pool_prepare(moe_expert_pool* p, int32_t layer, const int32_t
       any_copy = true;
     }
   }
-  if (any_copy) {
+  // (a prefetched blob may still be on its way: the event covers every copy enqueued so far)
+  if (any_copy || p->copies_pending) {
     if ((st = check_hip(hipEventRecord(p->copied, p->copy_stream), "hipEventRecord")) != MOE_OK) return st;
     if ((st = check_hip(hipStreamWaitEvent(cs, p->copied, 0), "hipStreamWaitEvent")) != MOE_OK) return st;
+    p->copies_pending = false;
   }
   return check_hip(hipMemcpyAsync(dev_offsets, p->offsets_host, sizeof(int64_t) * p->E, hipMemcpyHostToDevice, cs), "hipMemcpyAsync(offsets)");
+}
+
+int32_t moe_expert_pool_prefetch(moe_expert_pool* p, int32_t layer, const int32_t* counts_dev, void* stream,
+                                 int32_t* n_copied) {
+  if (!p || !counts_dev) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_prefetch: NULL argument");
+  if (layer < 0 || layer >= p->n_layers) return fail(MOE_ERR_INVALID_ARG, "moe_expert_pool_prefetch: layer %d of %d", layer, p->n_layers);
+  hipStream_t ss = (hipStream_t)stream;
+  int32_t* guess = p->counts_host + p->E;
+  int32_t st = check_hip(hipMemcpyAsync(guess, counts_dev, sizeof(int32_t) * p->E, hipMemcpyDeviceToHost, ss), "hipMemcpyAsync(counts)");
+  if (st != MOE_OK) return st;
+  if ((st = check_hip(hipStreamSynchronize(ss), "hipStreamSynchronize")) != MOE_OK) return st;
+  int32_t n = 0;
+  for (int32_t e = 0; e < p->E; ++e) {
+    if (guess[e] <= 0) continue;
+    const int64_t item = (int64_t)layer * p->E + e;
+    int32_t slot = -1;
+    if ((st = moe_expert_cache_lookup(p->policy, item, &slot, nullptr)) != MOE_OK) return st;
+    if (slot >= 0) continue;  // resident already: a guess is not a use, the counts stay as they are
+    // a request inside the current batch: the experts of the layer that is running are not victims
+    st = moe_expert_cache_schedule(p->policy, item, &slot, nullptr, nullptr);
+    if (st == MOE_ERR_STATE) break;  // no slot outside the batch is left: stop guessing
+    if (st != MOE_OK) return st;
+    st = check_hip(hipMemcpyAsync(p->dev_pool + (size_t)slot * p->slot_bytes, p->host[(size_t)item], p->blob_bytes,
+                                  hipMemcpyHostToDevice, p->copy_stream), "hipMemcpyAsync(expert)");
+    if (st != MOE_OK) return st;
+    p->bytes_copied += p->blob_bytes;
+    ++p->copies;
+    ++p->prefetched;
+    p->copies_pending = true;
+    ++n;
+  }
+  if (n_copied) *n_copied = n;
+  return MOE_OK;
 }
 
 int32_t moe_expert_pool_stats(const moe_expert_pool* p, uint64_t* bytes_copied, uint64_t* copies, uint64_t* hits,

@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--threshold", type=float, default=2.0)
     ap.add_argument("--beta", type=float, default=0.9)
     ap.add_argument("--decay-steps", type=int, default=256)
+    ap.add_argument("--prefetch", action="store_true",
+                    help="while a layer's experts run, route the next layer on this layer's input (second stream) and copy "
+                         "the guessed experts that are not resident ahead of time")
     args = ap.parse_args()
 
     import numpy as np
@@ -74,8 +77,12 @@ def main():
             wl = base_wl.scaled(T=T)
             cfg = M.MoEConfig.from_workload(wl)
             ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+            ws_guess = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
             lay = M.moe_workspace_layout(cfg)
             counts_dev = ws[lay["expert_counts"]:lay["expert_counts"] + 4 * E].view(torch.int32)
+            guess_dev = ws_guess[lay["expert_counts"]:lay["expert_counts"] + 4 * E].view(torch.int32)
+            side = torch.cuda.Stream()
+            ahead = [0]
             pool = M.ExpertPool(dev_pool, slot_bytes, blobs, N, E, blob_bytes, args.threshold, args.beta, args.decay_steps)
             Ws = []
             for l in range(N):
@@ -93,6 +100,10 @@ def main():
                     M.moe_layer_route(cfg, Ws[l], x, ws, compute)
                     pool.prepare(l, counts_dev, 2, offs, compute)
                     M.moe_layer_experts(cfg, Ws[l], x, x, nxt, ws, compute)
+                    if args.prefetch and l + 1 < N:
+                        # (x is complete: prepare() waited for the compute stream after this layer's routing)
+                        M.moe_layer_route(cfg, Ws[l + 1], x, ws_guess, side)
+                        ahead[0] += pool.prefetch(l + 1, guess_dev, side)
                     x, nxt = nxt, x
                 return x
 
@@ -100,6 +111,7 @@ def main():
                 step()
             torch.cuda.synchronize()
             s0 = pool.stats()
+            ahead[0] = 0
             t1 = time.perf_counter()
             for _ in range(args.steps):
                 step()
@@ -107,15 +119,17 @@ def main():
             dt = time.perf_counter() - t1
             s1 = pool.stats()
             pool.close()
-            req = (s1["hits"] - s0["hits"]) + (s1["misses"] - s0["misses"])
+            # (a copy ahead of time is a miss of the policy; the request that follows it is a hit)
+            req = (s1["hits"] - s0["hits"]) + (s1["misses"] - s0["misses"]) - ahead[0]
             copied = s1["bytes_copied"] - s0["bytes_copied"]
             res = {
                 "workload": f"expert pool: {N} layers, T={T} d_model={d} d_ff={f} E={E} top-{wl.k}, "
-                            f"{slots} slots, router {'log-Zipf(1.2) bias' if skew else 'unbiased'}",
+                            f"{slots} slots, router {'log-Zipf(1.2) bias' if skew else 'unbiased'}{', next layer guessed and copied ahead' if args.prefetch else ''}",
                 "step_ms": dt / args.steps * 1e3, "tokens_per_s": T * args.steps / dt,
                 "experts_requested_per_step": req / args.steps,
                 "hit_rate": (s1["hits"] - s0["hits"]) / max(req, 1),
                 "gib_copied_per_step": copied / args.steps / 2 ** 30,
+                **({"copied_ahead_per_step": ahead[0] / args.steps} if args.prefetch else {}),
                 "h2d_gbs_over_whole_step": copied / dt / 1e9,
                 "whole_layer_streaming_gib_per_step": N * E * blob_bytes / 2 ** 30,
             }

@@ -100,6 +100,98 @@ def test_pool_stack_matches_resident_and_policy_oracle(T, slots, steps):
     pool.close()
 
 
+@pytest.mark.parametrize("T,slots,steps", [(3, 16, 10), (1, 9, 16), (24, 20, 5)])
+def test_pool_prefetch_keeps_the_bits_and_follows_the_policy_oracle(T, slots, steps):
+    """moe_expert_pool_prefetch: while layer l's experts run, layer l+1 is routed on layer l's INPUT (a guess: the
+    residual stream changes little per layer) on a second stream and workspace, and the guessed experts that are not
+    resident are copied ahead.  The outputs stay bit-identical to the resident stack whatever the guesses were worth;
+    the policy oracle, fed the same requests (a guess that is not resident = a request inside the running batch),
+    predicts every slot, hit, copy and eviction."""
+    N, thr, beta, K = 3, 2.0, 0.5, 7
+    wl = WORKLOADS["ring"].scaled(T=T, d_model=256, d_ff=512, E=8, capacity_factor=0.0)
+    print(f"pool prefetch T={T} slots={slots} steps={steps} {wl}", flush=True)
+    _, layers = make_ring_stack(wl, N)
+    cfg = M.MoEConfig.from_workload(wl)
+    Ws = [upload_weights(L, wl.dtype, nullable_bias=True) for L in layers]
+    host, sizes = [], None
+    for W in Ws:
+        parts = [W.tensors[n] for n in ("w1", "w2")]
+        sizes = [p[0].numel() for p in parts]
+        for e in range(wl.E):
+            b = torch.empty(sum(sizes), dtype=torch.bfloat16, pin_memory=True)
+            b[:sizes[0]] = parts[0][e].reshape(-1).cpu()
+            b[sizes[0]:] = parts[1][e].reshape(-1).cpu()
+            host.append(b)
+    blob_elems = sum(sizes)
+    slot_bytes = (blob_elems * 2 + 255) // 256 * 256
+    dev_pool = torch.full((slots * slot_bytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    pool = M.ExpertPool(dev_pool, slot_bytes, host, N, wl.E, blob_elems * 2, thr, beta, K)
+    offs = torch.zeros(wl.E, dtype=torch.int64, device="cuda")
+    base = dev_pool.data_ptr()
+    Wp = []
+    for l in range(N):
+        t = {"w_router": Ws[l].tensors["w_router"], "expert_elem_offset": offs, "w1": base, "w2": base + 2 * sizes[0]}
+        if "w_router_packed" in Ws[l].tensors:
+            t["w_router_packed"] = Ws[l].tensors["w_router_packed"]
+        Wp.append(M.Weights(t))
+    ref_policy = SparseParameterCache(slots, thr, beta, K)
+    want = dict(copies=0, hits=0, evictions=0)
+    ws, ws_guess = alloc_ws(cfg), alloc_ws(cfg)
+    lay = M.moe_workspace_layout(cfg)
+    counts_dev = ws_view(ws, lay["expert_counts"], wl.E, torch.int32)
+    guess_dev = ws_view(ws_guess, lay["expert_counts"], wl.E, torch.int32)
+    side = torch.cuda.Stream()
+    rng = np.random.default_rng(11)
+    useful = 0
+    for step in range(steps):
+        x = to_dev(rng.standard_normal((T, wl.d_model)).astype(np.float32), wl.dtype)
+        x_ref = x.clone()
+        guessed = set()
+        for l in range(N):
+            nxt_ref = torch.empty_like(x_ref)
+            M.moe_layer_forward(cfg, Ws[l], x_ref, x_ref, nxt_ref, alloc_ws(cfg))
+            M.moe_layer_route(cfg, Wp[l], x, ws)
+            pool.prepare(l, counts_dev, 2, offs)
+            counts = counts_dev.cpu().numpy()
+            ref_policy.begin_batch()
+            for e in range(wl.E):
+                if counts[e] > 0:
+                    slot, hit, gone = ref_policy.schedule(l * wl.E + e)
+                    want["hits"] += hit
+                    want["copies"] += not hit
+                    want["evictions"] += gone is not None
+                    useful += (l * wl.E + e) in guessed
+                    assert int(offs[e].item()) == slot * slot_bytes // 2
+            nxt = torch.empty_like(x)
+            M.moe_layer_experts(cfg, Wp[l], x, x, nxt, ws)                 # runs while the next layer is guessed
+            if l + 1 < N:
+                M.moe_layer_route(cfg, Wp[l + 1], x, ws_guess, side)
+                n = pool.prefetch(l + 1, guess_dev, side)
+                g = guess_dev.cpu().numpy()
+                expect = 0
+                for e in range(wl.E):
+                    item = (l + 1) * wl.E + e
+                    if g[e] > 0 and item not in ref_policy.residents:
+                        if not ref_policy.evictable() and len(ref_policy.residents) >= slots:
+                            break
+                        _, hit, gone = ref_policy.schedule(item)
+                        assert not hit
+                        want["copies"] += 1
+                        want["evictions"] += gone is not None
+                        guessed.add(item)
+                        expect += 1
+                assert n == expect
+            torch.cuda.synchronize()
+            assert torch.equal(nxt, nxt_ref), f"step {step} layer {l}"
+            x, x_ref = nxt, nxt_ref
+    st = pool.stats()
+    print(st, "guesses that were used:", useful, flush=True)
+    assert st == {"bytes_copied": want["copies"] * blob_elems * 2, "copies": want["copies"], "hits": want["hits"],
+                  "misses": want["copies"], "evictions": want["evictions"]}
+    assert useful > 0
+    pool.close()
+
+
 def test_pool_smaller_than_one_layers_experts_is_refused():
     wl = WORKLOADS["ring"].scaled(T=64, d_model=256, d_ff=512, E=8, capacity_factor=0.0)
     _, layers = make_ring_stack(wl, 1)
