@@ -116,6 +116,8 @@ template <> struct AccBlock<true> {
     for (int i = 0; i < 4; ++i) q[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 };
+// s_waitcnt operand: at most n vector memory operations in flight, no LDS or scalar one, exports untouched
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }
 constexpr bool use_mi16(int tok, int wt, int epi) { return tok <= 256 && (tok / 32 / wt) % 2 == 0 && ((MOE_MI16_MASK >> epi) & 1); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -158,19 +160,24 @@ __device__ __forceinline__ float phi_addend(const f32x2* tab) {
   const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)tab;
   return 8388608.0f + PHI_RANGE * PHI_SCALE * 8.0f + (float)base;  // (all integers below 2^24: exact)
 }
-__device__ __forceinline__ f32x2 phi_cell(float u, float addend) {
+// The read is written as table base + (address - table base): the two constants cancel in the generated code, and
+// the compiler still knows which LDS object is read.  With a bare integer address it cannot tell the read from
+// the LDS writes of the direct-to-LDS loads in flight (the next tile's first stages) and waits for all of them.
+__device__ __forceinline__ f32x2 phi_cell(float u, float addend, const f32x2* tab) {
   const float c = __builtin_amdgcn_fmed3f(u, -PHI_RANGE, PHI_CLAMP_HI);
   const float tm = fmaf(c, PHI_SCALE * 8.0f, addend);
-  return *(phi_lds_ptr)(uintptr_t)(__float_as_uint(tm) & 0x3fff8u);  // (LDS addresses are below 2^18)
+  const uint32_t addr = __float_as_uint(tm) & 0x3fff8u;  // (LDS addresses are below 2^18)
+  const auto base = (__attribute__((address_space(3))) const char*)tab;
+  return *(phi_lds_ptr)(base + (addr - (uint32_t)(uintptr_t)base));
 }
 // B values at a time, in three passes: table positions, the B table reads back to back, the
 // interpolations.  (One value at a time the compiler waits for every read before it starts the next
 // value, and the epilogue then runs at the latency of the LDS instead of at the rate of the vector ALU.)
 template <int B>
-__device__ __forceinline__ void gelu_table_n(float* u, float addend) {
+__device__ __forceinline__ void gelu_table_n(float* u, float addend, const f32x2* tab) {
   f32x2 e[B];
 #pragma unroll
-  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend);
+  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend, tab);
 #pragma unroll
   for (int r = 0; r < B; ++r) u[r] *= fmaf(u[r], e[r].y, e[r].x);
 }
@@ -190,10 +197,10 @@ __device__ __forceinline__ void fill_gelu_prime_table(f32x2* tab) {
 }
 // u[r] <- dh[r] * gelu'(u[r]), gelu' read from its table like Phi in the forward pass
 template <int B>
-__device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, float addend) {
+__device__ __forceinline__ void dgelu_table_n(float* u, const float* dh, float addend, const f32x2* tab) {
   f32x2 e[B];
 #pragma unroll
-  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend);
+  for (int r = 0; r < B; ++r) e[r] = phi_cell(u[r], addend, tab);
 #pragma unroll
   for (int r = 0; r < B; ++r) u[r] = dh[r] * fmaf(u[r], e[r].y, e[r].x);
 }
@@ -471,14 +478,13 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // selected by the uniform offset.  `live` = false turns the loads into no-ops (zero-length descriptors),
   // so that the number of loads in flight at every wait is fixed.  A stage is requested in two halves
   // (token rows, then weight rows) at two different points of the K loop, see `step`.
-#define MOE_TILE_LOADS(rsrc, voff, n_loads, lds_tile)                                                            \
-  _Pragma("unroll") for (int i_ = 0; i_ < (n_loads); ++i_)                                                       \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                  \
-          rsrc, (__attribute__((address_space(3))) void*)((lds_tile) + (i_ * NW + wave) * 1024), 16, voff[i_], koff, 0, 0)
   auto issue_tokens = [&](int kt, bool live, unsigned char* stage) {
     const int koff = kt * ROW_BYTES;
     const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(a_ptr, live ? a_bytes : 0u);
-    MOE_TILE_LOADS(a_rsrc, a_voff, A_LOADS, stage);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)(stage + (i * NW + wave) * 1024), 16,
+                                               a_voff[i], koff, 0, 0);
   };
   auto issue_weights = [&](int kt, bool live, unsigned char* stage) {
     unsigned char* B = stage + A_BYTES;
@@ -498,7 +504,6 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             woff + i * b_blk, 0, 0);
     }
   };
-#undef MOE_TILE_LOADS
   const int KT = K / KS;
 
   // L2 prefetch.  One instruction per wavefront and K-step touches one dword of a 128-byte line per lane
@@ -580,7 +585,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     }
   };
 
-  MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0; } pf = {};
+  MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0, ewait, tail, pro; } pf = {};
            pf.c0 = __builtin_readcyclecounter(); pf.r0 = __builtin_amdgcn_s_memrealtime();)
   // (16x16x32: acc[i][j] holds the four 16x16 sub-blocks of the 32x32 block, four registers each, number
   // 2 * (token half) + (feature half); the fragment sets hold half of the token blocks, 16 rows at a time)
@@ -786,16 +791,25 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   bind_prefetch(ti);
   issue_prologue(ti);
 
+  // stores per wavefront in the epilogue of a tile without missing rows (its loads, if any, are not counted: a
+  // lower bound of what is issued after the next tile's first requests is what the wait below needs)
+  constexpr int EPI_STORES = TB * 2 * (EPI == EPI_SWIGLU ? FBH : EPI == EPI_DSWIGLU ? 2 : FB);
+  bool stores_behind = false;
   while (true) {
 #pragma unroll
     for (int i = 0; i < TB; ++i)
 #pragma unroll
       for (int j = 0; j < FB; ++j) acc[i][j].clear();
 
-    // Everything this wavefront has in flight (the tile's first stages and bias; the previous tile's stores,
-    // which do not retire in order with loads) completes, then the workgroup meets: stage 0 is readable.
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    MOE_PROF({ const unsigned long long t = __builtin_readcyclecounter(); if (pf.tiles) pf.epi += t - pf.last; pf.last = t; })
+    // The tile's first stages and bias have landed, then the workgroup meets: stage 0 is readable.  Vector memory
+    // operations leave the counter in the order they were issued, and the previous tile's epilogue came after the
+    // requests for this tile's first stages: when that epilogue issued every one of its EPI_STORES stores (a
+    // wavefront whose rows all exist), waiting until no more than those are in flight is enough, and the stores
+    // complete under the first K-step (whose own wait covers them, being older than its loads).
+    MOE_PROF(const unsigned long long t_w = __builtin_readcyclecounter();)
+    if (stores_behind) __builtin_amdgcn_s_waitcnt(waitcnt_vm(EPI_STORES));
+    else __builtin_amdgcn_s_waitcnt(0x0070);
+    MOE_PROF({ const unsigned long long t = __builtin_readcyclecounter(); if (pf.tiles) { pf.epi += t - pf.last; pf.ewait += t - t_w; } pf.last = t; })
     __builtin_amdgcn_s_barrier();
     MOE_PROF({ const unsigned long long t = __builtin_readcyclecounter(); if (pf.tiles) pf.tbar += t - pf.last; else pf.start = t - pf.c0;
                pf.last = t; ++pf.tiles; })
@@ -821,21 +835,22 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     }
 
     // ---- next tile: bind it and request its first stages before this tile's epilogue ---------------
+    MOE_PROF(const unsigned long long t_k = __builtin_readcyclecounter(); pf.tail += t_k - pf.last;)
     const TileInfo done = ti;
     ti = nx;
     have = have_nx;
-    if constexpr (GATHER) {
-      if (have) gather_voff(ti);
-    }
     // every fragment read of real data finished before the last barrier; what the last sub-step read
     // afterwards is never used, so the stage buffers may be overwritten now
     const int done_set = bias_set;
     if (have) {
       bias_set ^= 1;
+      if constexpr (GATHER) gather_voff(ti);
       bind_tile(ti);
       bind_prefetch(ti);
       issue_prologue(ti);
     }
+    MOE_PROF(pf.pro += __builtin_readcyclecounter() - t_k;)
+    __builtin_amdgcn_sched_barrier(0);  // the epilogue's stores stay behind those requests (the next tile's wait counts on it)
 
     // ---- epilogue: lane holds token (lane&31), features 8*i + 4*(lane>>5) + r of each 32x32 block ----
     // Lanes l and l+32 hold the two halves of the same token's 8-feature groups.  For a pair of groups
@@ -959,7 +974,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
             if (EPI == EPI_GELU) {
               constexpr int GB = TOK > 256 ? 4 : 8;  // (8 at a time in the 320-row kernel: at the register limit, no faster)
 #pragma unroll
-              for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, phi_add);
+              for (int r = 0; r < 8; r += GB) gelu_table_n<GB>(p + r, phi_add, s_phi);
             }
             if constexpr (EPI == EPI_DGELU) {
               // (every element is read by the lane that multiplies it, before the lanes trade halves and before
@@ -983,7 +998,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
                 dh[4 * g + 3] = __uint_as_float(rv.y & 0xffff0000u);
               }
 #pragma unroll
-              for (int r = 0; r < 8; r += 4) dgelu_table_n<4>(p + r, dh + r, phi_add);
+              for (int r = 0; r < 8; r += 4) dgelu_table_n<4>(p + r, dh + r, phi_add, s_phi);
             }
             if constexpr (EPI == EPI_COMBINE) {
               // before the lanes trade halves: this lane's 4 + 4 features of the residual row
@@ -1004,13 +1019,15 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       }
     }
     if (!have) break;
+    // the epilogue above ran all its stores with every lane alive: this wavefront's last row of the tile exists
+    stores_behind = done.rows >= ((TB - 1) * WT + wt + 1) * 32;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only zero-length loads and stores remain; retire them
   MOE_PROF(if (g_gemm_prof && lane == 0) {
     unsigned long long* o = g_gemm_prof + ((size_t)(EPI >= EPI_BIAS ? NUM_CU : 0) * 8 + (size_t)blockIdx.x * NW + wave) * PROF_SLOTS;
     const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
     o[0] = pf.comp; o[1] = pf.vm; o[2] = pf.bar; o[3] = pf.steps; o[4] = pf.epi; o[5] = pf.tiles; o[6] = c1 - pf.last;
-    o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1;
+    o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1; o[12] = pf.ewait; o[13] = pf.tail; o[14] = pf.pro;
   })
 #endif
 }

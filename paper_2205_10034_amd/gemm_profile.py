@@ -72,7 +72,7 @@ def run(name: str) -> None:
               f"start to first tile ready: mean {q[:, 8].mean():.0f}")
         total = life.mean()
         for i, lab in ((0, "multiply (barrier to wait)"), (1, "wait for own loads"), (2, "wait at K-step barrier"),
-                       (4, "epilogue and tile switch"), (7, "wait at tile-start barrier"), (6, "last epilogue")):
+                       (4, "epilogue and tile switch"), (13, "  of it: last quarter K-step"), (14, "  of it: next tile's requests"), (12, "  of it: wait for first stage"), (7, "wait at tile-start barrier"), (6, "last epilogue")):
             v = q[:, i].mean()
             print(f"    {lab:28s} {v:12.0f} clocks  {100 * v / total:5.1f} %   per K-step {v / steps.mean():7.1f}   "
                   f"per tile {v / tiles.mean():9.1f}")
