@@ -256,46 +256,66 @@ __host__ __device__ inline int64_t block_count(int64_t MT, int n_tiles) {
 // the tiles of blocks x, x+8, x+16, ... are numbered consecutively and workgroup j of the G on the XCD
 // takes number j first and then whatever number the XCD's counter hands out next (`want` is set by the
 // caller before each call and must grow): workgroups that drew short tiles simply draw more of them.
+// floor(a / b) for 0 <= a, 1 <= b and a quotient below 2^22, without the forty-odd instructions of the general
+// 32-bit division: a reciprocal estimate is within one of the quotient, the exact remainder corrects it.  (The walk
+// below runs once per tile on every wavefront while the matrix pipes wait, and is mostly divisions.)
+__device__ __forceinline__ int div_small(int a, int b) {
+  int q = (int)((float)a * __builtin_amdgcn_rcpf((float)b));
+  const int r = a - q * b;
+  q += r >= b ? 1 : 0;
+  q -= r < 0 ? 1 : 0;
+  return q;
+}
+// the same for operands that every lane holds alike: the quotient goes back to a scalar register
+__device__ __forceinline__ int div_small_uniform(int a, int b) { return __builtin_amdgcn_readfirstlane(div_small(a, b)); }
+
 template <int TOK, int UNIT>
 struct TileWalker {
   int MT, NT, GM, GN, MG, NG;
   int xcd, G;
-  int q, base, want;
+  int b, msg, rem;  // this workgroup's current block b = NUM_XCD * q + xcd, and b = msg * NUM_XCD * NG + rem
+  int base, want;
 
   __device__ __forceinline__ void init(int mt_total, int n_tiles) {
     MT = mt_total; NT = n_tiles;
     GN = group_n(n_tiles); GM = CU_PER_XCD / GN;
     MG = (MT + GM - 1) / GM; NG = (NT + GN - 1) / GN;
     xcd = blockIdx.x % NUM_XCD; G = gridDim.x / NUM_XCD;
-    q = 0; base = 0; want = blockIdx.x / NUM_XCD;
+    b = xcd; msg = 0; rem = xcd;  // (xcd < NUM_XCD <= NUM_XCD * NG)
+    base = 0; want = blockIdx.x / NUM_XCD;
   }
-  // Next tile of this workgroup; false when there is none.  All values are wave-uniform.
+  // Next tile of this workgroup; false when there is none.  All values are wave-uniform; the whole wavefront
+  // calls it (the search for the expert is one read per lane and a ballot).
   __device__ __forceinline__ bool next(const int32_t* __restrict__ offsets, int E, const int* s_pref, TileInfo& ti) {
     const int n_blocks = MG * NG;
     while (true) {
-      const int b = q * NUM_XCD + xcd;
       if (b >= n_blocks) return false;
-      const int msg = b / (NUM_XCD * NG), rem = b - msg * NUM_XCD * NG;
       const int P = min(NUM_XCD, MG - msg * NUM_XCD);
-      const int ng = rem / P, mg = msg * NUM_XCD + rem % P;
+      static_assert(NUM_XCD == 8, "the shifts below");
+      const int ng = P == NUM_XCD ? rem >> 3 : div_small_uniform(rem, P);
+      const int mg = msg * NUM_XCD + (rem - ng * P);
       const int gm = min(GM, MT - mg * GM), gn = min(GN, NT - ng * GN);
       const int cnt = gm * gn;
       if (want < base + cnt) {
-        const int r = want - base;
-        const int mt = mg * GM + r / gn, nt = ng * GN + r % gn;
-        int lo = 0, hi = E;  // largest e with s_pref[e] <= mt
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (s_pref[mid] <= mt) lo = mid; else hi = mid;
+        const int r = want - base;  // (below 32)
+        const int rq = gn == 8 ? r >> 3 : div_small_uniform(r, gn);
+        const int mt = mg * GM + rq, nt = ng * GN + (r - rq * gn);
+        // largest e with s_pref[e] <= mt = the number of e in 1..E with s_pref[e] <= mt (s_pref does not
+        // decrease, and s_pref[E] = MT > mt)
+        const int lane = threadIdx.x & 63;
+        int lo = 0;
+        for (int e0 = 0; e0 < E; e0 += 64) {
+          const int e = e0 + lane + 1;
+          lo += __builtin_popcountll(__ballot(e <= E && s_pref[min(e, E)] <= mt));
         }
         // every lane computed the same values; say so to the compiler (they feed scalar descriptors)
         lo = __builtin_amdgcn_readfirstlane(lo);
         ti.expert = lo;
-        // tile m of the expert's nt tiles: the units are dealt out evenly, the first `rem` tiles hold one more
+        // tile m of the expert's nt tiles: the units are dealt out evenly, the first `extra` tiles hold one more
         const int e0 = offsets[lo], n_rows = offsets[lo + 1] - e0;
         const int m = mt - s_pref[lo], nt_e = s_pref[lo + 1] - s_pref[lo];
-        const int units = (n_rows + UNIT - 1) / UNIT, per = units / nt_e, rem = units - per * nt_e;
-        const int u0 = m * per + min(m, rem), un = per + (m < rem ? 1 : 0);
+        const int units = (n_rows + UNIT - 1) / UNIT, per = div_small_uniform(units, nt_e), extra = units - per * nt_e;
+        const int u0 = m * per + min(m, extra), un = per + (m < extra ? 1 : 0);
         const int r0 = __builtin_amdgcn_readfirstlane(e0 + u0 * UNIT);
         ti.row0 = r0;
         ti.rows = __builtin_amdgcn_readfirstlane(min(un * UNIT, e0 + n_rows - r0));
@@ -305,12 +325,17 @@ struct TileWalker {
         const int m_lo = max(mg * GM, s_pref[lo]), m_hi = min(mg * GM + gm, s_pref[lo + 1]);
         ti.pm = __builtin_amdgcn_readfirstlane(mt - m_lo);
         ti.gm = __builtin_amdgcn_readfirstlane(m_hi - m_lo);
-        ti.pn = __builtin_amdgcn_readfirstlane(r % gn);
+        ti.pn = __builtin_amdgcn_readfirstlane(r - rq * gn);
         ti.gn = __builtin_amdgcn_readfirstlane(gn);
         return true;
       }
       base += cnt;
-      ++q;
+      b += NUM_XCD;
+      rem += NUM_XCD;
+      if (rem >= NUM_XCD * NG) {
+        rem -= NUM_XCD * NG;
+        ++msg;
+      }
     }
   }
 };
@@ -519,8 +544,8 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
   // latency) it costs 5-20 %, so short K loops do not prefetch and unshared tiles are left out.
   const uint16_t* pf_ptr = wa;  // this lane's line at K-step 0 of the bound tile
   auto bind_prefetch = [&](const TileInfo& t) {
-    const int a_lo = t.pn * TOK / t.gn, a_n = t.gn > 1 ? (t.pn + 1) * TOK / t.gn - a_lo : 0;
-    const int b_lo = t.pm * FEAT / t.gm, b_n = t.gm > 1 ? (t.pm + 1) * FEAT / t.gm - b_lo : 0;
+    const int a_lo = div_small_uniform(t.pn * TOK, t.gn), a_n = t.gn > 1 ? div_small_uniform((t.pn + 1) * TOK, t.gn) - a_lo : 0;
+    const int b_lo = div_small_uniform(t.pm * FEAT, t.gm), b_n = t.gm > 1 ? div_small_uniform((t.pm + 1) * FEAT, t.gm) - b_lo : 0;
     pf_ptr = b_ptr;
     if (KT < PF_MIN_KT) return;
     if (tid < a_n) {
@@ -585,7 +610,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     }
   };
 
-  MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0, ewait, tail, pro; } pf = {};
+  MOE_PROF(struct { unsigned long long comp, vm, bar, steps, epi, tiles, tbar, start, last, c0, r0, ewait, tail, pro, walk; } pf = {};
            pf.c0 = __builtin_readcyclecounter(); pf.r0 = __builtin_amdgcn_s_memrealtime();)
   // (16x16x32: acc[i][j] holds the four 16x16 sub-blocks of the 32x32 block, four registers each, number
   // 2 * (token half) + (feature half); the fragment sets hold half of the token blocks, 16 rows at a time)
@@ -773,7 +798,11 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
       any_step(kt, s0, s1);
       any_step(kt + 1, s1, s0);
       if (kt == 0) publish_next();
-      if (kt == 2) resolve_next();  // the two K-steps since publish_next() each passed a barrier
+      if (kt == 2) {  // the two K-steps since publish_next() each passed a barrier
+        MOE_PROF(const unsigned long long t_r = __builtin_readcyclecounter();)
+        resolve_next();
+        MOE_PROF(pf.walk += __builtin_readcyclecounter() - t_r;)
+      }
     }
     if (kt < KT) any_step(kt, s0, s1);
   };
@@ -1027,7 +1056,7 @@ __global__ __launch_bounds__(WT * WF * 64, WPE) void grouped_gemm_kernel(
     unsigned long long* o = g_gemm_prof + ((size_t)(EPI >= EPI_BIAS ? NUM_CU : 0) * 8 + (size_t)blockIdx.x * NW + wave) * PROF_SLOTS;
     const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
     o[0] = pf.comp; o[1] = pf.vm; o[2] = pf.bar; o[3] = pf.steps; o[4] = pf.epi; o[5] = pf.tiles; o[6] = c1 - pf.last;
-    o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1; o[12] = pf.ewait; o[13] = pf.tail; o[14] = pf.pro;
+    o[7] = pf.tbar; o[8] = pf.start; o[9] = c1 - pf.c0; o[10] = pf.r0; o[11] = r1; o[12] = pf.ewait; o[13] = pf.tail; o[14] = pf.pro; o[15] = pf.walk;
   })
 #endif
 }

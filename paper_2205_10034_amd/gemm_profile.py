@@ -76,6 +76,7 @@ def run(name: str) -> None:
             v = q[:, i].mean()
             print(f"    {lab:28s} {v:12.0f} clocks  {100 * v / total:5.1f} %   per K-step {v / steps.mean():7.1f}   "
                   f"per tile {v / tiles.mean():9.1f}")
+        print(f"    (inside multiply: finding the next tile, once per tile    {q[:, 15].mean() / tiles.mean():9.1f} clocks per tile)")
         half = len(q) // 2
         print("    per K-step, wavefronts 0-3 / 4-7 of a workgroup: multiply "
               f"{_by_wave(q, 0, 0):.0f} / {_by_wave(q, 0, 1):.0f}, barrier wait {_by_wave(q, 2, 0):.0f} / {_by_wave(q, 2, 1):.0f}")
