@@ -186,6 +186,37 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
+def _need(t, nbytes: int, what: str) -> None:
+    """The library takes plain pointers and trusts the configuration for what lies behind them: a tensor of the wrong
+    dtype or shape (bfloat16 tensors under a float32 configuration, say) would be read or written past its end on the
+    device.  Every tensor the binding knows the size of is therefore checked here, on the host, before the call."""
+    if t is None or isinstance(t, int):
+        return
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise ValueError(f"{what} holds {have} bytes, the configuration needs {nbytes} (wrong dtype or shape?)")
+
+
+def _esize(cfg) -> int:
+    return {"f32": 4, "bf16": 2}[cfg.dtype]
+
+
+def _need_tokens(cfg, **tensors) -> None:
+    for name, t in tensors.items():
+        _need(t, cfg.T * cfg.d_model * _esize(cfg), name)
+
+
+def _need_routing(cfg, topk_idx=None, topk_w=None, probs=None, assign_to_row=None, row_to_assign=None,
+                  expert_counts=None, expert_offsets=None) -> None:
+    A = cfg.k * cfg.T
+    _need(topk_idx, 4 * A, "topk_idx")
+    _need(topk_w, 4 * A, "topk_w")
+    _need(probs, 4 * cfg.T * cfg.E, "probs")
+    _need(assign_to_row, 4 * A, "assign_to_row")
+    _need(expert_counts, 4 * cfg.E, "expert_counts")
+    _need(expert_offsets, 4 * (cfg.E + 1), "expert_offsets")
+
+
 def _stream(stream) -> Optional[int]:
     import torch
     if stream is None:
@@ -204,6 +235,21 @@ class Weights:
                           g("w_router"), g("b_router"),
                           MOE_LAYOUT_OUTPUT_MAJOR if layout == "output_major" else MOE_LAYOUT_INPUT_MAJOR,
                           g("expert_elem_offset"), g("w_router_packed"))
+
+    def need(self, cfg) -> None:
+        """Raises ValueError if a parameter tensor is smaller than `cfg` says (see _need)."""
+        t, s = self.tensors, _esize(cfg)
+        E, d, f = cfg.E, cfg.d_model, cfg.d_ff
+        _need(t.get("w_router"), 4 * d * E, "w_router")
+        _need(t.get("b_router"), 4 * E, "b_router")
+        _need(t.get("w_router_packed"), moe_router_pack_bytes(d, E) if t.get("w_router_packed") is not None else 0,
+              "w_router_packed")
+        _need(t.get("expert_elem_offset"), 8 * E, "expert_elem_offset")
+        if t.get("expert_elem_offset") is None:  # (with per-expert offsets the matrices are pools of any size)
+            for n in ("w1", "w2", "w_gate_proj", "w_up", "w_down"):
+                _need(t.get(n), E * d * f * s, n)
+            _need(t.get("b1"), E * f * s, "b1")
+            _need(t.get("b2"), E * d * s, "b2")
 
 
 MOE_TUNE_GEMM_TILE_ROWS, MOE_TUNE_FEW_TOKEN_KERNELS, MOE_TUNE_GATE_TOKENS, MOE_TUNE_GEMM_MFMA = 0, 1, 2, 3
@@ -243,6 +289,10 @@ def moe_workspace_layout(cfg: MoEConfig) -> Dict[str, int]:
 
 def moe_gate(cfg, x, w_router, b_router, topk_idx, topk_w, probs=None, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x)
+    _need(w_router, 4 * cfg.d_model * cfg.E, "w_router")
+    _need(b_router, 4 * cfg.E, "b_router")
+    _need_routing(cfg, topk_idx=topk_idx, topk_w=topk_w, probs=probs)
     _check(lib().moe_gate(C.byref(c), _ptr(x), _ptr(w_router), _ptr(b_router), _ptr(topk_idx), _ptr(topk_w),
                           _ptr(probs), _stream(stream)), "moe_gate")
 
@@ -259,6 +309,11 @@ def moe_pack_router(w_router, packed, stream=None):
 
 def moe_gate_packed(cfg, x, w_router, b_router, w_router_packed, topk_idx, topk_w, probs=None, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x)
+    _need(w_router, 4 * cfg.d_model * cfg.E, "w_router")
+    _need(b_router, 4 * cfg.E, "b_router")
+    _need(w_router_packed, moe_router_pack_bytes(cfg.d_model, cfg.E), "w_router_packed")
+    _need_routing(cfg, topk_idx=topk_idx, topk_w=topk_w, probs=probs)
     _check(lib().moe_gate_packed(C.byref(c), _ptr(x), _ptr(w_router), _ptr(b_router), _ptr(w_router_packed), _ptr(topk_idx),
                                  _ptr(topk_w), _ptr(probs), _stream(stream)), "moe_gate_packed")
 
@@ -266,6 +321,9 @@ def moe_gate_packed(cfg, x, w_router, b_router, w_router_packed, topk_idx, topk_
 def moe_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, ws,
                  stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x)
+    _need_routing(cfg, topk_idx=topk_idx, assign_to_row=assign_to_row, row_to_assign=None, expert_counts=expert_counts,
+                  expert_offsets=expert_offsets)
     _check(lib().moe_dispatch(C.byref(c), _ptr(x), _ptr(topk_idx), _ptr(expert_counts), _ptr(expert_offsets),
                               _ptr(assign_to_row), _ptr(row_to_assign), _ptr(xd), _ptr(ws),
                               ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
@@ -274,6 +332,9 @@ def moe_dispatch(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row,
 
 def moe_dispatch_static(cfg, x, topk_idx, expert_counts, expert_offsets, assign_to_row, row_to_assign, xd, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x)
+    _need_routing(cfg, topk_idx=topk_idx, assign_to_row=assign_to_row, expert_counts=expert_counts,
+                  expert_offsets=expert_offsets)
     _check(lib().moe_dispatch_static(C.byref(c), _ptr(x), _ptr(topk_idx), _ptr(expert_counts), _ptr(expert_offsets),
                                      _ptr(assign_to_row), _ptr(row_to_assign), _ptr(xd), _stream(stream)),
            "moe_dispatch_static")
@@ -281,6 +342,8 @@ def moe_dispatch_static(cfg, x, topk_idx, expert_counts, expert_offsets, assign_
 
 def moe_expert_ffn(cfg, weights: Weights, xd, expert_offsets, yd, ws, stream=None):
     c = cfg.c()
+    weights.need(cfg)
+    _need_routing(cfg, expert_offsets=expert_offsets)
     _check(lib().moe_expert_ffn(C.byref(c), C.byref(weights.c), _ptr(xd), _ptr(expert_offsets), _ptr(yd), _ptr(ws),
                                 ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_expert_ffn")
@@ -288,12 +351,16 @@ def moe_expert_ffn(cfg, weights: Weights, xd, expert_offsets, yd, ws, stream=Non
 
 def moe_combine(cfg, yd, assign_to_row, topk_w, residual, out, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, residual=residual, out=out)
+    _need_routing(cfg, topk_w=topk_w, assign_to_row=assign_to_row)
     _check(lib().moe_combine(C.byref(c), _ptr(yd), _ptr(assign_to_row), _ptr(topk_w), _ptr(residual), _ptr(out),
                              _stream(stream)), "moe_combine")
 
 
 def moe_layer_forward(cfg, weights: Weights, x, residual, out, ws, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x, residual=residual, out=out)
+    weights.need(cfg)
     _check(lib().moe_layer_forward(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_forward")
@@ -301,6 +368,8 @@ def moe_layer_forward(cfg, weights: Weights, x, residual, out, ws, stream=None):
 
 def moe_layer_route(cfg, weights: Weights, x, ws, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x)
+    weights.need(cfg)
     _check(lib().moe_layer_route(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(ws),
                                  ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_route")
@@ -308,6 +377,8 @@ def moe_layer_route(cfg, weights: Weights, x, ws, stream=None):
 
 def moe_layer_experts(cfg, weights: Weights, x, residual, out, ws, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x, residual=residual, out=out)
+    weights.need(cfg)
     _check(lib().moe_layer_experts(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out), _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "moe_layer_experts")
@@ -349,6 +420,10 @@ def moe_layer_backward_workspace_bytes(cfg) -> int:
 def moe_layer_backward(cfg, weights: Weights, w1_input_major, w2_input_major, x, d_out, add_to_d_x, fwd_ws, d_x,
                        d_w_router, d_b_router, d_w1, d_b1, d_w2, d_b2, ws, stream=None, aux_loss_coef: float = 0.0):
     c = cfg.c()
+    _need_tokens(cfg, x=x, d_out=d_out, add_to_d_x=add_to_d_x, d_x=d_x)
+    weights.need(cfg)
+    _need(d_w_router, 4 * cfg.d_model * cfg.E, "d_w_router")
+    _need(d_b_router, 4 * cfg.E, "d_b_router")
     _check(lib().moe_layer_backward(C.byref(c), C.byref(weights.c), _ptr(w1_input_major), _ptr(w2_input_major), _ptr(x),
                                     _ptr(d_out), _ptr(add_to_d_x), aux_loss_coef, _ptr(fwd_ws),
                                     fwd_ws.numel() * fwd_ws.element_size(),
@@ -396,6 +471,8 @@ class StageTimer:
 
 def moe_layer_forward_timed(cfg, weights: Weights, x, residual, out, ws, timer: StageTimer, stream=None):
     c = cfg.c()
+    _need_tokens(cfg, x=x, residual=residual, out=out)
+    weights.need(cfg)
     _check(lib().moe_layer_forward_timed(C.byref(c), C.byref(weights.c), _ptr(x), _ptr(residual), _ptr(out),
                                          _ptr(ws), ws.numel() * ws.element_size(), _stream(stream), timer.h),
            "moe_layer_forward_timed")

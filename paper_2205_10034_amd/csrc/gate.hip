@@ -58,6 +58,34 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int m) {
   return __hiloint2double(hi, lo);
 }
 
+// A lane's partner inside its group of eight consecutive lanes, for the three steps of a reduction over the group:
+// steps 0 and 1 swap lanes inside a quad (lane ^ 1, lane ^ 2), step 2 mirrors the eight lanes (lane i with 7 - i,
+// which lies in the other quad).  Data-parallel-primitive moves on the vector ALU: a few clocks each, where a
+// general lane permutation goes through the LDS crossbar (a hundred clocks, and a reduction is a chain of them).
+template <int STEP>
+__device__ __forceinline__ int group8_partner(int v) {
+  constexpr int ctrl = STEP == 0 ? 0xB1 /* quad_perm 1,0,3,2 */ : STEP == 1 ? 0x4E /* quad_perm 2,3,0,1 */ : 0x141 /* row_half_mirror */;
+  return __builtin_amdgcn_update_dpp(0, v, ctrl, 0xF, 0xF, true);
+}
+template <int STEP>
+__device__ __forceinline__ float group8_partner(float v) { return __int_as_float(group8_partner<STEP>(__float_as_int(v))); }
+template <int STEP>
+__device__ __forceinline__ double group8_partner(double v) {
+  return __hiloint2double(group8_partner<STEP>(__double2hiint(v)), group8_partner<STEP>(__double2loint(v)));
+}
+// f(step) for the three steps, unrolled
+template <typename F>
+__device__ __forceinline__ void group8_steps(F&& f) {
+  f(std::integral_constant<int, 0>{});
+  f(std::integral_constant<int, 1>{});
+  f(std::integral_constant<int, 2>{});
+}
+
+// Workgroup barrier for data exchanged through LDS: waits for this wavefront's LDS operations only.  (__syncthreads
+// also waits for every global load and store in flight: for the results just stored, a microsecond at the end of a
+// kernel that lasts ten, and for refill loads that nobody will use.)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int W, int M>
 __device__ __forceinline__ void rs_step(double (&acc)[NE], int lane) {
   const bool upper = (lane & M) != 0;
@@ -320,16 +348,15 @@ __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E,
   float mx = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NPL; ++i) mx = fmaxf(mx, (float)z[i]);
-#pragma unroll
-  for (int m = 1; m <= 4; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  group8_steps([&](auto st) { mx = fmaxf(mx, group8_partner<decltype(st)::value>(mx)); });
   float ex[NPL], sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NPL; ++i) {
     ex[i] = (sub + 8 * i) < E ? expf((float)z[i] - mx) : 0.f;
     sum += ex[i];
   }
-#pragma unroll
-  for (int m = 1; m <= 4; m <<= 1) sum += __shfl_xor(sum, m, 64);
+  // (the same pairs in the same order in every lane of the group: all eight hold the same sum, bit for bit)
+  group8_steps([&](auto st) { sum += group8_partner<decltype(st)::value>(sum); });
 #pragma unroll
   for (int i = 0; i < NPL; ++i) {
     ex[i] = ex[i] / sum;
@@ -348,13 +375,13 @@ __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E,
       const int e = sub + 8 * i;
       if (e < E && (z[i] > bz || (z[i] == bz && e < be))) { bz = z[i]; be = e; bp = ex[i]; }
     }
-#pragma unroll
-    for (int m = 1; m <= 4; m <<= 1) {
-      const double oz = shfl_xor_f64(bz, m);
-      const int oe = __shfl_xor(be, m, 64);
-      const float op = __shfl_xor(bp, m, 64);
+    group8_steps([&](auto st) {
+      constexpr int S = decltype(st)::value;
+      const double oz = group8_partner<S>(bz);
+      const int oe = group8_partner<S>(be);
+      const float op = group8_partner<S>(bp);
       if (oz > bz || (oz == bz && oe < be)) { bz = oz; be = oe; bp = op; }
-    }
+    });
 #pragma unroll
     for (int i = 0; i < NPL; ++i)
       if (sub + 8 * i == be) z[i] = -INFINITY;  // retire the winner (every lane of the group agrees on be)
@@ -386,7 +413,10 @@ __device__ __forceinline__ bool finalize_group(double (&z)[NPL], int sub, int E,
 template <int EB>
 constexpr int gate_waves() { return EB == 1 ? 4 : 8; }
 
-template <int EB, bool VEC>
+// TT = 16-token tiles per workgroup.  The split of the router into its three pieces is the larger part of a
+// workgroup's work and does not depend on the tokens: two tiles share it (and the 64 KB of router a workgroup reads
+// per 16 experts), which is worth it once there are enough tokens to keep every CU busy with half as many workgroups.
+template <int EB, bool VEC, int TT>
 __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ wr,
                                                         const float* __restrict__ br, int T, int d, int E, int k,
                                                         int renorm, int32_t* __restrict__ topk_idx,
@@ -396,21 +426,27 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
   constexpr int NWV = gate_waves<EB>();
   constexpr int W_WAVE_BYTES = 3 * 16 * FT_ROW;  // one wavefront's hi/mid/lo pieces of one expert block's chunk
   constexpr int PF = EB == 1 ? 4 : 2;            // chunks in flight per wavefront (register-staged)
+  constexpr int NTOK = FT_TOK * TT;              // tokens per workgroup
+  static_assert(NTOK <= 32 && NTOK * 8 <= NWV * 64, "one flag bit and eight finalising lanes per token");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int s_flag[FT_TOK];
+  __shared__ int s_flag[NTOK];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned char* wl = smem + wave * W_WAVE_BYTES;
-  const int t0 = blockIdx.x * FT_TOK;
+  const int t0 = blockIdx.x * NTOK;
   const int tl = lane & 15, kq = lane >> 4;  // MFMA operand coordinates of this lane
 
-  // activation row of this lane (clamped: tail tokens recompute the last row, never stored)
-  const uint16_t* xrow = x + (size_t)min(t0 + tl, T - 1) * d + kq * 16;
+  // activation rows of this lane, one per token tile (clamped: tail tokens recompute the last row, never stored)
+  const uint16_t* xrow[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) xrow[tt] = x + (size_t)min(t0 + tt * FT_TOK + tl, T - 1) * d + kq * 16;
 
-  double zacc[EB][4];
+  double zacc[TT][EB][4];
 #pragma unroll
-  for (int b = 0; b < EB; ++b)
+  for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) zacc[b][r] = 0.0;
+    for (int b = 0; b < EB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) zacc[tt][b][r] = 0.0;
 
   // router-weight micro-tiles of this lane: 4 consecutive k x 4 consecutive experts each
   // (micro-tile m of a lane belongs to expert block m: expert group m*4 + lane%4, K group lane/4)
@@ -420,13 +456,15 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
   // PF register stages.  Every stage load is unconditional (a chunk index past the end re-reads the last
   // chunk and is never used), so the number of loads in flight is fixed and the wait before a stage's
   // first use can leave the younger stages outstanding.
-  u32x4 xa[PF][2];
+  u32x4 xa[PF][TT][2];
   float wv[PF][MT_PER_LANE][4][4];
 #define GATE_LOAD_STAGE(s_, c_)                                                                         \
   {                                                                                                     \
     const int k0_ = min((c_), n_chunks - 1) * FT_KC;                                                    \
-    xa[s_][0] = *reinterpret_cast<const u32x4*>(xrow + k0_);                                            \
-    xa[s_][1] = *reinterpret_cast<const u32x4*>(xrow + k0_ + 8);                                        \
+    _Pragma("unroll") for (int tt_ = 0; tt_ < TT; ++tt_) {                                              \
+      xa[s_][tt_][0] = *reinterpret_cast<const u32x4*>(xrow[tt_] + k0_);                                \
+      xa[s_][tt_][1] = *reinterpret_cast<const u32x4*>(xrow[tt_] + k0_ + 8);                            \
+    }                                                                                                   \
     _Pragma("unroll") for (int m = 0; m < MT_PER_LANE; ++m) {                                           \
       const int eg = m * 4 + (lane & 3), kg = lane >> 2;                                                \
       _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
@@ -456,11 +494,14 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
     for (int s = 0; s < PF; ++s) {
       const int c = base + NWV * s;
       const bool live = c < n_chunks;  // uniform
-      bf16x8 xb[2];
-      f32x4 acc[EB];
+      bf16x8 xb[TT][2];
+      f32x4 acc[TT][EB];
       if (live) {
-        xb[0] = __builtin_bit_cast(bf16x8, xa[s][0]);
-        xb[1] = __builtin_bit_cast(bf16x8, xa[s][1]);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          xb[tt][0] = __builtin_bit_cast(bf16x8, xa[s][tt][0]);
+          xb[tt][1] = __builtin_bit_cast(bf16x8, xa[s][tt][1]);
+        }
         // one expert block at a time: split its router weights into three bf16 pieces, stage them
         // K-contiguous per expert, multiply
 #pragma unroll
@@ -488,13 +529,16 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
             *reinterpret_cast<u32x2*>(row + 2 * 16 * FT_ROW) = v;
           }
           asm volatile("" ::: "memory");  // keep the LDS reads below the LDS writes above (same wavefront: in order)
-          acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) acc[tt][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
               const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + (p * 16 + tl) * FT_ROW + kq * 32 + s2 * 16);
-              acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[s2], acc[m], 0, 0, 0);
+#pragma unroll
+              for (int tt = 0; tt < TT; ++tt)
+                acc[tt][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xb[tt][s2], acc[tt][m], 0, 0, 0);
             }
           asm volatile("" ::: "memory");  // ... and the next block's writes below these reads
         }
@@ -502,23 +546,28 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
       GATE_LOAD_STAGE(s, c + NWV * PF)  // refill this register stage
       if (live) {
 #pragma unroll
-        for (int b = 0; b < EB; ++b)
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) zacc[b][r] += (double)acc[b][r];
+          for (int b = 0; b < EB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) zacc[tt][b][r] += (double)acc[tt][b][r];
       }
     }
   }
 #undef GATE_LOAD_STAGE
-  __syncthreads();  // every wavefront is done with its staging area
+  lds_barrier();     // every wavefront is done with its staging area
 
   // ---- cross-wavefront sum of the partial logits (float64) and per-token finalisation ------------
-  double* part = reinterpret_cast<double*>(smem);  // [NWV][EP][FT_TOK]
+  double* part = reinterpret_cast<double*>(smem);  // [NWV][EP][NTOK]
 #pragma unroll
-  for (int b = 0; b < EB; ++b)
+  for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) part[((size_t)wave * EP + b * 16 + kq * 4 + r) * FT_TOK + tl] = zacc[b][r];
-  __syncthreads();
-  if (tid < FT_TOK * 8) {
+    for (int b = 0; b < EB; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        part[((size_t)wave * EP + b * 16 + kq * 4 + r) * NTOK + tt * FT_TOK + tl] = zacc[tt][b][r];
+  lds_barrier();
+  if (tid < NTOK * 8) {
     const int tok = tid >> 3, sub = tid & 7;
     const int t = t0 + tok;
     double z[NPL];
@@ -527,9 +576,9 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
       const int e = sub + 8 * i;
       double v = -INFINITY;
       if (e < E) {
-        v = part[(size_t)e * FT_TOK + tok];
+        v = part[(size_t)e * NTOK + tok];
 #pragma unroll
-        for (int w = 1; w < NWV; ++w) v += part[((size_t)w * EP + e) * FT_TOK + tok];
+        for (int w = 1; w < NWV; ++w) v += part[((size_t)w * EP + e) * NTOK + tok];
         if (br) v += (double)br[e];
       }
       z[i] = v;
@@ -539,15 +588,14 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
 #pragma unroll
     for (int i = 0; i < NPL; ++i)
       if (sub + 8 * i < E) zmax = fmaxf(zmax, fabsf((float)z[i]));
-#pragma unroll
-    for (int m = 1; m <= 4; m <<= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, m, 64));
+    group8_steps([&](auto st) { zmax = fmaxf(zmax, group8_partner<decltype(st)::value>(zmax)); });
     bool flag = false;
     if (t < T)
       flag = finalize_group<NPL>(z, sub, E, k, renorm, GATE_MARGIN_REL * zmax, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,
                                  probs ? probs + (size_t)tc * E : nullptr);
     if (sub == 0) s_flag[tok] = flag ? 1 : 0;
   }
-  __syncthreads();
+  lds_barrier();
 
   // ---- exact recompute of the rare tokens whose ranking is within the margin -------------------
   // Each wavefront takes a contiguous K range; a load instruction covers whole router rows (lane = expert
@@ -555,7 +603,7 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
   // workgroup delays the whole kernel by the time this takes.  The products are exact in float64 and so is
   // their sum up to rounding at 2^-53, far below any gap that can decide a ranking.  The flags are turned
   // into one wave-uniform mask first (no LDS read per token).
-  uint32_t flagged = (uint32_t)__ballot(lane < FT_TOK && s_flag[lane & (FT_TOK - 1)] != 0);
+  uint32_t flagged = (uint32_t)__ballot(lane < NTOK && s_flag[lane & (NTOK - 1)] != 0);
   flagged = __builtin_amdgcn_readfirstlane(flagged);
   constexpr int QN = EP / 4;    // expert quads per router row
   constexpr int RPI = 64 / QN;  // router rows per load instruction of a wavefront
@@ -597,14 +645,14 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
 #pragma unroll
       for (int j = 0; j < 4; ++j) zpart[wave * EP + q * 4 + j] = a[j];
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < E) {
       double v = zpart[tid];
 #pragma unroll
       for (int w = 1; w < NWV; ++w) v += zpart[w * EP + tid];
       zex[tid] = v + (br ? (double)br[tid] : 0.0);
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < 8) {
       double z[NPL];
 #pragma unroll
@@ -612,7 +660,7 @@ __global__ __launch_bounds__(gate_waves<EB>() * 64) void gate_mfma_kernel(const 
       finalize_group<NPL>(z, tid, E, k, renorm, 0.f, topk_idx + (size_t)t * k, topk_w + (size_t)t * k,
                           probs ? probs + (size_t)t * E : nullptr);
     }
-    __syncthreads();
+    lds_barrier();
   }
 }
 
@@ -622,15 +670,19 @@ int32_t launch_fast(const moe_config* cfg, const void* x, const float* w_router,
   constexpr int EP = EB * 16;
   constexpr int NWV = gate_waves<EB>();
   const size_t w_bytes = (size_t)NWV * 3 * 16 * FT_ROW;
-  const size_t z_bytes = (size_t)NWV * EP * FT_TOK * sizeof(double) + 256;
+  // two token tiles per workgroup for narrow routers once that still leaves a workgroup for every CU
+  constexpr int TT_MAX = EB == 1 ? 2 : 1;
+  const int tt = (TT_MAX == 2 && cfg->T >= 2 * FT_TOK * 256) ? 2 : 1;  // (256 CUs)
+  const size_t z_bytes = (size_t)NWV * EP * FT_TOK * tt * sizeof(double) + 256;
   const size_t shmem = w_bytes > z_bytes ? w_bytes : z_bytes;
   const bool vec = cfg->E % 4 == 0 && ((uintptr_t)w_router & 15) == 0;
-  auto kern = vec ? gate_mfma_kernel<EB, true> : gate_mfma_kernel<EB, false>;
+  auto kern = tt == 2 ? (vec ? gate_mfma_kernel<EB, true, TT_MAX> : gate_mfma_kernel<EB, false, TT_MAX>)
+                      : (vec ? gate_mfma_kernel<EB, true, 1> : gate_mfma_kernel<EB, false, 1>);
   if (shmem > 65536) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return check_hip(e, "hipFuncSetAttribute(gate LDS)");
   }
-  hipLaunchKernelGGL(kern, dim3((cfg->T + FT_TOK - 1) / FT_TOK), dim3(NWV * 64), shmem, s, (const uint16_t*)x, w_router,
+  hipLaunchKernelGGL(kern, dim3((cfg->T + FT_TOK * tt - 1) / (FT_TOK * tt)), dim3(NWV * 64), shmem, s, (const uint16_t*)x, w_router,
                      b_router, cfg->T, cfg->d_model, cfg->E, cfg->k, cfg->renormalize, topk_idx, topk_w, probs);
   return check_hip(hipGetLastError(), "gate launch");
 }
@@ -889,8 +941,7 @@ __device__ __forceinline__ void gate_finish(f32x16 (&acc)[NB][FR], unsigned char
         }
         z[i] = v;
       }
-#pragma unroll
-      for (int m = 1; m <= 4; m <<= 1) zabs = fmaxf(zabs, __shfl_xor(zabs, m, 64));
+      group8_steps([&](auto st) { zabs = fmaxf(zabs, group8_partner<decltype(st)::value>(zabs)); });
       const int tc = min(t, T - 1);
       if (t < T)
         finalize_group<NPL>(z, sub, E, k, renorm, GATE_REL_MARGIN * zabs, topk_idx + (size_t)tc * k, topk_w + (size_t)tc * k,

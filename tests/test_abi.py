@@ -305,3 +305,27 @@ def test_ring_recycles_its_copy_events_without_a_stats_call():
     assert st["copies"] == K + 50 * N and st["copy_ms"] == 2.0 * st["copies"]
     ring.close()
     assert be.n_events == 0
+
+
+def test_binding_refuses_tensors_smaller_than_the_configuration_says():
+    """bfloat16 tensors under a float32 configuration (or a short buffer) must fail on the host, before any launch:
+    behind the C ABI they would be read and written past their end on the device."""
+    import torch
+    cfg = M.MoEConfig(T=64, d_model=128, d_ff=256, E=4, k=1, capacity_factor=0.0, act="gelu", dtype="f32")
+    x = torch.zeros(64, 128, dtype=torch.bfloat16)       # half the bytes the configuration needs
+    ok = torch.zeros(64, 128, dtype=torch.float32)
+    wr = torch.zeros(128, 4)
+    idx = torch.zeros(64, 1, dtype=torch.int32)
+    w = torch.zeros(64, 1)
+    with pytest.raises(ValueError, match="x holds"):
+        M.moe_gate(cfg, x, wr, None, idx, w)
+    with pytest.raises(ValueError, match="topk_idx holds"):
+        M.moe_gate(cfg, ok, wr, None, idx[:32], w)
+    with pytest.raises(ValueError, match="w_router holds"):
+        M.moe_gate(cfg, ok, wr[:, :2].contiguous(), None, idx, w)
+    W = M.Weights.__new__(M.Weights)                      # (no device pointers needed for the size check)
+    W.tensors = {"w_router": wr, "w1": torch.zeros(4, 256, 128, dtype=torch.bfloat16), "w2": torch.zeros(4, 128, 256)}
+    with pytest.raises(ValueError, match="w1 holds"):
+        W.need(cfg)
+    with pytest.raises(ValueError, match="out holds"):
+        M.moe_combine(cfg, None, idx, w, None, x)
