@@ -45,6 +45,11 @@ GATE_CASES = [
     small("tiny", T=16, E=4, k=4),                        # float32 activations, k = E
     small("gpt", T=5, E=33, k=3, d_model=320),            # other expert counts: the general kernels
     small("gpt", T=16, E=65, k=2, d_model=256),
+    # 8192 tokens and more with at most 16 experts: two 16-token tiles per workgroup; ragged ends (a last workgroup
+    # with one token in its second tile, with half a first tile and no second one), a router read element-wise
+    small("gpt", T=8209, d_model=256),
+    small("skew", T=8200, d_model=128),
+    small("gpt", T=8197, E=5, k=3, d_model=192),
 ]
 
 
@@ -110,14 +115,15 @@ def test_gate_packed_router(wl):
     assert np.allclose(probs, p_ref, rtol=GATE_RTOL, atol=1e-30)
 
 
+@pytest.mark.parametrize("T", [700, 8217], ids=["one-tile", "two-tiles"])
 @pytest.mark.parametrize("packed", [True, False])
 @pytest.mark.parametrize("scale", [1.0, 1e3, 1e-3])
-def test_gate_near_ties_at_any_scale(scale, packed):
+def test_gate_near_ties_at_any_scale(scale, packed, T):
     """Planted near-ties: pairs of router columns that differ in the last bits of a few weights, so that two
     experts' logits differ by far less than the fast path's accumulation error, at three input scales (the
     recompute margin scales with the partial sums).  Ranking must still equal the float64 oracle's."""
     rng = np.random.default_rng(11)
-    T, d, E, k = 700, 1024, 16, 2
+    d, E, k = 1024, 16, 2                                     # (T >= 8192: moe_gate takes two token tiles per workgroup)
     x = bf16_round_np(rng.standard_normal((T, d)).astype(np.float32) * np.float32(scale))
     wr = (rng.standard_normal((d, E)) / 32).astype(np.float32)
     for a, b in ((0, 5), (3, 9), (7, 12)):                   # b is a, a few weights nudged by one unit in the last place
